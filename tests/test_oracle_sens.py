@@ -1,0 +1,249 @@
+"""Pins for the oracle's absmax/scale, the two sums E and A, and the epilogue.
+
+No GPU, no GPU library.  Pins: hand-worked cases (tests/golden/sens_hand_case.txt), an
+fp64 library dot product for A, exact rational closed forms for the rounding error of
+uniform mantissas, the bounds that follow from half-ulp rounding, additivity and
+masking identities, and the constants the paper prints (alpha_f, Sec. 2.2).
+"""
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+from helpers import bf16_bits_to_f64, f32_to_bf16_bits
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "sens_hand_case.txt")
+FMAX = {oracle.E4M3: 448.0, oracle.E5M2: 57344.0}
+MBITS = {oracle.E4M3: 3, oracle.E5M2: 2}
+
+
+def hand_cases():
+    cases = {}
+    for line in open(GOLDEN):
+        tok = line.split("#")[0].split()
+        if not tok:
+            continue
+        c = cases.setdefault(tok[0], {})
+        if tok[1] == "scale":
+            c["scale"], c["inv"] = float(tok[2]), float(tok[4])
+        elif tok[1] in ("x", "xdot"):
+            c[tok[1]] = np.array([float(t) for t in tok[2:]], dtype=np.float32)
+        else:
+            c[tok[1]] = float(tok[2])
+    return cases
+
+
+@pytest.mark.parametrize("name", ["case1", "case2"])
+def test_hand_worked_sums(name):
+    c = hand_cases()[name]
+    x, g = f32_to_bf16_bits(c["x"]), f32_to_bf16_bits(c["xdot"])
+    assert np.array_equal(bf16_bits_to_f64(x), c["x"].astype(np.float64))   # inputs are bf16-exact
+    E, A = oracle.sens_operand(x, g, 1, x.size, c["scale"], c["inv"], oracle.E4M3)
+    assert E[0] == c["E"]
+    assert A[0] == c["A"]
+
+
+def test_alpha_constants():
+    # alpha_f = 2^(-2 m_f)/12: 1/768 for three mantissa bits, 1/192 for two
+    assert oracle.alpha(3) == 1.0 / 768.0
+    assert oracle.alpha(2) == 1.0 / 192.0
+    assert oracle.alpha(0) == 1.0 / 12.0
+
+
+def rand_bf16(rng, n, sigma=1.0):
+    return f32_to_bf16_bits((rng.standard_normal(n) * sigma).astype(np.float32))
+
+
+@pytest.mark.parametrize("fmt", [oracle.E4M3, oracle.E5M2])
+def test_A_is_squared_norm_of_elementwise_product(fmt):
+    rng = np.random.default_rng(3)
+    R, n = 3, 5001
+    x, g = rand_bf16(rng, R * n), rand_bf16(rng, R * n, 1e-3)
+    am, sc, iv, fl = oracle.absmax_scale(x, fmt)
+    E, A = oracle.sens_operand(x, g, R, n, sc, iv, fmt)
+    xv, gv = bf16_bits_to_f64(x).reshape(R, n), bf16_bits_to_f64(g).reshape(R, n)
+    for r in range(R):
+        t = xv[r] * gv[r]
+        assert A[r] == pytest.approx(np.dot(t, t), rel=1e-13)
+    # xdot == 1 -> A = ||x||^2 ; xdot == c -> E scales by c^2
+    ones = f32_to_bf16_bits(np.ones(R * n, dtype=np.float32))
+    E1, A1 = oracle.sens_operand(x, ones, R, n, sc, iv, fmt)
+    assert A1[0] == pytest.approx(np.dot(xv[0], xv[0]), rel=1e-13)
+    fours = f32_to_bf16_bits(np.full(R * n, 4.0, dtype=np.float32))
+    E4, A4 = oracle.sens_operand(x, fours, R, n, sc, iv, fmt)
+    assert np.allclose(E4, 16.0 * E1, rtol=1e-14) and np.allclose(A4, 16.0 * A1, rtol=1e-14)
+
+
+@pytest.mark.parametrize("fmt", [oracle.E4M3, oracle.E5M2])
+def test_E_equals_error_of_dequantised_tensor(fmt):
+    """E recomputed from the oracle's own codes via the pinned decode table (ties the sum to
+    the separately pinned cast) and checked against the half-ulp bound."""
+    rng = np.random.default_rng(11)
+    n = 20000
+    x, g = rand_bf16(rng, n), rand_bf16(rng, n, 1e-3)
+    am, sc, iv, fl = oracle.absmax_scale(x, fmt)
+    codes, deq = oracle.fake_quant_fp8(x, sc, iv, fmt)
+    q = oracle.fp8_decode_table(fmt)[codes]
+    xv, gv = bf16_bits_to_f64(x), bf16_bits_to_f64(g)
+    e = xv - q * np.float64(sc)
+    E, A = oracle.sens_operand(x, g, 1, n, sc, iv, fmt)
+    assert E[0] == pytest.approx(np.sum((gv * e) ** 2), rel=1e-13)
+    # dequant is one fp32 multiply of q by scale
+    assert np.array_equal(deq, (q.astype(np.float32) * np.float32(sc)))
+
+
+@pytest.mark.parametrize("fmt", [oracle.E4M3, oracle.E5M2])
+@pytest.mark.parametrize("exp", [-3, 0, 5])
+def test_closed_form_uniform_mantissas(fmt, exp):
+    """All 128 bf16 mantissas of one normal binade, scale 1, xdot = 1:
+    mean(e^2)/ulp^2 = (1 + 2/n^2)/12 exactly, n = 2^(7-m) inputs per FP8 interval."""
+    m = MBITS[fmt]
+    n_per = 2 ** (7 - m)
+    xs = [Fraction(2) ** exp * (1 + Fraction(k, 128)) for k in range(128)]
+    x = f32_to_bf16_bits(np.array([float(v) for v in xs], dtype=np.float32))
+    ones = f32_to_bf16_bits(np.ones(128, dtype=np.float32))
+    E, A = oracle.sens_operand(x, ones, 1, 128, 1.0, 1.0, fmt)
+    ulp = Fraction(2) ** (exp - m)
+    want_E = 128 * ulp ** 2 * (1 + Fraction(2, n_per ** 2)) / 12
+    want_A = sum(v * v for v in xs)
+    assert E[0] == pytest.approx(float(want_E), rel=1e-15)
+    assert A[0] == pytest.approx(float(want_A), rel=1e-15)
+    ratio = (E[0] / A[0]) / oracle.alpha(m)
+    assert ratio == pytest.approx(0.4341 if fmt == oracle.E4M3 else 0.4316, abs=5e-4)
+
+
+@pytest.mark.parametrize("fmt", [oracle.E4M3, oracle.E5M2])
+def test_noise_model_envelope_on_random_mantissas(fmt):
+    """Random uniform mantissas over many normal binades: the measured E/A sits near the
+    3/7-type constant of the closed form and inside (alpha/4, alpha]; hard bound E <= 3 alpha A."""
+    rng = np.random.default_rng(5)
+    n = 400000
+    m = MBITS[fmt]
+    lo = -4 if fmt == oracle.E4M3 else -12
+    mant = 1.0 + rng.integers(0, 128, n) / 128.0
+    x = f32_to_bf16_bits((mant * np.exp2(rng.integers(lo, 8, n)) * rng.choice([-1, 1], n)).astype(np.float32))
+    g = f32_to_bf16_bits(np.exp(rng.normal(0, 0.5, n)).astype(np.float32))
+    E, A = oracle.sens_operand(x, g, 1, n, 1.0, 1.0, fmt)
+    ratio = E[0] / A[0] / oracle.alpha(m)
+    assert 0.25 < ratio <= 1.0
+    assert ratio == pytest.approx(0.4341 if fmt == oracle.E4M3 else 0.4316, rel=0.02)
+    assert E[0] <= 3 * oracle.alpha(m) * A[0]
+
+
+@pytest.mark.parametrize("fmt", [oracle.E4M3, oracle.E5M2])
+def test_zero_error_on_grid_values_at_scale_one(fmt):
+    t = oracle.fp8_decode_table(fmt)
+    grid = t[np.isfinite(t)].astype(np.float32)
+    x = f32_to_bf16_bits(grid)
+    assert np.array_equal(bf16_bits_to_f64(x), grid.astype(np.float64))     # grid fits bf16
+    g = f32_to_bf16_bits(np.full(grid.size, 3.0, dtype=np.float32))
+    E, A = oracle.sens_operand(x, g, 1, grid.size, 1.0, 1.0, fmt)
+    assert E[0] == 0.0 and A[0] > 0.0
+
+
+def test_additive_over_concatenation_and_permutation():
+    rng = np.random.default_rng(9)
+    n = 4096
+    x, g = rand_bf16(rng, 2 * n), rand_bf16(rng, 2 * n, 1e-3)
+    sc, iv = np.float32(0.013), np.float32(1 / 0.013)
+    E, A = oracle.sens_operand(x, g, 1, 2 * n, sc, iv, oracle.E4M3)
+    Eh, Ah = oracle.sens_operand(x, g, 2, n, sc, iv, oracle.E4M3)      # same data as two samples
+    assert E[0] == pytest.approx(Eh.sum(), rel=1e-13) and A[0] == pytest.approx(Ah.sum(), rel=1e-13)
+    p = rng.permutation(2 * n)
+    Ep, Ap = oracle.sens_operand(x[p], g[p], 1, 2 * n, sc, iv, oracle.E4M3)
+    assert E[0] == pytest.approx(Ep[0], rel=1e-12) and A[0] == pytest.approx(Ap[0], rel=1e-12)
+
+
+@pytest.mark.parametrize("rows,cols", [(8, 8), (5, 9), (7, 3), (16, 24)])
+def test_causal_equals_dense_with_explicit_zeros(rows, cols):
+    rng = np.random.default_rng(rows * 100 + cols)
+    R, batch = 2, 3
+    n = batch * rows * cols
+    x, g = rand_bf16(rng, R * n), rand_bf16(rng, R * n)
+    i = np.arange(rows)[:, None]
+    j = np.arange(cols)[None, :]
+    keep = (j <= i + (cols - rows))
+    mask = np.broadcast_to(keep, (R, batch, rows, cols)).reshape(-1)
+    xz, gz = np.where(mask, x, 0).astype(np.uint16), np.where(mask, g, 0).astype(np.uint16)
+    sc, iv = np.float32(0.01), np.float32(100.0)
+    Ec, Ac = oracle.sens_operand(x, g, R, 0, sc, iv, oracle.E4M3, causal=(batch, rows, cols))
+    Ed, Ad = oracle.sens_operand(xz, gz, R, n, sc, iv, oracle.E4M3)
+    assert np.array_equal(Ec, Ed) and np.array_equal(Ac, Ad)
+    # absmax over a causal operand ignores the masked entries
+    big = x.copy()
+    big[~mask] = f32_to_bf16_bits(np.array([1e6], dtype=np.float32))[0]
+    am_c = oracle.absmax_scale(big, oracle.E4M3, causal=(batch, rows, cols))[0]
+    am_d = oracle.absmax_scale(xz, oracle.E4M3)[0]
+    assert am_c == am_d
+
+
+@pytest.mark.parametrize("fmt", [oracle.E4M3, oracle.E5M2])
+def test_absmax_scale_pins(fmt):
+    F = np.float32(FMAX[fmt])
+    x = f32_to_bf16_bits(np.array([0.5, -3.0, 2.0, float(F)], dtype=np.float32))
+    am, sc, iv, fl = oracle.absmax_scale(x, fmt)
+    assert (am, sc, iv, fl) == (F, 1.0, 1.0, 0)                      # amax = FMAX -> unit scale
+    x = f32_to_bf16_bits(np.array([0.5, -3.0, 2.0], dtype=np.float32))
+    am, sc, iv, fl = oracle.absmax_scale(x, fmt)
+    assert am == 3.0 and sc == np.float32(3.0) / F and iv == F / np.float32(3.0) and fl == 0
+    assert abs(float(sc) * float(F) - 3.0) <= 3.0 * 2.0 ** -23
+    zeros = np.zeros(7, dtype=np.uint16)
+    zeros[3] = 0x8000
+    assert oracle.absmax_scale(zeros, fmt) == (0.0, 1.0, 1.0, 0)
+    tiny = np.array([0x0001], dtype=np.uint16)                      # bf16 subnormal 2^-133
+    am, sc, iv, fl = oracle.absmax_scale(tiny, fmt)
+    assert am == np.float32(2.0 ** -133) and (sc, iv) == (1.0, 1.0)  # reciprocal would overflow
+    inf = np.array([0x3F80, 0xFF80], dtype=np.uint16)
+    assert oracle.absmax_scale(inf, fmt)[3] == 1
+    nan = np.array([0x3F80, 0x7FC0], dtype=np.uint16)
+    assert oracle.absmax_scale(nan, fmt)[3] == 1
+    # the largest element maps onto the largest code (the clamp absorbs a 1-ulp overshoot)
+    rng = np.random.default_rng(1)
+    for _ in range(50):
+        x = rand_bf16(rng, 64, float(np.exp(rng.normal(0, 3))))
+        am, sc, iv, fl = oracle.absmax_scale(x, fmt)
+        codes, _ = oracle.fake_quant_fp8(x, sc, iv, fmt)
+        k = np.argmax(np.abs(bf16_bits_to_f64(x)))
+        assert codes[k] & 0x7F == (0x7E if fmt == oracle.E4M3 else 0x7B)
+
+
+def test_linear_and_bgemm_wrappers_compose_operands():
+    rng = np.random.default_rng(21)
+    R, Cd, K = 3, 24, 10
+    row_off = np.array([0, 5, 6, 13], dtype=np.int64)               # ragged samples
+    x, dx = rand_bf16(rng, 13 * Cd), rand_bf16(rng, 13 * Cd, 1e-3)
+    w, dw = rand_bf16(rng, K * Cd, 0.02), rand_bf16(rng, R * K * Cd, 1e-3)
+    _, xs, xi, _ = oracle.absmax_scale(x, oracle.E5M2)
+    _, ws, wi, _ = oracle.absmax_scale(w, oracle.E5M2)
+    out = oracle.sens_linear(x, dx, w, dw, Cd, K, R, row_off, xs, xi, ws, wi, oracle.E5M2)
+    for r in range(R):
+        a, b = row_off[r] * Cd, row_off[r + 1] * Cd
+        E, A = oracle.sens_operand(x[a:b], dx[a:b], 1, b - a, xs, xi, oracle.E5M2)
+        assert (out[r, 0], out[r, 1]) == (E[0], A[0])
+    Ew, Aw = oracle.sens_operand(w, dw, R, K * Cd, ws, wi, oracle.E5M2, x_shared=True)
+    assert np.array_equal(out[:, 2], Ew) and np.array_equal(out[:, 3], Aw)
+
+    H, S, D = 2, 8, 4
+    p, dp = rand_bf16(rng, R * H * S * S), rand_bf16(rng, R * H * S * S, 1e-3)
+    v, dv = rand_bf16(rng, R * H * S * D), rand_bf16(rng, R * H * S * D, 1e-3)
+    out = oracle.sens_bgemm(p, dp, ("causal", H, S, S), v, dv, ("dense", H * S * D), R,
+                            0.01, 100.0, 0.02, 50.0, oracle.E4M3)
+    E0, A0 = oracle.sens_operand(p, dp, R, 0, 0.01, 100.0, oracle.E4M3, causal=(H, S, S))
+    E1, A1 = oracle.sens_operand(v, dv, R, H * S * D, 0.02, 50.0, oracle.E4M3)
+    assert np.array_equal(out, np.stack([E0, A0, E1, A1], axis=1))
+
+
+def test_epilogue_mean_sensitivity_and_group_mse():
+    # s_l = mean_r (A_0^r + A_1^r); d_{l,f} = s_l alpha_f; d_{j,p} additive over a group's layers
+    A0, A1 = np.array([1.0, 2.0, 6.0]), np.array([0.5, 0.25, 0.25])
+    assert oracle.layer_sensitivity(A0, A1) == pytest.approx(10.0 / 3.0, rel=1e-15)
+    s = np.array([2.0, 3.0, 5.0])
+    alphas = np.array([0.0, 1.0 / 768.0, 1.0 / 192.0])              # BF16, E4M3, E5M2
+    d = oracle.group_mse(s, alphas)
+    assert d.size == 27 and d[0] == 0.0
+    for p in range(27):
+        digits = [(p // 3 ** l) % 3 for l in range(3)]
+        assert d[p] == pytest.approx(sum(s[l] * alphas[digits[l]] for l in range(3)), rel=1e-15)
+    assert d[26] == pytest.approx(10.0 / 192.0, rel=1e-15)
