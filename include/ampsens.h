@@ -1,0 +1,212 @@
+/* libampsens -- per-operator loss-MSE sensitivity statistics for FP8 mixed precision,
+ * hand-written for AMD MI355X (gfx950).
+ *
+ * What the library computes (paper: "Automatic mixed precision for optimizing gained time
+ * with constrained loss mean-squared-error based on model partition to sequential
+ * sub-graphs", arXiv 2505.13060):
+ *
+ *   For every linear operation l of a network (a linear layer with operands X_l, W_l, or a
+ *   BGEMM with operands X_{0,l}, X_{1,l}; Sec. 2.2, definition of the extended input z_l)
+ *   and every calibration sample r, with zdot = dg/dz evaluated at high precision:
+ *
+ *     A = sum_k zdot_k^2 z_k^2            the sensitivity s_l^r = ||z (.) zdot||^2 of Sec. 2.2,
+ *                                         restricted to one operand;
+ *     E = sum_k zdot_k^2 (z_k - ztilde_k)^2   the first-order Taylor term (ztilde)^T zdot of
+ *                                         Sec. 2.2 with the actual rounding error of an FP8 cast
+ *                                         in place of the uniform-noise model, components taken
+ *                                         as independent as the paper does.
+ *
+ *   ztilde is the per-tensor-absmax-scaled FP8 fake quantisation of z.  The paper names the
+ *   format only as "FP8-E4M3: 4 exponent, 3 mantissa bits" (Sec. 3.1) and does not describe
+ *   the cast; this library uses the OCP 8-bit formats (E4M3: max 448, no infinities; E5M2:
+ *   max 57344), round to nearest even, saturating:
+ *
+ *     amax  = max_k |z_k| over the whole operand buffer
+ *     scale = amax / FMAX, inv = FMAX / amax   (fp32 divisions; amax == 0, or an inv that
+ *                                               overflows fp32, gives scale = inv = 1)
+ *     y     = fl32(z_k * inv) clamped to +-FMAX;  code = RNE_f(y);  q = decode_f(code)
+ *     ztilde_k = q * scale;   z_k - ztilde_k is formed as one fused multiply-add in fp32.
+ *
+ *   The sums then feed the host-side selection of eq. (ip) (Sec. 2.1): one format combination
+ *   per sequential sub-graph, maximising gained time under a loss-MSE budget.
+ *
+ * Conventions
+ *   - bf16 tensors are uint16_t storage.  "device" pointers are HIP device memory, "host"
+ *     pointers ordinary memory.  Inputs are never written.  The caller owns every buffer,
+ *     including the workspace; the library allocates no device memory and frees nothing.
+ *   - Device calls validate their arguments on the host first (no launch happens on an error),
+ *     then enqueue on the caller's stream (a hipStream_t passed as void*, NULL = the null
+ *     stream).  They do not wait for the GPU.  Each call copies a small descriptor table from
+ *     pageable host memory into the workspace with hipMemcpyAsync, which may block the host
+ *     until earlier work on that stream has drained.
+ *   - Pointers need only 2-byte alignment; 16-byte aligned buffers take the fast path
+ *     (128-bit loads).  Results do not depend on the launch grid.
+ *   - Every call returns amp_status_t.  After AMP_ERR_DEVICE, amp_last_device_error() gives
+ *     the hipError_t of the failing runtime call (per host thread).
+ *   - Non-finite inputs: amp_absmax_scale raises bit 0 of the tensor's flag word; the sums of
+ *     an operand that holds NaN or Inf are unspecified.
+ */
+#ifndef AMPSENS_H
+#define AMPSENS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum amp_status {
+    AMP_OK = 0,
+    AMP_ERR_INVALID_ARG = 1,         /* null pointer, negative size, inconsistent descriptor */
+    AMP_ERR_BAD_FORMAT = 2,          /* format enum out of range, or n_fmts not in [1, AMP_MAX_FORMATS] */
+    AMP_ERR_WORKSPACE_TOO_SMALL = 3,
+    AMP_ERR_NONFINITE_INPUT = 4,     /* reserved for callers that read the flag words back */
+    AMP_ERR_DEVICE = 5,              /* a HIP runtime call failed; see amp_last_device_error() */
+    AMP_ERR_INFEASIBLE = 6,          /* amp_select_subgraphs: no configuration meets the budget */
+    AMP_ERR_TOO_LARGE = 7            /* more work than the 32-bit chunk index can address */
+} amp_status_t;
+
+typedef enum amp_fp8_format {
+    AMP_FP8_E4M3 = 0,                /* OCP E4M3: bias 7, max 448, S.1111.111 = NaN, m_f = 3 */
+    AMP_FP8_E5M2 = 1                 /* OCP E5M2: bias 15, max 57344, IEEE-like, m_f = 2 */
+} amp_fp8_format_t;
+
+#define AMP_MAX_FORMATS 2
+
+/* Shape of one sample's block of an operand.
+ * causal == 0: n_elems consecutive elements (batch/rows/cols ignored).
+ * causal == 1: a [batch, rows, cols] array of which entry (b, i, j) belongs to the operand
+ *              iff j <= i + (cols - rows) (lower triangle, aligned bottom-right; the attention
+ *              probabilities P of a causal model).  Other entries are never read and count as
+ *              zero.  n_elems is ignored; the block spans batch*rows*cols elements. */
+typedef struct amp_layout {
+    int64_t n_elems;
+    int64_t batch, rows, cols;
+    int32_t causal;
+    int32_t reserved;
+} amp_layout_t;
+
+/* One operand buffer for amp_absmax_scale: n_samples consecutive blocks of `layout`. */
+typedef struct amp_tensor {
+    const uint16_t* data;            /* device, bf16 */
+    amp_layout_t layout;
+    int64_t n_samples;
+} amp_tensor_t;
+
+/* Linear layer Y = X W^T (+ bias, which is not part of z; Sec. 2.2 eq. (lin_layer)).
+ * X stacks the R samples along its rows. */
+typedef struct amp_linear_desc {
+    const uint16_t* x;               /* device bf16 [rows_total, C] */
+    const uint16_t* dx;              /* device bf16 [rows_total, C]: dg/dX */
+    const uint16_t* w;               /* device bf16 [K, C], shared by all samples */
+    const uint16_t* dw;              /* device bf16 [R, K, C]: dg^r/dW of each sample */
+    int64_t C, K;
+    int64_t tokens;                  /* rows per sample, used when sample_row_offsets == NULL */
+    const int64_t* sample_row_offsets; /* HOST, R+1 non-decreasing entries, first 0: sample r owns
+                                          rows [off[r], off[r+1]); NULL = equal blocks of `tokens` */
+    int32_t R;
+    int32_t reserved;
+    const float* x_scale;            /* device [n_fmts]: scale of X per candidate format */
+    const float* x_inv;              /* device [n_fmts]: reciprocal scale of X */
+    const float* w_scale;            /* device [n_fmts] */
+    const float* w_inv;              /* device [n_fmts] */
+} amp_linear_desc_t;
+
+/* BGEMM (Sec. 2.2 eq. (bgemm_layer)); both operands carry one block per sample. */
+typedef struct amp_bgemm_desc {
+    const uint16_t* x0;              /* device bf16 [R] x layout0 */
+    const uint16_t* dx0;             /* device bf16, same shape: dg/dX0 */
+    const uint16_t* x1;              /* device bf16 [R] x layout1 */
+    const uint16_t* dx1;
+    amp_layout_t layout0, layout1;
+    int32_t R;
+    int32_t reserved;
+    const float* scale0;             /* device [n_fmts] */
+    const float* inv0;
+    const float* scale1;
+    const float* inv1;
+} amp_bgemm_desc_t;
+
+/* ---- step 1: per-tensor absmax and scales ----------------------------------------------
+ * For tensor t and format index f:
+ *   d_amax[t]                = max |x| over the entries that belong to the tensor
+ *   d_scale[t*n_fmts + f]    = amax / FMAX_f          d_inv[t*n_fmts + f] = FMAX_f / amax
+ *   d_flags[t]               = bit 0 set iff a NaN or Inf was seen
+ * One launch sequence covers all tensors.  Outputs are device arrays; workspace is device
+ * memory of at least amp_absmax_workspace_bytes() bytes, 256-byte aligned, and must not be
+ * shared with a call still in flight.  n_tensors == 0 is a no-op. */
+amp_status_t amp_absmax_workspace_bytes(const amp_tensor_t* tensors, int n_tensors, size_t* bytes);
+amp_status_t amp_absmax_scale(const amp_tensor_t* tensors /* host array */, int n_tensors,
+                              const amp_fp8_format_t* fmts /* host */, int n_fmts,
+                              float* d_amax, float* d_scale, float* d_inv, uint32_t* d_flags,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- step 2 (standalone): FP8 fake quantisation ------------------------------------------
+ *   d_codes[i]   = RNE_sat_f(fl32(x_i * inv_scale))      (uint8 FP8 code)
+ *   d_dequant[i] = fl32(decode_f(d_codes[i]) * scale)     (optional, may be NULL)
+ * d_x, d_codes, d_dequant: device, n elements each.  n == 0 is a no-op. */
+amp_status_t amp_fake_quant_fp8(const uint16_t* d_x, int64_t n, float scale, float inv_scale,
+                                amp_fp8_format_t fmt, uint8_t* d_codes, float* d_dequant,
+                                void* stream);
+
+/* ---- step 3: the fused sensitivity pass --------------------------------------------------
+ * One pass over x and xdot of every operand of every op, for all n_fmts candidate formats at
+ * once (each byte is read once whatever n_fmts is).
+ * Output, fp32, device:  with base(k) = sum of R over ops before k,
+ *   d_out[((base(k) + r) * n_fmts + f) * 4 + {0,1,2,3}] = (E_op0, A_op0, E_op1, A_op1)
+ * for op k, sample r, format index f; operand 0 is X (linear) / X0 (BGEMM), operand 1 is W / X1.
+ * A does not depend on f and is repeated.  Sample blocks of zero elements give zeros.
+ * Workspace as for amp_absmax_scale, sized by the matching *_workspace_bytes call. */
+amp_status_t amp_sens_linear_workspace_bytes(const amp_linear_desc_t* ops, int n_ops, int n_fmts,
+                                             size_t* bytes);
+amp_status_t amp_sens_linear(const amp_linear_desc_t* ops /* host array */, int n_ops,
+                             const amp_fp8_format_t* fmts /* host */, int n_fmts, float* d_out,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
+amp_status_t amp_sens_bgemm_workspace_bytes(const amp_bgemm_desc_t* ops, int n_ops, int n_fmts,
+                                            size_t* bytes);
+amp_status_t amp_sens_bgemm(const amp_bgemm_desc_t* ops /* host array */, int n_ops,
+                            const amp_fp8_format_t* fmts /* host */, int n_fmts, float* d_out,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- step 4 (host): epilogue of Sec. 2.2 -------------------------------------------------
+ * sums: HOST copy of one op's block of d_out, [R][n_fmts][4].
+ *   *s_layer       = (1/R) sum_r (A_op0^r + A_op1^r)                 (eq. (sensl))
+ *   d_model[f]     = s_layer * alpha_f, alpha_f = 2^(-2 m_f)/12      (noise-model loss MSE)
+ *   d_measured[f]  = (1/R) sum_r (E_op0^r + E_op1^r)                 (measured first-order term)
+ * d_model / d_measured: host arrays of n_fmts doubles, either may be NULL. */
+amp_status_t amp_layer_loss_mse(const float* sums, int R, const amp_fp8_format_t* fmts, int n_fmts,
+                                double* s_layer, double* d_model, double* d_measured);
+
+/* alpha_f = 2^(-2 m)/12 for a float format with m mantissa bits (Sec. 2.2). */
+double amp_alpha(int mantissa_bits);
+
+/* Tables of one group V_j of L_j layers with F formats each (Sec. 2.1, matrix Q_j):
+ * column p is the base-F digit string of p, layer 0 least significant;
+ *   d[p] = sum_l layer_mse[l*F + digit_l(p)],   c[p] = sum_l layer_gain[l*F + digit_l(p)]
+ * (last equation of Sec. 2.2; additive gain of Sec. 2.3.2).  d and c hold F^L_j doubles.
+ * All host pointers.  F^L_j above 2^24 is rejected. */
+amp_status_t amp_group_tables(int n_layers, int F, const double* layer_mse, const double* layer_gain,
+                              double* d, double* c);
+
+/* ---- step 5 (host): eq. (ip) of Sec. 2.1 --------------------------------------------------
+ * Maximise sum_j gain[j][p_j] subject to sum_j mse[j][p_j] <= mse_budget, one p_j per group.
+ * n_choices[J]; gain and mse are the concatenation of the groups' vectors (sum n_choices
+ * doubles).  Exact (branch and bound).  Among optimal configurations the one with the smaller
+ * total mse is returned.  All pointers host; choice[J] receives p_j; total_gain / total_mse may
+ * be NULL.  AMP_ERR_INFEASIBLE when no configuration meets the budget.  Non-finite or negative
+ * mse entries are AMP_ERR_INVALID_ARG. */
+amp_status_t amp_select_subgraphs(int J, const int32_t* n_choices, const double* gain,
+                                  const double* mse, double mse_budget, int32_t* choice,
+                                  double* total_gain, double* total_mse);
+
+/* ---- misc ---------------------------------------------------------------------------------*/
+const char* amp_status_string(amp_status_t status);
+int amp_last_device_error(void);
+int amp_version(void);               /* major*10000 + minor*100 + patch */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AMPSENS_H */

@@ -1,0 +1,419 @@
+// C-ABI layer of libampsens: argument validation, work-table construction on the host, and
+// the launches.  See include/ampsens.h for the contract of every entry point.
+#include "../../include/ampsens.h"
+#include "internal.h"
+#include "walk.h"
+
+#include <cmath>
+#include <cstring>
+#include <mutex>
+#include <vector>
+
+using namespace ampsens;
+
+namespace {
+
+thread_local int g_last_device_error = 0;
+
+amp_status_t device_error(hipError_t e) {
+    g_last_device_error = (int)e;
+    return AMP_ERR_DEVICE;
+}
+
+#define AMP_HIP(call)                                          \
+    do {                                                       \
+        hipError_t e_ = (call);                                \
+        if (e_ != hipSuccess) return device_error(e_);         \
+    } while (0)
+
+constexpr int64_t kMaxDim = (int64_t)1 << 30;          // causal rows / cols
+constexpr int64_t kMaxElems = (int64_t)1 << 46;        // per unit
+constexpr uint64_t kMaxChunks = 0x7FFFFFFFull;
+constexpr int kWavesPerSimd = 8;                       // persistent grid: 8 workgroups per CU
+
+bool fmt_ok(int f) { return f == AMP_FP8_E4M3 || f == AMP_FP8_E5M2; }
+
+amp_status_t check_fmts(const amp_fp8_format_t* fmts, int n_fmts) {
+    if (n_fmts < 1 || n_fmts > AMP_MAX_FORMATS) return AMP_ERR_BAD_FORMAT;
+    if (!fmts) return AMP_ERR_INVALID_ARG;
+    for (int f = 0; f < n_fmts; ++f)
+        if (!fmt_ok((int)fmts[f])) return AMP_ERR_BAD_FORMAT;
+    return AMP_OK;
+}
+
+bool aligned2(const void* p) { return ((uintptr_t)p & 1u) == 0; }
+
+amp_status_t check_layout(const amp_layout_t& L) {
+    if (L.causal != 0 && L.causal != 1) return AMP_ERR_INVALID_ARG;
+    if (L.causal) {
+        if (L.batch < 0 || L.rows < 0 || L.cols < 0) return AMP_ERR_INVALID_ARG;
+        if (L.rows > kMaxDim || L.cols > kMaxDim) return AMP_ERR_TOO_LARGE;
+        if (L.rows && L.cols && L.batch > kMaxElems / L.rows / L.cols) return AMP_ERR_TOO_LARGE;
+    } else {
+        if (L.n_elems < 0) return AMP_ERR_INVALID_ARG;
+        if (L.n_elems > kMaxElems) return AMP_ERR_TOO_LARGE;
+    }
+    return AMP_OK;
+}
+
+int64_t layout_span(const amp_layout_t& L) {
+    return L.causal ? L.batch * L.rows * L.cols : L.n_elems;
+}
+
+// The table that travels to the device: units, then chunk_begin[n_units + 1].
+struct WorkTable {
+    std::vector<WorkUnit> units;
+    std::vector<uint32_t> chunk_begin;
+    uint64_t n_chunks = 0;
+
+    // x / dx may be null only for blocks without elements.
+    amp_status_t add(const uint16_t* x, const uint16_t* dx, const amp_layout_t& L, int64_t batch_mul,
+                     const float* scale, const float* inv, uint32_t out) {
+        WorkUnit u;
+        std::memset(&u, 0, sizeof(u));
+        u.x = x; u.dx = dx; u.scale = scale; u.inv = inv; u.out = out;
+        uint64_t chunks;
+        if (L.causal) {
+            const int64_t batch = L.batch * batch_mul;
+            u.flags = kUnitCausal;
+            u.n = batch;
+            u.rows = (int32_t)L.rows;
+            u.cols = (int32_t)L.cols;
+            const bool nice = ((uintptr_t)x % 16 == 0) && (dx == nullptr || (uintptr_t)dx % 16 == 0) &&
+                              (L.cols % kVec == 0);
+            if (!nice) u.flags |= kUnitScalar;
+            u.chunks_per_mat = (L.rows > 0 && L.cols > 0) ? causal_chunks_per_mat(L.rows) : 0;
+            chunks = (uint64_t)batch * u.chunks_per_mat;
+            if (chunks == 0) u.chunks_per_mat = 1;         // never divide by zero on the device
+        } else {
+            const int64_t n = L.n_elems * batch_mul;
+            u.n = n;
+            const uint32_t hx = (uint32_t)(((uintptr_t)x % 16) / 2);
+            const bool mutual = dx == nullptr || ((uintptr_t)x % 16) == ((uintptr_t)dx % 16);
+            if (mutual) u.head = hx; else { u.flags |= kUnitScalar; u.head = 0; }
+            u.chunks_per_mat = 1;
+            chunks = unit_chunks_dense(n, u.head);
+        }
+        chunk_begin.push_back((uint32_t)n_chunks);
+        n_chunks += chunks;
+        if (n_chunks > kMaxChunks) return AMP_ERR_TOO_LARGE;
+        units.push_back(u);
+        return AMP_OK;
+    }
+
+    size_t table_bytes() const {
+        return units.size() * sizeof(WorkUnit) + (units.size() + 1) * sizeof(uint32_t);
+    }
+};
+
+size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+int device_cus() {
+    static std::mutex mu;
+    static int cached[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    std::lock_guard<std::mutex> lock(mu);
+    if (cached[dev] == 0) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+            cus = 256;
+        cached[dev] = cus;
+    }
+    return cached[dev];
+}
+
+int g_grid_cap = 0;                                    // test hook: 0 = no cap
+
+int persistent_grid(uint64_t n_chunks) {
+    uint64_t cap = (uint64_t)device_cus() * kWavesPerSimd;
+    if (g_grid_cap > 0 && (uint64_t)g_grid_cap < cap) cap = (uint64_t)g_grid_cap;
+    return (int)(n_chunks < cap ? n_chunks : cap);
+}
+
+// Copies units + chunk_begin (+ extra zero words) to the head of the workspace.
+amp_status_t upload(const WorkTable& t, size_t extra_zero_words, void* workspace, hipStream_t stream) {
+    std::vector<uint8_t> blob(t.table_bytes() + extra_zero_words * 4, 0);
+    std::memcpy(blob.data(), t.units.data(), t.units.size() * sizeof(WorkUnit));
+    std::vector<uint32_t> cb = t.chunk_begin;
+    cb.push_back((uint32_t)t.n_chunks);
+    std::memcpy(blob.data() + t.units.size() * sizeof(WorkUnit), cb.data(), cb.size() * 4);
+    AMP_HIP(hipMemcpyAsync(workspace, blob.data(), blob.size(), hipMemcpyHostToDevice, stream));
+    return AMP_OK;
+}
+
+// ---- sens: shared by linear and bgemm --------------------------------------------------------
+
+size_t sens_workspace(const WorkTable& t, int n_fmts) {
+    return round_up(t.table_bytes(), 256) + round_up((size_t)t.n_chunks * (n_fmts + 1) * sizeof(float), 256);
+}
+
+amp_status_t run_sens(const WorkTable& t, const amp_fp8_format_t* fmts, int n_fmts, float* d_out,
+                      void* workspace, size_t workspace_bytes, void* stream_) {
+    if (t.units.empty()) return AMP_OK;
+    if (!d_out || !aligned2(d_out) || (uintptr_t)d_out % 4) return AMP_ERR_INVALID_ARG;
+    if (!workspace || (uintptr_t)workspace % 256) return AMP_ERR_INVALID_ARG;
+    if (workspace_bytes < sens_workspace(t, n_fmts)) return AMP_ERR_WORKSPACE_TOO_SMALL;
+    hipStream_t stream = (hipStream_t)stream_;
+    amp_status_t st = upload(t, 0, workspace, stream);
+    if (st != AMP_OK) return st;
+    const WorkUnit* d_units = (const WorkUnit*)workspace;
+    const uint32_t* d_cb = (const uint32_t*)((const uint8_t*)workspace + t.units.size() * sizeof(WorkUnit));
+    float* d_partials = (float*)((uint8_t*)workspace + round_up(t.table_bytes(), 256));
+    const int f0 = (int)fmts[0], f1 = (int)fmts[n_fmts - 1];
+    if (t.n_chunks > 0)
+        AMP_HIP(launch_sens(d_units, d_cb, (uint32_t)t.units.size(), (uint32_t)t.n_chunks, n_fmts, f0,
+                            f1, d_partials, persistent_grid(t.n_chunks), stream));
+    AMP_HIP(launch_sens_finalize(d_units, d_cb, (uint32_t)t.units.size(), n_fmts, d_partials, d_out, stream));
+    return AMP_OK;
+}
+
+amp_status_t build_linear(const amp_linear_desc_t* ops, int n_ops, int n_fmts, WorkTable* t) {
+    if (n_ops < 0 || (n_ops > 0 && !ops)) return AMP_ERR_INVALID_ARG;
+    if (n_fmts < 1 || n_fmts > AMP_MAX_FORMATS) return AMP_ERR_BAD_FORMAT;
+    uint64_t base = 0;
+    for (int k = 0; k < n_ops; ++k) {
+        const amp_linear_desc_t& op = ops[k];
+        if (op.R < 0 || op.C < 0 || op.K < 0 || op.tokens < 0) return AMP_ERR_INVALID_ARG;
+        if (op.C > kMaxElems || op.K > kMaxElems || (op.C && op.K > kMaxElems / op.C)) return AMP_ERR_TOO_LARGE;
+        if (!aligned2(op.x) || !aligned2(op.dx) || !aligned2(op.w) || !aligned2(op.dw)) return AMP_ERR_INVALID_ARG;
+        const int64_t wn = op.K * op.C;
+        int64_t prev = 0;
+        for (int r = 0; r < op.R; ++r) {
+            int64_t r0, r1;
+            if (op.sample_row_offsets) {
+                r0 = op.sample_row_offsets[r];
+                r1 = op.sample_row_offsets[r + 1];
+                if ((r == 0 && r0 != 0) || r0 != prev || r1 < r0) return AMP_ERR_INVALID_ARG;
+                prev = r1;
+            } else {
+                r0 = (int64_t)r * op.tokens;
+                r1 = r0 + op.tokens;
+            }
+            if (op.C && r1 > kMaxElems / op.C) return AMP_ERR_TOO_LARGE;
+            const int64_t xn = (r1 - r0) * op.C;
+            if (xn > 0 && (!op.x || !op.dx || !op.x_scale || !op.x_inv)) return AMP_ERR_INVALID_ARG;
+            if (wn > 0 && (!op.w || !op.dw || !op.w_scale || !op.w_inv)) return AMP_ERR_INVALID_ARG;
+            const uint64_t o = (base + r) * (uint64_t)n_fmts * 4;
+            if (o + 4 * n_fmts > 0xFFFFFFFFull) return AMP_ERR_TOO_LARGE;
+            amp_layout_t Lx = {xn, 0, 0, 0, 0, 0};
+            amp_layout_t Lw = {wn, 0, 0, 0, 0, 0};
+            amp_status_t st = t->add(xn ? op.x + r0 * op.C : op.x, xn ? op.dx + r0 * op.C : op.dx, Lx, 1,
+                                     op.x_scale, op.x_inv, (uint32_t)o);
+            if (st != AMP_OK) return st;
+            st = t->add(op.w, wn ? op.dw + (int64_t)r * wn : op.dw, Lw, 1, op.w_scale, op.w_inv, (uint32_t)o + 2);
+            if (st != AMP_OK) return st;
+        }
+        base += (uint64_t)op.R;
+    }
+    return AMP_OK;
+}
+
+amp_status_t build_bgemm(const amp_bgemm_desc_t* ops, int n_ops, int n_fmts, WorkTable* t) {
+    if (n_ops < 0 || (n_ops > 0 && !ops)) return AMP_ERR_INVALID_ARG;
+    if (n_fmts < 1 || n_fmts > AMP_MAX_FORMATS) return AMP_ERR_BAD_FORMAT;
+    uint64_t base = 0;
+    for (int k = 0; k < n_ops; ++k) {
+        const amp_bgemm_desc_t& op = ops[k];
+        if (op.R < 0) return AMP_ERR_INVALID_ARG;
+        amp_status_t st = check_layout(op.layout0);
+        if (st != AMP_OK) return st;
+        st = check_layout(op.layout1);
+        if (st != AMP_OK) return st;
+        if (!aligned2(op.x0) || !aligned2(op.dx0) || !aligned2(op.x1) || !aligned2(op.dx1)) return AMP_ERR_INVALID_ARG;
+        const int64_t n0 = layout_span(op.layout0), n1 = layout_span(op.layout1);
+        if (op.R > 0 && n0 > 0 && (!op.x0 || !op.dx0 || !op.scale0 || !op.inv0)) return AMP_ERR_INVALID_ARG;
+        if (op.R > 0 && n1 > 0 && (!op.x1 || !op.dx1 || !op.scale1 || !op.inv1)) return AMP_ERR_INVALID_ARG;
+        if (op.R > 0 && (n0 > kMaxElems / op.R || n1 > kMaxElems / op.R)) return AMP_ERR_TOO_LARGE;
+        for (int r = 0; r < op.R; ++r) {
+            const uint64_t o = (base + r) * (uint64_t)n_fmts * 4;
+            if (o + 4 * n_fmts > 0xFFFFFFFFull) return AMP_ERR_TOO_LARGE;
+            st = t->add(n0 ? op.x0 + r * n0 : op.x0, n0 ? op.dx0 + r * n0 : op.dx0, op.layout0, 1, op.scale0,
+                        op.inv0, (uint32_t)o);
+            if (st != AMP_OK) return st;
+            st = t->add(n1 ? op.x1 + r * n1 : op.x1, n1 ? op.dx1 + r * n1 : op.dx1, op.layout1, 1, op.scale1,
+                        op.inv1, (uint32_t)o + 2);
+            if (st != AMP_OK) return st;
+        }
+        base += (uint64_t)op.R;
+    }
+    return AMP_OK;
+}
+
+amp_status_t build_absmax(const amp_tensor_t* tensors, int n_tensors, WorkTable* t) {
+    if (n_tensors < 0 || (n_tensors > 0 && !tensors)) return AMP_ERR_INVALID_ARG;
+    for (int k = 0; k < n_tensors; ++k) {
+        const amp_tensor_t& T = tensors[k];
+        amp_status_t st = check_layout(T.layout);
+        if (st != AMP_OK) return st;
+        if (T.n_samples < 0 || !aligned2(T.data)) return AMP_ERR_INVALID_ARG;
+        const int64_t span = layout_span(T.layout);
+        if (span > 0 && T.n_samples > kMaxElems / span) return AMP_ERR_TOO_LARGE;
+        if (span * T.n_samples > 0 && !T.data) return AMP_ERR_INVALID_ARG;
+        st = t->add(T.data, nullptr, T.layout, T.n_samples, nullptr, nullptr, (uint32_t)k);
+        if (st != AMP_OK) return st;
+    }
+    return AMP_OK;
+}
+
+size_t absmax_workspace(const WorkTable& t) {
+    return round_up(t.table_bytes() + t.units.size() * sizeof(uint32_t), 256);
+}
+
+// ---- test hook (not part of the public header) ------------------------------------------------
+// Replays on the host, thread by thread, the element walk the kernels perform for one unit
+// and reports how often each element was touched.  counts has `span` entries (the unit's
+// memory span in elements); returns the number of accesses that fell outside [0, span), plus
+// the number of "full" vectors that were not 16-byte aligned.
+struct ReplayCtx {
+    int32_t* counts;
+    int64_t span;
+    uintptr_t addr;          // byte address the unit would have
+    int64_t bad;
+    __host__ __device__ void touch(int64_t e) { if (e < 0 || e >= span) ++bad; else ++counts[e]; }
+    template <int U> __host__ __device__ void full(int64_t e, int64_t stride) {
+        for (int k = 0; k < U; ++k) {
+            const int64_t s = e + k * stride;
+            if ((addr + 2 * (uintptr_t)s) % 16) ++bad;
+            for (int j = 0; j < kVec; ++j) touch(s + j);
+        }
+    }
+    __host__ __device__ void partial(int64_t e, int jlo, int jhi) { for (int j = jlo; j < jhi; ++j) touch(e + j); }
+};
+
+
+}  // namespace
+
+extern "C" {
+
+amp_status_t amp_absmax_workspace_bytes(const amp_tensor_t* tensors, int n_tensors, size_t* bytes) {
+    if (!bytes) return AMP_ERR_INVALID_ARG;
+    WorkTable t;
+    amp_status_t st = build_absmax(tensors, n_tensors, &t);
+    if (st != AMP_OK) return st;
+    *bytes = absmax_workspace(t);
+    return AMP_OK;
+}
+
+amp_status_t amp_absmax_scale(const amp_tensor_t* tensors, int n_tensors, const amp_fp8_format_t* fmts,
+                              int n_fmts, float* d_amax, float* d_scale, float* d_inv,
+                              uint32_t* d_flags, void* workspace, size_t workspace_bytes,
+                              void* stream_) {
+    amp_status_t st = check_fmts(fmts, n_fmts);
+    if (st != AMP_OK) return st;
+    WorkTable t;
+    st = build_absmax(tensors, n_tensors, &t);
+    if (st != AMP_OK) return st;
+    if (n_tensors == 0) return AMP_OK;
+    if (!d_amax || !d_scale || !d_inv || !d_flags) return AMP_ERR_INVALID_ARG;
+    if (((uintptr_t)d_amax | (uintptr_t)d_scale | (uintptr_t)d_inv | (uintptr_t)d_flags) % 4) return AMP_ERR_INVALID_ARG;
+    if (!workspace || (uintptr_t)workspace % 256) return AMP_ERR_INVALID_ARG;
+    if (workspace_bytes < absmax_workspace(t)) return AMP_ERR_WORKSPACE_TOO_SMALL;
+    hipStream_t stream = (hipStream_t)stream_;
+    st = upload(t, t.units.size(), workspace, stream);        // trailing words: zeroed running maxima
+    if (st != AMP_OK) return st;
+    const WorkUnit* d_units = (const WorkUnit*)workspace;
+    const uint32_t* d_cb = (const uint32_t*)((const uint8_t*)workspace + t.units.size() * sizeof(WorkUnit));
+    uint32_t* d_maxbits = (uint32_t*)((uint8_t*)workspace + t.table_bytes());
+    if (t.n_chunks > 0)
+        AMP_HIP(launch_absmax(d_units, d_cb, (uint32_t)t.units.size(), (uint32_t)t.n_chunks, d_maxbits,
+                              persistent_grid(t.n_chunks), stream));
+    AMP_HIP(launch_absmax_finalize(d_maxbits, n_tensors, n_fmts, (int)fmts[0], (int)fmts[n_fmts - 1],
+                                   d_amax, d_scale, d_inv, d_flags, stream));
+    return AMP_OK;
+}
+
+amp_status_t amp_fake_quant_fp8(const uint16_t* d_x, int64_t n, float scale, float inv_scale,
+                                amp_fp8_format_t fmt, uint8_t* d_codes, float* d_dequant,
+                                void* stream_) {
+    if (!fmt_ok((int)fmt)) return AMP_ERR_BAD_FORMAT;
+    if (n < 0) return AMP_ERR_INVALID_ARG;
+    if (n == 0) return AMP_OK;
+    if (!d_x || !d_codes || !aligned2(d_x) || (d_dequant && (uintptr_t)d_dequant % 4)) return AMP_ERR_INVALID_ARG;
+    if (n > kMaxElems) return AMP_ERR_TOO_LARGE;
+    const uint64_t blocks = ((uint64_t)n / kVec + kWG - 1) / kWG + 1;
+    const uint64_t cap = (uint64_t)device_cus() * kWavesPerSimd;
+    AMP_HIP(launch_fake_quant(d_x, n, scale, inv_scale, (int)fmt, d_codes, d_dequant,
+                              (int)(blocks < cap ? blocks : cap), (hipStream_t)stream_));
+    return AMP_OK;
+}
+
+amp_status_t amp_sens_linear_workspace_bytes(const amp_linear_desc_t* ops, int n_ops, int n_fmts, size_t* bytes) {
+    if (!bytes) return AMP_ERR_INVALID_ARG;
+    WorkTable t;
+    amp_status_t st = build_linear(ops, n_ops, n_fmts, &t);
+    if (st != AMP_OK) return st;
+    *bytes = sens_workspace(t, n_fmts);
+    return AMP_OK;
+}
+
+amp_status_t amp_sens_linear(const amp_linear_desc_t* ops, int n_ops, const amp_fp8_format_t* fmts,
+                             int n_fmts, float* d_out, void* workspace, size_t workspace_bytes,
+                             void* stream) {
+    amp_status_t st = check_fmts(fmts, n_fmts);
+    if (st != AMP_OK) return st;
+    WorkTable t;
+    st = build_linear(ops, n_ops, n_fmts, &t);
+    if (st != AMP_OK) return st;
+    return run_sens(t, fmts, n_fmts, d_out, workspace, workspace_bytes, stream);
+}
+
+amp_status_t amp_sens_bgemm_workspace_bytes(const amp_bgemm_desc_t* ops, int n_ops, int n_fmts, size_t* bytes) {
+    if (!bytes) return AMP_ERR_INVALID_ARG;
+    WorkTable t;
+    amp_status_t st = build_bgemm(ops, n_ops, n_fmts, &t);
+    if (st != AMP_OK) return st;
+    *bytes = sens_workspace(t, n_fmts);
+    return AMP_OK;
+}
+
+amp_status_t amp_sens_bgemm(const amp_bgemm_desc_t* ops, int n_ops, const amp_fp8_format_t* fmts,
+                            int n_fmts, float* d_out, void* workspace, size_t workspace_bytes,
+                            void* stream) {
+    amp_status_t st = check_fmts(fmts, n_fmts);
+    if (st != AMP_OK) return st;
+    WorkTable t;
+    st = build_bgemm(ops, n_ops, n_fmts, &t);
+    if (st != AMP_OK) return st;
+    return run_sens(t, fmts, n_fmts, d_out, workspace, workspace_bytes, stream);
+}
+
+const char* amp_status_string(amp_status_t status) {
+    switch (status) {
+        case AMP_OK: return "ok";
+        case AMP_ERR_INVALID_ARG: return "invalid argument";
+        case AMP_ERR_BAD_FORMAT: return "bad FP8 format or format count";
+        case AMP_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case AMP_ERR_NONFINITE_INPUT: return "non-finite input";
+        case AMP_ERR_DEVICE: return "HIP runtime error";
+        case AMP_ERR_INFEASIBLE: return "no configuration meets the loss-MSE budget";
+        case AMP_ERR_TOO_LARGE: return "problem too large";
+    }
+    return "unknown status";
+}
+
+int amp_last_device_error(void) { return g_last_device_error; }
+
+int amp_version(void) { return 100; }
+
+// Test hook: cap the persistent grid (0 = default) to show that results do not depend on it.
+void ampsens_debug_set_grid_cap(int cap) { g_grid_cap = cap; }
+
+int64_t ampsens_debug_replay_unit(uint64_t x_addr, uint64_t dx_addr, const amp_layout_t* layout,
+                                  int64_t batch_mul, int32_t* counts, int64_t span, uint64_t* n_chunks_out) {
+    WorkTable t;
+    if (t.add((const uint16_t*)(uintptr_t)x_addr, (const uint16_t*)(uintptr_t)dx_addr, *layout, batch_mul,
+              nullptr, nullptr, 0) != AMP_OK)
+        return -1;
+    std::vector<uint32_t> cb = t.chunk_begin;
+    cb.push_back((uint32_t)t.n_chunks);
+    ReplayCtx ctx{counts, span, (uintptr_t)x_addr, 0};
+    for (uint32_t c = 0; c < t.n_chunks; ++c) {
+        if (find_unit(cb.data(), 1, c) != 0) ++ctx.bad;
+        for (int tid = 0; tid < kWG; ++tid) walk_chunk(t.units[0], c, tid, ctx);
+    }
+    if (n_chunks_out) *n_chunks_out = t.n_chunks;
+    return ctx.bad;
+}
+
+}  // extern "C"

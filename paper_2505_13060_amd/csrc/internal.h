@@ -1,0 +1,76 @@
+// Internal declarations shared by the C-ABI layer and the HIP kernels of libampsens.
+// Not installed; the public interface is include/ampsens.h.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace ampsens {
+
+// ---- work decomposition ------------------------------------------------------------------
+// Every operand block of one calibration sample is a "unit".  A unit is cut into chunks by a
+// rule that depends only on the unit (never on the grid), and chunk c of a launch writes its
+// partial sums into slot c, so results are independent of how many workgroups run.
+//
+// Dense unit: its elements are viewed as 8-element vectors on the 16-byte grid of the x
+// pointer (the first and last vector may be partial); a chunk is kChunkVecs vectors.
+// Causal unit [batch, rows, cols]: a band is 8 consecutive rows of one batch entry; all rows
+// of a band need the same number of vectors when rows/cols are multiples of 8, so a band is a
+// small rectangle of vectors with a ragged last column.  A chunk is kBandsPerChunk bands.
+constexpr int kWG = 256;             // threads per workgroup (4 wave64)
+constexpr int kVec = 8;              // bf16 elements per 128-bit load
+constexpr int kChunkVecs = 2048;     // dense: vectors per chunk (64 KiB of x + xdot)
+constexpr int kBandRows = 8;
+constexpr int kBandsPerChunk = 4;
+constexpr int kMaxFormats = 2;
+
+enum : uint32_t {
+    kUnitCausal = 1u,                // causal layout
+    kUnitScalar = 2u,                // x and xdot are not mutually 16-byte aligned (or causal rows
+                                     // are not): every vector takes the guarded 2-byte path
+};
+
+struct alignas(16) WorkUnit {        // 64 bytes
+    const uint16_t* x;               // first element of the block
+    const uint16_t* dx;              // gradient block (sens) / unused (absmax)
+    const float* scale;              // device [n_fmts] (sens) / unused
+    const float* inv;                // device [n_fmts] (sens) / unused
+    int64_t n;                       // dense: elements; causal: batch (number of matrices)
+    int32_t rows, cols;              // causal
+    uint32_t flags;
+    uint32_t head;                   // dense: elements between the 16-byte grid and x (0..7)
+    uint32_t out;                    // sens: float offset of this unit's (E, A) pair for format 0
+                                     // absmax: tensor index
+    uint32_t chunks_per_mat;         // causal: chunks per [rows, cols] matrix
+};
+static_assert(sizeof(WorkUnit) == 64, "WorkUnit layout");
+
+// Number of chunks of a unit (host side; the kernels use the same constants).
+inline uint64_t unit_chunks_dense(int64_t n, uint32_t head) {
+    if (n <= 0) return 0;
+    uint64_t vecs = ((uint64_t)n + head + kVec - 1) / kVec;
+    return (vecs + kChunkVecs - 1) / kChunkVecs;
+}
+inline uint32_t causal_chunks_per_mat(int64_t rows) {
+    uint64_t bands = ((uint64_t)rows + kBandRows - 1) / kBandRows;
+    return (uint32_t)((bands + kBandsPerChunk - 1) / kBandsPerChunk);
+}
+
+// ---- launchers (kernels.hip) ---------------------------------------------------------------
+// All enqueue on `stream` and return the launch error, never synchronise.
+hipError_t launch_absmax(const WorkUnit* d_units, const uint32_t* d_chunk_begin, uint32_t n_units,
+                         uint32_t n_chunks, uint32_t* d_maxbits, int grid, hipStream_t stream);
+hipError_t launch_absmax_finalize(const uint32_t* d_maxbits, int n_tensors, int n_fmts, int fmt0,
+                                  int fmt1, float* d_amax, float* d_scale, float* d_inv,
+                                  uint32_t* d_flags, hipStream_t stream);
+hipError_t launch_fake_quant(const uint16_t* d_x, int64_t n, float scale, float inv, int fmt,
+                             uint8_t* d_codes, float* d_dequant, int grid, hipStream_t stream);
+hipError_t launch_sens(const WorkUnit* d_units, const uint32_t* d_chunk_begin, uint32_t n_units,
+                       uint32_t n_chunks, int n_fmts, int fmt0, int fmt1, float* d_partials,
+                       int grid, hipStream_t stream);
+hipError_t launch_sens_finalize(const WorkUnit* d_units, const uint32_t* d_chunk_begin,
+                                uint32_t n_units, int n_fmts, const float* d_partials,
+                                float* d_out, hipStream_t stream);
+
+}  // namespace ampsens

@@ -1,0 +1,246 @@
+// Host side of libampsens: the epilogue of Sec. 2.2 (mean sensitivity, loss MSE per layer and
+// per group) and the exact solution of the selection problem eq. (ip) of Sec. 2.1, a
+// multiple-choice knapsack: one format combination per sequential sub-graph, maximum total
+// gain, total loss MSE within the budget.
+//
+// Solver: groups are first reduced to their non-dominated choices; the search then walks the
+// groups in order keeping a list of partial configurations (total mse, total gain) from which
+// it drops (i) every partial that another one dominates and (ii) every partial whose upper
+// bound -- its gain plus the LP relaxation of the remaining groups under the remaining
+// budget, evaluated on the groups' upper convex hulls -- cannot reach the best complete
+// configuration found so far.  Both rules keep at least one optimal configuration, so the
+// result is exact.
+#include "../../include/ampsens.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <limits>
+#include <vector>
+
+namespace {
+
+struct Choice {
+    double d, g;
+    int32_t idx;
+};
+
+struct Segment {            // one edge of a group's upper convex hull
+    double dd, dg;          // increments, dd > 0, dg > 0
+};
+
+// LP relaxation of groups j..J-1 as a concave piecewise-linear function of the budget:
+// start from every group's cheapest choice, then take hull edges in order of decreasing slope.
+struct Tail {
+    double base_d = 0, base_g = 0;
+    std::vector<double> cum_d, cum_g;    // prefix sums over edges sorted by slope, starting at 0
+    double bound(double budget) const {  // -inf when even the cheapest choices do not fit
+        double room = budget - base_d;
+        if (room < 0) return -std::numeric_limits<double>::infinity();
+        // last k with cum_d[k] <= room
+        size_t k = std::upper_bound(cum_d.begin(), cum_d.end(), room) - cum_d.begin() - 1;
+        double g = base_g + cum_g[k];
+        if (k + 1 < cum_d.size()) {
+            double dd = cum_d[k + 1] - cum_d[k];
+            g += (cum_g[k + 1] - cum_g[k]) * ((room - cum_d[k]) / dd);
+        }
+        return g;
+    }
+};
+
+struct State {
+    double d, g;
+    int32_t parent, pick;   // index into the previous stage's list; position in the reduced group
+};
+
+}  // namespace
+
+extern "C" {
+
+double amp_alpha(int mantissa_bits) { return std::ldexp(1.0, -2 * mantissa_bits) / 12.0; }
+
+amp_status_t amp_layer_loss_mse(const float* sums, int R, const amp_fp8_format_t* fmts, int n_fmts,
+                                double* s_layer, double* d_model, double* d_measured) {
+    if (n_fmts < 1 || n_fmts > AMP_MAX_FORMATS) return AMP_ERR_BAD_FORMAT;
+    if (!fmts) return AMP_ERR_INVALID_ARG;
+    for (int f = 0; f < n_fmts; ++f)
+        if (fmts[f] != AMP_FP8_E4M3 && fmts[f] != AMP_FP8_E5M2) return AMP_ERR_BAD_FORMAT;
+    if (R < 1 || !sums || !s_layer) return AMP_ERR_INVALID_ARG;
+    double s = 0.0;
+    for (int r = 0; r < R; ++r) {
+        const float* p = sums + (size_t)r * n_fmts * 4;       // A is repeated per format; use f = 0
+        s += (double)p[1] + (double)p[3];
+    }
+    s /= (double)R;
+    *s_layer = s;
+    for (int f = 0; f < n_fmts; ++f) {
+        if (d_model) d_model[f] = s * amp_alpha(fmts[f] == AMP_FP8_E4M3 ? 3 : 2);
+        if (d_measured) {
+            double e = 0.0;
+            for (int r = 0; r < R; ++r) {
+                const float* p = sums + ((size_t)r * n_fmts + f) * 4;
+                e += (double)p[0] + (double)p[2];
+            }
+            d_measured[f] = e / (double)R;
+        }
+    }
+    return AMP_OK;
+}
+
+amp_status_t amp_group_tables(int n_layers, int F, const double* layer_mse, const double* layer_gain,
+                              double* d, double* c) {
+    if (n_layers < 0 || F < 1 || !d || !c) return AMP_ERR_INVALID_ARG;
+    if (n_layers > 0 && (!layer_mse || !layer_gain)) return AMP_ERR_INVALID_ARG;
+    int64_t ncol = 1;
+    for (int l = 0; l < n_layers; ++l) {
+        ncol *= F;
+        if (ncol > ((int64_t)1 << 24)) return AMP_ERR_TOO_LARGE;
+    }
+    for (int64_t p = 0; p < ncol; ++p) {
+        int64_t q = p;
+        double dm = 0.0, cg = 0.0;
+        for (int l = 0; l < n_layers; ++l) {
+            const int f = (int)(q % F);
+            q /= F;
+            dm += layer_mse[(size_t)l * F + f];
+            cg += layer_gain[(size_t)l * F + f];
+        }
+        d[p] = dm;
+        c[p] = cg;
+    }
+    return AMP_OK;
+}
+
+amp_status_t amp_select_subgraphs(int J, const int32_t* n_choices, const double* gain,
+                                  const double* mse, double mse_budget, int32_t* choice,
+                                  double* total_gain, double* total_mse) {
+    if (J < 0) return AMP_ERR_INVALID_ARG;
+    if (J > 0 && (!n_choices || !gain || !mse || !choice)) return AMP_ERR_INVALID_ARG;
+    if (std::isnan(mse_budget)) return AMP_ERR_INVALID_ARG;
+    size_t total = 0;
+    for (int j = 0; j < J; ++j) {
+        if (n_choices[j] < 1) return AMP_ERR_INVALID_ARG;
+        total += (size_t)n_choices[j];
+    }
+    for (size_t i = 0; i < total; ++i)
+        if (!std::isfinite(gain[i]) || !std::isfinite(mse[i]) || mse[i] < 0) return AMP_ERR_INVALID_ARG;
+
+    // 1. Non-dominated choices of every group, by increasing mse (and then increasing gain).
+    std::vector<std::vector<Choice>> groups(J);
+    size_t off = 0;
+    for (int j = 0; j < J; ++j) {
+        std::vector<Choice> all(n_choices[j]);
+        for (int32_t p = 0; p < n_choices[j]; ++p) all[p] = Choice{mse[off + p], gain[off + p], p};
+        std::sort(all.begin(), all.end(), [](const Choice& a, const Choice& b) {
+            if (a.d != b.d) return a.d < b.d;
+            if (a.g != b.g) return a.g > b.g;
+            return a.idx < b.idx;
+        });
+        double best = -std::numeric_limits<double>::infinity();
+        for (const Choice& ch : all)
+            if (ch.g > best) { groups[j].push_back(ch); best = ch.g; }
+        off += (size_t)n_choices[j];
+    }
+
+    // 2. LP-relaxation tails.
+    std::vector<Tail> tails(J + 1);
+    {
+        std::vector<std::vector<Segment>> hull(J);
+        for (int j = 0; j < J; ++j) {
+            // upper convex hull of the (d, g) points, which are sorted by d with increasing g
+            std::vector<Choice> h;
+            for (const Choice& ch : groups[j]) {
+                while (h.size() >= 2) {
+                    const Choice& a = h[h.size() - 2];
+                    const Choice& b = h[h.size() - 1];
+                    // drop b when it lies on or below the chord a -> ch
+                    if ((b.g - a.g) * (ch.d - a.d) <= (ch.g - a.g) * (b.d - a.d)) h.pop_back();
+                    else break;
+                }
+                h.push_back(ch);
+            }
+            for (size_t k = 1; k < h.size(); ++k)
+                hull[j].push_back(Segment{h[k].d - h[k - 1].d, h[k].g - h[k - 1].g});
+        }
+        std::vector<Segment> pool;
+        tails[J].cum_d = {0.0};
+        tails[J].cum_g = {0.0};
+        for (int j = J - 1; j >= 0; --j) {
+            for (const Segment& s : hull[j]) pool.push_back(s);
+            std::sort(pool.begin(), pool.end(), [](const Segment& a, const Segment& b) {
+                return a.dg * b.dd > b.dg * a.dd;               // slope a > slope b
+            });
+            Tail& t = tails[j];
+            t.base_d = tails[j + 1].base_d + groups[j].front().d;
+            t.base_g = tails[j + 1].base_g + groups[j].front().g;
+            t.cum_d.assign(1, 0.0);
+            t.cum_g.assign(1, 0.0);
+            for (const Segment& s : pool) {
+                t.cum_d.push_back(t.cum_d.back() + s.dd);
+                t.cum_g.push_back(t.cum_g.back() + s.dg);
+            }
+        }
+    }
+    if (J == 0) {
+        if (mse_budget < 0) return AMP_ERR_INFEASIBLE;
+        if (total_gain) *total_gain = 0.0;
+        if (total_mse) *total_mse = 0.0;
+        return AMP_OK;
+    }
+    if (tails[0].base_d > mse_budget) return AMP_ERR_INFEASIBLE;
+
+    // 3. Stage-wise search with dominance and bound pruning.
+    const double ninf = -std::numeric_limits<double>::infinity();
+    double incumbent = tails[0].base_g;             // all-cheapest configuration is feasible
+    auto slack = [](double v) { return 1e-12 * (std::fabs(v) + 1.0); };
+    std::vector<std::vector<State>> stages(J + 1);
+    stages[0].push_back(State{0.0, 0.0, -1, -1});
+    std::vector<State> cand;
+    for (int j = 0; j < J; ++j) {
+        cand.clear();
+        const Tail& rest = tails[j + 1];
+        for (int32_t s = 0; s < (int32_t)stages[j].size(); ++s) {
+            const State& st = stages[j][s];
+            for (int32_t p = 0; p < (int32_t)groups[j].size(); ++p) {
+                const double d = st.d + groups[j][p].d;
+                if (d + rest.base_d > mse_budget) break;         // choices are sorted by mse
+                const double g = st.g + groups[j][p].g;
+                const double done = g + rest.base_g;             // complete with the cheapest choices
+                if (done > incumbent) incumbent = done;
+                cand.push_back(State{d, g, s, p});
+            }
+        }
+        std::sort(cand.begin(), cand.end(), [](const State& a, const State& b) {
+            if (a.d != b.d) return a.d < b.d;
+            if (a.g != b.g) return a.g > b.g;
+            if (a.parent != b.parent) return a.parent < b.parent;
+            return a.pick < b.pick;
+        });
+        double best = ninf;
+        std::vector<State>& next = stages[j + 1];
+        for (const State& c : cand) {
+            if (!(c.g > best)) continue;                          // dominated
+            best = c.g;
+            const double ub = c.g + rest.bound(mse_budget - c.d);
+            if (ub < incumbent - slack(incumbent)) continue;      // cannot reach the incumbent
+            next.push_back(c);
+        }
+        if (next.empty()) return AMP_ERR_INFEASIBLE;              // cannot happen once base fits
+    }
+
+    // 4. Best final state: largest gain, then smallest mse (list is sorted by mse, gains increase).
+    const std::vector<State>& last = stages[J];
+    int32_t bi = 0;
+    for (int32_t s = 1; s < (int32_t)last.size(); ++s)
+        if (last[s].g > last[bi].g) bi = s;
+    if (total_gain) *total_gain = last[bi].g;
+    if (total_mse) *total_mse = last[bi].d;
+    int32_t s = bi;
+    for (int j = J; j >= 1; --j) {
+        choice[j - 1] = groups[j - 1][stages[j][s].pick].idx;
+        s = stages[j][s].parent;
+    }
+    return AMP_OK;
+}
+
+}  // extern "C"

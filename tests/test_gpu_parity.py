@@ -1,0 +1,282 @@
+"""GPU parity tests: libampsens (through its C-ABI, via the ctypes binding) against the CPU
+oracle on the same seeded bytes.  Codes, amax and scales bit-exact; sums within 1e-4 relative
+(see tests/parity.py).  Every test prints what it is about to run before touching the GPU."""
+import ctypes as C
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2505_13060_amd as amp
+from paper_2505_13060_amd import workloads as wl
+from paper_2505_13060_amd.pipeline import SensPass
+from helpers import all_bf16_patterns, bf16_bits_to_f64, f32_to_bf16_bits, finite_mask
+import parity
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def say(msg):
+    print("[gpu-test] " + msg, flush=True)
+    sys.stdout.flush()
+
+
+def dev_bits(bits):
+    """numpy uint16 -> device int16 tensor holding the same bytes."""
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(DEV)
+
+
+def to_device(workload):
+    for op in workload.linears:
+        op.x, op.dx, op.w, op.dw = (t.to(DEV) for t in (op.x, op.dx, op.w, op.dw))
+    for op in workload.bgemms:
+        op.x0, op.dx0, op.x1, op.dx1 = (t.to(DEV) for t in (op.x0, op.dx0, op.x1, op.dx1))
+    return workload
+
+
+# ---------------------------------------------------------------------------------------------
+# fake quantisation: bit-exact codes over every bf16 pattern
+# ---------------------------------------------------------------------------------------------
+
+SCALES = [(1.0, 1.0), (2.0, 0.5), (0.0123, None), (3.7e-3, None), (911.0, None), (2.0 ** -20, 2.0 ** 20)]
+
+
+@pytest.mark.parametrize("fmt", [amp.E4M3, amp.E5M2])
+@pytest.mark.parametrize("scale,inv", SCALES)
+def test_fake_quant_all_bf16_patterns(fmt, scale, inv):
+    if inv is None:                                   # an absmax-style pair: both are fp32 divisions
+        fm = np.float32(oracle.fp8_max(fmt))
+        amax = np.float32(scale)
+        scale, inv = float(amax / fm), float(fm / amax)
+    h = all_bf16_patterns()
+    keep = finite_mask(h) | ((h & 0x7FFF) == 0x7F80)  # all finite patterns and +-inf (saturate)
+    h = h[keep]
+    say("fake_quant all patterns fmt=%d scale=%g inv=%g n=%d" % (fmt, scale, inv, h.size))
+    x = dev_bits(h)
+    codes = torch.zeros(h.size, dtype=torch.uint8, device=DEV)
+    deq = torch.zeros(h.size, dtype=torch.float32, device=DEV)
+    amp.amp_fake_quant_fp8(x, h.size, scale, inv, fmt, codes, deq)
+    torch.cuda.synchronize()
+    want_c, want_d = oracle.fake_quant_fp8(h, scale, inv, fmt)
+    got_c = codes.cpu().numpy()
+    bad = np.nonzero(got_c != want_c)[0]
+    assert bad.size == 0, [(hex(h[i]), hex(got_c[i]), hex(want_c[i])) for i in bad[:8]]
+    assert np.array_equal(parity.bits32(deq.cpu().numpy()), parity.bits32(want_d))
+
+
+@pytest.mark.parametrize("fmt", [amp.E4M3, amp.E5M2])
+@pytest.mark.parametrize("n,off", [(1, 0), (7, 0), (8, 0), (9, 1), (4099, 3), (100003, 0), (65536 * 3 + 5, 5)])
+def test_fake_quant_tails_and_misalignment(fmt, n, off):
+    rng = np.random.default_rng(n + off)
+    h = f32_to_bf16_bits((rng.standard_normal(n + off) * 3).astype(np.float32))
+    say("fake_quant tails fmt=%d n=%d off=%d" % (fmt, n, off))
+    x = dev_bits(h)
+    codes = torch.full((n + off + 8,), 0xAA, dtype=torch.uint8, device=DEV)
+    am, sc, iv, fl = oracle.absmax_scale(h[off:], fmt)
+    amp.amp_fake_quant_fp8(x[off:], n, sc, iv, fmt, codes[off:], None)
+    torch.cuda.synchronize()
+    want_c, _ = oracle.fake_quant_fp8(h[off:], sc, iv, fmt, want_dequant=False)
+    got = codes.cpu().numpy()
+    assert np.array_equal(got[off:off + n], want_c)
+    assert np.all(got[:off] == 0xAA) and np.all(got[off + n:] == 0xAA)      # nothing written outside
+
+
+# ---------------------------------------------------------------------------------------------
+# absmax / scales: bit-exact
+# ---------------------------------------------------------------------------------------------
+
+def test_absmax_scale_bit_exact_many_tensors():
+    rng = np.random.default_rng(12)
+    specs = []            # (bits, layout, n_samples, causal tuple for the oracle, element offset)
+    for n, sigma, off in [(1, 1.0, 0), (5, 0.02, 0), (16384, 1.0, 0), (16385, 40.0, 3), (300001, 1e-3, 1),
+                          (16384 * 5, 7.0, 0), (2048 * 8 - 1, 1e-30, 7)]:
+        b = f32_to_bf16_bits((rng.standard_normal(n + off) * sigma).astype(np.float32))
+        specs.append((b, amp.dense(n), 1, None, off))
+    zeros = np.zeros(777, dtype=np.uint16)
+    zeros[5] = 0x8000
+    specs.append((zeros, amp.dense(777), 1, None, 0))
+    specs.append((np.array([0x0001, 0x8002, 0x0000], dtype=np.uint16), amp.dense(3), 1, None, 0))  # subnormals
+    withinf = f32_to_bf16_bits(rng.standard_normal(5000).astype(np.float32))
+    withinf[4321] = 0xFF80
+    specs.append((withinf, amp.dense(5000), 1, None, 0))
+    withnan = f32_to_bf16_bits(rng.standard_normal(5000).astype(np.float32))
+    withnan[17] = 0x7FC1
+    specs.append((withnan, amp.dense(5000), 1, None, 0))
+    for (R, H, S, S2) in [(2, 3, 64, 64), (1, 2, 37, 48), (3, 1, 48, 24), (1, 1, 33, 33)]:
+        b = f32_to_bf16_bits(rng.standard_normal(R * H * S * S2).astype(np.float32))
+        # plant huge values in the masked part: they must be ignored
+        i = np.arange(S)[:, None]
+        j = np.arange(S2)[None, :]
+        masked = np.broadcast_to(j > i + (S2 - S), (R * H, S, S2)).reshape(-1)
+        b[masked] = f32_to_bf16_bits(np.array([1e9], dtype=np.float32))[0]
+        specs.append((b, amp.causal(H, S, S2), R, (R * H, S, S2), 0))
+    specs.append((np.zeros(0, dtype=np.uint16), amp.dense(0), 1, None, 0))   # empty tensor
+    say("absmax %d tensors" % len(specs))
+    keep, tensors = [], []
+    for b, lay, ns, _, off in specs:
+        d = dev_bits(b if b.size else np.zeros(8, dtype=np.uint16))
+        keep.append(d)
+        tensors.append(amp.tensor(d[off:] if b.size else None, lay, ns))
+    nt = len(tensors)
+    fmts = [amp.E4M3, amp.E5M2]
+    d_amax = torch.zeros(nt, device=DEV)
+    d_scale = torch.zeros(nt, 2, device=DEV)
+    d_inv = torch.zeros(nt, 2, device=DEV)
+    d_flags = torch.zeros(nt, dtype=torch.int32, device=DEV)
+    ws = torch.empty(amp.amp_absmax_workspace_bytes(tensors), dtype=torch.uint8, device=DEV)
+    amp.amp_absmax_scale(tensors, fmts, d_amax, d_scale, d_inv, d_flags, ws)
+    torch.cuda.synchronize()
+    res = dict(amax=d_amax.cpu().numpy(), scale=d_scale.cpu().numpy(), inv=d_inv.cpu().numpy(),
+               flags=d_flags.cpu().numpy())
+    for t, (b, lay, ns, c, off) in enumerate(specs):
+        ref = [oracle.absmax_scale(b[off:], f, causal=c) for f in fmts]
+        assert res["flags"][t] == ref[0][3], t
+        if ref[0][3]:
+            # non-finite: amax is inf or NaN like the oracle's, scales unspecified
+            assert np.isnan(res["amax"][t]) == np.isnan(ref[0][0]) and not np.isfinite(res["amax"][t])
+            continue
+        assert parity.bits32(res["amax"][t]) == parity.bits32(ref[0][0]), t
+        for fi in range(2):
+            assert parity.bits32(res["scale"][t, fi]) == parity.bits32(ref[fi][1]), (t, fi)
+            assert parity.bits32(res["inv"][t, fi]) == parity.bits32(ref[fi][2]), (t, fi)
+
+
+# ---------------------------------------------------------------------------------------------
+# the fused pass on the benchmark configurations (reduced where the oracle would take minutes)
+# ---------------------------------------------------------------------------------------------
+
+def run_and_check(workload):
+    say("workload %s: %d linears, %d bgemms, %.1f M pairs, fmts=%s" %
+        (workload.name, len(workload.linears), len(workload.bgemms), workload.pairs() / 1e6, workload.fmts))
+    to_device(workload)
+    p = SensPass(workload, DEV)
+    p.run()
+    res = p.results()
+    parity.check_workload(workload, res)
+    return p, res
+
+
+def test_config0_full():
+    run_and_check(wl.config0("cpu"))
+
+
+def test_config1_reduced_block_both_formats():
+    # same structure as the 7B block, sized so that every operand spans several chunks with a tail
+    run_and_check(wl.config1("cpu", R=3, S=200, hidden=520, ffn=1384, H=4, D=64))
+
+
+def test_config3_reduced_gqa_student_t():
+    run_and_check(wl.config3("cpu", R=2, S=264, hidden=512, ffn=1800, Hq=8, Hkv=2, D=64))
+
+
+def test_config4_reduced_ragged_many_small():
+    run_and_check(wl.config4("cpu", R=5, experts=6, C=512, K=176, tok_lo=1, tok_hi=40, n_bgemm=4, S=72, H=2, D=32))
+
+
+def test_single_format_e5m2_and_format_order():
+    w = wl.config1("cpu", R=2, S=64, hidden=128, ffn=256, H=2, D=32)
+    w.fmts = [amp.E5M2]
+    run_and_check(w)
+    w = wl.config1("cpu", R=2, S=64, hidden=128, ffn=256, H=2, D=32)
+    w.fmts = [amp.E5M2, amp.E4M3]
+    run_and_check(w)
+
+
+def test_results_do_not_depend_on_grid_and_repeat_bit_identically():
+    w = to_device(wl.config1("cpu", R=2, S=136, hidden=256, ffn=520, H=2, D=64))
+    say("determinism: grid caps 0 (default), 1, 7, 64")
+    p = SensPass(w, DEV)
+    L = amp.lib()
+    outs = []
+    for cap in (0, 0, 1, 7, 64):
+        L.ampsens_debug_set_grid_cap(C.c_int(cap))
+        p.d_lin_out.zero_()
+        p.d_bg_out.zero_()
+        p.run()
+        r = p.results()
+        outs.append((np.concatenate(r["linear"]).copy(), np.concatenate(r["bgemm"]).copy(), r["scale"].copy()))
+    L.ampsens_debug_set_grid_cap(C.c_int(0))
+    for o in outs[1:]:
+        for a, b in zip(outs[0], o):
+            assert np.array_equal(parity.bits32(a), parity.bits32(b))
+
+
+def _mk(rng, n, sigma):
+    return f32_to_bf16_bits((rng.standard_normal(n) * sigma).astype(np.float32))
+
+
+def test_edge_cases_empty_tiny_misaligned_and_odd_causal():
+    rng = np.random.default_rng(99)
+    lin, bg = [], []
+    # (a) a sample without tokens, a one-token sample, ragged rest; C not a multiple of 8
+    off = np.array([0, 0, 1, 1, 40], dtype=np.int64)
+    Cd, K, R = 52, 9, 4
+    lin.append(wl.LinearOp("ragged", torch.from_numpy(_mk(rng, 40 * Cd, 1.0).view(np.int16)).view(torch.bfloat16).view(40, Cd),
+                           torch.from_numpy(_mk(rng, 40 * Cd, 1e-3).view(np.int16)).view(torch.bfloat16).view(40, Cd),
+                           torch.from_numpy(_mk(rng, K * Cd, 0.02).view(np.int16)).view(torch.bfloat16).view(K, Cd),
+                           torch.from_numpy(_mk(rng, R * K * Cd, 1e-3).view(np.int16)).view(torch.bfloat16).view(R, K, Cd),
+                           R, Cd, K, off))
+    # (b) all-zero activations and an all-on-grid weight
+    z = np.zeros(3 * 64, dtype=np.uint16)
+    grid = f32_to_bf16_bits(np.array([448.0, 1.0, -0.5, 0.015625] * 16, dtype=np.float32))
+    lin.append(wl.LinearOp("zeros_and_grid", torch.from_numpy(z.view(np.int16)).view(torch.bfloat16).view(3, 64),
+                           torch.from_numpy(_mk(rng, 3 * 64, 1.0).view(np.int16)).view(torch.bfloat16).view(3, 64),
+                           torch.from_numpy(grid.view(np.int16)).view(torch.bfloat16).view(1, 64),
+                           torch.from_numpy(_mk(rng, 3 * 64, 1.0).view(np.int16)).view(torch.bfloat16).view(3, 1, 64),
+                           3, 64, 1, np.array([0, 1, 2, 3], dtype=np.int64)))
+    # (c) causal operands whose rows are not multiples of 8 / not square, dense operand of odd size
+    for (H, S, S2, n1) in [(2, 37, 48, 333), (1, 48, 24, 8), (3, 33, 33, 16385), (2, 16, 16, 1)]:
+        R = 2
+        p = _mk(rng, R * H * S * S2, 0.3)
+        dp = _mk(rng, R * H * S * S2, 1e-3)
+        v, dv = _mk(rng, R * n1, 1.0), _mk(rng, R * n1, 1e-3)
+
+        def t(b):
+            return torch.from_numpy(b.view(np.int16)).view(torch.bfloat16)
+
+        bg.append(wl.BgemmOp("odd_causal_%dx%d" % (S, S2), t(p), t(dp), ("causal", H, S, S2), t(v), t(dv), ("dense", n1), R))
+    w = wl.Workload("edge", [amp.E4M3, amp.E5M2], lin, bg)
+    p, res = run_and_check(w)
+    assert np.all(res["linear"][0][0, :, :2] == 0)         # the empty sample
+    assert np.all(res["linear"][1][:, :, 0] == 0) and np.all(res["linear"][1][:, :, 1] == 0)   # zeros
+    assert np.all(res["linear"][1][:, :, 2] == 0) and np.all(res["linear"][1][:, :, 3] > 0)    # on-grid W, scale 1
+
+
+def test_misaligned_operand_pointers():
+    """Operands that start 2, 6 or 14 bytes off a 16-byte boundary, equal and unequal for x / xdot."""
+    rng = np.random.default_rng(5)
+    say("misaligned pointers")
+    n, R = 40000, 2
+    for ox, og in [(1, 1), (3, 3), (7, 7), (1, 4), (0, 5)]:
+        xb, gb = _mk(rng, R * n + 8, 1.0), _mk(rng, R * n + 8, 1e-3)
+        x1b, g1b = _mk(rng, R * 64, 1.0), _mk(rng, R * 64, 1.0)
+        X, G, X1, G1 = dev_bits(xb), dev_bits(gb), dev_bits(x1b), dev_bits(g1b)
+        sc = torch.tensor([[0.011, 0.0002]], device=DEV)
+        iv = torch.tensor([[91.0, 5000.0]], device=DEV)
+        d = amp.bgemm_desc(X[ox:], G[og:], amp.dense(n), X1, G1, amp.dense(64), R, sc, iv, sc, iv)
+        out = torch.zeros(R, 2, 4, device=DEV)
+        ws = torch.empty(amp.amp_sens_bgemm_workspace_bytes([d], 2), dtype=torch.uint8, device=DEV)
+        amp.amp_sens_bgemm([d], [amp.E4M3, amp.E5M2], out, ws)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+        for fi, f in enumerate([amp.E4M3, amp.E5M2]):
+            s, i = np.float32(sc[0, fi].item()), np.float32(iv[0, fi].item())
+            want = oracle.sens_bgemm(xb[ox:ox + R * n], gb[og:og + R * n], ("dense", n), x1b, g1b, ("dense", 64),
+                                     R, s, i, s, i, f)
+            for r in range(R):
+                parity.assert_sum_close(got[r, fi, 1], want[r, 1], 0.0, "A ox=%d og=%d" % (ox, og))
+                parity.assert_sum_close(got[r, fi, 0], want[r, 0], parity.E_FLOOR * want[r, 1], "E ox=%d og=%d" % (ox, og))
+                parity.assert_sum_close(got[r, fi, 2], want[r, 2], parity.E_FLOOR * want[r, 3], "E1")
+
+
+def test_workspace_too_small_is_reported_on_gpu_box_too():
+    w = to_device(wl.config0("cpu"))
+    p = SensPass(w, DEV)
+    small = torch.empty(256, dtype=torch.uint8, device=DEV)
+    with pytest.raises(amp.AmpError) as ei:
+        amp.amp_sens_linear(p.lin_desc, p.fmts, p.d_lin_out, small)
+    assert ei.value.status == amp.ERR_WORKSPACE_TOO_SMALL
