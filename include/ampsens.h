@@ -201,6 +201,17 @@ amp_status_t amp_select_subgraphs(int J, const int32_t* n_choices, const double*
                                   const double* mse, double mse_budget, int32_t* choice,
                                   double* total_gain, double* total_mse);
 
+/* ---- optional kernel timing ---------------------------------------------------------------
+ * amp_profile_enable(n > 0) creates n pairs of HIP events on the current device; from then on
+ * each launch of the fused sensitivity kernel (one per amp_sens_linear / amp_sens_bgemm call
+ * with work) records one pair on the call's stream, immediately before and after the kernel,
+ * until n launches have been recorded.  amp_profile_read waits for the recorded events, writes
+ * the elapsed milliseconds of each launch to ms[0..*n_launches) (host; capacity must be >= the
+ * n given to enable) and resets the count.  amp_profile_enable(0) destroys the events.
+ * Not thread-safe; meant for benchmarks. */
+amp_status_t amp_profile_enable(int max_launches);
+amp_status_t amp_profile_read(float* ms, int capacity, int* n_launches);
+
 /* ---- misc ---------------------------------------------------------------------------------*/
 const char* amp_status_string(amp_status_t status);
 int amp_last_device_error(void);

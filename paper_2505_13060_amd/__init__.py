@@ -246,5 +246,18 @@ def amp_select_subgraphs(n_choices, gain, mse, mse_budget):
     return choice[:J], tg.value, td.value
 
 
+def amp_profile_enable(max_launches):
+    _check(lib().amp_profile_enable(int(max_launches)), "amp_profile_enable")
+
+
+def amp_profile_read(capacity):
+    """Per-launch milliseconds of the fused sensitivity kernel since the last read."""
+    ms = np.zeros(max(capacity, 1), dtype=np.float32)
+    n = C.c_int()
+    _check(lib().amp_profile_read(ms.ctypes.data_as(C.c_void_p), int(capacity), C.byref(n)),
+           "amp_profile_read")
+    return ms[:n.value].copy()
+
+
 def amp_version():
     return lib().amp_version()

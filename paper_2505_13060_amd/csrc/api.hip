@@ -29,7 +29,6 @@ amp_status_t device_error(hipError_t e) {
 constexpr int64_t kMaxDim = (int64_t)1 << 30;          // causal rows / cols
 constexpr int64_t kMaxElems = (int64_t)1 << 46;        // per unit
 constexpr uint64_t kMaxChunks = 0x7FFFFFFFull;
-constexpr int kWavesPerSimd = 8;                       // persistent grid: 8 workgroups per CU
 
 bool fmt_ok(int f) { return f == AMP_FP8_E4M3 || f == AMP_FP8_E5M2; }
 
@@ -68,14 +67,15 @@ struct WorkTable {
 
     // x / dx may be null only for blocks without elements.
     amp_status_t add(const uint16_t* x, const uint16_t* dx, const amp_layout_t& L, int64_t batch_mul,
-                     const float* scale, const float* inv, uint32_t out) {
+                     const float* scale, const float* inv, uint32_t out, uint32_t extra_flags = 0) {
         WorkUnit u;
         std::memset(&u, 0, sizeof(u));
         u.x = x; u.dx = dx; u.scale = scale; u.inv = inv; u.out = out;
+        u.flags = extra_flags;
         uint64_t chunks;
         if (L.causal) {
             const int64_t batch = L.batch * batch_mul;
-            u.flags = kUnitCausal;
+            u.flags |= kUnitCausal;
             u.n = batch;
             u.rows = (int32_t)L.rows;
             u.cols = (int32_t)L.cols;
@@ -108,11 +108,17 @@ struct WorkTable {
 
 size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+int device_index() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return -1;
+    return dev;
+}
+
 int device_cus() {
     static std::mutex mu;
     static int cached[64];
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    const int dev = device_index();
+    if (dev < 0) return 256;
     std::lock_guard<std::mutex> lock(mu);
     if (cached[dev] == 0) {
         int cus = 0;
@@ -125,15 +131,65 @@ int device_cus() {
 
 int g_grid_cap = 0;                                    // test hook: 0 = no cap
 
-int persistent_grid(uint64_t n_chunks) {
-    uint64_t cap = (uint64_t)device_cus() * kWavesPerSimd;
+// Persistent grid: as many workgroups as the kernel keeps resident on the device, never more
+// than there are chunks.
+int persistent_grid(uint64_t n_chunks, int resident) {
+    uint64_t cap = resident > 0 ? (uint64_t)resident : 1;
     if (g_grid_cap > 0 && (uint64_t)g_grid_cap < cap) cap = (uint64_t)g_grid_cap;
     return (int)(n_chunks < cap ? n_chunks : cap);
 }
 
-// Copies units + chunk_begin (+ extra zero words) to the head of the workspace.
-amp_status_t upload(const WorkTable& t, size_t extra_zero_words, void* workspace, hipStream_t stream) {
-    std::vector<uint8_t> blob(t.table_bytes() + extra_zero_words * 4, 0);
+int sens_grid(uint64_t n_chunks, int n_fmts, int f0, int f1) {
+    static std::mutex mu;
+    static int cached[64][2][2][2];
+    const int dev = device_index();
+    int resident;
+    if (dev < 0) {
+        resident = sens_resident_blocks(n_fmts, f0, f1, device_cus());
+    } else {
+        std::lock_guard<std::mutex> lock(mu);
+        int& slot = cached[dev][n_fmts - 1][f0][f1];
+        if (slot == 0) slot = sens_resident_blocks(n_fmts, f0, f1, device_cus());
+        resident = slot;
+    }
+    return persistent_grid(n_chunks, resident);
+}
+
+int absmax_grid(uint64_t n_chunks) {
+    static std::mutex mu;
+    static int cached[64];
+    const int dev = device_index();
+    int resident;
+    if (dev < 0) {
+        resident = absmax_resident_blocks(device_cus());
+    } else {
+        std::lock_guard<std::mutex> lock(mu);
+        if (cached[dev] == 0) cached[dev] = absmax_resident_blocks(device_cus());
+        resident = cached[dev];
+    }
+    return persistent_grid(n_chunks, resident);
+}
+
+// Workspace layout shared by the absmax and the sensitivity calls:
+//   [ WorkUnit x n_units | chunk_begin x (n_units + 1) ]   uploaded from the host
+//   [ ResolvedUnit x n_units ] [ ChunkRef x n_chunks ]       written by the prepare kernel
+//   [ per-wave partials ]                                    written by the streaming kernel
+struct WsLayout {
+    size_t runits, map, partials, total;
+};
+
+WsLayout ws_layout(const WorkTable& t, size_t partial_bytes_per_chunk) {
+    WsLayout L;
+    L.runits = round_up(t.table_bytes(), 256);
+    L.map = L.runits + round_up(t.units.size() * sizeof(ResolvedUnit), 256);
+    L.partials = L.map + round_up((size_t)t.n_chunks * sizeof(ChunkRef), 256);
+    L.total = L.partials + round_up((size_t)t.n_chunks * partial_bytes_per_chunk, 256);
+    return L;
+}
+
+// Copies units + chunk_begin to the head of the workspace.
+amp_status_t upload(const WorkTable& t, void* workspace, hipStream_t stream) {
+    std::vector<uint8_t> blob(t.table_bytes(), 0);
     std::memcpy(blob.data(), t.units.data(), t.units.size() * sizeof(WorkUnit));
     std::vector<uint32_t> cb = t.chunk_begin;
     cb.push_back((uint32_t)t.n_chunks);
@@ -142,29 +198,46 @@ amp_status_t upload(const WorkTable& t, size_t extra_zero_words, void* workspace
     return AMP_OK;
 }
 
+// ---- optional timing of the sensitivity kernel ------------------------------------------------
+struct Profile {
+    std::vector<hipEvent_t> start, stop;
+    int used = 0;
+};
+Profile g_profile;
+
 // ---- sens: shared by linear and bgemm --------------------------------------------------------
 
-size_t sens_workspace(const WorkTable& t, int n_fmts) {
-    return round_up(t.table_bytes(), 256) + round_up((size_t)t.n_chunks * (n_fmts + 1) * sizeof(float), 256);
+WsLayout sens_layout(const WorkTable& t, int n_fmts) {
+    return ws_layout(t, (size_t)kWaves * (n_fmts + 1) * sizeof(float));
 }
 
 amp_status_t run_sens(const WorkTable& t, const amp_fp8_format_t* fmts, int n_fmts, float* d_out,
                       void* workspace, size_t workspace_bytes, void* stream_) {
     if (t.units.empty()) return AMP_OK;
-    if (!d_out || !aligned2(d_out) || (uintptr_t)d_out % 4) return AMP_ERR_INVALID_ARG;
+    if (!d_out || (uintptr_t)d_out % 4) return AMP_ERR_INVALID_ARG;
     if (!workspace || (uintptr_t)workspace % 256) return AMP_ERR_INVALID_ARG;
-    if (workspace_bytes < sens_workspace(t, n_fmts)) return AMP_ERR_WORKSPACE_TOO_SMALL;
+    const WsLayout L = sens_layout(t, n_fmts);
+    if (workspace_bytes < L.total) return AMP_ERR_WORKSPACE_TOO_SMALL;
     hipStream_t stream = (hipStream_t)stream_;
-    amp_status_t st = upload(t, 0, workspace, stream);
+    amp_status_t st = upload(t, workspace, stream);
     if (st != AMP_OK) return st;
-    const WorkUnit* d_units = (const WorkUnit*)workspace;
-    const uint32_t* d_cb = (const uint32_t*)((const uint8_t*)workspace + t.units.size() * sizeof(WorkUnit));
-    float* d_partials = (float*)((uint8_t*)workspace + round_up(t.table_bytes(), 256));
+    uint8_t* ws = (uint8_t*)workspace;
+    const uint32_t n_units = (uint32_t)t.units.size(), n_chunks = (uint32_t)t.n_chunks;
+    const WorkUnit* d_units = (const WorkUnit*)ws;
+    const uint32_t* d_cb = (const uint32_t*)(ws + t.units.size() * sizeof(WorkUnit));
+    ResolvedUnit* d_runits = (ResolvedUnit*)(ws + L.runits);
+    ChunkRef* d_map = (ChunkRef*)(ws + L.map);
+    float* d_partials = (float*)(ws + L.partials);
     const int f0 = (int)fmts[0], f1 = (int)fmts[n_fmts - 1];
-    if (t.n_chunks > 0)
-        AMP_HIP(launch_sens(d_units, d_cb, (uint32_t)t.units.size(), (uint32_t)t.n_chunks, n_fmts, f0,
-                            f1, d_partials, persistent_grid(t.n_chunks), stream));
-    AMP_HIP(launch_sens_finalize(d_units, d_cb, (uint32_t)t.units.size(), n_fmts, d_partials, d_out, stream));
+    AMP_HIP(launch_prepare(d_units, d_cb, n_units, n_chunks, n_fmts, d_runits, d_map, stream));
+    if (n_chunks > 0) {
+        const int grid = sens_grid(n_chunks, n_fmts, f0, f1);
+        const bool timed = g_profile.used < (int)g_profile.start.size();
+        if (timed) AMP_HIP(hipEventRecord(g_profile.start[g_profile.used], stream));
+        AMP_HIP(launch_sens(d_runits, d_map, n_chunks, n_fmts, f0, f1, d_partials, grid, stream));
+        if (timed) AMP_HIP(hipEventRecord(g_profile.stop[g_profile.used++], stream));
+    }
+    AMP_HIP(launch_sens_finalize(d_runits, d_cb, n_units, n_fmts, d_partials, d_out, stream));
     return AMP_OK;
 }
 
@@ -201,7 +274,8 @@ amp_status_t build_linear(const amp_linear_desc_t* ops, int n_ops, int n_fmts, W
             amp_status_t st = t->add(xn ? op.x + r0 * op.C : op.x, xn ? op.dx + r0 * op.C : op.dx, Lx, 1,
                                      op.x_scale, op.x_inv, (uint32_t)o);
             if (st != AMP_OK) return st;
-            st = t->add(op.w, wn ? op.dw + (int64_t)r * wn : op.dw, Lw, 1, op.w_scale, op.w_inv, (uint32_t)o + 2);
+            st = t->add(op.w, wn ? op.dw + (int64_t)r * wn : op.dw, Lw, 1, op.w_scale, op.w_inv, (uint32_t)o + 2,
+                        op.R > 1 ? kUnitKeepX : 0u);
             if (st != AMP_OK) return st;
         }
         base += (uint64_t)op.R;
@@ -256,9 +330,7 @@ amp_status_t build_absmax(const amp_tensor_t* tensors, int n_tensors, WorkTable*
     return AMP_OK;
 }
 
-size_t absmax_workspace(const WorkTable& t) {
-    return round_up(t.table_bytes() + t.units.size() * sizeof(uint32_t), 256);
-}
+WsLayout absmax_layout(const WorkTable& t) { return ws_layout(t, (size_t)kWaves * sizeof(uint32_t)); }
 
 // ---- test hook (not part of the public header) ------------------------------------------------
 // Replays on the host, thread by thread, the element walk the kernels perform for one unit
@@ -271,9 +343,9 @@ struct ReplayCtx {
     uintptr_t addr;          // byte address the unit would have
     int64_t bad;
     __host__ __device__ void touch(int64_t e) { if (e < 0 || e >= span) ++bad; else ++counts[e]; }
-    template <int U> __host__ __device__ void full(int64_t e, int64_t stride) {
+    template <int U> __host__ __device__ void full(int64_t eu, int le, int64_t stride) {
         for (int k = 0; k < U; ++k) {
-            const int64_t s = e + k * stride;
+            const int64_t s = eu + le + k * stride;
             if ((addr + 2 * (uintptr_t)s) % 16) ++bad;
             for (int j = 0; j < kVec; ++j) touch(s + j);
         }
@@ -291,7 +363,7 @@ amp_status_t amp_absmax_workspace_bytes(const amp_tensor_t* tensors, int n_tenso
     WorkTable t;
     amp_status_t st = build_absmax(tensors, n_tensors, &t);
     if (st != AMP_OK) return st;
-    *bytes = absmax_workspace(t);
+    *bytes = absmax_layout(t).total;
     return AMP_OK;
 }
 
@@ -308,18 +380,23 @@ amp_status_t amp_absmax_scale(const amp_tensor_t* tensors, int n_tensors, const 
     if (!d_amax || !d_scale || !d_inv || !d_flags) return AMP_ERR_INVALID_ARG;
     if (((uintptr_t)d_amax | (uintptr_t)d_scale | (uintptr_t)d_inv | (uintptr_t)d_flags) % 4) return AMP_ERR_INVALID_ARG;
     if (!workspace || (uintptr_t)workspace % 256) return AMP_ERR_INVALID_ARG;
-    if (workspace_bytes < absmax_workspace(t)) return AMP_ERR_WORKSPACE_TOO_SMALL;
+    const WsLayout L = absmax_layout(t);
+    if (workspace_bytes < L.total) return AMP_ERR_WORKSPACE_TOO_SMALL;
     hipStream_t stream = (hipStream_t)stream_;
-    st = upload(t, t.units.size(), workspace, stream);        // trailing words: zeroed running maxima
+    st = upload(t, workspace, stream);
     if (st != AMP_OK) return st;
-    const WorkUnit* d_units = (const WorkUnit*)workspace;
-    const uint32_t* d_cb = (const uint32_t*)((const uint8_t*)workspace + t.units.size() * sizeof(WorkUnit));
-    uint32_t* d_maxbits = (uint32_t*)((uint8_t*)workspace + t.table_bytes());
-    if (t.n_chunks > 0)
-        AMP_HIP(launch_absmax(d_units, d_cb, (uint32_t)t.units.size(), (uint32_t)t.n_chunks, d_maxbits,
-                              persistent_grid(t.n_chunks), stream));
-    AMP_HIP(launch_absmax_finalize(d_maxbits, n_tensors, n_fmts, (int)fmts[0], (int)fmts[n_fmts - 1],
-                                   d_amax, d_scale, d_inv, d_flags, stream));
+    uint8_t* ws = (uint8_t*)workspace;
+    const uint32_t n_units = (uint32_t)t.units.size(), n_chunks = (uint32_t)t.n_chunks;
+    const WorkUnit* d_units = (const WorkUnit*)ws;
+    const uint32_t* d_cb = (const uint32_t*)(ws + t.units.size() * sizeof(WorkUnit));
+    ResolvedUnit* d_runits = (ResolvedUnit*)(ws + L.runits);
+    ChunkRef* d_map = (ChunkRef*)(ws + L.map);
+    uint32_t* d_partial_max = (uint32_t*)(ws + L.partials);
+    AMP_HIP(launch_prepare(d_units, d_cb, n_units, n_chunks, 0, d_runits, d_map, stream));
+    if (n_chunks > 0)
+        AMP_HIP(launch_absmax(d_runits, d_map, n_chunks, d_partial_max, absmax_grid(n_chunks), stream));
+    AMP_HIP(launch_absmax_finalize(d_cb, d_partial_max, n_tensors, n_fmts, (int)fmts[0],
+                                   (int)fmts[n_fmts - 1], d_amax, d_scale, d_inv, d_flags, stream));
     return AMP_OK;
 }
 
@@ -332,7 +409,7 @@ amp_status_t amp_fake_quant_fp8(const uint16_t* d_x, int64_t n, float scale, flo
     if (!d_x || !d_codes || !aligned2(d_x) || (d_dequant && (uintptr_t)d_dequant % 4)) return AMP_ERR_INVALID_ARG;
     if (n > kMaxElems) return AMP_ERR_TOO_LARGE;
     const uint64_t blocks = ((uint64_t)n / kVec + kWG - 1) / kWG + 1;
-    const uint64_t cap = (uint64_t)device_cus() * kWavesPerSimd;
+    const uint64_t cap = (uint64_t)device_cus() * 8;
     AMP_HIP(launch_fake_quant(d_x, n, scale, inv_scale, (int)fmt, d_codes, d_dequant,
                               (int)(blocks < cap ? blocks : cap), (hipStream_t)stream_));
     return AMP_OK;
@@ -343,7 +420,7 @@ amp_status_t amp_sens_linear_workspace_bytes(const amp_linear_desc_t* ops, int n
     WorkTable t;
     amp_status_t st = build_linear(ops, n_ops, n_fmts, &t);
     if (st != AMP_OK) return st;
-    *bytes = sens_workspace(t, n_fmts);
+    *bytes = sens_layout(t, n_fmts).total;
     return AMP_OK;
 }
 
@@ -363,7 +440,7 @@ amp_status_t amp_sens_bgemm_workspace_bytes(const amp_bgemm_desc_t* ops, int n_o
     WorkTable t;
     amp_status_t st = build_bgemm(ops, n_ops, n_fmts, &t);
     if (st != AMP_OK) return st;
-    *bytes = sens_workspace(t, n_fmts);
+    *bytes = sens_layout(t, n_fmts).total;
     return AMP_OK;
 }
 
@@ -376,6 +453,35 @@ amp_status_t amp_sens_bgemm(const amp_bgemm_desc_t* ops, int n_ops, const amp_fp
     st = build_bgemm(ops, n_ops, n_fmts, &t);
     if (st != AMP_OK) return st;
     return run_sens(t, fmts, n_fmts, d_out, workspace, workspace_bytes, stream);
+}
+
+amp_status_t amp_profile_enable(int max_launches) {
+    if (max_launches < 0) return AMP_ERR_INVALID_ARG;
+    for (hipEvent_t e : g_profile.start) (void)hipEventDestroy(e);
+    for (hipEvent_t e : g_profile.stop) (void)hipEventDestroy(e);
+    g_profile.start.clear();
+    g_profile.stop.clear();
+    g_profile.used = 0;
+    for (int i = 0; i < max_launches; ++i) {
+        hipEvent_t a, b;
+        AMP_HIP(hipEventCreate(&a));
+        g_profile.start.push_back(a);
+        AMP_HIP(hipEventCreate(&b));
+        g_profile.stop.push_back(b);
+    }
+    return AMP_OK;
+}
+
+amp_status_t amp_profile_read(float* ms, int capacity, int* n_launches) {
+    if (!n_launches || capacity < 0 || (capacity > 0 && !ms)) return AMP_ERR_INVALID_ARG;
+    if (capacity < g_profile.used) return AMP_ERR_INVALID_ARG;
+    for (int i = 0; i < g_profile.used; ++i) {
+        AMP_HIP(hipEventSynchronize(g_profile.stop[i]));
+        AMP_HIP(hipEventElapsedTime(&ms[i], g_profile.start[i], g_profile.stop[i]));
+    }
+    *n_launches = g_profile.used;
+    g_profile.used = 0;
+    return AMP_OK;
 }
 
 const char* amp_status_string(amp_status_t status) {

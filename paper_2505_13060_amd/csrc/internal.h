@@ -20,15 +20,18 @@ namespace ampsens {
 // small rectangle of vectors with a ragged last column.  A chunk is kBandsPerChunk bands.
 constexpr int kWG = 256;             // threads per workgroup (4 wave64)
 constexpr int kVec = 8;              // bf16 elements per 128-bit load
-constexpr int kChunkVecs = 2048;     // dense: vectors per chunk (64 KiB of x + xdot)
+constexpr int kChunkVecs = 4096;     // dense: vectors per chunk (128 KiB of x + xdot)
 constexpr int kBandRows = 8;
 constexpr int kBandsPerChunk = 4;
 constexpr int kMaxFormats = 2;
+constexpr int kWaves = kWG / 64;     // every wave writes its own partial, so no barrier is needed
 
 enum : uint32_t {
     kUnitCausal = 1u,                // causal layout
     kUnitScalar = 2u,                // x and xdot are not mutually 16-byte aligned (or causal rows
                                      // are not): every vector takes the guarded 2-byte path
+    kUnitKeepX = 4u,                 // x is read again soon (a weight shared by the samples): load it
+                                     // with ordinary caching; everything else streams non-temporally
 };
 
 struct alignas(16) WorkUnit {        // 64 bytes
@@ -46,6 +49,28 @@ struct alignas(16) WorkUnit {        // 64 bytes
 };
 static_assert(sizeof(WorkUnit) == 64, "WorkUnit layout");
 
+// Device-side companions of the table, written by the prepare kernel of each call:
+// the unit with its scales resolved to values, and for every chunk its unit and its index
+// inside that unit, so that the streaming kernels need no search.
+struct alignas(16) ResolvedUnit {    // 64 bytes
+    const uint16_t* x;
+    const uint16_t* dx;
+    int64_t n;
+    int32_t rows, cols;
+    uint32_t flags;
+    uint32_t head;
+    uint32_t out;
+    uint32_t chunks_per_mat;
+    float inv[kMaxFormats];
+    float scale[kMaxFormats];
+};
+static_assert(sizeof(ResolvedUnit) == 64, "ResolvedUnit layout");
+
+struct ChunkRef {
+    uint32_t unit;
+    uint32_t local;                  // chunk index inside the unit
+};
+
 // Number of chunks of a unit (host side; the kernels use the same constants).
 inline uint64_t unit_chunks_dense(int64_t n, uint32_t head) {
     if (n <= 0) return 0;
@@ -59,17 +84,25 @@ inline uint32_t causal_chunks_per_mat(int64_t rows) {
 
 // ---- launchers (kernels.hip) ---------------------------------------------------------------
 // All enqueue on `stream` and return the launch error, never synchronise.
-hipError_t launch_absmax(const WorkUnit* d_units, const uint32_t* d_chunk_begin, uint32_t n_units,
-                         uint32_t n_chunks, uint32_t* d_maxbits, int grid, hipStream_t stream);
-hipError_t launch_absmax_finalize(const uint32_t* d_maxbits, int n_tensors, int n_fmts, int fmt0,
-                                  int fmt1, float* d_amax, float* d_scale, float* d_inv,
-                                  uint32_t* d_flags, hipStream_t stream);
+// Persistent-grid size for the streaming kernels on the current device (resident workgroups).
+int sens_resident_blocks(int n_fmts, int fmt0, int fmt1, int cus);
+int absmax_resident_blocks(int cus);
+
+hipError_t launch_prepare(const WorkUnit* d_units, const uint32_t* d_chunk_begin, uint32_t n_units,
+                          uint32_t n_chunks, int n_fmts, ResolvedUnit* d_runits, ChunkRef* d_map,
+                          hipStream_t stream);
+hipError_t launch_absmax(const ResolvedUnit* d_runits, const ChunkRef* d_map, uint32_t n_chunks,
+                         uint32_t* d_partial_max, int grid, hipStream_t stream);
+hipError_t launch_absmax_finalize(const uint32_t* d_chunk_begin, const uint32_t* d_partial_max,
+                                  int n_tensors, int n_fmts, int fmt0, int fmt1, float* d_amax,
+                                  float* d_scale, float* d_inv, uint32_t* d_flags,
+                                  hipStream_t stream);
 hipError_t launch_fake_quant(const uint16_t* d_x, int64_t n, float scale, float inv, int fmt,
                              uint8_t* d_codes, float* d_dequant, int grid, hipStream_t stream);
-hipError_t launch_sens(const WorkUnit* d_units, const uint32_t* d_chunk_begin, uint32_t n_units,
-                       uint32_t n_chunks, int n_fmts, int fmt0, int fmt1, float* d_partials,
-                       int grid, hipStream_t stream);
-hipError_t launch_sens_finalize(const WorkUnit* d_units, const uint32_t* d_chunk_begin,
+hipError_t launch_sens(const ResolvedUnit* d_runits, const ChunkRef* d_map, uint32_t n_chunks,
+                       int n_fmts, int fmt0, int fmt1, float* d_partials, int grid,
+                       hipStream_t stream);
+hipError_t launch_sens_finalize(const ResolvedUnit* d_runits, const uint32_t* d_chunk_begin,
                                 uint32_t n_units, int n_fmts, const float* d_partials,
                                 float* d_out, hipStream_t stream);
 

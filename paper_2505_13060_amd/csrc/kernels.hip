@@ -8,6 +8,13 @@
 // scale, a clamp, half a packed convert to FP8 (gfx950's OCP conversion instructions), half a
 // packed convert back, one FMA for the error and a multiply + FMA for the sum.
 //
+// Streaming design: a persistent grid (as many workgroups as are resident) strides over the
+// chunk list of all units of a call; chunk c is found through a device-built map (no search),
+// the next chunk's map entry is fetched while the current chunk streams; operands are read
+// with 128-bit non-temporal loads addressed as uniform base + lane offset; every wave reduces
+// its lanes with DPP and writes its own partial (no LDS, no barrier); a second small kernel
+// adds each unit's partials in a fixed order in fp64.
+//
 // Build with -ffp-contract=off: the multiply that decides an FP8 code must stay a plain fp32
 // multiply; every fusion that is wanted is written as fmaf.
 #include "internal.h"
@@ -17,8 +24,8 @@ namespace ampsens {
 namespace {
 
 typedef float float2_t __attribute__((ext_vector_type(2)));
-typedef const uint16_t __attribute__((address_space(1)))* gptr16_t;   // global address space
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));             // one 128-bit load
+typedef const uint16_t __attribute__((address_space(1)))* gptr16_t;   // global address space
 typedef const u32x4 __attribute__((address_space(1)))* gptr128_t;
 
 template <int FMT> struct Fp8;
@@ -53,10 +60,24 @@ __device__ __forceinline__ float clamp_fmax(float y) {
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
+// ---- wave64 reductions ------------------------------------------------------------------------
+
+// v + (v moved by a DPP pattern); rows the mask leaves out, and lanes without a source, add 0.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_add(float v) {
+    const int moved = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xF, false);
+    return v + __int_as_float(moved);
+}
+
+// Sum over the 64 lanes in a fixed order; the total is returned in every lane.
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-    return v;
+    v = dpp_add<0xB1, 0xF>(v);        // quad_perm [1,0,3,2]
+    v = dpp_add<0x4E, 0xF>(v);        // quad_perm [2,3,0,1]
+    v = dpp_add<0x141, 0xF>(v);       // row_half_mirror
+    v = dpp_add<0x140, 0xF>(v);       // row_mirror: every lane of a 16-lane row holds the row sum
+    v = dpp_add<0x142, 0xA>(v);       // row_bcast15 into rows 1 and 3
+    v = dpp_add<0x143, 0xC>(v);       // row_bcast31 into rows 2 and 3: lane 63 holds the total
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 __device__ __forceinline__ double wave_sum(double v) {
 #pragma unroll
@@ -72,6 +93,14 @@ __device__ __forceinline__ uint32_t wave_max(uint32_t v) {
     return v;
 }
 
+// ---- loads --------------------------------------------------------------------------------------
+
+template <bool NT>
+__device__ __forceinline__ u32x4 load128(gptr128_t p) {
+    if constexpr (NT) return __builtin_nontemporal_load(p);
+    else return *p;
+}
+
 // Fetch x[e + j] for jlo <= j < jhi one element at a time, zero elsewhere, packed like a
 // 128-bit load would deliver them.
 __device__ __forceinline__ u32x4 gather8(gptr16_t p, int64_t e, int jlo, int jhi) {
@@ -82,12 +111,42 @@ __device__ __forceinline__ u32x4 gather8(gptr16_t p, int64_t e, int jlo, int jhi
     return v;
 }
 
+// ---- prepare: resolve scales, build the chunk map ---------------------------------------------
+
+__global__ __launch_bounds__(kWG) void prepare_kernel(const WorkUnit* __restrict__ units,
+                                                      const uint32_t* __restrict__ chunk_begin,
+                                                      uint32_t n_units, uint32_t n_chunks, int n_fmts,
+                                                      ResolvedUnit* __restrict__ runits,
+                                                      ChunkRef* __restrict__ map) {
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n_units) {
+        const WorkUnit u = units[i];
+        ResolvedUnit r;
+        r.x = u.x; r.dx = u.dx; r.n = u.n; r.rows = u.rows; r.cols = u.cols; r.flags = u.flags;
+        r.head = u.head; r.out = u.out; r.chunks_per_mat = u.chunks_per_mat;
+        for (int f = 0; f < kMaxFormats; ++f) {
+            const bool have = f < n_fmts && u.inv != nullptr && u.scale != nullptr;
+            r.inv[f] = have ? u.inv[f] : 1.0f;
+            r.scale[f] = have ? u.scale[f] : 1.0f;
+        }
+        runits[i] = r;
+    }
+    if (i < n_chunks) {
+        const uint32_t ui = find_unit(chunk_begin, n_units, i);
+        ChunkRef ref;
+        ref.unit = ui;
+        ref.local = i - chunk_begin[ui];
+        map[i] = ref;
+    }
+}
+
 // ---- the fused sensitivity pass --------------------------------------------------------------
 
 template <int NF, int F0, int F1>
 struct SensCtx {
     gptr16_t x;
     gptr16_t g;
+    bool keep_x;                                   // x is re-read soon: ordinary caching
     float inv[NF], scale[NF];
     float E[NF];
     float A;
@@ -135,13 +194,22 @@ struct SensCtx {
     }
 
     template <int U>
-    __device__ __forceinline__ void full(int64_t e, int64_t stride) {
+    __device__ __forceinline__ void full(int64_t eu, int le, int64_t stride) {
+        // uniform base (scalar registers) + this lane's vector index: one address VGPR in all
+        const gptr128_t bx = reinterpret_cast<gptr128_t>(x + eu);
+        const gptr128_t bg = reinterpret_cast<gptr128_t>(g + eu);
+        const int lv = le / kVec;
+        const int64_t sv = stride / kVec;
         u32x4 xr[U], gr[U];
+        if (keep_x) {
 #pragma unroll
-        for (int k = 0; k < U; ++k) {
-            xr[k] = *reinterpret_cast<gptr128_t>(x + e + k * stride);
-            gr[k] = *reinterpret_cast<gptr128_t>(g + e + k * stride);
+            for (int k = 0; k < U; ++k) xr[k] = load128<false>(bx + k * sv + lv);
+        } else {
+#pragma unroll
+            for (int k = 0; k < U; ++k) xr[k] = load128<true>(bx + k * sv + lv);
         }
+#pragma unroll
+        for (int k = 0; k < U; ++k) gr[k] = load128<true>(bg + k * sv + lv);
 #pragma unroll
         for (int k = 0; k < U; ++k) vec(xr[k], gr[k]);
     }
@@ -154,20 +222,25 @@ struct SensCtx {
 };
 
 template <int NF, int F0, int F1>
-__global__ __launch_bounds__(kWG) void sens_kernel(const WorkUnit* __restrict__ units,
-                                                   const uint32_t* __restrict__ chunk_begin,
-                                                   uint32_t n_units, uint32_t n_chunks,
-                                                   float* __restrict__ partials) {
-    __shared__ float red[2][kWG / 64][NF + 1];
+__global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) void sens_kernel(const ResolvedUnit* __restrict__ runits,
+                                                   const ChunkRef* __restrict__ map,
+                                                   uint32_t n_chunks, float* __restrict__ partials) {
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    uint32_t it = 0;
-    for (uint32_t c = blockIdx.x; c < n_chunks; c += gridDim.x, ++it) {
-        const uint32_t ui = find_unit(chunk_begin, n_units, c);
-        const WorkUnit u = units[ui];
+    uint32_t c = blockIdx.x;
+    if (c >= n_chunks) return;
+    ChunkRef ref = map[c];
+    while (true) {
+        const ResolvedUnit u = runits[ref.unit];
+        const uint32_t local = ref.local;
+        const uint32_t cn = c + gridDim.x;
+        const bool more = cn < n_chunks;
+        if (more) ref = map[cn];                    // next chunk's entry travels while this one streams
+
         SensCtx<NF, F0, F1> ctx;
         ctx.x = (gptr16_t)u.x;
         ctx.g = (gptr16_t)u.dx;
+        ctx.keep_x = (u.flags & kUnitKeepX) != 0;
 #pragma unroll
         for (int f = 0; f < NF; ++f) {
             ctx.inv[f] = u.inv[f];
@@ -176,52 +249,44 @@ __global__ __launch_bounds__(kWG) void sens_kernel(const WorkUnit* __restrict__ 
             ctx.pk[f] = 0;
         }
         ctx.A = 0.0f;
-        walk_chunk(u, c - chunk_begin[ui], tid, ctx);
+        walk_chunk(u, local, tid, ctx);
 
         float v[NF + 1];
 #pragma unroll
         for (int f = 0; f < NF; ++f) v[f] = wave_sum(ctx.E[f]);
         v[NF] = wave_sum(ctx.A);
-        float (*slot)[NF + 1] = red[it & 1];
         if (lane == 0) {
+            float* slot = partials + ((size_t)c * kWaves + wave) * (NF + 1);
 #pragma unroll
-            for (int k = 0; k <= NF; ++k) slot[wave][k] = v[k];
+            for (int k = 0; k <= NF; ++k) slot[k] = v[k];
         }
-        __syncthreads();
-        // Two alternating slots and one barrier per chunk: a wave can reach the writes of
-        // chunk it+2 only after every wave passed the barrier of chunk it+1, hence after
-        // thread 0 finished reading the slot of chunk it.
-        if (tid == 0) {
-#pragma unroll
-            for (int k = 0; k <= NF; ++k)
-                partials[(size_t)c * (NF + 1) + k] =
-                    (slot[0][k] + slot[1][k]) + (slot[2][k] + slot[3][k]);
-        }
+        if (!more) break;
+        c = cn;
     }
 }
 
-// One wave per unit: fixed-order fp64 sum of the unit's chunk partials.
+// One wave per unit: fixed-order fp64 sum of the unit's per-wave chunk partials.
 template <int NF>
-__global__ __launch_bounds__(kWG) void sens_finalize_kernel(const WorkUnit* __restrict__ units,
+__global__ __launch_bounds__(kWG) void sens_finalize_kernel(const ResolvedUnit* __restrict__ runits,
                                                             const uint32_t* __restrict__ chunk_begin,
                                                             uint32_t n_units,
                                                             const float* __restrict__ partials,
                                                             float* __restrict__ out) {
-    const uint32_t ui = blockIdx.x * (kWG / 64) + (threadIdx.x >> 6);
+    const uint32_t ui = blockIdx.x * kWaves + (threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     if (ui >= n_units) return;
-    const uint32_t c0 = chunk_begin[ui], c1 = chunk_begin[ui + 1];
+    const size_t p0 = (size_t)chunk_begin[ui] * kWaves, p1 = (size_t)chunk_begin[ui + 1] * kWaves;
     double acc[NF + 1];
 #pragma unroll
     for (int k = 0; k <= NF; ++k) acc[k] = 0.0;
-    for (uint32_t c = c0 + lane; c < c1; c += 64) {
+    for (size_t p = p0 + lane; p < p1; p += 64) {
 #pragma unroll
-        for (int k = 0; k <= NF; ++k) acc[k] += (double)partials[(size_t)c * (NF + 1) + k];
+        for (int k = 0; k <= NF; ++k) acc[k] += (double)partials[p * (NF + 1) + k];
     }
 #pragma unroll
     for (int k = 0; k <= NF; ++k) acc[k] = wave_sum(acc[k]);
     if (lane == 0) {
-        const uint32_t o = units[ui].out;
+        const uint32_t o = runits[ui].out;
 #pragma unroll
         for (int f = 0; f < NF; ++f) {
             out[o + 4 * f] = (float)acc[f];
@@ -244,43 +309,70 @@ struct AbsmaxCtx {
     __device__ __forceinline__ void vec(const u32x4& v) { word(v.x); word(v.y); word(v.z); word(v.w); }
 
     template <int U>
-    __device__ __forceinline__ void full(int64_t e, int64_t stride) {
+    __device__ __forceinline__ void full(int64_t eu, int le, int64_t stride) {
+        const gptr128_t bx = reinterpret_cast<gptr128_t>(x + eu);
+        const int lv = le / kVec;
+        const int64_t sv = stride / kVec;
         u32x4 xr[U];
 #pragma unroll
-        for (int k = 0; k < U; ++k) xr[k] = *reinterpret_cast<gptr128_t>(x + e + k * stride);
+        for (int k = 0; k < U; ++k) xr[k] = load128<true>(bx + k * sv + lv);
 #pragma unroll
         for (int k = 0; k < U; ++k) vec(xr[k]);
     }
     __device__ __forceinline__ void partial(int64_t e, int jlo, int jhi) { vec(gather8(x, e, jlo, jhi)); }
 };
 
-__global__ __launch_bounds__(kWG) void absmax_kernel(const WorkUnit* __restrict__ units,
-                                                     const uint32_t* __restrict__ chunk_begin,
-                                                     uint32_t n_units, uint32_t n_chunks,
-                                                     uint32_t* __restrict__ maxbits) {
+// Per-wave maxima of every chunk go to their own slots: integer max is exact and order-free,
+// and without atomics there is no contention on the few per-tensor words.
+__global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) void absmax_kernel(const ResolvedUnit* __restrict__ runits,
+                                                     const ChunkRef* __restrict__ map,
+                                                     uint32_t n_chunks,
+                                                     uint32_t* __restrict__ partial_max) {
     const int tid = threadIdx.x;
-    for (uint32_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
-        const uint32_t ui = find_unit(chunk_begin, n_units, c);
-        const WorkUnit u = units[ui];
+    uint32_t c = blockIdx.x;
+    if (c >= n_chunks) return;
+    ChunkRef ref = map[c];
+    while (true) {
+        const ResolvedUnit u = runits[ref.unit];
+        const uint32_t local = ref.local;
+        const uint32_t cn = c + gridDim.x;
+        const bool more = cn < n_chunks;
+        if (more) ref = map[cn];
         AbsmaxCtx ctx;
         ctx.x = (gptr16_t)u.x;
         ctx.m = 0;
-        walk_chunk(u, c - chunk_begin[ui], tid, ctx);
+        walk_chunk(u, local, tid, ctx);
         const uint32_t m = wave_max(ctx.m);
-        // integer max is exact and order-free, so an atomic keeps the result deterministic
-        if ((tid & 63) == 0 && m != 0) atomicMax(&maxbits[u.out], m);
+        if ((tid & 63) == 0) partial_max[(size_t)c * kWaves + (tid >> 6)] = m;
+        if (!more) break;
+        c = cn;
     }
 }
 
 __device__ __forceinline__ float fmax_of(int fmt) { return fmt == 0 ? 448.0f : 57344.0f; }
 
-__global__ void absmax_finalize_kernel(const uint32_t* __restrict__ maxbits, int n_tensors,
-                                       int n_fmts, int fmt0, int fmt1, float* __restrict__ amax_out,
-                                       float* __restrict__ scale_out, float* __restrict__ inv_out,
-                                       uint32_t* __restrict__ flags_out) {
-    const int t = blockIdx.x * blockDim.x + threadIdx.x;
-    if (t >= n_tensors) return;
-    const uint32_t bits = maxbits[t];
+// One workgroup per tensor (unit t of an absmax call is tensor t).
+__global__ __launch_bounds__(kWG) void absmax_finalize_kernel(const uint32_t* __restrict__ chunk_begin,
+                                                              const uint32_t* __restrict__ partial_max,
+                                                              int n_fmts, int fmt0, int fmt1,
+                                                              float* __restrict__ amax_out,
+                                                              float* __restrict__ scale_out,
+                                                              float* __restrict__ inv_out,
+                                                              uint32_t* __restrict__ flags_out) {
+    __shared__ uint32_t red[kWaves];
+    const int t = blockIdx.x;
+    const size_t p0 = (size_t)chunk_begin[t] * kWaves, p1 = (size_t)chunk_begin[t + 1] * kWaves;
+    uint32_t m = 0;
+    for (size_t p = p0 + threadIdx.x; p < p1; p += kWG) {
+        const uint32_t v = partial_max[p];
+        m = m > v ? m : v;
+    }
+    m = wave_max(m);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x != 0) return;
+    uint32_t bits = 0;
+    for (int w = 0; w < kWaves; ++w) bits = bits > red[w] ? bits : red[w];
     const float amax = __uint_as_float(bits << 16);
     amax_out[t] = amax;
     flags_out[t] = bits >= 0x7F80u ? 1u : 0u;
@@ -339,37 +431,53 @@ __global__ __launch_bounds__(kWG) void fake_quant_kernel(const uint16_t* __restr
     }
 }
 
-template <int NF>
-hipError_t launch_sens_nf(int fmt0, int fmt1, dim3 grid, hipStream_t stream, const WorkUnit* units,
-                          const uint32_t* cb, uint32_t n_units, uint32_t n_chunks, float* partials) {
-    if constexpr (NF == 1) {
-        if (fmt0 == 0) hipLaunchKernelGGL((sens_kernel<1, 0, 0>), grid, dim3(kWG), 0, stream, units, cb, n_units, n_chunks, partials);
-        else hipLaunchKernelGGL((sens_kernel<1, 1, 1>), grid, dim3(kWG), 0, stream, units, cb, n_units, n_chunks, partials);
-    } else {
-        if (fmt0 == 0 && fmt1 == 0) hipLaunchKernelGGL((sens_kernel<2, 0, 0>), grid, dim3(kWG), 0, stream, units, cb, n_units, n_chunks, partials);
-        else if (fmt0 == 0 && fmt1 == 1) hipLaunchKernelGGL((sens_kernel<2, 0, 1>), grid, dim3(kWG), 0, stream, units, cb, n_units, n_chunks, partials);
-        else if (fmt0 == 1 && fmt1 == 0) hipLaunchKernelGGL((sens_kernel<2, 1, 0>), grid, dim3(kWG), 0, stream, units, cb, n_units, n_chunks, partials);
-        else hipLaunchKernelGGL((sens_kernel<2, 1, 1>), grid, dim3(kWG), 0, stream, units, cb, n_units, n_chunks, partials);
-    }
-    return hipGetLastError();
+// ---- launch helpers -----------------------------------------------------------------------------
+
+typedef void (*sens_fn_t)(const ResolvedUnit*, const ChunkRef*, uint32_t, float*);
+
+sens_fn_t sens_variant(int n_fmts, int fmt0, int fmt1) {
+    if (n_fmts == 1) return fmt0 == 0 ? sens_kernel<1, 0, 0> : sens_kernel<1, 1, 1>;
+    if (fmt0 == 0) return fmt1 == 0 ? sens_kernel<2, 0, 0> : sens_kernel<2, 0, 1>;
+    return fmt1 == 0 ? sens_kernel<2, 1, 0> : sens_kernel<2, 1, 1>;
+}
+
+int resident_blocks(const void* fn, int cus) {
+    int per_cu = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kWG, 0) != hipSuccess || per_cu < 1)
+        per_cu = 4;
+    return per_cu * cus;
 }
 
 }  // namespace
 
-hipError_t launch_absmax(const WorkUnit* d_units, const uint32_t* d_chunk_begin, uint32_t n_units,
-                         uint32_t n_chunks, uint32_t* d_maxbits, int grid, hipStream_t stream) {
-    hipLaunchKernelGGL(absmax_kernel, dim3(grid), dim3(kWG), 0, stream, d_units, d_chunk_begin,
-                       n_units, n_chunks, d_maxbits);
+int sens_resident_blocks(int n_fmts, int fmt0, int fmt1, int cus) {
+    return resident_blocks((const void*)sens_variant(n_fmts, fmt0, fmt1), cus);
+}
+
+int absmax_resident_blocks(int cus) { return resident_blocks((const void*)absmax_kernel, cus); }
+
+hipError_t launch_prepare(const WorkUnit* d_units, const uint32_t* d_chunk_begin, uint32_t n_units,
+                          uint32_t n_chunks, int n_fmts, ResolvedUnit* d_runits, ChunkRef* d_map,
+                          hipStream_t stream) {
+    const uint32_t n = n_units > n_chunks ? n_units : n_chunks;
+    hipLaunchKernelGGL(prepare_kernel, dim3((n + kWG - 1) / kWG), dim3(kWG), 0, stream, d_units,
+                       d_chunk_begin, n_units, n_chunks, n_fmts, d_runits, d_map);
     return hipGetLastError();
 }
 
-hipError_t launch_absmax_finalize(const uint32_t* d_maxbits, int n_tensors, int n_fmts, int fmt0,
-                                  int fmt1, float* d_amax, float* d_scale, float* d_inv,
-                                  uint32_t* d_flags, hipStream_t stream) {
-    const int threads = 64;
-    hipLaunchKernelGGL(absmax_finalize_kernel, dim3((n_tensors + threads - 1) / threads),
-                       dim3(threads), 0, stream, d_maxbits, n_tensors, n_fmts, fmt0, fmt1, d_amax,
-                       d_scale, d_inv, d_flags);
+hipError_t launch_absmax(const ResolvedUnit* d_runits, const ChunkRef* d_map, uint32_t n_chunks,
+                         uint32_t* d_partial_max, int grid, hipStream_t stream) {
+    hipLaunchKernelGGL(absmax_kernel, dim3(grid), dim3(kWG), 0, stream, d_runits, d_map, n_chunks,
+                       d_partial_max);
+    return hipGetLastError();
+}
+
+hipError_t launch_absmax_finalize(const uint32_t* d_chunk_begin, const uint32_t* d_partial_max,
+                                  int n_tensors, int n_fmts, int fmt0, int fmt1, float* d_amax,
+                                  float* d_scale, float* d_inv, uint32_t* d_flags,
+                                  hipStream_t stream) {
+    hipLaunchKernelGGL(absmax_finalize_kernel, dim3(n_tensors), dim3(kWG), 0, stream, d_chunk_begin,
+                       d_partial_max, n_fmts, fmt0, fmt1, d_amax, d_scale, d_inv, d_flags);
     return hipGetLastError();
 }
 
@@ -386,25 +494,23 @@ hipError_t launch_fake_quant(const uint16_t* d_x, int64_t n, float scale, float 
     return hipGetLastError();
 }
 
-hipError_t launch_sens(const WorkUnit* d_units, const uint32_t* d_chunk_begin, uint32_t n_units,
-                       uint32_t n_chunks, int n_fmts, int fmt0, int fmt1, float* d_partials,
-                       int grid, hipStream_t stream) {
-    if (n_fmts == 1)
-        return launch_sens_nf<1>(fmt0, fmt0, dim3(grid), stream, d_units, d_chunk_begin, n_units,
-                                 n_chunks, d_partials);
-    return launch_sens_nf<2>(fmt0, fmt1, dim3(grid), stream, d_units, d_chunk_begin, n_units,
-                             n_chunks, d_partials);
+hipError_t launch_sens(const ResolvedUnit* d_runits, const ChunkRef* d_map, uint32_t n_chunks,
+                       int n_fmts, int fmt0, int fmt1, float* d_partials, int grid,
+                       hipStream_t stream) {
+    hipLaunchKernelGGL(sens_variant(n_fmts, fmt0, fmt1), dim3(grid), dim3(kWG), 0, stream, d_runits,
+                       d_map, n_chunks, d_partials);
+    return hipGetLastError();
 }
 
-hipError_t launch_sens_finalize(const WorkUnit* d_units, const uint32_t* d_chunk_begin,
+hipError_t launch_sens_finalize(const ResolvedUnit* d_runits, const uint32_t* d_chunk_begin,
                                 uint32_t n_units, int n_fmts, const float* d_partials,
                                 float* d_out, hipStream_t stream) {
-    const dim3 grid((n_units + (kWG / 64) - 1) / (kWG / 64));
+    const dim3 grid((n_units + kWaves - 1) / kWaves);
     if (n_fmts == 1)
-        hipLaunchKernelGGL(sens_finalize_kernel<1>, grid, dim3(kWG), 0, stream, d_units,
+        hipLaunchKernelGGL(sens_finalize_kernel<1>, grid, dim3(kWG), 0, stream, d_runits,
                            d_chunk_begin, n_units, d_partials, d_out);
     else
-        hipLaunchKernelGGL(sens_finalize_kernel<2>, grid, dim3(kWG), 0, stream, d_units,
+        hipLaunchKernelGGL(sens_finalize_kernel<2>, grid, dim3(kWG), 0, stream, d_runits,
                            d_chunk_begin, n_units, d_partials, d_out);
     return hipGetLastError();
 }

@@ -4,10 +4,12 @@
 // is visited exactly once and that no access leaves the unit) run the very same index code.
 //
 // A context provides
-//   template <int U> void full(int64_t e, int64_t stride)   U whole 8-element vectors whose
-//       first elements are x[e], x[e + stride], ...; each is 16-byte aligned in memory
-//   void partial(int64_t e, int jlo, int jhi)                elements x[e + j], jlo <= j < jhi,
-//       to be fetched one by one
+//   template <int U> void full(int64_t eu, int le, int64_t stride)
+//       U whole 8-element vectors whose first elements are x[eu + le + k*stride], k < U; eu and
+//       stride are the same for every thread of the workgroup, le is the thread's own offset;
+//       each vector is 16-byte aligned in memory
+//   void partial(int64_t e, int jlo, int jhi)
+//       elements x[e + j], jlo <= j < jhi, to be fetched one by one
 // Element indices are relative to the unit's first element.
 #pragma once
 
@@ -23,19 +25,23 @@ namespace ampsens {
 
 constexpr int kUnroll = 4;           // independent 128-bit loads per stream in flight per lane
 
+// True when every vector of dense chunk `chunk_local` is whole and aligned.
+AMPSENS_HD bool dense_chunk_interior(int64_t n, uint32_t head, bool scalar, uint32_t chunk_local) {
+    const int64_t v0 = (int64_t)chunk_local * kChunkVecs;
+    return !scalar && (v0 * kVec >= (int64_t)head) && ((v0 + kChunkVecs) * kVec - head <= n);
+}
+
 template <class Ctx>
 AMPSENS_HD void walk_dense_chunk(int64_t n, uint32_t head, bool scalar, uint32_t chunk_local,
                                  int tid, Ctx& ctx) {
     const int64_t nvec = (n + head + (kVec - 1)) / kVec;
     const int64_t v0 = (int64_t)chunk_local * kChunkVecs;
     int64_t v1 = v0 + kChunkVecs;
-    // every vector of the chunk whole and aligned?
-    const bool interior = !scalar && (v0 * kVec >= (int64_t)head) && (v1 * kVec - head <= n);
-    if (interior) {
+    if (dense_chunk_interior(n, head, scalar, chunk_local)) {
+        const int64_t eu = v0 * kVec - head;
 #pragma unroll
         for (int k = 0; k < kChunkVecs / kWG; k += kUnroll)
-            ctx.template full<kUnroll>((v0 + tid + (int64_t)k * kWG) * kVec - head,
-                                       (int64_t)kWG * kVec);
+            ctx.template full<kUnroll>(eu + (int64_t)k * kWG * kVec, tid * kVec, (int64_t)kWG * kVec);
         return;
     }
     if (v1 > nvec) v1 = nvec;
@@ -44,7 +50,7 @@ AMPSENS_HD void walk_dense_chunk(int64_t n, uint32_t head, bool scalar, uint32_t
         const int jlo = e < 0 ? (int)(-e) : 0;
         const int64_t rem = n - e;
         const int jhi = rem < kVec ? (int)rem : kVec;
-        if (!scalar && jlo == 0 && jhi == kVec) ctx.template full<1>(e, 0);
+        if (!scalar && jlo == 0 && jhi == kVec) ctx.template full<1>(e, 0, 0);
         else ctx.partial(e, jlo, jhi);
     }
 }
@@ -78,14 +84,14 @@ AMPSENS_HD void walk_causal_chunk(int32_t rows, int32_t cols, bool scalar, uint3
             if (e0 >= li) continue;
             const int jhi = (li - e0 < kVec) ? (li - e0) : kVec;
             const int64_t e = mat_base + (int64_t)i * cols + e0;
-            if (!scalar && jhi == kVec) ctx.template full<1>(e, 0);
+            if (!scalar && jhi == kVec) ctx.template full<1>(e, 0, 0);
             else ctx.partial(e, 0, jhi);
         }
     }
 }
 
-template <class Ctx>
-AMPSENS_HD void walk_chunk(const WorkUnit& u, uint32_t chunk_local, int tid, Ctx& ctx) {
+template <class Unit, class Ctx>
+AMPSENS_HD void walk_chunk(const Unit& u, uint32_t chunk_local, int tid, Ctx& ctx) {
     const bool scalar = (u.flags & kUnitScalar) != 0;
     if (u.flags & kUnitCausal)
         walk_causal_chunk(u.rows, u.cols, scalar, u.chunks_per_mat, chunk_local, tid, ctx);

@@ -10,7 +10,7 @@ Recipes
               activations, output channel for weights)
   P           bf16 row-softmax of causally masked N(0, 2^2) logits, exact zeros above the diagonal;
               its gradient is zero there as well
-Seeds: 1000*config + 16*block + tensor id, one torch.Generator per tensor.
+Seeds: (1000*config + 16*block)*100 + tensor id, one torch.Generator per tensor.
 """
 from dataclasses import dataclass, field
 from typing import List, Optional
@@ -88,6 +88,10 @@ class LinearOp:
     K: int
     row_offsets: np.ndarray  # int64 [R+1]
 
+    @property
+    def macs(self):
+        return float(int(self.row_offsets[-1]) * self.C * self.K)
+
     def pairs(self):
         return int(self.row_offsets[-1]) * self.C + self.R * self.K * self.C
 
@@ -102,6 +106,7 @@ class BgemmOp:
     dx1: torch.Tensor
     lay1: tuple
     R: int
+    macs: float = 0.0        # multiply-accumulates of the batched product, all samples
 
     @staticmethod
     def _valid(lay):
@@ -147,10 +152,12 @@ def _attention(prefix, seed, R, Hq, Hkv, S, D, device, g_sigma=1e-3, outliers=0,
         return gradient(s, S, D, device, g_sigma, lead=(R, H))
 
     qk = BgemmOp(prefix + "qk_matmul", act(seed, Hq), grad(seed + 1, Hq), ("dense", Hq * S * D),
-                 act(seed + 2, Hkv), grad(seed + 3, Hkv), ("dense", Hkv * S * D), R)
+                 act(seed + 2, Hkv), grad(seed + 3, Hkv), ("dense", Hkv * S * D), R,
+                 float(R * Hq * S * S * D))
     pv = BgemmOp(prefix + "av_matmul", causal_probs(seed + 4, R, Hq, S, device),
                  causal_grad(seed + 5, R, Hq, S, device, g_sigma), ("causal", Hq, S, S),
-                 act(seed + 6, Hkv), grad(seed + 7, Hkv), ("dense", Hkv * S * D), R)
+                 act(seed + 6, Hkv), grad(seed + 7, Hkv), ("dense", Hkv * S * D), R,
+                 float(R * Hq * S * S * D))
     return [qk, pv]
 
 

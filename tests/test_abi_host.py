@@ -79,16 +79,17 @@ def test_argument_validation_without_a_gpu():
     assert L.amp_sens_linear_workspace_bytes(C.byref(d), 1, 2, C.byref(n)) == amp.ERR_INVALID_ARG
     off[:] = [0, 3, 5]
     assert L.amp_sens_linear_workspace_bytes(C.byref(d), 1, 2, C.byref(n)) == amp.OK
-    # 4 units (X and W of 2 samples), one chunk each: table + partials
-    assert n.value == 512 + 256
+    # 4 units (X and W of 2 samples), one chunk each: uploaded table, resolved units, chunk map,
+    # per-wave partials, each rounded up to 256 bytes
+    assert n.value == 512 + 256 + 256 + 256
 
 
 REPLAY_CASES = [
     # (layout, x offset in bytes from a 16-byte boundary, dx offset, batch_mul)
     (("dense", 1), 0, 0, 1), (("dense", 7), 0, 0, 1), (("dense", 8), 0, 0, 1),
-    (("dense", 16384), 0, 0, 1), (("dense", 16385), 0, 0, 1), (("dense", 16383), 0, 0, 1),
-    (("dense", 50000), 6, 6, 1), (("dense", 16384 * 3), 14, 14, 1), (("dense", 3), 10, 10, 1),
-    (("dense", 40000), 2, 4, 1), (("dense", 123), 0, 8, 1), (("dense", 5000), 0, 0, 7),
+    (("dense", 32768), 0, 0, 1), (("dense", 32769), 0, 0, 1), (("dense", 32767), 0, 0, 1),
+    (("dense", 100000), 6, 6, 1), (("dense", 32768 * 3), 14, 14, 1), (("dense", 3), 10, 10, 1),
+    (("dense", 40000), 2, 4, 1), (("dense", 123), 0, 8, 1), (("dense", 5000), 0, 0, 7), (("dense", 32768 * 2 + 8), 2, 2, 1),
     (("causal", 3, 64, 64), 0, 0, 1), (("causal", 2, 40, 40), 0, 0, 2), (("causal", 1, 37, 48), 0, 0, 1),
     (("causal", 2, 48, 24), 0, 0, 1), (("causal", 1, 33, 33), 0, 0, 1), (("causal", 2, 16, 72), 4, 4, 1),
     (("causal", 1, 100, 8), 0, 0, 1), (("causal", 1, 1, 1), 0, 0, 1), (("causal", 4, 8, 8), 0, 2, 1),
