@@ -78,8 +78,10 @@ typedef enum amp_fp8_format {
  * causal == 0: n_elems consecutive elements (batch/rows/cols ignored).
  * causal == 1: a [batch, rows, cols] array of which entry (b, i, j) belongs to the operand
  *              iff j <= i + (cols - rows) (lower triangle, aligned bottom-right; the attention
- *              probabilities P of a causal model).  Other entries are never read and count as
- *              zero.  n_elems is ignored; the block spans batch*rows*cols elements. */
+ *              probabilities P of a causal model).  Other entries count as zero whatever they
+ *              hold (they may be fetched along with neighbouring entries of the same row, but
+ *              their values, NaN included, have no effect).  n_elems is ignored; the block
+ *              spans batch*rows*cols elements. */
 typedef struct amp_layout {
     int64_t n_elems;
     int64_t batch, rows, cols;

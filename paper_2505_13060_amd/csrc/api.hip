@@ -350,6 +350,16 @@ struct ReplayCtx {
             for (int j = 0; j < kVec; ++j) touch(s + j);
         }
     }
+    template <int U> __host__ __device__ void full_masked(int64_t e, int stride, int count, int tail) {
+        if (count < 0 || count > U || (count > 0 && (tail < 1 || tail > kVec))) ++bad;
+        for (int k = 0; k < count; ++k) {
+            const int64_t s = e + (int64_t)k * stride;
+            if ((addr + 2 * (uintptr_t)s) % 16) ++bad;
+            if (s < 0 || s + kVec > span) ++bad;              // the whole vector is fetched
+            const int valid = (k == count - 1) ? tail : kVec;
+            for (int j = 0; j < valid; ++j) touch(s + j);
+        }
+    }
     __host__ __device__ void partial(int64_t e, int jlo, int jhi) { for (int j = jlo; j < jhi; ++j) touch(e + j); }
 };
 

@@ -15,9 +15,9 @@ namespace ampsens {
 //
 // Dense unit: its elements are viewed as 8-element vectors on the 16-byte grid of the x
 // pointer (the first and last vector may be partial); a chunk is kChunkVecs vectors.
-// Causal unit [batch, rows, cols]: a band is 8 consecutive rows of one batch entry; all rows
-// of a band need the same number of vectors when rows/cols are multiples of 8, so a band is a
-// small rectangle of vectors with a ragged last column.  A chunk is kBandsPerChunk bands.
+// Causal unit [batch, rows, cols]: a band is 8 consecutive rows of one batch entry; band j is
+// paired with band nbands-1-j into a slot, so that every slot of a triangle carries the same
+// work; a chunk is kBandsPerChunk slots.
 constexpr int kWG = 256;             // threads per workgroup (4 wave64)
 constexpr int kVec = 8;              // bf16 elements per 128-bit load
 constexpr int kChunkVecs = 4096;     // dense: vectors per chunk (128 KiB of x + xdot)
@@ -79,7 +79,8 @@ inline uint64_t unit_chunks_dense(int64_t n, uint32_t head) {
 }
 inline uint32_t causal_chunks_per_mat(int64_t rows) {
     uint64_t bands = ((uint64_t)rows + kBandRows - 1) / kBandRows;
-    return (uint32_t)((bands + kBandsPerChunk - 1) / kBandsPerChunk);
+    uint64_t slots = (bands + 1) / 2;                  // bands are paired top with bottom
+    return (uint32_t)((slots + kBandsPerChunk - 1) / kBandsPerChunk);
 }
 
 // ---- launchers (kernels.hip) ---------------------------------------------------------------

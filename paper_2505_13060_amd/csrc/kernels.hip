@@ -111,6 +111,18 @@ __device__ __forceinline__ u32x4 gather8(gptr16_t p, int64_t e, int jlo, int jhi
     return v;
 }
 
+// Keep the first `tail` (1..8) bf16 elements of a vector, clear the rest.
+__device__ __forceinline__ u32x4 keep_leading(u32x4 v, int tail) {
+    uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const uint32_t m = tail >= 2 * k + 2 ? 0xFFFFFFFFu : (tail == 2 * k + 1 ? 0x0000FFFFu : 0u);
+        w[k] &= m;
+    }
+    u32x4 r = {w[0], w[1], w[2], w[3]};
+    return r;
+}
+
 // ---- prepare: resolve scales, build the chunk map ---------------------------------------------
 
 __global__ __launch_bounds__(kWG) void prepare_kernel(const WorkUnit* __restrict__ units,
@@ -212,6 +224,27 @@ struct SensCtx {
         for (int k = 0; k < U; ++k) gr[k] = load128<true>(bg + k * sv + lv);
 #pragma unroll
         for (int k = 0; k < U; ++k) vec(xr[k], gr[k]);
+    }
+
+    template <int U>
+    __device__ __forceinline__ void full_masked(int64_t e, int stride, int count, int tail) {
+        const gptr128_t px = reinterpret_cast<gptr128_t>(x + e);
+        const gptr128_t pg = reinterpret_cast<gptr128_t>(g + e);
+        const int sv = stride / kVec;
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+        u32x4 xr[U], gr[U];
+#pragma unroll
+        for (int k = 0; k < U; ++k) {
+            xr[k] = k < count ? load128<true>(px + k * sv) : zero;
+            gr[k] = k < count ? load128<true>(pg + k * sv) : zero;
+        }
+        if (tail < kVec) {
+#pragma unroll
+            for (int k = 0; k < U; ++k)
+                if (k == count - 1) { xr[k] = keep_leading(xr[k], tail); gr[k] = keep_leading(gr[k], tail); }
+        }
+#pragma unroll
+        for (int k = 0; k < U; ++k) vec(xr[k], gr[k]);   // cleared vectors add exactly 0
     }
 
     __device__ __forceinline__ void partial(int64_t e, int jlo, int jhi) {
@@ -316,6 +349,22 @@ struct AbsmaxCtx {
         u32x4 xr[U];
 #pragma unroll
         for (int k = 0; k < U; ++k) xr[k] = load128<true>(bx + k * sv + lv);
+#pragma unroll
+        for (int k = 0; k < U; ++k) vec(xr[k]);
+    }
+    template <int U>
+    __device__ __forceinline__ void full_masked(int64_t e, int stride, int count, int tail) {
+        const gptr128_t px = reinterpret_cast<gptr128_t>(x + e);
+        const int sv = stride / kVec;
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+        u32x4 xr[U];
+#pragma unroll
+        for (int k = 0; k < U; ++k) xr[k] = k < count ? load128<true>(px + k * sv) : zero;
+        if (tail < kVec) {
+#pragma unroll
+            for (int k = 0; k < U; ++k)
+                if (k == count - 1) xr[k] = keep_leading(xr[k], tail);
+        }
 #pragma unroll
         for (int k = 0; k < U; ++k) vec(xr[k]);
     }

@@ -8,6 +8,11 @@
 //       U whole 8-element vectors whose first elements are x[eu + le + k*stride], k < U; eu and
 //       stride are the same for every thread of the workgroup, le is the thread's own offset;
 //       each vector is 16-byte aligned in memory
+//   template <int U> void full_masked(int64_t e, int stride, int count, int tail)
+//       `count` (0..U) whole, 16-byte aligned vectors starting at x[e + k*stride], k < count, of
+//       which the last one contributes only its first `tail` (1..8) elements: the rest of that
+//       vector lies inside the unit's memory but does not belong to the operand and must not
+//       influence the result; e differs from lane to lane
 //   void partial(int64_t e, int jlo, int jhi)
 //       elements x[e + j], jlo <= j < jhi, to be fetched one by one
 // Element indices are relative to the unit's first element.
@@ -62,30 +67,85 @@ AMPSENS_HD int32_t causal_row_len(int32_t i, int32_t rows, int32_t cols) {
     return (int32_t)len;
 }
 
+// Causal chunks.  A band is 8 consecutive rows of one matrix.  Band j of a lower-triangular
+// matrix holds about (j + 1) vectors per row, so bands are paired, j with nbands - 1 - j, into
+// slots of equal work; a chunk is kBandsPerChunk consecutive slots (one per wave on the aligned
+// path).  Slot s < nbands / 2 has two bands, the middle band of an odd count stands alone.
+AMPSENS_HD int32_t causal_bands(int32_t rows) { return (rows + kBandRows - 1) / kBandRows; }
+
+// The bands of slot `slot`: returns how many (0, 1 or 2) and writes them to band[].
+AMPSENS_HD int causal_slot_bands(int32_t nbands, int32_t slot, int32_t band[2]) {
+    const int32_t mirror = nbands - 1 - slot;
+    if (slot > mirror) return 0;
+    band[0] = slot;
+    if (slot == mirror) return 1;
+    band[1] = mirror;
+    return 2;
+}
+
+// Generic causal walk (any alignment): all threads stride over the vectors of each band.
 template <class Ctx>
 AMPSENS_HD void walk_causal_chunk(int32_t rows, int32_t cols, bool scalar, uint32_t chunks_per_mat,
                                   uint32_t chunk_local, int tid, Ctx& ctx) {
     const uint32_t mat = chunk_local / chunks_per_mat;
-    const int32_t band0 = (int32_t)(chunk_local % chunks_per_mat) * kBandsPerChunk;
+    const int32_t slot0 = (int32_t)(chunk_local % chunks_per_mat) * kBandsPerChunk;
     const int64_t mat_base = (int64_t)mat * rows * cols;
-    const int32_t nbands = (rows + kBandRows - 1) / kBandRows;
-    for (int b = 0; b < kBandsPerChunk; ++b) {
-        const int32_t band = band0 + b;
-        if (band >= nbands) break;
-        const int32_t i0 = band * kBandRows;
+    const int32_t nbands = causal_bands(rows);
+    for (int s = 0; s < kBandsPerChunk; ++s) {
+        int32_t bands[2];
+        const int nb = causal_slot_bands(nbands, slot0 + s, bands);
+        for (int b = 0; b < nb; ++b) {
+            const int32_t i0 = bands[b] * kBandRows;
+            const int32_t ilast = (i0 + kBandRows - 1 < rows) ? i0 + kBandRows - 1 : rows - 1;
+            const int32_t lmax = causal_row_len(ilast, rows, cols);
+            const int32_t items = ((lmax + kVec - 1) / kVec) * kBandRows;
+            for (int32_t k = tid; k < items; k += kWG) {
+                const int32_t i = i0 + (k & (kBandRows - 1));
+                const int32_t e0 = (k / kBandRows) * kVec;
+                if (i >= rows) continue;
+                const int32_t li = causal_row_len(i, rows, cols);
+                if (e0 >= li) continue;
+                const int jhi = (li - e0 < kVec) ? (li - e0) : kVec;
+                const int64_t e = mat_base + (int64_t)i * cols + e0;
+                if (!scalar && jhi == kVec) ctx.template full<1>(e, 0, 0);
+                else ctx.partial(e, 0, jhi);
+            }
+        }
+    }
+}
+
+// Causal chunk whose rows start on 16-byte boundaries (aligned base, cols a multiple of 8):
+// wave w of the workgroup owns slot w of the chunk, i.e. one band from the top of the triangle
+// and its mirror from the bottom; its 64 lanes cover 8 rows x 8 vectors (128 contiguous bytes
+// of each row) per step and run along the rows; the vector that holds a row's end is loaded
+// whole and masked.
+template <class Ctx>
+AMPSENS_HD void walk_causal_chunk_aligned(int32_t rows, int32_t cols, uint32_t chunks_per_mat,
+                                          uint32_t chunk_local, int tid, Ctx& ctx) {
+    static_assert(kBandsPerChunk == kWaves, "one wave per slot");
+    const uint32_t mat = chunk_local / chunks_per_mat;
+    const int32_t slot = (int32_t)(chunk_local % chunks_per_mat) * kBandsPerChunk + (tid >> 6);
+    const int32_t nbands = causal_bands(rows);
+    int32_t bands[2];
+    const int nb = causal_slot_bands(nbands, slot, bands);
+    const int lane = tid & 63;
+    constexpr int kStep = 64 / kBandRows;                       // vectors of a row per wave step
+    for (int b = 0; b < nb; ++b) {
+        const int32_t i0 = bands[b] * kBandRows;
+        const int32_t i = i0 + (lane & (kBandRows - 1));
         const int32_t ilast = (i0 + kBandRows - 1 < rows) ? i0 + kBandRows - 1 : rows - 1;
-        const int32_t lmax = causal_row_len(ilast, rows, cols);
-        const int32_t items = ((lmax + kVec - 1) / kVec) * kBandRows;
-        for (int32_t k = tid; k < items; k += kWG) {
-            const int32_t i = i0 + (k & (kBandRows - 1));
-            const int32_t e0 = (k / kBandRows) * kVec;
-            if (i >= rows) continue;
-            const int32_t li = causal_row_len(i, rows, cols);
-            if (e0 >= li) continue;
-            const int jhi = (li - e0 < kVec) ? (li - e0) : kVec;
-            const int64_t e = mat_base + (int64_t)i * cols + e0;
-            if (!scalar && jhi == kVec) ctx.template full<1>(e, 0, 0);
-            else ctx.partial(e, 0, jhi);
+        const int32_t nv_band = (causal_row_len(ilast, rows, cols) + kVec - 1) / kVec;   // same for the wave
+        const int32_t li = i < rows ? causal_row_len(i, rows, cols) : 0;
+        const int32_t nv_row = (li + kVec - 1) / kVec;
+        const int tail = li - (nv_row - 1) * kVec;              // 1..8 when the row has elements
+        const int64_t e_row = ((int64_t)mat * rows + (i < rows ? i : 0)) * cols;
+        for (int32_t v0 = 0; v0 < nv_band; v0 += kStep * kUnroll) {
+            const int32_t v = v0 + (lane / kBandRows);
+            int count = nv_row > v ? (nv_row - v + kStep - 1) / kStep : 0;
+            if (count > kUnroll) count = kUnroll;
+            const bool ends = count > 0 && v + (count - 1) * kStep == nv_row - 1;
+            ctx.template full_masked<kUnroll>(e_row + (int64_t)v * kVec, kStep * kVec, count,
+                                              ends ? tail : kVec);
         }
     }
 }
@@ -93,7 +153,9 @@ AMPSENS_HD void walk_causal_chunk(int32_t rows, int32_t cols, bool scalar, uint3
 template <class Unit, class Ctx>
 AMPSENS_HD void walk_chunk(const Unit& u, uint32_t chunk_local, int tid, Ctx& ctx) {
     const bool scalar = (u.flags & kUnitScalar) != 0;
-    if (u.flags & kUnitCausal)
+    if ((u.flags & kUnitCausal) && !scalar)
+        walk_causal_chunk_aligned(u.rows, u.cols, u.chunks_per_mat, chunk_local, tid, ctx);
+    else if (u.flags & kUnitCausal)
         walk_causal_chunk(u.rows, u.cols, scalar, u.chunks_per_mat, chunk_local, tid, ctx);
     else
         walk_dense_chunk(u.n, u.head, scalar, chunk_local, tid, ctx);

@@ -93,6 +93,8 @@ REPLAY_CASES = [
     (("causal", 3, 64, 64), 0, 0, 1), (("causal", 2, 40, 40), 0, 0, 2), (("causal", 1, 37, 48), 0, 0, 1),
     (("causal", 2, 48, 24), 0, 0, 1), (("causal", 1, 33, 33), 0, 0, 1), (("causal", 2, 16, 72), 4, 4, 1),
     (("causal", 1, 100, 8), 0, 0, 1), (("causal", 1, 1, 1), 0, 0, 1), (("causal", 4, 8, 8), 0, 2, 1),
+    (("causal", 1, 2048, 2048), 0, 0, 1), (("causal", 2, 520, 512), 0, 0, 1), (("causal", 1, 200, 1024), 0, 0, 3),
+    (("causal", 3, 8, 16), 0, 0, 1), (("causal", 1, 31, 64), 0, 0, 1), (("causal", 2, 72, 8), 0, 0, 1),
 ]
 
 

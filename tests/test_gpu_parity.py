@@ -229,10 +229,16 @@ def test_edge_cases_empty_tiny_misaligned_and_odd_causal():
                            torch.from_numpy(_mk(rng, 3 * 64, 1.0).view(np.int16)).view(torch.bfloat16).view(3, 1, 64),
                            3, 64, 1, np.array([0, 1, 2, 3], dtype=np.int64)))
     # (c) causal operands whose rows are not multiples of 8 / not square, dense operand of odd size
-    for (H, S, S2, n1) in [(2, 37, 48, 333), (1, 48, 24, 8), (3, 33, 33, 16385), (2, 16, 16, 1)]:
+    for (H, S, S2, n1) in [(2, 37, 48, 333), (1, 48, 24, 8), (3, 33, 33, 32769), (2, 16, 16, 1), (1, 136, 136, 7), (2, 40, 64, 9)]:
         R = 2
         p = _mk(rng, R * H * S * S2, 0.3)
         dp = _mk(rng, R * H * S * S2, 1e-3)
+        # entries outside the causal region hold NaN: they must have no effect
+        i = np.arange(S)[:, None]
+        j = np.arange(S2)[None, :]
+        outside = np.broadcast_to(j > i + (S2 - S), (R * H, S, S2)).reshape(-1)
+        p[outside] = 0x7FC0
+        dp[outside] = 0xFFC0
         v, dv = _mk(rng, R * n1, 1.0), _mk(rng, R * n1, 1e-3)
 
         def t(b):
