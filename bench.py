@@ -155,6 +155,8 @@ def main():
     ap.add_argument("--workload", default="config2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference reading for HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (--gpus 1); multi-GPU runs are not part of it",
@@ -181,6 +183,12 @@ def main():
     for op in workload.bgemms:
         abs_elems += op.pairs()
 
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, device=dev, dtype=torch.float32)       # 1 GiB
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         p.run()
     torch.cuda.synchronize()

@@ -244,7 +244,8 @@ struct SensCtx {
                 if (k == count - 1) { xr[k] = keep_leading(xr[k], tail); gr[k] = keep_leading(gr[k], tail); }
         }
 #pragma unroll
-        for (int k = 0; k < U; ++k) vec(xr[k], gr[k]);   // cleared vectors add exactly 0
+        for (int k = 0; k < U; ++k)
+            if (k < count) vec(xr[k], gr[k]);
     }
 
     __device__ __forceinline__ void partial(int64_t e, int jlo, int jhi) {
@@ -298,32 +299,40 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
     }
 }
 
-// One wave per unit: fixed-order fp64 sum of the unit's per-wave chunk partials.
+// One workgroup per unit: fixed-order fp64 sum of the unit's per-wave chunk partials (thread t
+// adds partials t, t + 256, ...; lanes, then waves, are combined in a fixed order).
 template <int NF>
 __global__ __launch_bounds__(kWG) void sens_finalize_kernel(const ResolvedUnit* __restrict__ runits,
                                                             const uint32_t* __restrict__ chunk_begin,
                                                             uint32_t n_units,
                                                             const float* __restrict__ partials,
                                                             float* __restrict__ out) {
-    const uint32_t ui = blockIdx.x * kWaves + (threadIdx.x >> 6);
-    const int lane = threadIdx.x & 63;
-    if (ui >= n_units) return;
+    __shared__ double red[kWaves][NF + 1];
+    const uint32_t ui = blockIdx.x;
     const size_t p0 = (size_t)chunk_begin[ui] * kWaves, p1 = (size_t)chunk_begin[ui + 1] * kWaves;
     double acc[NF + 1];
 #pragma unroll
     for (int k = 0; k <= NF; ++k) acc[k] = 0.0;
-    for (size_t p = p0 + lane; p < p1; p += 64) {
+    for (size_t p = p0 + threadIdx.x; p < p1; p += kWG) {
 #pragma unroll
         for (int k = 0; k <= NF; ++k) acc[k] += (double)partials[p * (NF + 1) + k];
     }
 #pragma unroll
     for (int k = 0; k <= NF; ++k) acc[k] = wave_sum(acc[k]);
-    if (lane == 0) {
+    if ((threadIdx.x & 63) == 0) {
+#pragma unroll
+        for (int k = 0; k <= NF; ++k) red[threadIdx.x >> 6][k] = acc[k];
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double tot[NF + 1];
+#pragma unroll
+        for (int k = 0; k <= NF; ++k) tot[k] = (red[0][k] + red[1][k]) + (red[2][k] + red[3][k]);
         const uint32_t o = runits[ui].out;
 #pragma unroll
         for (int f = 0; f < NF; ++f) {
-            out[o + 4 * f] = (float)acc[f];
-            out[o + 4 * f + 1] = (float)acc[NF];
+            out[o + 4 * f] = (float)tot[f];
+            out[o + 4 * f + 1] = (float)tot[NF];
         }
     }
 }
@@ -400,19 +409,21 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
 
 __device__ __forceinline__ float fmax_of(int fmt) { return fmt == 0 ? 448.0f : 57344.0f; }
 
-// One workgroup per tensor (unit t of an absmax call is tensor t).
-__global__ __launch_bounds__(kWG) void absmax_finalize_kernel(const uint32_t* __restrict__ chunk_begin,
+// One workgroup of 1024 threads per tensor (unit t of an absmax call is tensor t).
+constexpr int kFinThreads = 1024;
+__global__ __launch_bounds__(kFinThreads) void absmax_finalize_kernel(const uint32_t* __restrict__ chunk_begin,
                                                               const uint32_t* __restrict__ partial_max,
                                                               int n_fmts, int fmt0, int fmt1,
                                                               float* __restrict__ amax_out,
                                                               float* __restrict__ scale_out,
                                                               float* __restrict__ inv_out,
                                                               uint32_t* __restrict__ flags_out) {
-    __shared__ uint32_t red[kWaves];
+    __shared__ uint32_t red[kFinThreads / 64];
     const int t = blockIdx.x;
     const size_t p0 = (size_t)chunk_begin[t] * kWaves, p1 = (size_t)chunk_begin[t + 1] * kWaves;
     uint32_t m = 0;
-    for (size_t p = p0 + threadIdx.x; p < p1; p += kWG) {
+#pragma unroll 4
+    for (size_t p = p0 + threadIdx.x; p < p1; p += kFinThreads) {
         const uint32_t v = partial_max[p];
         m = m > v ? m : v;
     }
@@ -421,7 +432,7 @@ __global__ __launch_bounds__(kWG) void absmax_finalize_kernel(const uint32_t* __
     __syncthreads();
     if (threadIdx.x != 0) return;
     uint32_t bits = 0;
-    for (int w = 0; w < kWaves; ++w) bits = bits > red[w] ? bits : red[w];
+    for (int w = 0; w < kFinThreads / 64; ++w) bits = bits > red[w] ? bits : red[w];
     const float amax = __uint_as_float(bits << 16);
     amax_out[t] = amax;
     flags_out[t] = bits >= 0x7F80u ? 1u : 0u;
@@ -525,7 +536,7 @@ hipError_t launch_absmax_finalize(const uint32_t* d_chunk_begin, const uint32_t*
                                   int n_tensors, int n_fmts, int fmt0, int fmt1, float* d_amax,
                                   float* d_scale, float* d_inv, uint32_t* d_flags,
                                   hipStream_t stream) {
-    hipLaunchKernelGGL(absmax_finalize_kernel, dim3(n_tensors), dim3(kWG), 0, stream, d_chunk_begin,
+    hipLaunchKernelGGL(absmax_finalize_kernel, dim3(n_tensors), dim3(kFinThreads), 0, stream, d_chunk_begin,
                        d_partial_max, n_fmts, fmt0, fmt1, d_amax, d_scale, d_inv, d_flags);
     return hipGetLastError();
 }
@@ -554,7 +565,7 @@ hipError_t launch_sens(const ResolvedUnit* d_runits, const ChunkRef* d_map, uint
 hipError_t launch_sens_finalize(const ResolvedUnit* d_runits, const uint32_t* d_chunk_begin,
                                 uint32_t n_units, int n_fmts, const float* d_partials,
                                 float* d_out, hipStream_t stream) {
-    const dim3 grid((n_units + kWaves - 1) / kWaves);
+    const dim3 grid(n_units);
     if (n_fmts == 1)
         hipLaunchKernelGGL(sens_finalize_kernel<1>, grid, dim3(kWG), 0, stream, d_runits,
                            d_chunk_begin, n_units, d_partials, d_out);

@@ -286,3 +286,68 @@ def test_workspace_too_small_is_reported_on_gpu_box_too():
     with pytest.raises(amp.AmpError) as ei:
         amp.amp_sens_linear(p.lin_desc, p.fmts, p.d_lin_out, small)
     assert ei.value.status == amp.ERR_WORKSPACE_TOO_SMALL
+
+
+# ---------------------------------------------------------------------------------------------
+# full benchmark size (config 1: one 7B-shaped block, S = 2048, R = 8, both formats), in the launch
+# configuration bench.py times; the oracle recomputes sampled (op, operand, sample) units in full
+# ---------------------------------------------------------------------------------------------
+
+def test_config1_full_size_sampled_units():
+    say("config1 at full size: generating 13.9 GB on the GPU")
+    w = wl.config1(DEV)
+    torch.cuda.synchronize()
+    say("config1 at full size: %.1f M pairs; running the pass" % (w.pairs() / 1e6))
+    p = SensPass(w, DEV)
+    p.run()
+    res = p.results()
+    fmts = w.fmts
+    nl = len(w.linears)
+    lin = {op.name: (k, op) for k, op in enumerate(w.linears)}
+    bg = {op.name: (k, op) for k, op in enumerate(w.bgemms)}
+
+    def check_unit(tag, got4, col, x_bits, dx_bits, n, scales, causal=None):
+        for fi, f in enumerate(fmts):
+            E, A = oracle.sens_operand(x_bits, dx_bits, 1, n, scales[fi][0], scales[fi][1], f, causal=causal)
+            parity.assert_sum_close(got4[fi, col + 1], A[0], 0.0, tag + " A fmt=%d" % f)
+            parity.assert_sum_close(got4[fi, col], E[0], parity.E_FLOOR * A[0], tag + " E fmt=%d" % f)
+
+    # activations of q_proj, sample 3; down_proj, sample 0
+    for name, r in (("q_proj", 3), ("down_proj", 0)):
+        k, op = lin[name]
+        say("  %s X sample %d" % (name, r))
+        sc = parity.check_scales(res, 2 * k, wl.to_bits(op.x).reshape(-1), fmts, None, name + ".x")
+        rows = slice(int(op.row_offsets[r]), int(op.row_offsets[r + 1]))
+        xb, gb = wl.to_bits(op.x[rows]).reshape(-1), wl.to_bits(op.dx[rows]).reshape(-1)
+        check_unit("%s.X r=%d" % (name, r), res["linear"][k][r], 0, xb, gb, xb.size, sc)
+    # weights of gate_proj with the gradient of sample 5; o_proj with sample 7
+    for name, r in (("gate_proj", 5), ("o_proj", 7)):
+        k, op = lin[name]
+        say("  %s W sample %d" % (name, r))
+        wb = wl.to_bits(op.w).reshape(-1)
+        sc = parity.check_scales(res, 2 * k + 1, wb, fmts, None, name + ".w")
+        check_unit("%s.W r=%d" % (name, r), res["linear"][k][r], 2, wb, wl.to_bits(op.dw[r]).reshape(-1), wb.size, sc)
+    # K of QK^T, sample 7 (dense); P of PV, sample 1 (causal); V of PV, sample 6
+    k, op = bg["qk_matmul"]
+    say("  qk_matmul K sample 7")
+    sc = parity.check_scales(res, 2 * nl + 2 * k + 1, wl.to_bits(op.x1).reshape(-1), fmts, None, "K")
+    kb = wl.to_bits(op.x1[7]).reshape(-1)
+    check_unit("K r=7", res["bgemm"][k][7], 2, kb, wl.to_bits(op.dx1[7]).reshape(-1), kb.size, sc)
+    k, op = bg["av_matmul"]
+    _, H, S, S2 = op.lay0
+    say("  av_matmul P (causal %dx%dx%d) sample 1" % (H, S, S2))
+    sc = parity.check_scales(res, 2 * nl + 2 * k, wl.to_bits(op.x0).reshape(-1), fmts, (op.R * H, S, S2), "P")
+    check_unit("P r=1", res["bgemm"][k][1], 0, wl.to_bits(op.x0[1]).reshape(-1), wl.to_bits(op.dx0[1]).reshape(-1),
+               0, sc, causal=(H, S, S2))
+    say("  av_matmul V sample 6")
+    sc = parity.check_scales(res, 2 * nl + 2 * k + 1, wl.to_bits(op.x1).reshape(-1), fmts, None, "V")
+    vb = wl.to_bits(op.x1[6]).reshape(-1)
+    check_unit("V r=6", res["bgemm"][k][6], 2, vb, wl.to_bits(op.dx1[6]).reshape(-1), vb.size, sc)
+    # properties that hold at any size: A does not depend on the format; every sum is finite, positive
+    for arr in res["linear"] + res["bgemm"]:
+        assert np.all(np.isfinite(arr)) and np.all(arr > 0)
+        assert np.array_equal(parity.bits32(arr[:, 0, 1]), parity.bits32(arr[:, 1, 1]))
+        assert np.array_equal(parity.bits32(arr[:, 0, 3]), parity.bits32(arr[:, 1, 3]))
+    # E4M3 (three mantissa bits) must beat E5M2 (two) on these distributions
+    for arr in res["linear"] + res["bgemm"]:
+        assert np.all(arr[:, 0, 0] < arr[:, 1, 0]) and np.all(arr[:, 0, 2] < arr[:, 1, 2])
