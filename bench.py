@@ -147,6 +147,21 @@ def cpu_baseline(workload, target_seconds=15.0):
                       "device-to-host copy not timed" % (nf, "; ".join(picked), pairs / 1e6)}
 
 
+def measured_traffic(workload_name):
+    """HBM bytes per sens_kernel launch from the committed rocprofv3 counter summary (FETCH_SIZE and
+    WRITE_SIZE runs of this same command, scaled by a plain copy of known size); None if no
+    summary covers the workload."""
+    path = os.path.join(ROOT, "profiles", "sens_kernel_%s_block.md" % workload_name)
+    tag = "traffic_bytes_per_launch(sens_kernel, %s) =" % workload_name
+    try:
+        for line in open(path):
+            if line.startswith(tag):
+                return float(line.split("=")[1])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -238,7 +253,7 @@ def main():
         "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBS,
         "roofline": {"bound": "hbm", "kernel": "sens_kernel (fused E/A pass, %d formats)" % len(workload.fmts),
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(args.workload),
                      "bytes_per_launch": kern_bytes, "ms_per_launch": kern_ms, "launches": int(len(ms))},
         "absmax": {"ms_per_step": abs_ms, "GB/s": abs_elems * 2.0 / (abs_ms * 1e-3) / 1e9,
                    "bytes_per_step": abs_elems * 2.0},
