@@ -29,6 +29,7 @@ def build(force=True, verbose=False, extra=()):
     if not force and not stale():
         return LIB
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    extra = list(extra) + os.environ.get("AMPSENS_EXTRA_FLAGS", "").split()
     cmd = [hipcc] + FLAGS + list(extra) + ["-x", "hip"] + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", LIB]
     if verbose:
         print(" ".join(cmd), file=sys.stderr)

@@ -4,9 +4,11 @@
 #include "internal.h"
 #include "walk.h"
 
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <mutex>
+#include <unordered_map>
 #include <vector>
 
 using namespace ampsens;
@@ -63,11 +65,13 @@ int64_t layout_span(const amp_layout_t& L) {
 struct WorkTable {
     std::vector<WorkUnit> units;
     std::vector<uint32_t> chunk_begin;
+    std::vector<uint32_t> group;                  // units with the same non-zero id share their x
     uint64_t n_chunks = 0;
 
     // x / dx may be null only for blocks without elements.
     amp_status_t add(const uint16_t* x, const uint16_t* dx, const amp_layout_t& L, int64_t batch_mul,
-                     const float* scale, const float* inv, uint32_t out, uint32_t extra_flags = 0) {
+                     const float* scale, const float* inv, uint32_t out, uint32_t extra_flags = 0,
+                     uint32_t group_id = 0) {
         WorkUnit u;
         std::memset(&u, 0, sizeof(u));
         u.x = x; u.dx = dx; u.scale = scale; u.inv = inv; u.out = out;
@@ -95,14 +99,47 @@ struct WorkTable {
             chunks = unit_chunks_dense(n, u.head);
         }
         chunk_begin.push_back((uint32_t)n_chunks);
+        group.push_back(group_id);
         n_chunks += chunks;
         if (n_chunks > kMaxChunks) return AMP_ERR_TOO_LARGE;
         units.push_back(u);
         return AMP_OK;
     }
 
-    size_t table_bytes() const {
-        return units.size() * sizeof(WorkUnit) + (units.size() + 1) * sizeof(uint32_t);
+    // units | chunk_begin[n + 1] (+ pad to 8 bytes) | schedule[n]
+    size_t schedule_offset() const {
+        return round8(units.size() * sizeof(WorkUnit) + (units.size() + 1) * sizeof(uint32_t));
+    }
+    size_t table_bytes() const { return schedule_offset() + units.size() * sizeof(UnitSchedule); }
+    static size_t round8(size_t v) { return (v + 7) / 8 * 8; }
+
+    uint64_t chunks_of(size_t u) const {
+        return (u + 1 < units.size() ? chunk_begin[u + 1] : n_chunks) - chunk_begin[u];
+    }
+
+    // Schedule positions.  Units stay in call order, except that the members of a group (same
+    // group id, equal chunk counts, at most 65535 of them) are interleaved block by block.
+    std::vector<UnitSchedule> schedule(uint32_t block) const {
+        std::vector<UnitSchedule> sch(units.size());
+        std::unordered_map<uint32_t, std::vector<size_t>> by_group;
+        for (size_t u = 0; u < units.size(); ++u)
+            if (group[u] != 0) by_group[group[u]].push_back(u);
+        std::vector<char> done(units.size(), 0);
+        uint64_t run = 0;
+        for (size_t u = 0; u < units.size(); ++u) {
+            if (done[u]) continue;
+            std::vector<size_t> members(1, u);
+            if (group[u] != 0)
+                for (size_t v : by_group[group[u]])
+                    if (v > u && !done[v] && chunks_of(v) == chunks_of(u) && members.size() < 65535)
+                        members.push_back(v);
+            for (size_t m = 0; m < members.size(); ++m) {
+                sch[members[m]] = UnitSchedule{(uint32_t)run, (uint16_t)members.size(), (uint16_t)m, block, 0u};
+                done[members[m]] = 1;
+            }
+            run += chunks_of(u) * members.size();
+        }
+        return sch;
     }
 };
 
@@ -188,12 +225,18 @@ WsLayout ws_layout(const WorkTable& t, size_t partial_bytes_per_chunk) {
 }
 
 // Copies units + chunk_begin to the head of the workspace.
-amp_status_t upload(const WorkTable& t, void* workspace, hipStream_t stream) {
+int g_schedule_block = 0;                              // test / tuning hook: 0 = default
+constexpr uint32_t kDefaultScheduleBlock = 8;
+
+amp_status_t upload(const WorkTable& t, uint32_t block, void* workspace, hipStream_t stream) {
     std::vector<uint8_t> blob(t.table_bytes(), 0);
     std::memcpy(blob.data(), t.units.data(), t.units.size() * sizeof(WorkUnit));
     std::vector<uint32_t> cb = t.chunk_begin;
     cb.push_back((uint32_t)t.n_chunks);
     std::memcpy(blob.data() + t.units.size() * sizeof(WorkUnit), cb.data(), cb.size() * 4);
+    if (g_schedule_block > 0) block = (uint32_t)g_schedule_block;
+    const std::vector<UnitSchedule> sch = t.schedule(block < 1 ? 1 : block);
+    std::memcpy(blob.data() + t.schedule_offset(), sch.data(), sch.size() * sizeof(UnitSchedule));
     AMP_HIP(hipMemcpyAsync(workspace, blob.data(), blob.size(), hipMemcpyHostToDevice, stream));
     return AMP_OK;
 }
@@ -219,7 +262,9 @@ amp_status_t run_sens(const WorkTable& t, const amp_fp8_format_t* fmts, int n_fm
     const WsLayout L = sens_layout(t, n_fmts);
     if (workspace_bytes < L.total) return AMP_ERR_WORKSPACE_TOO_SMALL;
     hipStream_t stream = (hipStream_t)stream_;
-    amp_status_t st = upload(t, workspace, stream);
+    const int f0 = (int)fmts[0], f1 = (int)fmts[n_fmts - 1];
+    const int grid = t.n_chunks > 0 ? sens_grid(t.n_chunks, n_fmts, f0, f1) : 1;
+    amp_status_t st = upload(t, kDefaultScheduleBlock, workspace, stream);
     if (st != AMP_OK) return st;
     uint8_t* ws = (uint8_t*)workspace;
     const uint32_t n_units = (uint32_t)t.units.size(), n_chunks = (uint32_t)t.n_chunks;
@@ -228,10 +273,9 @@ amp_status_t run_sens(const WorkTable& t, const amp_fp8_format_t* fmts, int n_fm
     ResolvedUnit* d_runits = (ResolvedUnit*)(ws + L.runits);
     ChunkRef* d_map = (ChunkRef*)(ws + L.map);
     float* d_partials = (float*)(ws + L.partials);
-    const int f0 = (int)fmts[0], f1 = (int)fmts[n_fmts - 1];
-    AMP_HIP(launch_prepare(d_units, d_cb, n_units, n_chunks, n_fmts, d_runits, d_map, stream));
+    const UnitSchedule* d_sch = (const UnitSchedule*)(ws + t.schedule_offset());
+    AMP_HIP(launch_prepare(d_units, d_cb, d_sch, n_units, n_chunks, n_fmts, d_runits, d_map, stream));
     if (n_chunks > 0) {
-        const int grid = sens_grid(n_chunks, n_fmts, f0, f1);
         const bool timed = g_profile.used < (int)g_profile.start.size();
         if (timed) AMP_HIP(hipEventRecord(g_profile.start[g_profile.used], stream));
         AMP_HIP(launch_sens(d_runits, d_map, n_chunks, n_fmts, f0, f1, d_partials, grid, stream));
@@ -275,7 +319,7 @@ amp_status_t build_linear(const amp_linear_desc_t* ops, int n_ops, int n_fmts, W
                                      op.x_scale, op.x_inv, (uint32_t)o);
             if (st != AMP_OK) return st;
             st = t->add(op.w, wn ? op.dw + (int64_t)r * wn : op.dw, Lw, 1, op.w_scale, op.w_inv, (uint32_t)o + 2,
-                        op.R > 1 ? kUnitKeepX : 0u);
+                        op.R > 1 ? kUnitKeepX : 0u, op.R > 1 ? (uint32_t)k + 1u : 0u);
             if (st != AMP_OK) return st;
         }
         base += (uint64_t)op.R;
@@ -393,7 +437,7 @@ amp_status_t amp_absmax_scale(const amp_tensor_t* tensors, int n_tensors, const 
     const WsLayout L = absmax_layout(t);
     if (workspace_bytes < L.total) return AMP_ERR_WORKSPACE_TOO_SMALL;
     hipStream_t stream = (hipStream_t)stream_;
-    st = upload(t, workspace, stream);
+    st = upload(t, kDefaultScheduleBlock, workspace, stream);
     if (st != AMP_OK) return st;
     uint8_t* ws = (uint8_t*)workspace;
     const uint32_t n_units = (uint32_t)t.units.size(), n_chunks = (uint32_t)t.n_chunks;
@@ -402,7 +446,8 @@ amp_status_t amp_absmax_scale(const amp_tensor_t* tensors, int n_tensors, const 
     ResolvedUnit* d_runits = (ResolvedUnit*)(ws + L.runits);
     ChunkRef* d_map = (ChunkRef*)(ws + L.map);
     uint32_t* d_partial_max = (uint32_t*)(ws + L.partials);
-    AMP_HIP(launch_prepare(d_units, d_cb, n_units, n_chunks, 0, d_runits, d_map, stream));
+    const UnitSchedule* d_sch = (const UnitSchedule*)(ws + t.schedule_offset());
+    AMP_HIP(launch_prepare(d_units, d_cb, d_sch, n_units, n_chunks, 0, d_runits, d_map, stream));
     if (n_chunks > 0)
         AMP_HIP(launch_absmax(d_runits, d_map, n_chunks, d_partial_max, absmax_grid(n_chunks), stream));
     AMP_HIP(launch_absmax_finalize(d_cb, d_partial_max, n_tensors, n_fmts, (int)fmts[0],
@@ -511,6 +556,34 @@ const char* amp_status_string(amp_status_t status) {
 int amp_last_device_error(void) { return g_last_device_error; }
 
 int amp_version(void) { return 100; }
+
+// Test hook: checks on the host that the schedule of a linear call is a permutation of its
+// chunks; returns the number of positions that are out of range, hit twice or never hit, and
+// reports the number of chunks and how many units are interleaved with others.
+int64_t ampsens_debug_check_linear_schedule(const amp_linear_desc_t* ops, int n_ops, int n_fmts,
+                                            uint64_t* n_chunks_out, uint64_t* interleaved_units) {
+    WorkTable t;
+    if (build_linear(ops, n_ops, n_fmts, &t) != AMP_OK) return -1;
+    const std::vector<UnitSchedule> sch = t.schedule(g_schedule_block > 0 ? (uint32_t)g_schedule_block : kDefaultScheduleBlock);
+    std::vector<uint8_t> hit(t.n_chunks, 0);
+    int64_t bad = 0;
+    uint64_t inter = 0;
+    for (size_t u = 0; u < t.units.size(); ++u) {
+        const uint32_t chunks = (uint32_t)t.chunks_of(u);
+        if (sch[u].interleave > 1) ++inter;
+        for (uint32_t l = 0; l < chunks; ++l) {
+            const uint32_t pos = schedule_position(sch[u], l, chunks);
+            if (pos >= t.n_chunks || hit[pos]) ++bad; else hit[pos] = 1;
+        }
+    }
+    for (uint8_t h : hit) if (!h) ++bad;
+    if (n_chunks_out) *n_chunks_out = t.n_chunks;
+    if (interleaved_units) *interleaved_units = inter;
+    return bad;
+}
+
+// Test / tuning hook: chunks of one member that sit next to each other in the schedule (0 = default).
+void ampsens_debug_set_schedule_block(int block) { g_schedule_block = block; }
 
 // Test hook: cap the persistent grid (0 = default) to show that results do not depend on it.
 void ampsens_debug_set_grid_cap(int cap) { g_grid_cap = cap; }

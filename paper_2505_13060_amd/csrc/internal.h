@@ -66,9 +66,32 @@ struct alignas(16) ResolvedUnit {    // 64 bytes
 };
 static_assert(sizeof(ResolvedUnit) == 64, "ResolvedUnit layout");
 
+// Entry p of the map is the chunk processed at schedule position p.  The schedule is a
+// permutation chosen on the host (see UnitSchedule); `slot` is the chunk's canonical number
+// (chunk_begin[unit] + local): partial results are stored by slot, so the schedule never changes a
+// result.
 struct ChunkRef {
     uint32_t unit;
     uint32_t local;                  // chunk index inside the unit
+    uint32_t slot;
+    uint32_t reserved;
+};
+
+// Where the chunks of a unit sit in the schedule.  Units that read the same x with different
+// gradients (a weight and the R per-sample weight gradients) form a group of `interleave`
+// members with equal chunk counts; their chunks are laid out block by block (8 chunks), member
+// after member inside a block of `block` chunks:
+//     position = begin + (local / block) * block * interleave + member * w + local % block,
+//     w = min(block, chunks - block * (local / block)),
+// so that the `interleave` readers of one x chunk run at the same time and, the grid being a
+// multiple of 8, on the same XCD: x is fetched from HBM once and found in that XCD's L2 by the
+// others.  A unit on its own has interleave 1, member 0: position = begin + local.
+struct UnitSchedule {
+    uint32_t begin;
+    uint16_t interleave;
+    uint16_t member;
+    uint32_t block;                  // chunks of one member that sit next to each other
+    uint32_t reserved;
 };
 
 // Number of chunks of a unit (host side; the kernels use the same constants).
@@ -89,9 +112,9 @@ inline uint32_t causal_chunks_per_mat(int64_t rows) {
 int sens_resident_blocks(int n_fmts, int fmt0, int fmt1, int cus);
 int absmax_resident_blocks(int cus);
 
-hipError_t launch_prepare(const WorkUnit* d_units, const uint32_t* d_chunk_begin, uint32_t n_units,
-                          uint32_t n_chunks, int n_fmts, ResolvedUnit* d_runits, ChunkRef* d_map,
-                          hipStream_t stream);
+hipError_t launch_prepare(const WorkUnit* d_units, const uint32_t* d_chunk_begin,
+                          const UnitSchedule* d_schedule, uint32_t n_units, uint32_t n_chunks,
+                          int n_fmts, ResolvedUnit* d_runits, ChunkRef* d_map, hipStream_t stream);
 hipError_t launch_absmax(const ResolvedUnit* d_runits, const ChunkRef* d_map, uint32_t n_chunks,
                          uint32_t* d_partial_max, int grid, hipStream_t stream);
 hipError_t launch_absmax_finalize(const uint32_t* d_chunk_begin, const uint32_t* d_partial_max,

@@ -127,6 +127,7 @@ __device__ __forceinline__ u32x4 keep_leading(u32x4 v, int tail) {
 
 __global__ __launch_bounds__(kWG) void prepare_kernel(const WorkUnit* __restrict__ units,
                                                       const uint32_t* __restrict__ chunk_begin,
+                                                      const UnitSchedule* __restrict__ schedule,
                                                       uint32_t n_units, uint32_t n_chunks, int n_fmts,
                                                       ResolvedUnit* __restrict__ runits,
                                                       ChunkRef* __restrict__ map) {
@@ -148,7 +149,9 @@ __global__ __launch_bounds__(kWG) void prepare_kernel(const WorkUnit* __restrict
         ChunkRef ref;
         ref.unit = ui;
         ref.local = i - chunk_begin[ui];
-        map[i] = ref;
+        ref.slot = i;
+        ref.reserved = 0;
+        map[schedule_position(schedule[ui], ref.local, chunk_begin[ui + 1] - chunk_begin[ui])] = ref;
     }
 }
 
@@ -267,6 +270,7 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
     while (true) {
         const ResolvedUnit u = runits[ref.unit];
         const uint32_t local = ref.local;
+        const uint32_t slot_id = ref.slot;
         const uint32_t cn = c + gridDim.x;
         const bool more = cn < n_chunks;
         if (more) ref = map[cn];                    // next chunk's entry travels while this one streams
@@ -290,7 +294,7 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
         for (int f = 0; f < NF; ++f) v[f] = wave_sum(ctx.E[f]);
         v[NF] = wave_sum(ctx.A);
         if (lane == 0) {
-            float* slot = partials + ((size_t)c * kWaves + wave) * (NF + 1);
+            float* slot = partials + ((size_t)slot_id * kWaves + wave) * (NF + 1);
 #pragma unroll
             for (int k = 0; k <= NF; ++k) slot[k] = v[k];
         }
@@ -393,6 +397,7 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
     while (true) {
         const ResolvedUnit u = runits[ref.unit];
         const uint32_t local = ref.local;
+        const uint32_t slot_id = ref.slot;
         const uint32_t cn = c + gridDim.x;
         const bool more = cn < n_chunks;
         if (more) ref = map[cn];
@@ -401,7 +406,7 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
         ctx.m = 0;
         walk_chunk(u, local, tid, ctx);
         const uint32_t m = wave_max(ctx.m);
-        if ((tid & 63) == 0) partial_max[(size_t)c * kWaves + (tid >> 6)] = m;
+        if ((tid & 63) == 0) partial_max[(size_t)slot_id * kWaves + (tid >> 6)] = m;
         if (!more) break;
         c = cn;
     }
@@ -516,12 +521,12 @@ int sens_resident_blocks(int n_fmts, int fmt0, int fmt1, int cus) {
 
 int absmax_resident_blocks(int cus) { return resident_blocks((const void*)absmax_kernel, cus); }
 
-hipError_t launch_prepare(const WorkUnit* d_units, const uint32_t* d_chunk_begin, uint32_t n_units,
-                          uint32_t n_chunks, int n_fmts, ResolvedUnit* d_runits, ChunkRef* d_map,
-                          hipStream_t stream) {
+hipError_t launch_prepare(const WorkUnit* d_units, const uint32_t* d_chunk_begin,
+                          const UnitSchedule* d_schedule, uint32_t n_units, uint32_t n_chunks,
+                          int n_fmts, ResolvedUnit* d_runits, ChunkRef* d_map, hipStream_t stream) {
     const uint32_t n = n_units > n_chunks ? n_units : n_chunks;
     hipLaunchKernelGGL(prepare_kernel, dim3((n + kWG - 1) / kWG), dim3(kWG), 0, stream, d_units,
-                       d_chunk_begin, n_units, n_chunks, n_fmts, d_runits, d_map);
+                       d_chunk_begin, d_schedule, n_units, n_chunks, n_fmts, d_runits, d_map);
     return hipGetLastError();
 }
 

@@ -161,6 +161,14 @@ AMPSENS_HD void walk_chunk(const Unit& u, uint32_t chunk_local, int tid, Ctx& ct
         walk_dense_chunk(u.n, u.head, scalar, chunk_local, tid, ctx);
 }
 
+// Schedule position of chunk `local` of a unit with `chunks` chunks (see UnitSchedule).
+AMPSENS_HD uint32_t schedule_position(const UnitSchedule& sch, uint32_t local, uint32_t chunks) {
+    const uint32_t b = local / sch.block;
+    const uint32_t left = chunks - b * sch.block;
+    const uint32_t w = left < sch.block ? left : sch.block;
+    return sch.begin + b * sch.block * sch.interleave + sch.member * w + local % sch.block;
+}
+
 // Largest u with chunk_begin[u] <= c (chunk_begin has n_units + 1 entries, the last being the
 // total; units without chunks are skipped because a later unit shares their begin).
 AMPSENS_HD uint32_t find_unit(const uint32_t* chunk_begin, uint32_t n_units, uint32_t c) {

@@ -124,6 +124,36 @@ def test_kernel_walk_covers_every_element_once(lay, xo, dxo, mul):
     assert nch.value >= 1
 
 
+@pytest.mark.parametrize("shapes", [
+    [(4, 256, 1024, 1024)],                                   # config 0
+    [(16, 2048, 4096, 4096), (16, 2048, 4096, 11008)],        # two linears of the 7B block
+    [(3, 5, 8, 9), (1, 7, 64, 64), (5, 1, 4099, 33)],         # odd sizes: members differ in alignment
+    [(32, 100, 512, 176)] * 6,                                # several small experts
+])
+def test_schedule_is_a_permutation_of_the_chunks(shapes):
+    """Weight units of one op (same W, one gradient per sample) are interleaved in the schedule;
+    whatever the shapes, every chunk must get exactly one position."""
+    L = amp.lib()
+    L.ampsens_debug_check_linear_schedule.restype = C.c_int64
+    L.ampsens_debug_check_linear_schedule.argtypes = [C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_uint64),
+                                                      C.POINTER(C.c_uint64)]
+    descs = []
+    base = 0x100000
+    for (R, tokens, Cd, K) in shapes:
+        d = amp.LinearDesc()
+        d.x = d.dx = d.w = base
+        d.dw = base + 2                                        # 2 bytes off: alignment varies with r
+        d.C, d.K, d.tokens, d.R = Cd, K, tokens, R
+        d.x_scale = d.x_inv = d.w_scale = d.w_inv = base
+        descs.append(d)
+    arr = (amp.LinearDesc * len(descs))(*descs)
+    n, inter = C.c_uint64(), C.c_uint64()
+    assert L.ampsens_debug_check_linear_schedule(arr, len(descs), 2, C.byref(n), C.byref(inter)) == 0
+    assert n.value >= len(descs)
+    if shapes[0][0] > 1 and shapes[0][2] * shapes[0][3] % 8 == 0:
+        assert inter.value > 0
+
+
 def test_epilogue_matches_oracle():
     rng = np.random.default_rng(4)
     R, nf = 5, 2
