@@ -203,6 +203,35 @@ amp_status_t amp_select_subgraphs(int J, const int32_t* n_choices, const double*
                                   const double* mse, double mse_budget, int32_t* choice,
                                   double* total_gain, double* total_mse);
 
+/* ---- next to the path (host): partition, gain formulas, baseline strategies ------------------
+ *
+ * amp_partition_sequential: partition of a model's computation DAG into sequential sub-graphs
+ * (Appendix B, Algorithm 2): single-entry / single-exit regions, each closed by the first vertex
+ * through which every path to the sink passes; that vertex belongs to the group it closes.
+ * Vertices 0..n-1, edges src -> dst (host arrays); exactly one vertex without predecessors (the
+ * start vertex, never part of a group) and one without successors (the sink); the graph must be
+ * acyclic.  quantizable[v] != 0 marks the linear operations (NULL = all); other vertices are dropped
+ * and groups left empty disappear.  group_of[v] receives the group index in execution order, or -1.
+ * Residual connections are edges like any other: leave them out to obtain the per-block groups of
+ * the paper's figure for a Llama layer. */
+amp_status_t amp_partition_sequential(int n_vertices, int n_edges, const int32_t* edge_src,
+                                      const int32_t* edge_dst, const uint8_t* quantizable,
+                                      int32_t* group_of, int32_t* n_groups);
+
+/* Theoretical time gain of Sec. 2.3.2: N*C*K*delta_t for a linear layer, N*C*C*delta_t for a
+ * BGEMM; memory gain of Sec. 2.3.3: C*K*delta_m for a linear layer, 0 for a BGEMM. */
+double amp_time_gain_macs(int is_bgemm, double N, double C, double K, double delta_t);
+double amp_memory_gain(int is_bgemm, double C, double K, double delta_m);
+
+/* Baseline strategies of Sec. 3.1 under the same loss-MSE bound: walk the groups in `order`
+ * (host, a permutation of 0..J-1; NULL = 0,1,2,... which is the paper's Prefix; a random
+ * permutation gives its Random) and switch each group to its largest-gain choice while the total
+ * MSE stays within the budget; the first group that does not fit ends the walk.  Same table layout
+ * as amp_select_subgraphs; choice 0 of a group is its high-precision column. */
+amp_status_t amp_select_ordered(int J, const int32_t* n_choices, const double* gain, const double* mse,
+                                double mse_budget, const int32_t* order, int32_t* choice,
+                                double* total_gain, double* total_mse);
+
 /* ---- optional kernel timing ---------------------------------------------------------------
  * amp_profile_enable(n > 0) creates n pairs of HIP events on the current device; from then on
  * each launch of the fused sensitivity kernel (one per amp_sens_linear / amp_sens_bgemm call

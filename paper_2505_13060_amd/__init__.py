@@ -246,6 +246,53 @@ def amp_select_subgraphs(n_choices, gain, mse, mse_budget):
     return choice[:J], tg.value, td.value
 
 
+def amp_partition_sequential(n_vertices, edges, quantizable=None):
+    """edges: iterable of (src, dst).  Returns (group_of[n_vertices] with -1 for dropped vertices, n_groups)."""
+    edges = np.ascontiguousarray(np.asarray(list(edges), dtype=np.int32).reshape(-1, 2))
+    src = np.ascontiguousarray(edges[:, 0])
+    dst = np.ascontiguousarray(edges[:, 1])
+    q = None if quantizable is None else np.ascontiguousarray(quantizable, dtype=np.uint8)
+    group_of = np.full(n_vertices, -1, dtype=np.int32)
+    ng = C.c_int32()
+    _check(lib().amp_partition_sequential(int(n_vertices), int(src.size), src.ctypes.data_as(C.c_void_p),
+                                          dst.ctypes.data_as(C.c_void_p),
+                                          None if q is None else q.ctypes.data_as(C.c_void_p),
+                                          group_of.ctypes.data_as(C.c_void_p), C.byref(ng)),
+           "amp_partition_sequential")
+    return group_of, ng.value
+
+
+def amp_time_gain_macs(is_bgemm, N, C_, K, delta_t):
+    f = lib().amp_time_gain_macs
+    f.restype = C.c_double
+    f.argtypes = [C.c_int, C.c_double, C.c_double, C.c_double, C.c_double]
+    return f(int(is_bgemm), float(N), float(C_), float(K), float(delta_t))
+
+
+def amp_memory_gain(is_bgemm, C_, K, delta_m):
+    f = lib().amp_memory_gain
+    f.restype = C.c_double
+    f.argtypes = [C.c_int, C.c_double, C.c_double, C.c_double]
+    return f(int(is_bgemm), float(C_), float(K), float(delta_m))
+
+
+def amp_select_ordered(n_choices, gain, mse, mse_budget, order=None):
+    """Prefix (order=None) / Random (order = a permutation) baselines.  Returns (choice, gain, mse)."""
+    n_choices = np.ascontiguousarray(n_choices, dtype=np.int32)
+    gain = np.ascontiguousarray(gain, dtype=np.float64)
+    mse = np.ascontiguousarray(mse, dtype=np.float64)
+    J = n_choices.size
+    o = None if order is None else np.ascontiguousarray(order, dtype=np.int32)
+    choice = np.zeros(max(J, 1), dtype=np.int32)
+    tg, td = C.c_double(), C.c_double()
+    _check(lib().amp_select_ordered(J, n_choices.ctypes.data_as(C.c_void_p), gain.ctypes.data_as(C.c_void_p),
+                                    mse.ctypes.data_as(C.c_void_p), C.c_double(mse_budget),
+                                    None if o is None else o.ctypes.data_as(C.c_void_p),
+                                    choice.ctypes.data_as(C.c_void_p), C.byref(tg), C.byref(td)),
+           "amp_select_ordered")
+    return choice[:J], tg.value, td.value
+
+
 def amp_profile_enable(max_launches):
     _check(lib().amp_profile_enable(int(max_launches)), "amp_profile_enable")
 

@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libampsens.so")
-SOURCES = ["kernels.hip", "api.hip", "select.cpp"]
+SOURCES = ["kernels.hip", "api.hip", "select.cpp", "graph.cpp"]
 HEADERS = ["internal.h", "walk.h", os.path.join("..", "..", "include", "ampsens.h")]
 
 # -ffp-contract=off: the multiply that decides an FP8 code must not fuse with anything; wanted
