@@ -207,7 +207,10 @@ def main():
     for _ in range(args.warmup):
         p.run()
     torch.cuda.synchronize()
-    launches_per_step = (1 if workload.linears else 0) + (1 if workload.bgemms else 0)
+    # launches of the fused kernel per step: one per amp_sens_* call that has work
+    amp.amp_profile_enable(16)
+    p.run()
+    launches_per_step = len(amp.amp_profile_read(16))
     amp.amp_profile_enable(args.steps * launches_per_step)
 
     torch.cuda.synchronize()
@@ -228,12 +231,17 @@ def main():
     kern_ms = float(np.mean(ms)) if len(ms) else float("nan")
     achieved = kern_bytes / (kern_ms * 1e-3) / 1e9
     log("device steps + host tail: %.3f s; sens kernel avg %.3f ms over %d launches" % (wall, kern_ms, len(ms)))
-    if launches_per_step == 2 and len(ms) >= 2:
-        lin_b = sum(o.pairs() for o in workload.linears) * 4.0
-        bg_b = sum(o.pairs() for o in workload.bgemms) * 4.0
-        lin_ms, bg_ms = float(np.mean(ms[0::2])), float(np.mean(ms[1::2]))
-        log("  linear launch %.3f ms (%.0f GB/s), bgemm launch %.3f ms (%.0f GB/s)" %
-            (lin_ms, lin_b / lin_ms / 1e6, bg_ms, bg_b / bg_ms / 1e6))
+    kinds = []
+    if workload.linears:
+        kinds.append(("linears", sum(o.pairs() for o in workload.linears) * 4.0))
+    if workload.bgemms:
+        kinds.append(("bgemms", sum(o.pairs() for o in workload.bgemms) * 4.0))
+    launch_detail = []
+    if len(kinds) == launches_per_step and len(ms) == args.steps * launches_per_step:
+        per = ms.reshape(args.steps, launches_per_step).mean(axis=0)
+        for (name, nbytes), t in zip(kinds, per):
+            log("  %-22s %.3f ms  %.0f GB/s" % (name, t, nbytes / t / 1e6))
+            launch_detail.append({"launch": name, "ms": float(t), "GB/s": nbytes / float(t) / 1e6})
 
     # absmax alone (secondary line)
     torch.cuda.synchronize()
@@ -254,7 +262,8 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "sens_kernel (fused E/A pass, %d formats)" % len(workload.fmts),
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(args.workload),
-                     "bytes_per_launch": kern_bytes, "ms_per_launch": kern_ms, "launches": int(len(ms))},
+                     "bytes_per_launch": kern_bytes, "ms_per_launch": kern_ms, "launches": int(len(ms)),
+                     "launches_per_step": launch_detail},
         "absmax": {"ms_per_step": abs_ms, "GB/s": abs_elems * 2.0 / (abs_ms * 1e-3) / 1e9,
                    "bytes_per_step": abs_elems * 2.0},
         "select": tail,

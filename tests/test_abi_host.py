@@ -95,6 +95,9 @@ REPLAY_CASES = [
     (("causal", 1, 100, 8), 0, 0, 1), (("causal", 1, 1, 1), 0, 0, 1), (("causal", 4, 8, 8), 0, 2, 1),
     (("causal", 1, 2048, 2048), 0, 0, 1), (("causal", 2, 520, 512), 0, 0, 1), (("causal", 1, 200, 1024), 0, 0, 3),
     (("causal", 3, 8, 16), 0, 0, 1), (("causal", 1, 31, 64), 0, 0, 1), (("causal", 2, 72, 8), 0, 0, 1),
+    (("causal", 2, 512, 512), 0, 0, 1), (("causal", 1, 1024, 1024), 0, 0, 1), (("causal", 1, 4096, 4096), 0, 0, 1),
+    (("causal", 2, 16, 16), 0, 0, 1), (("causal", 3, 24, 24), 0, 0, 1), (("causal", 1, 8, 8), 0, 0, 1),
+    (("causal", 1, 1032, 1032), 0, 0, 1), (("causal", 1, 520, 1544), 0, 0, 1), (("causal", 1, 136, 136), 0, 0, 2),
 ]
 
 
