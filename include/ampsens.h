@@ -234,14 +234,17 @@ amp_status_t amp_select_ordered(int J, const int32_t* n_choices, const double* g
 
 /* ---- optional kernel timing ---------------------------------------------------------------
  * amp_profile_enable(n > 0) creates n pairs of HIP events on the current device; from then on
- * each launch of the fused sensitivity kernel (one per amp_sens_linear / amp_sens_bgemm call
- * with work) records one pair on the call's stream, immediately before and after the kernel,
- * until n launches have been recorded.  amp_profile_read waits for the recorded events, writes
- * the elapsed milliseconds of each launch to ms[0..*n_launches) (host; capacity must be >= the
- * n given to enable) and resets the count.  amp_profile_enable(0) destroys the events.
- * Not thread-safe; meant for benchmarks. */
+ * every launch of a fused sensitivity kernel records one pair on the call's stream, immediately
+ * before and after the kernel, until n launches have been recorded.  An amp_sens_linear call
+ * launches the weight kernel (W read once per batch of samples) if it has whole weight chunks for
+ * it, then the streaming kernel for everything else; an amp_sens_bgemm call launches the streaming
+ * kernel.  amp_profile_read waits for the recorded events, writes the elapsed milliseconds of each
+ * launch to ms[0..*n_launches) and, if not NULL, to pairs[] the number of element pairs the
+ * launch covered and to bytes[] the operand bytes it is defined to read (4 per pair for the
+ * streaming kernel; for the weight kernel 2 per pair plus W's bytes once per batch of samples)
+ * (host arrays; capacity must be >= the n given to enable), and resets the count.  amp_profile_enable(0) destroys the events.  Not thread-safe; meant for benchmarks. */
 amp_status_t amp_profile_enable(int max_launches);
-amp_status_t amp_profile_read(float* ms, int capacity, int* n_launches);
+amp_status_t amp_profile_read(float* ms, uint64_t* pairs, uint64_t* bytes, int capacity, int* n_launches);
 
 /* ---- misc ---------------------------------------------------------------------------------*/
 const char* amp_status_string(amp_status_t status);

@@ -298,12 +298,16 @@ def amp_profile_enable(max_launches):
 
 
 def amp_profile_read(capacity):
-    """Per-launch milliseconds of the fused sensitivity kernel since the last read."""
+    """(milliseconds, element pairs, bytes defined to be read) of every fused-kernel launch since the
+    last read."""
     ms = np.zeros(max(capacity, 1), dtype=np.float32)
+    pairs = np.zeros(max(capacity, 1), dtype=np.uint64)
+    nbytes = np.zeros(max(capacity, 1), dtype=np.uint64)
     n = C.c_int()
-    _check(lib().amp_profile_read(ms.ctypes.data_as(C.c_void_p), int(capacity), C.byref(n)),
+    _check(lib().amp_profile_read(ms.ctypes.data_as(C.c_void_p), pairs.ctypes.data_as(C.c_void_p),
+                                  nbytes.ctypes.data_as(C.c_void_p), int(capacity), C.byref(n)),
            "amp_profile_read")
-    return ms[:n.value].copy()
+    return ms[:n.value].copy(), pairs[:n.value].copy(), nbytes[:n.value].copy()
 
 
 def amp_version():

@@ -67,6 +67,7 @@ struct WorkTable {
     std::vector<uint32_t> chunk_begin;
     std::vector<uint32_t> group;                  // units with the same non-zero id share their x
     uint64_t n_chunks = 0;
+    uint64_t n_pairs = 0;                         // elements that belong to the operands
 
     // x / dx may be null only for blocks without elements.
     amp_status_t add(const uint16_t* x, const uint16_t* dx, const amp_layout_t& L, int64_t batch_mul,
@@ -89,6 +90,12 @@ struct WorkTable {
             u.chunks_per_mat = (L.rows > 0 && L.cols > 0) ? causal_chunks_per_mat(L.rows) : 0;
             chunks = (uint64_t)batch * u.chunks_per_mat;
             if (chunks == 0) u.chunks_per_mat = 1;         // never divide by zero on the device
+            uint64_t valid = 0;
+            for (int64_t i = 0; i < L.rows; ++i) {
+                int64_t len = i + 1 + (L.cols - L.rows);
+                valid += (uint64_t)(len < 0 ? 0 : (len > L.cols ? L.cols : len));
+            }
+            n_pairs += valid * (uint64_t)batch;
         } else {
             const int64_t n = L.n_elems * batch_mul;
             u.n = n;
@@ -97,6 +104,7 @@ struct WorkTable {
             if (mutual) u.head = hx; else { u.flags |= kUnitScalar; u.head = 0; }
             u.chunks_per_mat = 1;
             chunks = unit_chunks_dense(n, u.head);
+            n_pairs += (uint64_t)n;
         }
         chunk_begin.push_back((uint32_t)n_chunks);
         group.push_back(group_id);
@@ -106,26 +114,47 @@ struct WorkTable {
         return AMP_OK;
     }
 
-    // units | chunk_begin[n + 1] (+ pad to 8 bytes) | schedule[n]
+    // units | chunk_begin[n + 1] (+ pad to 8 bytes) | schedule[n] (+ pad to 16) | weight groups
     size_t schedule_offset() const {
         return round8(units.size() * sizeof(WorkUnit) + (units.size() + 1) * sizeof(uint32_t));
     }
-    size_t table_bytes() const { return schedule_offset() + units.size() * sizeof(UnitSchedule); }
+    size_t groups_offset() const {
+        return (schedule_offset() + units.size() * sizeof(UnitSchedule) + 15) / 16 * 16;
+    }
+    size_t max_groups() const {
+        std::vector<uint32_t> ids;
+        for (uint32_t g : group) if (g != 0) ids.push_back(g);
+        std::sort(ids.begin(), ids.end());
+        return (size_t)(std::unique(ids.begin(), ids.end()) - ids.begin());
+    }
+    size_t table_bytes() const { return groups_offset() + max_groups() * sizeof(WGroup); }
     static size_t round8(size_t v) { return (v + 7) / 8 * 8; }
 
     uint64_t chunks_of(size_t u) const {
         return (u + 1 < units.size() ? chunk_begin[u + 1] : n_chunks) - chunk_begin[u];
     }
 
-    // Schedule positions.  Units stay in call order, except that the members of a group (same
-    // group id, equal chunk counts, at most 65535 of them) are interleaved block by block.
-    std::vector<UnitSchedule> schedule(uint32_t block) const {
-        std::vector<UnitSchedule> sch(units.size());
+    // How a call is split between the two streaming kernels.
+    struct Plan {
+        std::vector<UnitSchedule> schedule;       // positions of the chunks the streaming kernel takes
+        std::vector<WGroup> wgroups;              // work of the weight kernel
+        uint64_t n_positions = 0;                 // streaming kernel
+        uint64_t n_items = 0;                     // weight kernel
+        uint64_t w_pairs = 0;                     // element pairs the weight kernel covers
+        uint64_t w_bytes = 0;                     // bytes it is defined to read: x once per batch, xdot per member
+    };
+
+    // Units stay in call order, except that the members of a group (same group id, equal chunk
+    // counts, at most 65535 of them) are interleaved block by block.  With use_w, a group whose
+    // members are whole-vector aligned and evenly spaced in the unit list hands its whole chunks to
+    // the weight kernel; the ragged last chunk stays with the streaming kernel.
+    Plan plan(uint32_t block, bool use_w) const {
+        Plan P;
+        P.schedule.resize(units.size());
         std::unordered_map<uint32_t, std::vector<size_t>> by_group;
         for (size_t u = 0; u < units.size(); ++u)
             if (group[u] != 0) by_group[group[u]].push_back(u);
         std::vector<char> done(units.size(), 0);
-        uint64_t run = 0;
         for (size_t u = 0; u < units.size(); ++u) {
             if (done[u]) continue;
             std::vector<size_t> members(1, u);
@@ -133,13 +162,41 @@ struct WorkTable {
                 for (size_t v : by_group[group[u]])
                     if (v > u && !done[v] && chunks_of(v) == chunks_of(u) && members.size() < 65535)
                         members.push_back(v);
+            uint32_t skip = 0;
+            if (use_w && members.size() >= 2) {
+                bool ok = true;
+                const size_t stride = members[1] - members[0];
+                for (size_t m = 0; m < members.size() && ok; ++m) {
+                    const WorkUnit& w = units[members[m]];
+                    ok = w.flags == units[u].flags && (w.flags & (kUnitCausal | kUnitScalar)) == 0 &&
+                         w.head == 0 && w.x == units[u].x && w.n == units[u].n &&
+                         members[m] == u + m * stride;
+                }
+                const uint64_t whole = (uint64_t)units[u].n / ((uint64_t)kChunkVecs * kVec);
+                if (ok && whole > 0) {
+                    skip = (uint32_t)whole;
+                    WGroup G;
+                    std::memset(&G, 0, sizeof(G));
+                    G.first_unit = (uint32_t)u;
+                    G.unit_stride = (uint32_t)stride;
+                    G.members = (uint32_t)members.size();
+                    G.chunks = skip;
+                    G.item_begin = (uint32_t)P.n_items;
+                    P.wgroups.push_back(G);
+                    P.n_items += whole * ((members.size() + kWBatch - 1) / kWBatch);
+                    P.w_pairs += whole * (uint64_t)kChunkVecs * kVec * members.size();
+                    P.w_bytes += whole * (uint64_t)kChunkVecs * kVec * 2 *
+                                 (members.size() + (members.size() + kWBatch - 1) / kWBatch);
+                }
+            }
             for (size_t m = 0; m < members.size(); ++m) {
-                sch[members[m]] = UnitSchedule{(uint32_t)run, (uint16_t)members.size(), (uint16_t)m, block, 0u};
+                P.schedule[members[m]] = UnitSchedule{(uint32_t)P.n_positions, (uint16_t)members.size(),
+                                                      (uint16_t)m, block, skip};
                 done[members[m]] = 1;
             }
-            run += chunks_of(u) * members.size();
+            P.n_positions += (chunks_of(u) - skip) * members.size();
         }
-        return sch;
+        return P;
     }
 };
 
@@ -192,6 +249,17 @@ int sens_grid(uint64_t n_chunks, int n_fmts, int f0, int f1) {
     return persistent_grid(n_chunks, resident);
 }
 
+int sens_w_grid(int n_fmts, int f0, int f1) {
+    static std::mutex mu;
+    static int cached[64][2][2][2];
+    const int dev = device_index();
+    if (dev < 0) return sens_w_resident_blocks(n_fmts, f0, f1, device_cus());
+    std::lock_guard<std::mutex> lock(mu);
+    int& slot = cached[dev][n_fmts - 1][f0][f1];
+    if (slot == 0) slot = sens_w_resident_blocks(n_fmts, f0, f1, device_cus());
+    return slot;
+}
+
 int absmax_grid(uint64_t n_chunks) {
     static std::mutex mu;
     static int cached[64];
@@ -228,15 +296,20 @@ WsLayout ws_layout(const WorkTable& t, size_t partial_bytes_per_chunk) {
 int g_schedule_block = 0;                              // test / tuning hook: 0 = default
 constexpr uint32_t kDefaultScheduleBlock = 8;
 
-amp_status_t upload(const WorkTable& t, uint32_t block, void* workspace, hipStream_t stream) {
+int g_use_w_kernel = 1;                                // test / tuning hook
+
+uint32_t schedule_block() { return g_schedule_block > 0 ? (uint32_t)g_schedule_block : kDefaultScheduleBlock; }
+
+amp_status_t upload(const WorkTable& t, const WorkTable::Plan& plan, void* workspace, hipStream_t stream) {
     std::vector<uint8_t> blob(t.table_bytes(), 0);
     std::memcpy(blob.data(), t.units.data(), t.units.size() * sizeof(WorkUnit));
     std::vector<uint32_t> cb = t.chunk_begin;
     cb.push_back((uint32_t)t.n_chunks);
     std::memcpy(blob.data() + t.units.size() * sizeof(WorkUnit), cb.data(), cb.size() * 4);
-    if (g_schedule_block > 0) block = (uint32_t)g_schedule_block;
-    const std::vector<UnitSchedule> sch = t.schedule(block < 1 ? 1 : block);
-    std::memcpy(blob.data() + t.schedule_offset(), sch.data(), sch.size() * sizeof(UnitSchedule));
+    std::memcpy(blob.data() + t.schedule_offset(), plan.schedule.data(),
+                plan.schedule.size() * sizeof(UnitSchedule));
+    if (!plan.wgroups.empty())
+        std::memcpy(blob.data() + t.groups_offset(), plan.wgroups.data(), plan.wgroups.size() * sizeof(WGroup));
     AMP_HIP(hipMemcpyAsync(workspace, blob.data(), blob.size(), hipMemcpyHostToDevice, stream));
     return AMP_OK;
 }
@@ -244,6 +317,7 @@ amp_status_t upload(const WorkTable& t, uint32_t block, void* workspace, hipStre
 // ---- optional timing of the sensitivity kernel ------------------------------------------------
 struct Profile {
     std::vector<hipEvent_t> start, stop;
+    std::vector<uint64_t> pairs, bytes;
     int used = 0;
 };
 Profile g_profile;
@@ -263,8 +337,8 @@ amp_status_t run_sens(const WorkTable& t, const amp_fp8_format_t* fmts, int n_fm
     if (workspace_bytes < L.total) return AMP_ERR_WORKSPACE_TOO_SMALL;
     hipStream_t stream = (hipStream_t)stream_;
     const int f0 = (int)fmts[0], f1 = (int)fmts[n_fmts - 1];
-    const int grid = t.n_chunks > 0 ? sens_grid(t.n_chunks, n_fmts, f0, f1) : 1;
-    amp_status_t st = upload(t, kDefaultScheduleBlock, workspace, stream);
+    const WorkTable::Plan plan = t.plan(schedule_block(), g_use_w_kernel != 0);
+    amp_status_t st = upload(t, plan, workspace, stream);
     if (st != AMP_OK) return st;
     uint8_t* ws = (uint8_t*)workspace;
     const uint32_t n_units = (uint32_t)t.units.size(), n_chunks = (uint32_t)t.n_chunks;
@@ -274,12 +348,30 @@ amp_status_t run_sens(const WorkTable& t, const amp_fp8_format_t* fmts, int n_fm
     ChunkRef* d_map = (ChunkRef*)(ws + L.map);
     float* d_partials = (float*)(ws + L.partials);
     const UnitSchedule* d_sch = (const UnitSchedule*)(ws + t.schedule_offset());
+    const WGroup* d_groups = (const WGroup*)(ws + t.groups_offset());
     AMP_HIP(launch_prepare(d_units, d_cb, d_sch, n_units, n_chunks, n_fmts, d_runits, d_map, stream));
-    if (n_chunks > 0) {
-        const bool timed = g_profile.used < (int)g_profile.start.size();
-        if (timed) AMP_HIP(hipEventRecord(g_profile.start[g_profile.used], stream));
-        AMP_HIP(launch_sens(d_runits, d_map, n_chunks, n_fmts, f0, f1, d_partials, grid, stream));
-        if (timed) AMP_HIP(hipEventRecord(g_profile.stop[g_profile.used++], stream));
+    auto timed_begin = [&](uint64_t pairs, uint64_t bytes) -> hipError_t {
+        if (g_profile.used >= (int)g_profile.start.size()) return hipSuccess;
+        g_profile.pairs[g_profile.used] = pairs;
+        g_profile.bytes[g_profile.used] = bytes;
+        return hipEventRecord(g_profile.start[g_profile.used], stream);
+    };
+    auto timed_end = [&]() -> hipError_t {
+        if (g_profile.used >= (int)g_profile.start.size()) return hipSuccess;
+        return hipEventRecord(g_profile.stop[g_profile.used++], stream);
+    };
+    if (plan.n_items > 0) {
+        const int grid = persistent_grid(plan.n_items, sens_w_grid(n_fmts, f0, f1));
+        AMP_HIP(timed_begin(plan.w_pairs, plan.w_bytes));
+        AMP_HIP(launch_sens_w(d_groups, (uint32_t)plan.wgroups.size(), (uint32_t)plan.n_items, d_runits, d_cb,
+                              n_fmts, f0, f1, d_partials, grid, stream));
+        AMP_HIP(timed_end());
+    }
+    if (plan.n_positions > 0) {
+        const int grid = sens_grid(plan.n_positions, n_fmts, f0, f1);
+        AMP_HIP(timed_begin(t.n_pairs - plan.w_pairs, (t.n_pairs - plan.w_pairs) * 4));
+        AMP_HIP(launch_sens(d_runits, d_map, (uint32_t)plan.n_positions, n_fmts, f0, f1, d_partials, grid, stream));
+        AMP_HIP(timed_end());
     }
     AMP_HIP(launch_sens_finalize(d_runits, d_cb, n_units, n_fmts, d_partials, d_out, stream));
     return AMP_OK;
@@ -437,7 +529,8 @@ amp_status_t amp_absmax_scale(const amp_tensor_t* tensors, int n_tensors, const 
     const WsLayout L = absmax_layout(t);
     if (workspace_bytes < L.total) return AMP_ERR_WORKSPACE_TOO_SMALL;
     hipStream_t stream = (hipStream_t)stream_;
-    st = upload(t, kDefaultScheduleBlock, workspace, stream);
+    const WorkTable::Plan plan = t.plan(schedule_block(), false);
+    st = upload(t, plan, workspace, stream);
     if (st != AMP_OK) return st;
     uint8_t* ws = (uint8_t*)workspace;
     const uint32_t n_units = (uint32_t)t.units.size(), n_chunks = (uint32_t)t.n_chunks;
@@ -516,6 +609,8 @@ amp_status_t amp_profile_enable(int max_launches) {
     for (hipEvent_t e : g_profile.stop) (void)hipEventDestroy(e);
     g_profile.start.clear();
     g_profile.stop.clear();
+    g_profile.pairs.assign((size_t)max_launches, 0);
+    g_profile.bytes.assign((size_t)max_launches, 0);
     g_profile.used = 0;
     for (int i = 0; i < max_launches; ++i) {
         hipEvent_t a, b;
@@ -527,12 +622,14 @@ amp_status_t amp_profile_enable(int max_launches) {
     return AMP_OK;
 }
 
-amp_status_t amp_profile_read(float* ms, int capacity, int* n_launches) {
+amp_status_t amp_profile_read(float* ms, uint64_t* pairs, uint64_t* bytes, int capacity, int* n_launches) {
     if (!n_launches || capacity < 0 || (capacity > 0 && !ms)) return AMP_ERR_INVALID_ARG;
     if (capacity < g_profile.used) return AMP_ERR_INVALID_ARG;
     for (int i = 0; i < g_profile.used; ++i) {
         AMP_HIP(hipEventSynchronize(g_profile.stop[i]));
         AMP_HIP(hipEventElapsedTime(&ms[i], g_profile.start[i], g_profile.stop[i]));
+        if (pairs) pairs[i] = g_profile.pairs[i];
+        if (bytes) bytes[i] = g_profile.bytes[i];
     }
     *n_launches = g_profile.used;
     g_profile.used = 0;
@@ -564,23 +661,43 @@ int64_t ampsens_debug_check_linear_schedule(const amp_linear_desc_t* ops, int n_
                                             uint64_t* n_chunks_out, uint64_t* interleaved_units) {
     WorkTable t;
     if (build_linear(ops, n_ops, n_fmts, &t) != AMP_OK) return -1;
-    const std::vector<UnitSchedule> sch = t.schedule(g_schedule_block > 0 ? (uint32_t)g_schedule_block : kDefaultScheduleBlock);
-    std::vector<uint8_t> hit(t.n_chunks, 0);
+    const WorkTable::Plan plan = t.plan(schedule_block(), g_use_w_kernel != 0);
+    const std::vector<UnitSchedule>& sch = plan.schedule;
+    std::vector<uint8_t> hit(plan.n_positions, 0);
     int64_t bad = 0;
     uint64_t inter = 0;
     for (size_t u = 0; u < t.units.size(); ++u) {
-        const uint32_t chunks = (uint32_t)t.chunks_of(u);
+        const uint32_t chunks = (uint32_t)t.chunks_of(u) - sch[u].skip;
         if (sch[u].interleave > 1) ++inter;
         for (uint32_t l = 0; l < chunks; ++l) {
             const uint32_t pos = schedule_position(sch[u], l, chunks);
-            if (pos >= t.n_chunks || hit[pos]) ++bad; else hit[pos] = 1;
+            if (pos >= plan.n_positions || hit[pos]) ++bad; else hit[pos] = 1;
         }
     }
     for (uint8_t h : hit) if (!h) ++bad;
+    // the weight kernel's items: every (member, whole chunk) of a group exactly once, in bounds
+    std::vector<uint32_t> covered(t.units.size(), 0);
+    uint64_t items = 0;
+    for (const WGroup& G : plan.wgroups) {
+        if (G.item_begin != items) ++bad;
+        items += (uint64_t)G.chunks * ((G.members + kWBatch - 1) / kWBatch);
+        for (uint32_t m = 0; m < G.members; ++m) {
+            const size_t u = G.first_unit + (size_t)m * G.unit_stride;
+            if (u >= t.units.size()) { ++bad; continue; }
+            covered[u] += G.chunks;
+            if ((uint64_t)G.chunks * kChunkVecs * kVec > (uint64_t)t.units[u].n) ++bad;
+        }
+    }
+    if (items != plan.n_items) ++bad;
+    for (size_t u = 0; u < t.units.size(); ++u)
+        if (covered[u] != sch[u].skip) ++bad;
     if (n_chunks_out) *n_chunks_out = t.n_chunks;
     if (interleaved_units) *interleaved_units = inter;
     return bad;
 }
+
+// Test / tuning hook: 0 sends weights through the streaming kernel like everything else.
+void ampsens_debug_set_w_kernel(int on) { g_use_w_kernel = on; }
 
 // Test / tuning hook: chunks of one member that sit next to each other in the schedule (0 = default).
 void ampsens_debug_set_schedule_block(int block) { g_schedule_block = block; }

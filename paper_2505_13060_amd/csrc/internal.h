@@ -91,8 +91,22 @@ struct UnitSchedule {
     uint16_t interleave;
     uint16_t member;
     uint32_t block;                  // chunks of one member that sit next to each other
-    uint32_t reserved;
+    uint32_t skip;                   // leading chunks of the unit that the weight kernel handles:
+                                     // they get no position; `local` above counts from the first
+                                     // chunk after them
 };
+
+// A weight shared by the samples of an op, for the weight kernel: `members` units (first_unit,
+// first_unit + unit_stride, ...) read the same x with their own gradients; the kernel takes the
+// first `chunks` (whole, aligned) chunks of each, kWBatch members at a time, reading and
+// quantising x once per batch.  Work item i of a call belongs to the group with the largest
+// item_begin <= i; inside the group items run chunk by chunk, batch after batch.
+constexpr int kWBatch = 8;
+struct alignas(16) WGroup {          // 32 bytes
+    uint32_t first_unit, unit_stride, members, chunks;
+    uint32_t item_begin, reserved[3];
+};
+static_assert(sizeof(WGroup) == 32, "WGroup layout");
 
 // Number of chunks of a unit (host side; the kernels use the same constants).
 inline uint64_t unit_chunks_dense(int64_t n, uint32_t head) {
@@ -126,6 +140,10 @@ hipError_t launch_fake_quant(const uint16_t* d_x, int64_t n, float scale, float 
 hipError_t launch_sens(const ResolvedUnit* d_runits, const ChunkRef* d_map, uint32_t n_chunks,
                        int n_fmts, int fmt0, int fmt1, float* d_partials, int grid,
                        hipStream_t stream);
+int sens_w_resident_blocks(int n_fmts, int fmt0, int fmt1, int cus);
+hipError_t launch_sens_w(const WGroup* d_groups, uint32_t n_groups, uint32_t n_items,
+                         const ResolvedUnit* d_runits, const uint32_t* d_chunk_begin, int n_fmts, int fmt0,
+                         int fmt1, float* d_partials, int grid, hipStream_t stream);
 hipError_t launch_sens_finalize(const ResolvedUnit* d_runits, const uint32_t* d_chunk_begin,
                                 uint32_t n_units, int n_fmts, const float* d_partials,
                                 float* d_out, hipStream_t stream);

@@ -151,7 +151,10 @@ __global__ __launch_bounds__(kWG) void prepare_kernel(const WorkUnit* __restrict
         ref.local = i - chunk_begin[ui];
         ref.slot = i;
         ref.reserved = 0;
-        map[schedule_position(schedule[ui], ref.local, chunk_begin[ui + 1] - chunk_begin[ui])] = ref;
+        const UnitSchedule sch = schedule[ui];
+        if (ref.local >= sch.skip)
+            map[schedule_position(sch, ref.local - sch.skip,
+                                  chunk_begin[ui + 1] - chunk_begin[ui] - sch.skip)] = ref;
     }
 }
 
@@ -300,6 +303,125 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
         }
         if (!more) break;
         c = cn;
+    }
+}
+
+// ---- the weight kernel ------------------------------------------------------------------------
+// A weight W is shared by the R samples of its op; only the gradient differs.  This kernel reads a
+// chunk of W once for up to kWBatch samples, forms x, and x - xtilde for every format, once, and
+// then streams the samples' gradient chunks against them: 7 VALU operations per element pair
+// instead of 16, and W's bytes once per batch instead of once per sample.  Each thread keeps one
+// 8-element vector of W per step; sums are kept per sample and written to the same per-wave
+// partial slots the streaming kernel would have used, so the finalisation does not change.
+template <int NF, int F0, int F1>
+__global__ __launch_bounds__(kWG) void sens_w_kernel(const WGroup* __restrict__ groups, uint32_t n_groups,
+                                                     uint32_t n_items,
+                                                     const ResolvedUnit* __restrict__ runits,
+                                                     const uint32_t* __restrict__ chunk_begin,
+                                                     float* __restrict__ partials) {
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    for (uint32_t item = blockIdx.x; item < n_items; item += gridDim.x) {
+        uint32_t gi = 0;
+        while (gi + 1 < n_groups && groups[gi + 1].item_begin <= item) ++gi;
+        const WGroup G = groups[gi];
+        const uint32_t batches = (G.members + kWBatch - 1) / kWBatch;
+        const uint32_t rel = item - G.item_begin;
+        const uint32_t j = rel / batches;                       // chunk of W
+        const uint32_t r0 = (rel % batches) * kWBatch;          // first member of the batch
+        const int nb = (int)(G.members - r0 < (uint32_t)kWBatch ? G.members - r0 : (uint32_t)kWBatch);
+        const ResolvedUnit u0 = runits[G.first_unit + r0 * G.unit_stride];
+        gptr16_t gp[kWBatch];
+        uint32_t slot[kWBatch];
+#pragma unroll
+        for (int k = 0; k < kWBatch; ++k) {
+            const uint32_t ui = G.first_unit + (r0 + (k < nb ? k : 0)) * G.unit_stride;
+            gp[k] = (gptr16_t)runits[ui].dx;
+            slot[k] = chunk_begin[ui] + j;
+        }
+        float inv[NF], scale[NF];
+#pragma unroll
+        for (int f = 0; f < NF; ++f) { inv[f] = u0.inv[f]; scale[f] = u0.scale[f]; }
+        float A[kWBatch], E[NF][kWBatch];
+#pragma unroll
+        for (int k = 0; k < kWBatch; ++k) {
+            A[k] = 0.0f;
+#pragma unroll
+            for (int f = 0; f < NF; ++f) E[f][k] = 0.0f;
+        }
+        const int64_t base = (int64_t)j * kChunkVecs * kVec;    // the unit starts on the 16-byte grid
+        const gptr128_t px = reinterpret_cast<gptr128_t>((gptr16_t)u0.x + base);
+        int pk = 0;
+#pragma unroll 1
+        for (int s = 0; s < kChunkVecs / kWG; ++s) {
+            const int v = s * kWG + tid;
+            const u32x4 xw = load128<false>(px + v);
+            u32x4 gr[kWBatch];
+#pragma unroll
+            for (int k = 0; k < kWBatch; ++k)
+                if (k < nb) gr[k] = load128<true>(reinterpret_cast<gptr128_t>(gp[k] + base) + v);
+            // x and the quantisation error of every format, once
+            const uint32_t w4[4] = {xw.x, xw.y, xw.z, xw.w};
+            float xv[kVec], ev[NF][kVec];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const float x4[4] = {bf16_lo(w4[2 * h]), bf16_hi(w4[2 * h]), bf16_lo(w4[2 * h + 1]),
+                                     bf16_hi(w4[2 * h + 1])};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) xv[4 * h + i] = x4[i];
+#pragma unroll
+                for (int f = 0; f < NF; ++f) {
+                    float q4[4];
+                    if (f == 0) {
+                        pk = Fp8<F0>::pack(clamp_fmax<F0>(x4[0] * inv[0]), clamp_fmax<F0>(x4[1] * inv[0]), pk, false);
+                        pk = Fp8<F0>::pack(clamp_fmax<F0>(x4[2] * inv[0]), clamp_fmax<F0>(x4[3] * inv[0]), pk, true);
+                        const float2_t a = Fp8<F0>::unpack(pk, false), b = Fp8<F0>::unpack(pk, true);
+                        q4[0] = a.x; q4[1] = a.y; q4[2] = b.x; q4[3] = b.y;
+                    } else {
+                        pk = Fp8<F1>::pack(clamp_fmax<F1>(x4[0] * inv[f]), clamp_fmax<F1>(x4[1] * inv[f]), pk, false);
+                        pk = Fp8<F1>::pack(clamp_fmax<F1>(x4[2] * inv[f]), clamp_fmax<F1>(x4[3] * inv[f]), pk, true);
+                        const float2_t a = Fp8<F1>::unpack(pk, false), b = Fp8<F1>::unpack(pk, true);
+                        q4[0] = a.x; q4[1] = a.y; q4[2] = b.x; q4[3] = b.y;
+                    }
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) ev[f][4 * h + i] = fmaf(-q4[i], scale[f], x4[i]);
+                }
+            }
+            // every sample's gradient against them
+#pragma unroll
+            for (int k = 0; k < kWBatch; ++k) {
+                if (k < nb) {
+                    const uint32_t g4[4] = {gr[k].x, gr[k].y, gr[k].z, gr[k].w};
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const float g0 = bf16_lo(g4[i]), g1 = bf16_hi(g4[i]);
+                        const float a0 = g0 * xv[2 * i], a1 = g1 * xv[2 * i + 1];
+                        A[k] = fmaf(a0, a0, A[k]);
+                        A[k] = fmaf(a1, a1, A[k]);
+#pragma unroll
+                        for (int f = 0; f < NF; ++f) {
+                            const float t0 = g0 * ev[f][2 * i], t1 = g1 * ev[f][2 * i + 1];
+                            E[f][k] = fmaf(t0, t0, E[f][k]);
+                            E[f][k] = fmaf(t1, t1, E[f][k]);
+                        }
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < kWBatch; ++k) {
+            if (k < nb) {
+                float v[NF + 1];
+#pragma unroll
+                for (int f = 0; f < NF; ++f) v[f] = wave_sum(E[f][k]);
+                v[NF] = wave_sum(A[k]);
+                if (lane == 0) {
+                    float* out = partials + ((size_t)slot[k] * kWaves + wave) * (NF + 1);
+#pragma unroll
+                    for (int i = 0; i <= NF; ++i) out[i] = v[i];
+                }
+            }
+        }
     }
 }
 
@@ -517,6 +639,26 @@ int resident_blocks(const void* fn, int cus) {
 
 int sens_resident_blocks(int n_fmts, int fmt0, int fmt1, int cus) {
     return resident_blocks((const void*)sens_variant(n_fmts, fmt0, fmt1), cus);
+}
+
+typedef void (*sens_w_fn_t)(const WGroup*, uint32_t, uint32_t, const ResolvedUnit*, const uint32_t*, float*);
+
+static sens_w_fn_t sens_w_variant(int n_fmts, int fmt0, int fmt1) {
+    if (n_fmts == 1) return fmt0 == 0 ? sens_w_kernel<1, 0, 0> : sens_w_kernel<1, 1, 1>;
+    if (fmt0 == 0) return fmt1 == 0 ? sens_w_kernel<2, 0, 0> : sens_w_kernel<2, 0, 1>;
+    return fmt1 == 0 ? sens_w_kernel<2, 1, 0> : sens_w_kernel<2, 1, 1>;
+}
+
+int sens_w_resident_blocks(int n_fmts, int fmt0, int fmt1, int cus) {
+    return resident_blocks((const void*)sens_w_variant(n_fmts, fmt0, fmt1), cus);
+}
+
+hipError_t launch_sens_w(const WGroup* d_groups, uint32_t n_groups, uint32_t n_items,
+                         const ResolvedUnit* d_runits, const uint32_t* d_chunk_begin, int n_fmts, int fmt0,
+                         int fmt1, float* d_partials, int grid, hipStream_t stream) {
+    hipLaunchKernelGGL(sens_w_variant(n_fmts, fmt0, fmt1), dim3(grid), dim3(kWG), 0, stream, d_groups,
+                       n_groups, n_items, d_runits, d_chunk_begin, d_partials);
+    return hipGetLastError();
 }
 
 int absmax_resident_blocks(int cus) { return resident_blocks((const void*)absmax_kernel, cus); }

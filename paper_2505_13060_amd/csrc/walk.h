@@ -161,7 +161,8 @@ AMPSENS_HD void walk_chunk(const Unit& u, uint32_t chunk_local, int tid, Ctx& ct
         walk_dense_chunk(u.n, u.head, scalar, chunk_local, tid, ctx);
 }
 
-// Schedule position of chunk `local` of a unit with `chunks` chunks (see UnitSchedule).
+// Schedule position of chunk `local` of a unit with `chunks` chunks, both counted after the
+// chunks the unit leaves to the weight kernel (see UnitSchedule).
 AMPSENS_HD uint32_t schedule_position(const UnitSchedule& sch, uint32_t local, uint32_t chunks) {
     const uint32_t b = local / sch.block;
     const uint32_t left = chunks - b * sch.block;

@@ -351,3 +351,25 @@ def test_config1_full_size_sampled_units():
     # E4M3 (three mantissa bits) must beat E5M2 (two) on these distributions
     for arr in res["linear"] + res["bgemm"]:
         assert np.all(arr[:, 0, 0] < arr[:, 1, 0]) and np.all(arr[:, 0, 2] < arr[:, 1, 2])
+
+
+def test_weight_kernel_and_streaming_kernel_agree():
+    """Weights go through the kernel that reads W once per batch of 8 samples; with the test hook off
+    they go through the streaming kernel.  Both must match the oracle, for sample counts that are not
+    multiples of the batch and weights with a ragged last chunk or an unaligned gradient."""
+    L = amp.lib()
+    for (R, tokens, Cd, K) in [(11, 40, 520, 190), (3, 16, 1024, 100), (9, 8, 333, 301), (2, 64, 4096, 24)]:
+        w = wl.Workload("wk", [amp.E4M3, amp.E5M2],
+                        [wl._linear("lin", 777 + R, R, tokens, Cd, K, "cpu", outliers=2)])
+        to_device(w)
+        outs = []
+        for on in (0, 1):
+            say("weight kernel %s: R=%d W=%dx%d (%d elements)" % ("on" if on else "off", R, K, Cd, K * Cd))
+            L.ampsens_debug_set_w_kernel(C.c_int(on))
+            p = SensPass(w, DEV)
+            p.run()
+            res = p.results()
+            parity.check_workload(w, res)
+            outs.append(res["linear"][0].copy())
+        L.ampsens_debug_set_w_kernel(C.c_int(1))
+        assert np.allclose(outs[0], outs[1], rtol=2e-6, atol=0)
