@@ -147,12 +147,13 @@ def cpu_baseline(workload, target_seconds=15.0):
                       "device-to-host copy not timed" % (nf, "; ".join(picked), pairs / 1e6)}
 
 
-def measured_traffic(workload_name):
-    """HBM bytes per sens_kernel launch from the committed rocprofv3 counter summary (FETCH_SIZE and
-    WRITE_SIZE runs of this same command, scaled by a plain copy of known size); None if no
-    summary covers the workload."""
-    path = os.path.join(ROOT, "profiles", "sens_kernel_%s_block.md" % workload_name)
-    tag = "traffic_bytes_per_launch(sens_kernel, %s) =" % workload_name
+def measured_traffic(kernel_label, workload_name):
+    """HBM bytes per launch of the named kernel from the committed rocprofv3 counter summary
+    (FETCH_SIZE and WRITE_SIZE runs of this same command, scaled by a plain copy of known size);
+    None if no summary covers the workload."""
+    kernel = (kernel_label or "").split(" ")[0]
+    path = os.path.join(ROOT, "profiles", "sens_kernels_%s_block.md" % workload_name)
+    tag = "traffic_bytes_per_launch(%s, %s) =" % (kernel, workload_name)
     try:
         for line in open(path):
             if line.startswith(tag):
@@ -270,7 +271,7 @@ def main():
         "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBS,
         "roofline": {"bound": "hbm", "kernel": dom["kernel"] if dom else None,
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(args.workload),
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(dom["kernel"] if dom else None, args.workload),
                      "bytes_per_launch": kern_bytes, "ms_per_launch": kern_ms,
                      "bytes": "operand bytes the kernel is defined to read: 4 B per (element, sample) pair, "
                               "except that the weight kernel reads W once per batch of 8 samples",

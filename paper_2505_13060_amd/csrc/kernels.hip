@@ -20,8 +20,14 @@
 #include "internal.h"
 #include "walk.h"
 
+#ifndef AMPSENS_W_LOAD
+#define AMPSENS_W_LOAD 8
+#endif
+
 namespace ampsens {
 namespace {
+
+constexpr int kWLoad = AMPSENS_W_LOAD;       // gradient vectors of one step in flight per lane
 
 typedef float float2_t __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));             // one 128-bit load
@@ -356,9 +362,9 @@ __global__ __launch_bounds__(kWG) void sens_w_kernel(const WGroup* __restrict__ 
         for (int s = 0; s < kChunkVecs / kWG; ++s) {
             const int v = s * kWG + tid;
             const u32x4 xw = load128<false>(px + v);
-            u32x4 gr[kWBatch];
+            u32x4 gr[kWLoad];
 #pragma unroll
-            for (int k = 0; k < kWBatch; ++k)
+            for (int k = 0; k < kWLoad; ++k)
                 if (k < nb) gr[k] = load128<true>(reinterpret_cast<gptr128_t>(gp[k] + base) + v);
             // x and the quantisation error of every format, once
             const uint32_t w4[4] = {xw.x, xw.y, xw.z, xw.w};
@@ -387,22 +393,29 @@ __global__ __launch_bounds__(kWG) void sens_w_kernel(const WGroup* __restrict__ 
                     for (int i = 0; i < 4; ++i) ev[f][4 * h + i] = fmaf(-q4[i], scale[f], x4[i]);
                 }
             }
-            // every sample's gradient against them
+            // every sample's gradient against them, kWLoad samples in flight at a time
 #pragma unroll
-            for (int k = 0; k < kWBatch; ++k) {
-                if (k < nb) {
-                    const uint32_t g4[4] = {gr[k].x, gr[k].y, gr[k].z, gr[k].w};
+            for (int k0 = 0; k0 < kWBatch; k0 += kWLoad) {
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const float g0 = bf16_lo(g4[i]), g1 = bf16_hi(g4[i]);
-                        const float a0 = g0 * xv[2 * i], a1 = g1 * xv[2 * i + 1];
-                        A[k] = fmaf(a0, a0, A[k]);
-                        A[k] = fmaf(a1, a1, A[k]);
+                for (int kk = 0; kk < kWLoad; ++kk) {
+                    const int k = k0 + kk;
+                    if (k < nb) {
+                        const uint32_t g4[4] = {gr[kk].x, gr[kk].y, gr[kk].z, gr[kk].w};
+                        // the slot is free: fetch the gradient of sample k + kWLoad into it
+                        if (k + kWLoad < kWBatch && k + kWLoad < nb)
+                            gr[kk] = load128<true>(reinterpret_cast<gptr128_t>(gp[(k + kWLoad) % kWBatch] + base) + v);
 #pragma unroll
-                        for (int f = 0; f < NF; ++f) {
-                            const float t0 = g0 * ev[f][2 * i], t1 = g1 * ev[f][2 * i + 1];
-                            E[f][k] = fmaf(t0, t0, E[f][k]);
-                            E[f][k] = fmaf(t1, t1, E[f][k]);
+                        for (int i = 0; i < 4; ++i) {
+                            const float g0 = bf16_lo(g4[i]), g1 = bf16_hi(g4[i]);
+                            const float a0 = g0 * xv[2 * i], a1 = g1 * xv[2 * i + 1];
+                            A[k] = fmaf(a0, a0, A[k]);
+                            A[k] = fmaf(a1, a1, A[k]);
+#pragma unroll
+                            for (int f = 0; f < NF; ++f) {
+                                const float t0 = g0 * ev[f][2 * i], t1 = g1 * ev[f][2 * i + 1];
+                                E[f][k] = fmaf(t0, t0, E[f][k]);
+                                E[f][k] = fmaf(t1, t1, E[f][k]);
+                            }
                         }
                     }
                 }
