@@ -8,10 +8,14 @@ amp_sens_bgemm).  After the K steps (K = 32 is the 32-block sweep of the headlin
 the small statistics are copied to the host, the epilogue of Sec. 2.2 builds the group tables
 and amp_select_subgraphs solves eq. (ip); that host tail is inside the timed region.
 
-value = (x + xdot bytes the method reads, 4 B per element pair, masked causal entries not
-counted) * K / wall time of the timed region, in GB/s.  "roofline" is the fused sensitivity
-kernel alone, timed per launch with HIP events recorded by the library on the launch stream.
-"cpu_baseline" times the CPU oracle on a bounded sample of the same tensors.
+value = (bytes of x and xdot that the kernels of a step are defined to read from HBM) * K / wall
+time of the timed region, in GB/s.  Per step that is 2 B per element of x for the absmax pass plus,
+for the sensitivity pass, 4 B per (element, sample) pair, except that a weight shared by the
+samples is read once per batch of 8 samples against their 8 gradients; masked causal entries,
+partial sums and tables are not counted.  The same step priced at 4 B per pair for every sample
+(as if W were re-read with each sample's gradient) is reported beside it.  "roofline" is the
+longest fused sensitivity launch alone, timed with HIP events recorded by the library on the
+launch stream.  "cpu_baseline" times the CPU oracle on a bounded sample of the same tensors.
 
 Prints ONE JSON line.
 """
@@ -227,7 +231,12 @@ def main():
     ms, lp, lb = amp.amp_profile_read(args.steps * launches_per_step)
     amp.amp_profile_enable(0)
     wall = t1 - t0
-    bytes_step = pairs * 4.0
+    if launches_per_step <= 0 or len(ms) != args.steps * launches_per_step:
+        raise SystemExit("bench.py: the library reported %d launch records for %d steps x %d launches"
+                         % (len(ms), args.steps, launches_per_step))
+    sens_bytes_step = float(lb.reshape(args.steps, launches_per_step)[0].astype(np.float64).sum())
+    abs_bytes_step = abs_elems * 2.0
+    bytes_step = sens_bytes_step + abs_bytes_step
     value = bytes_step * args.steps / wall / 1e9
     log("device steps + host tail: %.3f s over %d steps" % (wall, args.steps))
     names = {3: ["sens_w_kernel (weights of the linears)", "sens_kernel (activations of the linears)",
@@ -235,17 +244,16 @@ def main():
              2: ["sens_kernel (linears)", "sens_kernel (BGEMM operands)"],
              1: ["sens_kernel"]}.get(launches_per_step, ["launch %d" % i for i in range(launches_per_step)])
     launch_detail = []
-    if len(ms) == args.steps * launches_per_step and launches_per_step > 0:
-        per_ms = ms.reshape(args.steps, launches_per_step).mean(axis=0)
-        per_pairs = lp.reshape(args.steps, launches_per_step)[0].astype(np.float64)
-        per_bytes = lb.reshape(args.steps, launches_per_step)[0].astype(np.float64)
-        for name, t, n, nb in zip(names, per_ms, per_pairs, per_bytes):
-            log("  %-42s %.3f ms  %8.1f M pairs  reads %.2f GB: %.0f GB/s  (%.0f GB/s at 4 B per pair)" %
-                (name, t, n / 1e6, nb / 1e9, nb / t / 1e6, n * 4 / t / 1e6))
-            launch_detail.append({"kernel": name, "ms": float(t), "pairs": n, "bytes": nb,
-                                  "GB/s": nb / float(t) / 1e6, "GB/s_at_4B_per_pair": n * 4.0 / float(t) / 1e6})
+    per_ms = ms.reshape(args.steps, launches_per_step).mean(axis=0)
+    per_pairs = lp.reshape(args.steps, launches_per_step)[0].astype(np.float64)
+    per_bytes = lb.reshape(args.steps, launches_per_step)[0].astype(np.float64)
+    for name, t, n, nb in zip(names, per_ms, per_pairs, per_bytes):
+        log("  %-42s %.3f ms  %8.1f M pairs  reads %.2f GB: %.0f GB/s  (%.0f GB/s at 4 B per pair)" %
+            (name, t, n / 1e6, nb / 1e9, nb / t / 1e6, n * 4 / t / 1e6))
+        launch_detail.append({"kernel": name, "ms": float(t), "pairs": n, "bytes": nb,
+                              "GB/s": nb / float(t) / 1e6, "GB/s_at_4B_per_pair": n * 4.0 / float(t) / 1e6})
     # the dominant kernel: the launch that takes longest
-    dom = max(launch_detail, key=lambda d: d["ms"]) if launch_detail else None
+    dom = max(launch_detail, key=lambda d: d["ms"])
     kern_bytes = dom["bytes"] if dom else float("nan")
     kern_ms = dom["ms"] if dom else float("nan")
     achieved = dom["GB/s"] if dom else float("nan")
@@ -266,9 +274,12 @@ def main():
         "warmup": args.warmup, "ms_per_step": wall / args.steps * 1e3, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": label, "pairs_per_step": pairs, "bytes_per_step": bytes_step,
+                   "bytes_per_step_absmax": abs_bytes_step, "bytes_per_step_sens": sens_bytes_step,
                    "formats": ["E4M3" if f == 0 else "E5M2" for f in workload.fmts],
-                   "weights": "streaming mode: W re-read with each sample's gradient (4 B per pair)"},
+                   "weights": "resident mode: all R weight gradients of an op are in HBM, W is read "
+                              "once per batch of 8 samples; activations and BGEMM operands 4 B per pair"},
         "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBS,
+        "value_at_4B_per_pair": pairs * 4.0 * args.steps / wall / 1e9,
         "roofline": {"bound": "hbm", "kernel": dom["kernel"] if dom else None,
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(dom["kernel"] if dom else None, args.workload),
@@ -277,10 +288,10 @@ def main():
                               "except that the weight kernel reads W once per batch of 8 samples",
                      "all_fused_launches": {"ms_per_step": all_ms, "bytes_per_step": all_bytes, "GB/s": all_gbs,
                                             "frac": all_gbs / HBM_PEAK_GBS,
-                                            "GB/s_at_4B_per_pair": bytes_step / all_ms / 1e6},
+                                            "GB/s_at_4B_per_pair": pairs * 4.0 / all_ms / 1e6},
                      "launches_per_step": launch_detail},
-        "absmax": {"ms_per_step": abs_ms, "GB/s": abs_elems * 2.0 / (abs_ms * 1e-3) / 1e9,
-                   "bytes_per_step": abs_elems * 2.0},
+        "absmax": {"ms_per_step": abs_ms, "GB/s": abs_bytes_step / (abs_ms * 1e-3) / 1e9,
+                   "bytes_per_step": abs_bytes_step},
         "select": tail,
     }
     if not args.no_cpu_baseline:
