@@ -118,6 +118,39 @@ def sens_operand(x, dx, R, n, scale, inv, fmt, x_shared=False, causal=None):
     return E, A
 
 
+def absmax_scale_rows(x, n_rows, row_len, fmt, causal_rows=None):
+    """Per-row (amax, scale, inv) float32 arrays [n_rows] and the flag word.  causal_rows: the
+    operand is a stack of [causal_rows, row_len] matrices of which row i owns its first
+    i + 1 + (row_len - causal_rows) entries."""
+    x = _u16(x)
+    assert x.size >= n_rows * row_len
+    am = np.empty(n_rows, dtype=np.float32)
+    sc = np.empty(n_rows, dtype=np.float32)
+    iv = np.empty(n_rows, dtype=np.float32)
+    fl = C.c_uint32()
+    rc = lib().orc_absmax_scale_rows(_p(x, C.c_uint16), C.c_int64(n_rows), C.c_int64(row_len),
+                                     0 if causal_rows is None else 1, C.c_int64(causal_rows or 0), int(fmt),
+                                     _p(am, C.c_float), _p(sc, C.c_float), _p(iv, C.c_float), C.byref(fl))
+    assert rc == 0
+    return am, sc, iv, fl.value
+
+
+def sens_operand_rows(x, dx, n_rows, row_len, scale, inv, fmt, causal_rows=None):
+    """(E, A) of one sample's [n_rows, row_len] block, row i cast with scale[i], inv[i]."""
+    x, dx = _u16(x), _u16(dx)
+    scale = np.ascontiguousarray(scale, dtype=np.float32)
+    inv = np.ascontiguousarray(inv, dtype=np.float32)
+    assert x.size >= n_rows * row_len and dx.size >= n_rows * row_len
+    assert scale.size == n_rows and inv.size == n_rows
+    E, A = C.c_double(), C.c_double()
+    rc = lib().orc_sens_operand_rows(_p(x, C.c_uint16), _p(dx, C.c_uint16), C.c_int64(n_rows),
+                                     C.c_int64(row_len), 0 if causal_rows is None else 1,
+                                     C.c_int64(causal_rows or 0), _p(scale, C.c_float), _p(inv, C.c_float),
+                                     int(fmt), C.byref(E), C.byref(A))
+    assert rc == 0
+    return E.value, A.value
+
+
 def sens_linear(x, dx, w, dw, C_, K, R, row_off, x_scale, x_inv, w_scale, w_inv, fmt):
     """Returns out[R,4] = (E_X, A_X, E_W, A_W) per sample."""
     x, dx, w, dw = _u16(x), _u16(dx), _u16(w), _u16(dw)

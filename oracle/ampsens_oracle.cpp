@@ -327,6 +327,59 @@ int orc_sens_bgemm(const uint16_t* x0, const uint16_t* dx0, int64_t n0, int caus
     return 0;
 }
 
+// ---- scale per row (finer granularity than the tensor) ----------------------------------
+// The paper leaves the scale granularity open (it only mentions that scales exist, Sec. 3.1).
+// Per-row scales: the operand is a [n_rows, row_len] array (token x channel activations: one
+// scale per token; a weight [K, C]: one scale per output channel) and row i is cast with
+// its own scale_i = amax_i / FMAX, inv_i = FMAX / amax_i, the same two fp32 divisions as for a
+// whole tensor.  causal: n_rows = (number of matrices) * rows, row_len = cols, and row rho of
+// matrix rho / rows owns its first causal_row_len(rho % rows) entries.
+
+int orc_absmax_scale_rows(const uint16_t* x, int64_t n_rows, int64_t row_len, int causal,
+                          int64_t rows, int fmt, float* amax_out, float* scale_out,
+                          float* inv_out, uint32_t* flags_out) {
+    uint32_t flags = 0;
+    Layout L{0, 1, rows, row_len, 1};
+    for (int64_t rho = 0; rho < n_rows; ++rho) {
+        int64_t len = causal ? causal_row_len(L, rho % rows) : row_len;
+        uint32_t fl = 0;
+        int rc = orc_absmax_scale(x + rho * row_len, len, 0, 0, 0, 0, fmt, &amax_out[rho],
+                                  &scale_out[rho], &inv_out[rho], &fl);
+        if (rc) return rc;
+        flags |= fl;
+    }
+    *flags_out = flags;
+    return 0;
+}
+
+// E and A of one sample's block [n_rows, row_len] with one (scale, inv) per row.
+int orc_sens_operand_rows(const uint16_t* x, const uint16_t* dx, int64_t n_rows,
+                          int64_t row_len, int causal, int64_t rows, const float* scale,
+                          const float* inv, int fmt, double* out_E, double* out_A) {
+    Fmt f;
+    if (!fmt_of(fmt, &f)) return 1;
+    Layout L{0, 1, rows, row_len, 1};
+    double E = 0.0, A = 0.0;
+    for (int64_t rho = 0; rho < n_rows; ++rho) {
+        int64_t len = causal ? causal_row_len(L, rho % rows) : row_len;
+        for (int64_t j = 0; j < len; ++j) {
+            int64_t idx = rho * row_len + j;
+            float xf = bf16_val(x[idx]);
+            float gf = bf16_val(dx[idx]);
+            float y = xf * inv[rho];                        // the one fp32 multiply
+            double q = fp8_value(f, fp8_encode(f, y));
+            double e = (double)xf - q * (double)scale[rho];
+            double t = (double)gf * e;
+            E += t * t;
+            double a = (double)gf * (double)xf;
+            A += a * a;
+        }
+    }
+    *out_E = E;
+    *out_A = A;
+    return 0;
+}
+
 // ---- epilogue (Sec. 2.2) ---------------------------------------------------------------
 
 // s_l = (1/R) sum_r (A_0^r + A_1^r);  returns s_l.

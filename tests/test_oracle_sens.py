@@ -247,3 +247,105 @@ def test_epilogue_mean_sensitivity_and_group_mse():
         digits = [(p // 3 ** l) % 3 for l in range(3)]
         assert d[p] == pytest.approx(sum(s[l] * alphas[digits[l]] for l in range(3)), rel=1e-15)
     assert d[26] == pytest.approx(10.0 / 192.0, rel=1e-15)
+
+
+# ---- one scale per row ---------------------------------------------------------------------------
+
+def rows_hand_case():
+    c = {}
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "sens_rows_hand_case.txt")):
+        tok = line.split("#")[0].split()
+        if tok:
+            c[tok[0]] = [float(t) for t in tok[1:]]
+    return c
+
+
+def test_rows_hand_worked_sums():
+    c = rows_hand_case()
+    n_rows, row_len = int(c["rows"][0]), int(c["rows"][1])
+    x = f32_to_bf16_bits(np.array(c["x"], dtype=np.float32))
+    g = f32_to_bf16_bits(np.array(c["xdot"], dtype=np.float32))
+    assert np.array_equal(bf16_bits_to_f64(x), np.array(c["x"]))
+    E, A = oracle.sens_operand_rows(x, g, n_rows, row_len, c["scale"], c["inv"], oracle.E4M3)
+    assert E == c["E"][0] and A == c["A"][0]
+    # a row paired with the other row's scale is a different, also hand-worked, number
+    E2, A2 = oracle.sens_operand_rows(x, g, n_rows, row_len, c["scale"][::-1], c["inv"][::-1], oracle.E4M3)
+    assert E2 == c["E_exchanged"][0] and A2 == c["A"][0]
+
+
+@pytest.mark.parametrize("fmt", [oracle.E4M3, oracle.E5M2])
+def test_rows_with_one_common_scale_is_the_per_tensor_sum(fmt):
+    rng = np.random.default_rng(11)
+    n_rows, row_len = 7, 53
+    x, g = rand_bf16(rng, n_rows * row_len), rand_bf16(rng, n_rows * row_len, 1e-2)
+    am, sc, iv, fl = oracle.absmax_scale(x, fmt)
+    E, A = oracle.sens_operand(x, g, 1, x.size, sc, iv, fmt)
+    Er, Ar = oracle.sens_operand_rows(x, g, n_rows, row_len, np.full(n_rows, sc), np.full(n_rows, iv), fmt)
+    assert Er == pytest.approx(E[0], rel=1e-14) and Ar == pytest.approx(A[0], rel=1e-14)
+
+
+@pytest.mark.parametrize("fmt", [oracle.E4M3, oracle.E5M2])
+def test_rows_is_the_sum_over_rows_each_cast_as_its_own_tensor(fmt):
+    rng = np.random.default_rng(12)
+    n_rows, row_len = 9, 40
+    x = f32_to_bf16_bits((rng.standard_normal((n_rows, row_len)) *
+                          np.exp(rng.normal(0, 2, (n_rows, 1)))).astype(np.float32)).reshape(-1)
+    g = rand_bf16(rng, n_rows * row_len, 1e-2)
+    am, sc, iv, fl = oracle.absmax_scale_rows(x, n_rows, row_len, fmt)
+    xv = np.abs(bf16_bits_to_f64(x)).reshape(n_rows, row_len)
+    assert np.array_equal(am.astype(np.float64), xv.max(axis=1))
+    assert fl == 0
+    E = A = 0.0
+    for i in range(n_rows):
+        xi, gi = x[i * row_len:(i + 1) * row_len], g[i * row_len:(i + 1) * row_len]
+        a1, s1, i1, _ = oracle.absmax_scale(xi, fmt)
+        assert (a1, s1, i1) == (am[i], sc[i], iv[i])
+        e, a = oracle.sens_operand(xi, gi, 1, row_len, s1, i1, fmt)
+        E, A = E + e[0], A + a[0]
+    Er, Ar = oracle.sens_operand_rows(x, g, n_rows, row_len, sc, iv, fmt)
+    assert Er == pytest.approx(E, rel=1e-13) and Ar == pytest.approx(A, rel=1e-13)
+
+
+def test_rows_causal_rows_own_their_prefix_only():
+    rng = np.random.default_rng(13)
+    mats, rows, cols = 3, 5, 7                               # row i owns i + 3 entries
+    x = rand_bf16(rng, mats * rows * cols).reshape(mats, rows, cols)
+    g = rand_bf16(rng, mats * rows * cols, 1e-2).reshape(mats, rows, cols)
+    big = f32_to_bf16_bits(np.array([3e38], dtype=np.float32))[0]
+    lens = [min(cols, i + 1 + cols - rows) for i in range(rows)]
+    for i in range(rows):
+        x[:, i, lens[i]:] = big                              # junk outside the operand
+        g[:, i, lens[i]:] = big
+    fmt = oracle.E4M3
+    am, sc, iv, fl = oracle.absmax_scale_rows(x.reshape(-1), mats * rows, cols, fmt, causal_rows=rows)
+    assert fl == 0 and float(am.max()) < 10.0
+    E = A = 0.0
+    for m in range(mats):
+        for i in range(rows):
+            xi, gi = x[m, i, :lens[i]].copy(), g[m, i, :lens[i]].copy()
+            a1, s1, i1, _ = oracle.absmax_scale(xi, fmt)
+            assert (a1, s1, i1) == (am[m * rows + i], sc[m * rows + i], iv[m * rows + i])
+            e, a = oracle.sens_operand(xi, gi, 1, lens[i], s1, i1, fmt)
+            E, A = E + e[0], A + a[0]
+    Er, Ar = oracle.sens_operand_rows(x.reshape(-1), g.reshape(-1), mats * rows, cols, sc, iv, fmt, causal_rows=rows)
+    assert Er == pytest.approx(E, rel=1e-13) and Ar == pytest.approx(A, rel=1e-13)
+
+
+def test_rows_scale_removes_the_error_a_loud_row_causes_in_quiet_rows():
+    """Why finer granularity matters: with one scale for the tensor a row of large values pushes
+    the small rows into the subnormal range of the format; with a scale per row every row keeps
+    the relative accuracy of reading 6 (E <= 3 alpha A)."""
+    rng = np.random.default_rng(14)
+    n_rows, row_len = 4, 256
+    xv = rng.standard_normal((n_rows, row_len)).astype(np.float32)
+    xv[0] *= 2.0 ** 18
+    x = f32_to_bf16_bits(xv).reshape(-1)
+    g = f32_to_bf16_bits(np.ones(n_rows * row_len, dtype=np.float32))
+    fmt = oracle.E4M3
+    am, sc, iv, _ = oracle.absmax_scale(x, fmt)
+    Et, At = oracle.sens_operand(x[row_len:], g[row_len:], 1, 3 * row_len, sc, iv, fmt)
+    amr, scr, ivr, _ = oracle.absmax_scale_rows(x, n_rows, row_len, fmt)
+    Er, Ar = oracle.sens_operand_rows(x[row_len:], g[row_len:], 3, row_len, scr[1:], ivr[1:], fmt)
+    assert Ar == pytest.approx(At[0], rel=1e-14)
+    assert Er <= 3 * oracle.alpha(3) * Ar
+    assert Et[0] > 20 * Er
