@@ -16,7 +16,8 @@
  *                                         in place of the uniform-noise model, components taken
  *                                         as independent as the paper does.
  *
- *   ztilde is the per-tensor-absmax-scaled FP8 fake quantisation of z.  The paper names the
+ *   ztilde is the absmax-scaled FP8 fake quantisation of z, with one scale per tensor or,
+ *   optionally, one per row (see "scale granularity" below).  The paper names the
  *   format only as "FP8-E4M3: 4 exponent, 3 mantissa bits" (Sec. 3.1) and does not describe
  *   the cast; this library uses the OCP 8-bit formats (E4M3: max 448, no infinities; E5M2:
  *   max 57344), round to nearest even, saturating:
@@ -74,6 +75,18 @@ typedef enum amp_fp8_format {
 
 #define AMP_MAX_FORMATS 2
 
+/* Scale granularity.  The paper does not say at which granularity its FP8 casts are scaled (Sec. 3.1
+ * only mentions that scales exist).  By default every operand buffer has one scale per candidate
+ * format.  With a bit of `scale_rows` set in a descriptor, the operand is a [rows, row_len] array
+ * and row i is cast with its own scale: per token for the activations X of a linear layer
+ * (row_len = C), per output channel for its weight W [K, C], per row of a BGEMM operand.  The
+ * scale / reciprocal arrays of that operand are then device tables [rows][n_fmts] covering all
+ * samples (X: rows_total rows; W: K rows shared by the samples; BGEMM: R * rows-per-sample rows),
+ * as amp_absmax_scale_rows writes them.  Fast path: row_len a multiple of 8 and 16-byte aligned
+ * buffers; anything else is computed element by element. */
+#define AMP_ROWS_OPERAND0 1          /* X of a linear layer / X0 of a BGEMM */
+#define AMP_ROWS_OPERAND1 2          /* W of a linear layer / X1 of a BGEMM */
+
 /* Shape of one sample's block of an operand.
  * causal == 0: n_elems consecutive elements (batch/rows/cols ignored).
  * causal == 1: a [batch, rows, cols] array of which entry (b, i, j) belongs to the operand
@@ -84,7 +97,8 @@ typedef enum amp_fp8_format {
  *              spans batch*rows*cols elements. */
 typedef struct amp_layout {
     int64_t n_elems;
-    int64_t batch, rows, cols;
+    int64_t batch, rows, cols;       /* causal == 0: only cols is read, and only where rows matter (per-row
+                                        scales): the block is [n_elems / cols, cols] */
     int32_t causal;
     int32_t reserved;
 } amp_layout_t;
@@ -108,11 +122,13 @@ typedef struct amp_linear_desc {
     const int64_t* sample_row_offsets; /* HOST, R+1 non-decreasing entries, first 0: sample r owns
                                           rows [off[r], off[r+1]); NULL = equal blocks of `tokens` */
     int32_t R;
-    int32_t reserved;
-    const float* x_scale;            /* device [n_fmts]: scale of X per candidate format */
-    const float* x_inv;              /* device [n_fmts]: reciprocal scale of X */
-    const float* w_scale;            /* device [n_fmts] */
-    const float* w_inv;              /* device [n_fmts] */
+    int32_t scale_rows;              /* 0, or AMP_ROWS_OPERAND0 (one scale per token) | AMP_ROWS_OPERAND1
+                                        (one per output channel) */
+    const float* x_scale;            /* device [n_fmts]: scale of X per candidate format
+                                        (per token: [rows_total][n_fmts]) */
+    const float* x_inv;              /* device, same shape: reciprocal scale of X */
+    const float* w_scale;            /* device [n_fmts] (per output channel: [K][n_fmts]) */
+    const float* w_inv;              /* device, same shape */
 } amp_linear_desc_t;
 
 /* BGEMM (Sec. 2.2 eq. (bgemm_layer)); both operands carry one block per sample. */
@@ -123,8 +139,9 @@ typedef struct amp_bgemm_desc {
     const uint16_t* dx1;
     amp_layout_t layout0, layout1;
     int32_t R;
-    int32_t reserved;
-    const float* scale0;             /* device [n_fmts] */
+    int32_t scale_rows;              /* 0, or AMP_ROWS_OPERAND0 | AMP_ROWS_OPERAND1: one scale per row of
+                                        that operand; a dense layout then gives its row length in cols */
+    const float* scale0;             /* device [n_fmts] (per row: [R * rows per sample][n_fmts]) */
     const float* inv0;
     const float* scale1;
     const float* inv1;
@@ -143,6 +160,19 @@ amp_status_t amp_absmax_scale(const amp_tensor_t* tensors /* host array */, int 
                               const amp_fp8_format_t* fmts /* host */, int n_fmts,
                               float* d_amax, float* d_scale, float* d_inv, uint32_t* d_flags,
                               void* workspace, size_t workspace_bytes, void* stream);
+
+/* The same per row (scale granularity above): tensor t is n_samples blocks of `layout`, seen as
+ * rows of layout.cols entries (a causal row owns its valid prefix only).  With row_base(t) = rows
+ * of the tensors before t,
+ *   d_amax[row_base(t) + i], d_scale[(row_base(t) + i) * n_fmts + f], d_inv[...] as above per row,
+ *   d_flags[t] = bit 0 set iff a NaN or Inf was seen anywhere in tensor t.
+ * amp_absmax_rows_workspace_bytes also reports the total number of rows (n_rows, may be NULL). */
+amp_status_t amp_absmax_rows_workspace_bytes(const amp_tensor_t* tensors, int n_tensors, size_t* bytes,
+                                             int64_t* n_rows);
+amp_status_t amp_absmax_scale_rows(const amp_tensor_t* tensors /* host array */, int n_tensors,
+                                   const amp_fp8_format_t* fmts /* host */, int n_fmts,
+                                   float* d_amax, float* d_scale, float* d_inv, uint32_t* d_flags,
+                                   void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---- step 2 (standalone): FP8 fake quantisation ------------------------------------------
  *   d_codes[i]   = RNE_sat_f(fl32(x_i * inv_scale))      (uint8 FP8 code)

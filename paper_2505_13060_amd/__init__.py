@@ -15,6 +15,8 @@ from . import build as _build
 E4M3 = 0
 E5M2 = 1
 MAX_FORMATS = 2
+ROWS_OPERAND0 = 1          # one scale per row of X (linear) / X0 (BGEMM)
+ROWS_OPERAND1 = 2          # one scale per row of W (linear) / X1 (BGEMM)
 
 OK, ERR_INVALID_ARG, ERR_BAD_FORMAT, ERR_WORKSPACE_TOO_SMALL, ERR_NONFINITE_INPUT, ERR_DEVICE, \
     ERR_INFEASIBLE, ERR_TOO_LARGE = range(8)
@@ -42,13 +44,13 @@ class LinearDesc(C.Structure):
     _fields_ = [("x", C.c_void_p), ("dx", C.c_void_p), ("w", C.c_void_p), ("dw", C.c_void_p),
                 ("C", C.c_int64), ("K", C.c_int64), ("tokens", C.c_int64),
                 ("sample_row_offsets", C.POINTER(C.c_int64)), ("R", C.c_int32),
-                ("reserved", C.c_int32), ("x_scale", C.c_void_p), ("x_inv", C.c_void_p),
+                ("scale_rows", C.c_int32), ("x_scale", C.c_void_p), ("x_inv", C.c_void_p),
                 ("w_scale", C.c_void_p), ("w_inv", C.c_void_p)]
 
 
 class BgemmDesc(C.Structure):
     _fields_ = [("x0", C.c_void_p), ("dx0", C.c_void_p), ("x1", C.c_void_p), ("dx1", C.c_void_p),
-                ("layout0", Layout), ("layout1", Layout), ("R", C.c_int32), ("reserved", C.c_int32),
+                ("layout0", Layout), ("layout1", Layout), ("R", C.c_int32), ("scale_rows", C.c_int32),
                 ("scale0", C.c_void_p), ("inv0", C.c_void_p), ("scale1", C.c_void_p),
                 ("inv1", C.c_void_p)]
 
@@ -74,6 +76,9 @@ def lib():
                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
                                        C.c_void_p]
         L.amp_absmax_workspace_bytes.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_size_t)]
+        L.amp_absmax_scale_rows.argtypes = L.amp_absmax_scale.argtypes
+        L.amp_absmax_rows_workspace_bytes.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_size_t),
+                                                      C.POINTER(C.c_int64)]
         for name in ("amp_sens_linear", "amp_sens_bgemm"):
             getattr(L, name).argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p,
                                          C.c_void_p, C.c_size_t, C.c_void_p]
@@ -103,8 +108,9 @@ def _ptr(t):
     return None if t is None else t.data_ptr()
 
 
-def dense(n_elems):
-    return Layout(int(n_elems), 0, 0, 0, 0, 0)
+def dense(n_elems, cols=0):
+    """cols: row length, needed only where the operand has one scale per row."""
+    return Layout(int(n_elems), 0, 0, int(cols), 0, 0)
 
 
 def causal(batch, rows, cols):
@@ -117,8 +123,9 @@ def tensor(data, layout, n_samples=1):
 
 
 def linear_desc(x, dx, w, dw, C_, K, R, x_scale, x_inv, w_scale, w_inv, tokens=0,
-                sample_row_offsets=None):
+                sample_row_offsets=None, scale_rows=0):
     d = LinearDesc()
+    d.scale_rows = int(scale_rows)
     d.x, d.dx, d.w, d.dw = _ptr(x), _ptr(dx), _ptr(w), _ptr(dw)
     d.C, d.K, d.tokens, d.R = int(C_), int(K), int(tokens), int(R)
     if sample_row_offsets is not None:
@@ -129,8 +136,9 @@ def linear_desc(x, dx, w, dw, C_, K, R, x_scale, x_inv, w_scale, w_inv, tokens=0
     return d
 
 
-def bgemm_desc(x0, dx0, layout0, x1, dx1, layout1, R, scale0, inv0, scale1, inv1):
+def bgemm_desc(x0, dx0, layout0, x1, dx1, layout1, R, scale0, inv0, scale1, inv1, scale_rows=0):
     d = BgemmDesc()
+    d.scale_rows = int(scale_rows)
     d.x0, d.dx0, d.x1, d.dx1 = _ptr(x0), _ptr(dx0), _ptr(x1), _ptr(dx1)
     d.layout0, d.layout1, d.R = layout0, layout1, int(R)
     d.scale0, d.inv0, d.scale1, d.inv1 = _ptr(scale0), _ptr(inv0), _ptr(scale1), _ptr(inv1)
@@ -160,6 +168,24 @@ def amp_absmax_scale(tensors, fmts, d_amax, d_scale, d_inv, d_flags, workspace, 
                                   _ptr(d_scale), _ptr(d_inv), _ptr(d_flags), _ptr(workspace),
                                   workspace.numel() * workspace.element_size(), _stream(stream)),
            "amp_absmax_scale")
+
+
+def amp_absmax_rows_workspace_bytes(tensors):
+    """Returns (workspace bytes, total number of rows)."""
+    n, rows = C.c_size_t(), C.c_int64()
+    _check(lib().amp_absmax_rows_workspace_bytes(_array(Tensor, tensors), len(tensors), C.byref(n),
+                                                 C.byref(rows)), "amp_absmax_rows_workspace_bytes")
+    return n.value, rows.value
+
+
+def amp_absmax_scale_rows(tensors, fmts, d_amax, d_scale, d_inv, d_flags, workspace, stream=None):
+    """One scale per row: d_amax [rows] f32, d_scale / d_inv [rows, n_fmts] f32 over the rows of all
+    tensors in order, d_flags [n_tensors] i32."""
+    f, nf = _fmts(fmts)
+    _check(lib().amp_absmax_scale_rows(_array(Tensor, tensors), len(tensors), f, nf, _ptr(d_amax),
+                                       _ptr(d_scale), _ptr(d_inv), _ptr(d_flags), _ptr(workspace),
+                                       workspace.numel() * workspace.element_size(), _stream(stream)),
+           "amp_absmax_scale_rows")
 
 
 def amp_fake_quant_fp8(d_x, n, scale, inv_scale, fmt, d_codes, d_dequant=None, stream=None):

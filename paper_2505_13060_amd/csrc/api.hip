@@ -68,15 +68,22 @@ struct WorkTable {
     std::vector<uint32_t> group;                  // units with the same non-zero id share their x
     uint64_t n_chunks = 0;
     uint64_t n_pairs = 0;                         // elements that belong to the operands
+    bool any_rows = false;                        // some unit has one scale per row
 
     // x / dx may be null only for blocks without elements.
     amp_status_t add(const uint16_t* x, const uint16_t* dx, const amp_layout_t& L, int64_t batch_mul,
                      const float* scale, const float* inv, uint32_t out, uint32_t extra_flags = 0,
-                     uint32_t group_id = 0) {
+                     uint32_t group_id = 0, int64_t row_len = 0) {
+        // row_len != 0: scale / inv are [rows][n_fmts] tables starting at this unit's first row;
+        // a dense unit is [n / row_len, row_len], a causal unit uses its own rows (row_len = cols).
         WorkUnit u;
         std::memset(&u, 0, sizeof(u));
         u.x = x; u.dx = dx; u.scale = scale; u.inv = inv; u.out = out;
         u.flags = extra_flags;
+        if (row_len != 0) {
+            u.flags |= kUnitRowScale;
+            any_rows = true;
+        }
         uint64_t chunks;
         if (L.causal) {
             const int64_t batch = L.batch * batch_mul;
@@ -102,6 +109,13 @@ struct WorkTable {
             const uint32_t hx = (uint32_t)(((uintptr_t)x % 16) / 2);
             const bool mutual = dx == nullptr || ((uintptr_t)x % 16) == ((uintptr_t)dx % 16);
             if (mutual) u.head = hx; else { u.flags |= kUnitScalar; u.head = 0; }
+            if (row_len != 0) {
+                if (row_len < 0 || row_len > kMaxDim || n % row_len != 0) return AMP_ERR_INVALID_ARG;
+                if (n / row_len > 0x7FFFFFFFll) return AMP_ERR_TOO_LARGE;
+                u.cols = (int32_t)row_len;
+                // rows must be made of whole vectors for the vector path
+                if (row_len % kVec != 0 || u.head != 0) { u.flags |= kUnitScalar; u.head = 0; }
+            }
             u.chunks_per_mat = 1;
             chunks = unit_chunks_dense(n, u.head);
             n_pairs += (uint64_t)n;
@@ -170,6 +184,7 @@ struct WorkTable {
                     const WorkUnit& w = units[members[m]];
                     ok = w.flags == units[u].flags && (w.flags & (kUnitCausal | kUnitScalar)) == 0 &&
                          w.head == 0 && w.x == units[u].x && w.n == units[u].n &&
+                         w.scale == units[u].scale && w.inv == units[u].inv && w.cols == units[u].cols &&
                          members[m] == u + m * stride;
                 }
                 const uint64_t whole = (uint64_t)units[u].n / ((uint64_t)kChunkVecs * kVec);
@@ -233,30 +248,30 @@ int persistent_grid(uint64_t n_chunks, int resident) {
     return (int)(n_chunks < cap ? n_chunks : cap);
 }
 
-int sens_grid(uint64_t n_chunks, int n_fmts, int f0, int f1) {
+int sens_grid(uint64_t n_chunks, int n_fmts, int f0, int f1, int rows) {
     static std::mutex mu;
-    static int cached[64][2][2][2];
+    static int cached[64][2][2][2][2];
     const int dev = device_index();
     int resident;
     if (dev < 0) {
-        resident = sens_resident_blocks(n_fmts, f0, f1, device_cus());
+        resident = sens_resident_blocks(n_fmts, f0, f1, rows, device_cus());
     } else {
         std::lock_guard<std::mutex> lock(mu);
-        int& slot = cached[dev][n_fmts - 1][f0][f1];
-        if (slot == 0) slot = sens_resident_blocks(n_fmts, f0, f1, device_cus());
+        int& slot = cached[dev][n_fmts - 1][f0][f1][rows];
+        if (slot == 0) slot = sens_resident_blocks(n_fmts, f0, f1, rows, device_cus());
         resident = slot;
     }
     return persistent_grid(n_chunks, resident);
 }
 
-int sens_w_grid(int n_fmts, int f0, int f1) {
+int sens_w_grid(int n_fmts, int f0, int f1, int rows) {
     static std::mutex mu;
-    static int cached[64][2][2][2];
+    static int cached[64][2][2][2][2];
     const int dev = device_index();
-    if (dev < 0) return sens_w_resident_blocks(n_fmts, f0, f1, device_cus());
+    if (dev < 0) return sens_w_resident_blocks(n_fmts, f0, f1, rows, device_cus());
     std::lock_guard<std::mutex> lock(mu);
-    int& slot = cached[dev][n_fmts - 1][f0][f1];
-    if (slot == 0) slot = sens_w_resident_blocks(n_fmts, f0, f1, device_cus());
+    int& slot = cached[dev][n_fmts - 1][f0][f1][rows];
+    if (slot == 0) slot = sens_w_resident_blocks(n_fmts, f0, f1, rows, device_cus());
     return slot;
 }
 
@@ -349,7 +364,8 @@ amp_status_t run_sens(const WorkTable& t, const amp_fp8_format_t* fmts, int n_fm
     float* d_partials = (float*)(ws + L.partials);
     const UnitSchedule* d_sch = (const UnitSchedule*)(ws + t.schedule_offset());
     const WGroup* d_groups = (const WGroup*)(ws + t.groups_offset());
-    AMP_HIP(launch_prepare(d_units, d_cb, d_sch, n_units, n_chunks, n_fmts, d_runits, d_map, stream));
+    const int rows = t.any_rows ? 1 : 0;
+    AMP_HIP(launch_prepare(d_units, d_cb, d_sch, n_units, n_chunks, n_fmts, rows, d_runits, d_map, stream));
     auto timed_begin = [&](uint64_t pairs, uint64_t bytes) -> hipError_t {
         if (g_profile.used >= (int)g_profile.start.size()) return hipSuccess;
         g_profile.pairs[g_profile.used] = pairs;
@@ -361,16 +377,16 @@ amp_status_t run_sens(const WorkTable& t, const amp_fp8_format_t* fmts, int n_fm
         return hipEventRecord(g_profile.stop[g_profile.used++], stream);
     };
     if (plan.n_items > 0) {
-        const int grid = persistent_grid(plan.n_items, sens_w_grid(n_fmts, f0, f1));
+        const int grid = persistent_grid(plan.n_items, sens_w_grid(n_fmts, f0, f1, rows));
         AMP_HIP(timed_begin(plan.w_pairs, plan.w_bytes));
         AMP_HIP(launch_sens_w(d_groups, (uint32_t)plan.wgroups.size(), (uint32_t)plan.n_items, d_runits, d_cb,
-                              n_fmts, f0, f1, d_partials, grid, stream));
+                              n_fmts, f0, f1, rows, d_partials, grid, stream));
         AMP_HIP(timed_end());
     }
     if (plan.n_positions > 0) {
-        const int grid = sens_grid(plan.n_positions, n_fmts, f0, f1);
+        const int grid = sens_grid(plan.n_positions, n_fmts, f0, f1, rows);
         AMP_HIP(timed_begin(t.n_pairs - plan.w_pairs, (t.n_pairs - plan.w_pairs) * 4));
-        AMP_HIP(launch_sens(d_runits, d_map, (uint32_t)plan.n_positions, n_fmts, f0, f1, d_partials, grid, stream));
+        AMP_HIP(launch_sens(d_runits, d_map, (uint32_t)plan.n_positions, n_fmts, f0, f1, rows, d_partials, grid, stream));
         AMP_HIP(timed_end());
     }
     AMP_HIP(launch_sens_finalize(d_runits, d_cb, n_units, n_fmts, d_partials, d_out, stream));
@@ -384,6 +400,9 @@ amp_status_t build_linear(const amp_linear_desc_t* ops, int n_ops, int n_fmts, W
     for (int k = 0; k < n_ops; ++k) {
         const amp_linear_desc_t& op = ops[k];
         if (op.R < 0 || op.C < 0 || op.K < 0 || op.tokens < 0) return AMP_ERR_INVALID_ARG;
+        if (op.scale_rows & ~(AMP_ROWS_OPERAND0 | AMP_ROWS_OPERAND1)) return AMP_ERR_INVALID_ARG;
+        const bool x_rows = (op.scale_rows & AMP_ROWS_OPERAND0) != 0, w_rows = (op.scale_rows & AMP_ROWS_OPERAND1) != 0;
+        if ((x_rows || w_rows) && op.C > kMaxDim) return AMP_ERR_TOO_LARGE;
         if (op.C > kMaxElems || op.K > kMaxElems || (op.C && op.K > kMaxElems / op.C)) return AMP_ERR_TOO_LARGE;
         if (!aligned2(op.x) || !aligned2(op.dx) || !aligned2(op.w) || !aligned2(op.dw)) return AMP_ERR_INVALID_ARG;
         const int64_t wn = op.K * op.C;
@@ -407,15 +426,32 @@ amp_status_t build_linear(const amp_linear_desc_t* ops, int n_ops, int n_fmts, W
             if (o + 4 * n_fmts > 0xFFFFFFFFull) return AMP_ERR_TOO_LARGE;
             amp_layout_t Lx = {xn, 0, 0, 0, 0, 0};
             amp_layout_t Lw = {wn, 0, 0, 0, 0, 0};
+            const int64_t xs = x_rows ? r0 * n_fmts : 0;         // the sample's first token in the table
             amp_status_t st = t->add(xn ? op.x + r0 * op.C : op.x, xn ? op.dx + r0 * op.C : op.dx, Lx, 1,
-                                     op.x_scale, op.x_inv, (uint32_t)o);
+                                     op.x_scale ? op.x_scale + xs : op.x_scale, op.x_inv ? op.x_inv + xs : op.x_inv,
+                                     (uint32_t)o, 0u, 0u, x_rows && xn > 0 ? op.C : 0);
             if (st != AMP_OK) return st;
             st = t->add(op.w, wn ? op.dw + (int64_t)r * wn : op.dw, Lw, 1, op.w_scale, op.w_inv, (uint32_t)o + 2,
-                        op.R > 1 ? kUnitKeepX : 0u, op.R > 1 ? (uint32_t)k + 1u : 0u);
+                        op.R > 1 ? kUnitKeepX : 0u, op.R > 1 ? (uint32_t)k + 1u : 0u, w_rows && wn > 0 ? op.C : 0);
             if (st != AMP_OK) return st;
         }
         base += (uint64_t)op.R;
     }
+    return AMP_OK;
+}
+
+// Rows of one sample's block for per-row scales: a causal block has batch * rows rows of cols
+// entries; a dense block is [n_elems / cols, cols] and must say its row length in cols.
+amp_status_t row_geometry(const amp_layout_t& L, int64_t* row_len, int64_t* rows) {
+    if (L.causal) {
+        *row_len = L.cols;
+        *rows = L.batch * L.rows;
+        return AMP_OK;
+    }
+    if (L.n_elems == 0) { *row_len = 0; *rows = 0; return AMP_OK; }
+    if (L.cols <= 0 || L.cols > kMaxDim || L.n_elems % L.cols != 0) return AMP_ERR_INVALID_ARG;
+    *row_len = L.cols;
+    *rows = L.n_elems / L.cols;
     return AMP_OK;
 }
 
@@ -435,14 +471,27 @@ amp_status_t build_bgemm(const amp_bgemm_desc_t* ops, int n_ops, int n_fmts, Wor
         if (op.R > 0 && n0 > 0 && (!op.x0 || !op.dx0 || !op.scale0 || !op.inv0)) return AMP_ERR_INVALID_ARG;
         if (op.R > 0 && n1 > 0 && (!op.x1 || !op.dx1 || !op.scale1 || !op.inv1)) return AMP_ERR_INVALID_ARG;
         if (op.R > 0 && (n0 > kMaxElems / op.R || n1 > kMaxElems / op.R)) return AMP_ERR_TOO_LARGE;
+        if (op.scale_rows & ~(AMP_ROWS_OPERAND0 | AMP_ROWS_OPERAND1)) return AMP_ERR_INVALID_ARG;
+        int64_t len0 = 0, len1 = 0, rows0 = 0, rows1 = 0;    // row length and rows per sample, 0 = one scale
+        if (op.scale_rows & AMP_ROWS_OPERAND0) {
+            st = row_geometry(op.layout0, &len0, &rows0);
+            if (st != AMP_OK) return st;
+        }
+        if (op.scale_rows & AMP_ROWS_OPERAND1) {
+            st = row_geometry(op.layout1, &len1, &rows1);
+            if (st != AMP_OK) return st;
+        }
         for (int r = 0; r < op.R; ++r) {
             const uint64_t o = (base + r) * (uint64_t)n_fmts * 4;
             if (o + 4 * n_fmts > 0xFFFFFFFFull) return AMP_ERR_TOO_LARGE;
-            st = t->add(n0 ? op.x0 + r * n0 : op.x0, n0 ? op.dx0 + r * n0 : op.dx0, op.layout0, 1, op.scale0,
-                        op.inv0, (uint32_t)o);
+            const int64_t s0 = r * rows0 * n_fmts, s1 = r * rows1 * n_fmts;
+            st = t->add(n0 ? op.x0 + r * n0 : op.x0, n0 ? op.dx0 + r * n0 : op.dx0, op.layout0, 1,
+                        op.scale0 ? op.scale0 + s0 : op.scale0, op.inv0 ? op.inv0 + s0 : op.inv0, (uint32_t)o, 0u, 0u,
+                        n0 > 0 ? len0 : 0);
             if (st != AMP_OK) return st;
-            st = t->add(n1 ? op.x1 + r * n1 : op.x1, n1 ? op.dx1 + r * n1 : op.dx1, op.layout1, 1, op.scale1,
-                        op.inv1, (uint32_t)o + 2);
+            st = t->add(n1 ? op.x1 + r * n1 : op.x1, n1 ? op.dx1 + r * n1 : op.dx1, op.layout1, 1,
+                        op.scale1 ? op.scale1 + s1 : op.scale1, op.inv1 ? op.inv1 + s1 : op.inv1, (uint32_t)o + 2, 0u,
+                        0u, n1 > 0 ? len1 : 0);
             if (st != AMP_OK) return st;
         }
         base += (uint64_t)op.R;
@@ -478,11 +527,31 @@ struct ReplayCtx {
     int64_t span;
     uintptr_t addr;          // byte address the unit would have
     int64_t bad;
+    // row tracking as a context with one scale per row would do it; row_len 0 = no check
+    int32_t row_len = 0;
+    bool cursor_mode = false, have_row = false;
+    RowCursor cur;
+    int64_t row = 0;
+    __host__ __device__ void begin_dense(int64_t e0, int le) {
+        if (row_len > 0 && cursor_mode) cur.begin(e0, le, kWG * kVec, row_len);
+    }
+    __host__ __device__ void set_row(int64_t r) { row = r; have_row = true; }
+    // a vector that starts at element s is about to be consumed
+    __host__ __device__ void vector_row(int64_t s) {
+        if (row_len <= 0) return;
+        if (cursor_mode) {
+            if (cur.row != s / row_len || cur.col != s % row_len || cur.col + kVec > row_len) ++bad;
+            cur.advance();
+        } else if (!have_row || s / row_len != row || s % row_len + kVec > row_len) {
+            ++bad;
+        }
+    }
     __host__ __device__ void touch(int64_t e) { if (e < 0 || e >= span) ++bad; else ++counts[e]; }
     template <int U> __host__ __device__ void full(int64_t eu, int le, int64_t stride) {
         for (int k = 0; k < U; ++k) {
             const int64_t s = eu + le + k * stride;
             if ((addr + 2 * (uintptr_t)s) % 16) ++bad;
+            vector_row(s);
             for (int j = 0; j < kVec; ++j) touch(s + j);
         }
     }
@@ -492,11 +561,19 @@ struct ReplayCtx {
             const int64_t s = e + (int64_t)k * stride;
             if ((addr + 2 * (uintptr_t)s) % 16) ++bad;
             if (s < 0 || s + kVec > span) ++bad;              // the whole vector is fetched
+            vector_row(s);
             const int valid = (k == count - 1) ? tail : kVec;
             for (int j = 0; j < valid; ++j) touch(s + j);
         }
     }
-    __host__ __device__ void partial(int64_t e, int jlo, int jhi) { for (int j = jlo; j < jhi; ++j) touch(e + j); }
+    __host__ __device__ void partial(int64_t e, int jlo, int jhi) {
+        // element-wise contexts divide per element; a cursor context is never given a partial
+        // vector of a unit whose rows are whole vectors, except in causal chunks (explicit row)
+        if (row_len > 0 && cursor_mode) ++bad;
+        if (row_len > 0 && !cursor_mode && have_row)
+            for (int j = jlo; j < jhi; ++j) if ((e + j) / row_len != row) ++bad;
+        for (int j = jlo; j < jhi; ++j) touch(e + j);
+    }
 };
 
 
@@ -540,11 +617,100 @@ amp_status_t amp_absmax_scale(const amp_tensor_t* tensors, int n_tensors, const 
     ChunkRef* d_map = (ChunkRef*)(ws + L.map);
     uint32_t* d_partial_max = (uint32_t*)(ws + L.partials);
     const UnitSchedule* d_sch = (const UnitSchedule*)(ws + t.schedule_offset());
-    AMP_HIP(launch_prepare(d_units, d_cb, d_sch, n_units, n_chunks, 0, d_runits, d_map, stream));
+    AMP_HIP(launch_prepare(d_units, d_cb, d_sch, n_units, n_chunks, 0, 0, d_runits, d_map, stream));
     if (n_chunks > 0)
         AMP_HIP(launch_absmax(d_runits, d_map, n_chunks, d_partial_max, absmax_grid(n_chunks), stream));
     AMP_HIP(launch_absmax_finalize(d_cb, d_partial_max, n_tensors, n_fmts, (int)fmts[0],
                                    (int)fmts[n_fmts - 1], d_amax, d_scale, d_inv, d_flags, stream));
+    return AMP_OK;
+}
+
+// ---- absmax and scales per row ----------------------------------------------------------------
+namespace {
+struct RowPlan {
+    std::vector<RowTensor> tensors;
+    uint64_t n_items = 0, n_rows = 0;
+};
+
+amp_status_t build_absmax_rows(const amp_tensor_t* tensors, int n_tensors, RowPlan* P) {
+    if (n_tensors < 0 || (n_tensors > 0 && !tensors)) return AMP_ERR_INVALID_ARG;
+    for (int k = 0; k < n_tensors; ++k) {
+        const amp_tensor_t& T = tensors[k];
+        amp_status_t st = check_layout(T.layout);
+        if (st != AMP_OK) return st;
+        if (T.n_samples < 0 || !aligned2(T.data)) return AMP_ERR_INVALID_ARG;
+        int64_t row_len = 0, rows = 0;
+        st = row_geometry(T.layout, &row_len, &rows);
+        if (st != AMP_OK) return st;
+        if (rows > 0 && T.n_samples > kMaxElems / rows) return AMP_ERR_TOO_LARGE;
+        const int64_t n_rows = row_len > 0 ? rows * T.n_samples : 0;
+        if (n_rows > 0 && !T.data) return AMP_ERR_INVALID_ARG;
+        RowTensor R;
+        std::memset(&R, 0, sizeof(R));
+        R.x = T.data;
+        R.n_rows = n_rows;
+        R.row_len = (int32_t)row_len;
+        R.causal_rows = T.layout.causal ? (int32_t)T.layout.rows : 0;
+        R.aligned = ((uintptr_t)T.data % 16 == 0 && row_len % kVec == 0) ? 1u : 0u;
+        // about 8192 elements per work item, a whole number of rows
+        const int64_t per = row_len > 0 ? (8192 / row_len > 0 ? 8192 / row_len : 1) : 1;
+        R.rows_per_item = (uint32_t)per;
+        if (P->n_rows + (uint64_t)n_rows > 0xFFFFFFFFull) return AMP_ERR_TOO_LARGE;
+        R.out_row = (uint32_t)P->n_rows;
+        R.item_begin = (uint32_t)P->n_items;
+        P->n_rows += (uint64_t)n_rows;
+        P->n_items += ((uint64_t)n_rows + per - 1) / per;
+        if (P->n_items > kMaxChunks) return AMP_ERR_TOO_LARGE;
+        P->tensors.push_back(R);
+    }
+    return AMP_OK;
+}
+}  // namespace
+
+amp_status_t amp_absmax_rows_workspace_bytes(const amp_tensor_t* tensors, int n_tensors, size_t* bytes,
+                                             int64_t* n_rows) {
+    if (!bytes) return AMP_ERR_INVALID_ARG;
+    RowPlan P;
+    amp_status_t st = build_absmax_rows(tensors, n_tensors, &P);
+    if (st != AMP_OK) return st;
+    *bytes = round_up(P.tensors.size() * sizeof(RowTensor), 256);
+    if (n_rows) *n_rows = (int64_t)P.n_rows;
+    return AMP_OK;
+}
+
+amp_status_t amp_absmax_scale_rows(const amp_tensor_t* tensors, int n_tensors, const amp_fp8_format_t* fmts,
+                                   int n_fmts, float* d_amax, float* d_scale, float* d_inv, uint32_t* d_flags,
+                                   void* workspace, size_t workspace_bytes, void* stream_) {
+    amp_status_t st = check_fmts(fmts, n_fmts);
+    if (st != AMP_OK) return st;
+    RowPlan P;
+    st = build_absmax_rows(tensors, n_tensors, &P);
+    if (st != AMP_OK) return st;
+    if (n_tensors == 0) return AMP_OK;
+    if (!d_flags || (uintptr_t)d_flags % 4) return AMP_ERR_INVALID_ARG;
+    if (P.n_rows > 0 && (!d_amax || !d_scale || !d_inv)) return AMP_ERR_INVALID_ARG;
+    if (((uintptr_t)d_amax | (uintptr_t)d_scale | (uintptr_t)d_inv) % 4) return AMP_ERR_INVALID_ARG;
+    if (!workspace || (uintptr_t)workspace % 256) return AMP_ERR_INVALID_ARG;
+    const size_t bytes = P.tensors.size() * sizeof(RowTensor);
+    if (workspace_bytes < round_up(bytes, 256)) return AMP_ERR_WORKSPACE_TOO_SMALL;
+    hipStream_t stream = (hipStream_t)stream_;
+    AMP_HIP(hipMemcpyAsync(workspace, P.tensors.data(), bytes, hipMemcpyHostToDevice, stream));
+    const uint64_t waves = P.n_items;
+    const uint64_t wgs = (waves + kWaves - 1) / kWaves;
+    static std::mutex mu;
+    static int resident[64];
+    int res;
+    {
+        std::lock_guard<std::mutex> lock(mu);
+        const int dev = device_index();
+        int& slot = resident[dev < 0 ? 0 : dev];
+        if (slot == 0) slot = absmax_rows_resident_blocks(device_cus());
+        res = slot;
+    }
+    const int grid = persistent_grid(wgs > 0 ? wgs : 1, res);
+    AMP_HIP(launch_absmax_rows((const RowTensor*)workspace, (uint32_t)P.tensors.size(), (uint32_t)P.n_items,
+                               n_fmts, (int)fmts[0], (int)fmts[n_fmts - 1], d_amax, d_scale, d_inv, d_flags,
+                               grid, stream));
     return AMP_OK;
 }
 
@@ -704,6 +870,38 @@ void ampsens_debug_set_schedule_block(int block) { g_schedule_block = block; }
 
 // Test hook: cap the persistent grid (0 = default) to show that results do not depend on it.
 void ampsens_debug_set_grid_cap(int cap) { g_grid_cap = cap; }
+
+// row_len != 0 also replays the row tracking of a unit with one scale per row and counts every
+// vector whose tracked row differs from (element index / row_len), or that straddles two rows.
+int64_t ampsens_debug_replay_unit_rows(uint64_t x_addr, uint64_t dx_addr, const amp_layout_t* layout,
+                                       int64_t batch_mul, int64_t row_len, int32_t* counts, int64_t span,
+                                       uint64_t* n_chunks_out) {
+    WorkTable t;
+    if (t.add((const uint16_t*)(uintptr_t)x_addr, (const uint16_t*)(uintptr_t)dx_addr, *layout, batch_mul,
+              nullptr, nullptr, 0, 0u, 0u, row_len) != AMP_OK)
+        return -1;
+    std::vector<uint32_t> cb = t.chunk_begin;
+    cb.push_back((uint32_t)t.n_chunks);
+    const WorkUnit& u = t.units[0];
+    for (uint32_t c = 0; c < t.n_chunks; ++c) {
+        if (find_unit(cb.data(), 1, c) != 0) return -2;
+    }
+    int64_t bad = 0;
+    for (uint32_t c = 0; c < t.n_chunks; ++c) {
+        for (int tid = 0; tid < kWG; ++tid) {
+            ReplayCtx ctx{counts, span, (uintptr_t)x_addr, 0};
+            if (u.flags & kUnitRowScale) {
+                ctx.row_len = u.cols;
+                ctx.cursor_mode = !(u.flags & kUnitCausal) && !(u.flags & kUnitScalar);
+                if (!(u.flags & kUnitCausal) && (u.flags & kUnitScalar)) ctx.row_len = 0;   // divides per element
+            }
+            walk_chunk(u, c, tid, ctx);
+            bad += ctx.bad;
+        }
+    }
+    if (n_chunks_out) *n_chunks_out = t.n_chunks;
+    return bad;
+}
 
 int64_t ampsens_debug_replay_unit(uint64_t x_addr, uint64_t dx_addr, const amp_layout_t* layout,
                                   int64_t batch_mul, int32_t* counts, int64_t span, uint64_t* n_chunks_out) {

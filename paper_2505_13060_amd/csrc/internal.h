@@ -32,6 +32,9 @@ enum : uint32_t {
                                      // are not): every vector takes the guarded 2-byte path
     kUnitKeepX = 4u,                 // x is read again soon (a weight shared by the samples): load it
                                      // with ordinary caching; everything else streams non-temporally
+    kUnitRowScale = 8u,              // one scale per row: scale / inv point at [rows][n_fmts] tables whose
+                                     // first row is the unit's first row; dense units keep the row
+                                     // length in `cols`, causal units use their own rows and cols
 };
 
 struct alignas(16) WorkUnit {        // 64 bytes
@@ -61,8 +64,16 @@ struct alignas(16) ResolvedUnit {    // 64 bytes
     uint32_t head;
     uint32_t out;
     uint32_t chunks_per_mat;
-    float inv[kMaxFormats];
-    float scale[kMaxFormats];
+    union {
+        struct {                     // calls with one scale per tensor everywhere: the values
+            float inv[kMaxFormats];
+            float scale[kMaxFormats];
+        };
+        struct {                     // calls in which some unit has a scale per row: [rows][n_fmts]
+            const float* row_inv;    // tables (a per-tensor unit of such a call is a one-row table
+            const float* row_scale;  // with row length 0 = "every element is in row 0")
+        };
+    };
 };
 static_assert(sizeof(ResolvedUnit) == 64, "ResolvedUnit layout");
 
@@ -123,12 +134,16 @@ inline uint32_t causal_chunks_per_mat(int64_t rows) {
 // ---- launchers (kernels.hip) ---------------------------------------------------------------
 // All enqueue on `stream` and return the launch error, never synchronise.
 // Persistent-grid size for the streaming kernels on the current device (resident workgroups).
-int sens_resident_blocks(int n_fmts, int fmt0, int fmt1, int cus);
+// `rows`: the variant that reads its scales from row tables.
+int sens_resident_blocks(int n_fmts, int fmt0, int fmt1, int rows, int cus);
 int absmax_resident_blocks(int cus);
+int absmax_rows_resident_blocks(int cus);
 
+// row_tables != 0: keep the scale pointers (row tables) instead of resolving them to values.
 hipError_t launch_prepare(const WorkUnit* d_units, const uint32_t* d_chunk_begin,
                           const UnitSchedule* d_schedule, uint32_t n_units, uint32_t n_chunks,
-                          int n_fmts, ResolvedUnit* d_runits, ChunkRef* d_map, hipStream_t stream);
+                          int n_fmts, int row_tables, ResolvedUnit* d_runits, ChunkRef* d_map,
+                          hipStream_t stream);
 hipError_t launch_absmax(const ResolvedUnit* d_runits, const ChunkRef* d_map, uint32_t n_chunks,
                          uint32_t* d_partial_max, int grid, hipStream_t stream);
 hipError_t launch_absmax_finalize(const uint32_t* d_chunk_begin, const uint32_t* d_partial_max,
@@ -138,12 +153,31 @@ hipError_t launch_absmax_finalize(const uint32_t* d_chunk_begin, const uint32_t*
 hipError_t launch_fake_quant(const uint16_t* d_x, int64_t n, float scale, float inv, int fmt,
                              uint8_t* d_codes, float* d_dequant, int grid, hipStream_t stream);
 hipError_t launch_sens(const ResolvedUnit* d_runits, const ChunkRef* d_map, uint32_t n_chunks,
-                       int n_fmts, int fmt0, int fmt1, float* d_partials, int grid,
+                       int n_fmts, int fmt0, int fmt1, int rows, float* d_partials, int grid,
                        hipStream_t stream);
-int sens_w_resident_blocks(int n_fmts, int fmt0, int fmt1, int cus);
+int sens_w_resident_blocks(int n_fmts, int fmt0, int fmt1, int rows, int cus);
 hipError_t launch_sens_w(const WGroup* d_groups, uint32_t n_groups, uint32_t n_items,
                          const ResolvedUnit* d_runits, const uint32_t* d_chunk_begin, int n_fmts, int fmt0,
-                         int fmt1, float* d_partials, int grid, hipStream_t stream);
+                         int fmt1, int rows, float* d_partials, int grid, hipStream_t stream);
+
+// Per-row absmax (one scale per row).  One table entry per tensor; a work item is a run of
+// rows_per_item consecutive rows of one tensor and belongs to one wave.
+struct alignas(16) RowTensor {       // 48 bytes
+    const uint16_t* x;
+    int64_t n_rows;                  // all samples
+    int32_t row_len;                 // elements between row starts
+    int32_t causal_rows;             // 0: every row owns row_len entries; else rows per matrix, row i of a
+                                     // matrix owns its first i + 1 + (row_len - causal_rows) entries
+    uint32_t out_row;                // first row of this tensor in the output arrays
+    uint32_t item_begin;             // first work item of this tensor
+    uint32_t rows_per_item;
+    uint32_t aligned;                // rows start on 16-byte boundaries and row_len % 8 == 0
+    uint32_t reserved[2];
+};
+static_assert(sizeof(RowTensor) == 48, "RowTensor layout");
+hipError_t launch_absmax_rows(const RowTensor* d_tensors, uint32_t n_tensors, uint32_t n_items,
+                              int n_fmts, int fmt0, int fmt1, float* d_amax, float* d_scale,
+                              float* d_inv, uint32_t* d_flags, int grid, hipStream_t stream);
 hipError_t launch_sens_finalize(const ResolvedUnit* d_runits, const uint32_t* d_chunk_begin,
                                 uint32_t n_units, int n_fmts, const float* d_partials,
                                 float* d_out, hipStream_t stream);

@@ -33,6 +33,8 @@ typedef float float2_t __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));             // one 128-bit load
 typedef const uint16_t __attribute__((address_space(1)))* gptr16_t;   // global address space
 typedef const u32x4 __attribute__((address_space(1)))* gptr128_t;
+typedef const float __attribute__((address_space(1)))* gptrf_t;
+typedef const float2_t __attribute__((address_space(1)))* gptrf2_t;
 
 template <int FMT> struct Fp8;
 template <> struct Fp8<0> {                       // OCP E4M3
@@ -135,6 +137,7 @@ __global__ __launch_bounds__(kWG) void prepare_kernel(const WorkUnit* __restrict
                                                       const uint32_t* __restrict__ chunk_begin,
                                                       const UnitSchedule* __restrict__ schedule,
                                                       uint32_t n_units, uint32_t n_chunks, int n_fmts,
+                                                      int row_tables,
                                                       ResolvedUnit* __restrict__ runits,
                                                       ChunkRef* __restrict__ map) {
     const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -143,10 +146,15 @@ __global__ __launch_bounds__(kWG) void prepare_kernel(const WorkUnit* __restrict
         ResolvedUnit r;
         r.x = u.x; r.dx = u.dx; r.n = u.n; r.rows = u.rows; r.cols = u.cols; r.flags = u.flags;
         r.head = u.head; r.out = u.out; r.chunks_per_mat = u.chunks_per_mat;
-        for (int f = 0; f < kMaxFormats; ++f) {
-            const bool have = f < n_fmts && u.inv != nullptr && u.scale != nullptr;
-            r.inv[f] = have ? u.inv[f] : 1.0f;
-            r.scale[f] = have ? u.scale[f] : 1.0f;
+        if (row_tables) {
+            r.row_inv = u.inv;
+            r.row_scale = u.scale;
+        } else {
+            for (int f = 0; f < kMaxFormats; ++f) {
+                const bool have = f < n_fmts && u.inv != nullptr && u.scale != nullptr;
+                r.inv[f] = have ? u.inv[f] : 1.0f;
+                r.scale[f] = have ? u.scale[f] : 1.0f;
+            }
         }
         runits[i] = r;
     }
@@ -166,21 +174,12 @@ __global__ __launch_bounds__(kWG) void prepare_kernel(const WorkUnit* __restrict
 
 // ---- the fused sensitivity pass --------------------------------------------------------------
 
-template <int NF, int F0, int F1>
-struct SensCtx {
-    gptr16_t x;
-    gptr16_t g;
-    bool keep_x;                                   // x is re-read soon: ordinary caching
-    float inv[NF], scale[NF];
-    float E[NF];
-    float A;
-    int pk[NF];                                    // conversion scratch, carried so that the packed
-                                                   // converts never need a cleared destination
-
-    // Four elements (two input words) of one format.
-    template <int F>
-    __device__ __forceinline__ void one_format(const float (&xv)[4], const float (&gv)[4], float iv,
-                                               float sc, float& Ef, int& p) {
+// Four elements (two input words) of one format; p is conversion scratch, carried so that the
+// packed converts never need a cleared destination.
+template <int F>
+__device__ __forceinline__ void one_format(const float (&xv)[4], const float (&gv)[4], float iv,
+                                           float sc, float& Ef, int& p) {
+    {
         const float y0 = clamp_fmax<F>(xv[0] * iv);
         const float y1 = clamp_fmax<F>(xv[1] * iv);
         const float y2 = clamp_fmax<F>(xv[2] * iv);
@@ -199,6 +198,33 @@ struct SensCtx {
         Ef = fmaf(t2, t2, Ef);
         Ef = fmaf(t3, t3, Ef);
     }
+}
+
+template <int NF, int F0, int F1>
+struct SensCtx {
+    gptr16_t x;
+    gptr16_t g;
+    bool keep_x;                                   // x is re-read soon: ordinary caching
+    float inv[NF], scale[NF];
+    float E[NF];
+    float A;
+    int pk[NF];
+
+    __device__ __forceinline__ void init(const ResolvedUnit& u) {
+        x = (gptr16_t)u.x;
+        g = (gptr16_t)u.dx;
+        keep_x = (u.flags & kUnitKeepX) != 0;
+#pragma unroll
+        for (int f = 0; f < NF; ++f) {
+            inv[f] = u.inv[f];
+            scale[f] = u.scale[f];
+            E[f] = 0.0f;
+            pk[f] = 0;
+        }
+        A = 0.0f;
+    }
+    __device__ __forceinline__ void begin_dense(int64_t, int) {}
+    __device__ __forceinline__ void set_row(int64_t) {}
 
     __device__ __forceinline__ void quad(uint32_t xw0, uint32_t xw1, uint32_t gw0, uint32_t gw1) {
         const float xv[4] = {bf16_lo(xw0), bf16_hi(xw0), bf16_lo(xw1), bf16_hi(xw1)};
@@ -267,10 +293,191 @@ struct SensCtx {
     }
 };
 
+// The same pass with one scale per row (per-token activations, per-channel weights, rows of a
+// BGEMM operand).  Scales come from [rows][NF] tables.  Three ways to know a vector's row:
+//   dense, rows made of whole vectors: a RowCursor follows the thread's strided walk and the
+//       scales of every vector are fetched (they sit in L1/L2: a row's entry serves row_len/8 vectors);
+//   causal: the walker names the row of the vectors that follow, its scales are fetched once;
+//   dense, rows not made of whole vectors: element by element, one division per element (slow,
+//       only for odd row lengths or misaligned buffers).
+// A unit of such a call that has one scale for the whole tensor is a table of one row.
 template <int NF, int F0, int F1>
-__global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) void sens_kernel(const ResolvedUnit* __restrict__ runits,
-                                                   const ChunkRef* __restrict__ map,
-                                                   uint32_t n_chunks, float* __restrict__ partials) {
+struct SensRowCtx {
+    enum Mode { kRow, kCursor, kElem };
+    gptr16_t x;
+    gptr16_t g;
+    bool keep_x;
+    gptrf_t ri;                                    // inv[row][NF]
+    gptrf_t rs;                                    // scale[row][NF]
+    int32_t row_len;
+    Mode mode;
+    RowCursor cur;
+    float inv[NF], scale[NF];                      // kRow: the current row's
+    float E[NF];
+    float A;
+    int pk[NF];
+
+    // Row is a 32- or 64-bit index: the walks of a dense unit stay below 2^31 rows and then the
+    // table is addressed as uniform base + 32-bit offset.
+    template <class Row>
+    __device__ __forceinline__ void load_row(Row row, float (&iv)[NF], float (&sc)[NF]) const {
+        if constexpr (NF == 2) {
+            const float2_t a = *reinterpret_cast<gptrf2_t>(ri + row * 2);
+            const float2_t b = *reinterpret_cast<gptrf2_t>(rs + row * 2);
+            iv[0] = a.x; iv[1] = a.y; sc[0] = b.x; sc[1] = b.y;
+        } else {
+            iv[0] = ri[row];
+            sc[0] = rs[row];
+        }
+    }
+    __device__ __forceinline__ void init(const ResolvedUnit& u) {
+        x = (gptr16_t)u.x;
+        g = (gptr16_t)u.dx;
+        keep_x = (u.flags & kUnitKeepX) != 0;
+        ri = (gptrf_t)u.row_inv;
+        rs = (gptrf_t)u.row_scale;
+        row_len = u.cols;
+#pragma unroll
+        for (int f = 0; f < NF; ++f) { E[f] = 0.0f; pk[f] = 0; inv[f] = 1.0f; scale[f] = 1.0f; }
+        A = 0.0f;
+        if (!(u.flags & kUnitRowScale)) {
+            mode = kRow;
+            if (u.row_inv != nullptr && u.row_scale != nullptr) load_row(0u, inv, scale);
+        } else if (u.flags & kUnitCausal) {
+            mode = kRow;
+        } else {
+            mode = (u.flags & kUnitScalar) ? kElem : kCursor;
+        }
+    }
+    __device__ __forceinline__ void begin_dense(int64_t e0, int le) {
+        if (mode == kCursor) cur.begin(e0, le, kWG * kVec, row_len);
+    }
+    __device__ __forceinline__ void set_row(int64_t row) { load_row(row, inv, scale); }
+
+    __device__ __forceinline__ void quad(uint32_t xw0, uint32_t xw1, uint32_t gw0, uint32_t gw1,
+                                         const float (&iv)[NF], const float (&sc)[NF]) {
+        const float xv[4] = {bf16_lo(xw0), bf16_hi(xw0), bf16_lo(xw1), bf16_hi(xw1)};
+        const float gv[4] = {bf16_lo(gw0), bf16_hi(gw0), bf16_lo(gw1), bf16_hi(gw1)};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float a = gv[j] * xv[j];
+            A = fmaf(a, a, A);
+        }
+        one_format<F0>(xv, gv, iv[0], sc[0], E[0], pk[0]);
+        if constexpr (NF > 1) one_format<F1>(xv, gv, iv[1], sc[1], E[1], pk[1]);
+    }
+    __device__ __forceinline__ void vec(const u32x4& xv, const u32x4& gv, const float (&iv)[NF],
+                                        const float (&sc)[NF]) {
+        quad(xv.x, xv.y, gv.x, gv.y, iv, sc);
+        quad(xv.z, xv.w, gv.z, gv.w, iv, sc);
+    }
+    // One element with the scales of its own row.
+    __device__ __forceinline__ void elem(uint32_t xb, uint32_t gb, const float (&iv)[NF], const float (&sc)[NF]) {
+        const float xf = __uint_as_float(xb << 16), gf = __uint_as_float(gb << 16);
+        const float a = gf * xf;
+        A = fmaf(a, a, A);
+        {
+            const int p = Fp8<F0>::pack(clamp_fmax<F0>(xf * iv[0]), 0.0f, 0, false);
+            const float t = gf * fmaf(-Fp8<F0>::unpack(p, false).x, sc[0], xf);
+            E[0] = fmaf(t, t, E[0]);
+        }
+        if constexpr (NF > 1) {
+            const int p = Fp8<F1>::pack(clamp_fmax<F1>(xf * iv[1]), 0.0f, 0, false);
+            const float t = gf * fmaf(-Fp8<F1>::unpack(p, false).x, sc[1], xf);
+            E[1] = fmaf(t, t, E[1]);
+        }
+    }
+
+    template <int U>
+    __device__ __forceinline__ void full(int64_t eu, int le, int64_t stride) {
+        const gptr128_t bx = reinterpret_cast<gptr128_t>(x + eu);
+        const gptr128_t bg = reinterpret_cast<gptr128_t>(g + eu);
+        const int lv = le / kVec;
+        const int64_t sv = stride / kVec;
+        u32x4 xr[U], gr[U];
+        if (keep_x) {
+#pragma unroll
+            for (int k = 0; k < U; ++k) xr[k] = load128<false>(bx + k * sv + lv);
+        } else {
+#pragma unroll
+            for (int k = 0; k < U; ++k) xr[k] = load128<true>(bx + k * sv + lv);
+        }
+#pragma unroll
+        for (int k = 0; k < U; ++k) gr[k] = load128<true>(bg + k * sv + lv);
+        // one arithmetic path; only the source of the scales differs
+        float iv[U][NF], sc[U][NF];
+#pragma unroll
+        for (int k = 0; k < U; ++k) {
+            if (mode == kCursor) {
+                load_row((uint32_t)cur.row, iv[k], sc[k]);
+                cur.advance();
+            } else {
+#pragma unroll
+                for (int f = 0; f < NF; ++f) { iv[k][f] = inv[f]; sc[k][f] = scale[f]; }
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < U; ++k) vec(xr[k], gr[k], iv[k], sc[k]);
+        // keep the scheduler from pulling the next group's loads (and their scales) above this
+        // group's arithmetic: the registers do not allow more than one group in flight
+        __builtin_amdgcn_sched_barrier(0);
+    }
+
+    template <int U>
+    __device__ __forceinline__ void full_masked(int64_t e, int stride, int count, int tail) {
+        const gptr128_t px = reinterpret_cast<gptr128_t>(x + e);
+        const gptr128_t pg = reinterpret_cast<gptr128_t>(g + e);
+        const int sv = stride / kVec;
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+        u32x4 xr[U], gr[U];
+#pragma unroll
+        for (int k = 0; k < U; ++k) {
+            xr[k] = k < count ? load128<true>(px + k * sv) : zero;
+            gr[k] = k < count ? load128<true>(pg + k * sv) : zero;
+        }
+        if (tail < kVec) {
+#pragma unroll
+            for (int k = 0; k < U; ++k)
+                if (k == count - 1) { xr[k] = keep_leading(xr[k], tail); gr[k] = keep_leading(gr[k], tail); }
+        }
+#pragma unroll
+        for (int k = 0; k < U; ++k)
+            if (k < count) vec(xr[k], gr[k], inv, scale);
+    }
+
+    __device__ __forceinline__ void partial(int64_t e, int jlo, int jhi) {
+        if (mode == kElem) {
+            elements(e, jlo, jhi);
+            return;
+        }
+        const u32x4 xv = gather8(x, e, jlo, jhi);
+        const u32x4 gv = gather8(g, e, jlo, jhi);
+        float iv[NF], sc[NF];
+        if (mode == kCursor) {
+            load_row((uint32_t)cur.row, iv, sc);
+            cur.advance();
+        } else {
+#pragma unroll
+            for (int f = 0; f < NF; ++f) { iv[f] = inv[f]; sc[f] = scale[f]; }
+        }
+        vec(xv, gv, iv, sc);
+    }
+
+    // Rows that are not made of whole vectors: every element looks its row up by division.  Kept
+    // out of line: it is the rare path and must not cost the others registers.
+    __device__ __noinline__ void elements(int64_t e, int jlo, int jhi) {
+        for (int j = jlo; j < jhi; ++j) {
+            float iv[NF], sc[NF];
+            load_row(row_len > 0 ? (e + j) / row_len : (int64_t)0, iv, sc);
+            elem(x[e + j], g[e + j], iv, sc);
+        }
+    }
+};
+
+template <class Ctx, int NF>
+__device__ __forceinline__ void sens_body(const ResolvedUnit* __restrict__ runits,
+                                          const ChunkRef* __restrict__ map, uint32_t n_chunks,
+                                          float* __restrict__ partials) {
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     uint32_t c = blockIdx.x;
@@ -284,18 +491,8 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
         const bool more = cn < n_chunks;
         if (more) ref = map[cn];                    // next chunk's entry travels while this one streams
 
-        SensCtx<NF, F0, F1> ctx;
-        ctx.x = (gptr16_t)u.x;
-        ctx.g = (gptr16_t)u.dx;
-        ctx.keep_x = (u.flags & kUnitKeepX) != 0;
-#pragma unroll
-        for (int f = 0; f < NF; ++f) {
-            ctx.inv[f] = u.inv[f];
-            ctx.scale[f] = u.scale[f];
-            ctx.E[f] = 0.0f;
-            ctx.pk[f] = 0;
-        }
-        ctx.A = 0.0f;
+        Ctx ctx;
+        ctx.init(u);
         walk_chunk(u, local, tid, ctx);
 
         float v[NF + 1];
@@ -312,6 +509,23 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
     }
 }
 
+template <int NF, int F0, int F1>
+__global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) void sens_kernel(const ResolvedUnit* __restrict__ runits,
+                                                   const ChunkRef* __restrict__ map,
+                                                   uint32_t n_chunks, float* __restrict__ partials) {
+    sens_body<SensCtx<NF, F0, F1>, NF>(runits, map, n_chunks, partials);
+}
+
+#ifndef AMPSENS_ROWS_WAVES
+#define AMPSENS_ROWS_WAVES 4
+#endif
+template <int NF, int F0, int F1>
+__global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(AMPSENS_ROWS_WAVES, AMPSENS_ROWS_WAVES))) void sens_rows_kernel(const ResolvedUnit* __restrict__ runits,
+                                                        const ChunkRef* __restrict__ map,
+                                                        uint32_t n_chunks, float* __restrict__ partials) {
+    sens_body<SensRowCtx<NF, F0, F1>, NF>(runits, map, n_chunks, partials);
+}
+
 // ---- the weight kernel ------------------------------------------------------------------------
 // A weight W is shared by the R samples of its op; only the gradient differs.  This kernel reads a
 // chunk of W once for up to kWBatch samples, forms x, and x - xtilde for every format, once, and
@@ -319,7 +533,9 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
 // instead of 16, and W's bytes once per batch instead of once per sample.  Each thread keeps one
 // 8-element vector of W per step; sums are kept per sample and written to the same per-wave
 // partial slots the streaming kernel would have used, so the finalisation does not change.
-template <int NF, int F0, int F1>
+// ROWS: the scales of W come from a [K][NF] table (one per output channel), followed with a
+// RowCursor; they are needed once per vector of W and batch, not per sample.
+template <int NF, int F0, int F1, bool ROWS>
 __global__ __launch_bounds__(kWG) void sens_w_kernel(const WGroup* __restrict__ groups, uint32_t n_groups,
                                                      uint32_t n_items,
                                                      const ResolvedUnit* __restrict__ runits,
@@ -347,7 +563,15 @@ __global__ __launch_bounds__(kWG) void sens_w_kernel(const WGroup* __restrict__ 
         }
         float inv[NF], scale[NF];
 #pragma unroll
-        for (int f = 0; f < NF; ++f) { inv[f] = u0.inv[f]; scale[f] = u0.scale[f]; }
+        for (int f = 0; f < NF; ++f) {
+            if constexpr (ROWS) {
+                inv[f] = u0.row_inv[f];             // a table of one row unless the unit has row scales
+                scale[f] = u0.row_scale[f];
+            } else {
+                inv[f] = u0.inv[f];
+                scale[f] = u0.scale[f];
+            }
+        }
         float A[kWBatch], E[NF][kWBatch];
 #pragma unroll
         for (int k = 0; k < kWBatch; ++k) {
@@ -358,10 +582,23 @@ __global__ __launch_bounds__(kWG) void sens_w_kernel(const WGroup* __restrict__ 
         const int64_t base = (int64_t)j * kChunkVecs * kVec;    // the unit starts on the 16-byte grid
         const gptr128_t px = reinterpret_cast<gptr128_t>((gptr16_t)u0.x + base);
         int pk = 0;
+        RowCursor cur;
+        const bool by_row = ROWS && (u0.flags & kUnitRowScale) != 0;
+        if constexpr (ROWS) cur.begin(base, tid * kVec, kWG * kVec, by_row ? u0.cols : 0);
 #pragma unroll 1
         for (int s = 0; s < kChunkVecs / kWG; ++s) {
             const int v = s * kWG + tid;
             const u32x4 xw = load128<false>(px + v);
+            if constexpr (ROWS) {
+                if (by_row) {
+#pragma unroll
+                    for (int f = 0; f < NF; ++f) {
+                        inv[f] = ((gptrf_t)u0.row_inv)[(uint32_t)cur.row * NF + f];
+                        scale[f] = ((gptrf_t)u0.row_scale)[(uint32_t)cur.row * NF + f];
+                    }
+                    cur.advance();
+                }
+            }
             u32x4 gr[kWLoad];
 #pragma unroll
             for (int k = 0; k < kWLoad; ++k)
@@ -488,6 +725,8 @@ struct AbsmaxCtx {
         m = m > hi ? m : hi;
     }
     __device__ __forceinline__ void vec(const u32x4& v) { word(v.x); word(v.y); word(v.z); word(v.w); }
+    __device__ __forceinline__ void begin_dense(int64_t, int) {}
+    __device__ __forceinline__ void set_row(int64_t) {}
 
     template <int U>
     __device__ __forceinline__ void full(int64_t eu, int le, int64_t stride) {
@@ -549,6 +788,24 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
 
 __device__ __forceinline__ float fmax_of(int fmt) { return fmt == 0 ? 448.0f : 57344.0f; }
 
+// amax (as the maximum of bits & 0x7FFF) -> amax, flag, and the scales of every format.
+__device__ __forceinline__ void write_scales(uint32_t bits, int n_fmts, int fmt0, int fmt1, float* amax_out,
+                                             float* scale_out, float* inv_out) {
+    const float amax = __uint_as_float(bits << 16);
+    *amax_out = amax;
+    for (int f = 0; f < n_fmts; ++f) {
+        const float fm = fmax_of(f == 0 ? fmt0 : fmt1);
+        float scale = 1.0f, inv = 1.0f;
+        if (amax != 0.0f) {
+            scale = amax / fm;                      // correctly rounded fp32 divisions
+            inv = fm / amax;
+            if (__builtin_isinf(inv)) { scale = 1.0f; inv = 1.0f; }
+        }
+        scale_out[f] = scale;
+        inv_out[f] = inv;
+    }
+}
+
 // One workgroup of 1024 threads per tensor (unit t of an absmax call is tensor t).
 constexpr int kFinThreads = 1024;
 __global__ __launch_bounds__(kFinThreads) void absmax_finalize_kernel(const uint32_t* __restrict__ chunk_begin,
@@ -573,19 +830,99 @@ __global__ __launch_bounds__(kFinThreads) void absmax_finalize_kernel(const uint
     if (threadIdx.x != 0) return;
     uint32_t bits = 0;
     for (int w = 0; w < kFinThreads / 64; ++w) bits = bits > red[w] ? bits : red[w];
-    const float amax = __uint_as_float(bits << 16);
-    amax_out[t] = amax;
     flags_out[t] = bits >= 0x7F80u ? 1u : 0u;
-    for (int f = 0; f < n_fmts; ++f) {
-        const float fm = fmax_of(f == 0 ? fmt0 : fmt1);
-        float scale = 1.0f, inv = 1.0f;
-        if (amax != 0.0f) {
-            scale = amax / fm;                      // correctly rounded fp32 divisions
-            inv = fm / amax;
-            if (__builtin_isinf(inv)) { scale = 1.0f; inv = 1.0f; }
+    write_scales(bits, n_fmts, fmt0, fmt1, &amax_out[t], &scale_out[t * n_fmts], &inv_out[t * n_fmts]);
+}
+
+// ---- absmax and scales per row ----------------------------------------------------------------
+// A wave owns a run of consecutive rows of one tensor.  Rows made of whole, aligned vectors are
+// read with 128-bit loads by min(64, next power of two >= vectors per row) lanes each, so that
+// short rows (128 elements = 16 lanes) still fill the wave with 4 rows at a time; other rows are
+// read element by element.  Every row is reduced inside its lane group and written by one lane:
+// no partials, no second kernel.  flags must be zero before the launch.
+__device__ __forceinline__ uint32_t max_words(uint32_t m, const u32x4& v) {
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const uint32_t lo = w[k] & 0x7FFFu, hi = (w[k] >> 16) & 0x7FFFu;
+        m = m > lo ? m : lo;
+        m = m > hi ? m : hi;
+    }
+    return m;
+}
+
+__global__ __launch_bounds__(kWG) void zero_u32_kernel(uint32_t* __restrict__ p, uint32_t n) {
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
+__global__ __launch_bounds__(kWG) void absmax_rows_kernel(const RowTensor* __restrict__ tensors,
+                                                          uint32_t n_tensors, uint32_t n_items,
+                                                          int n_fmts, int fmt0, int fmt1,
+                                                          float* __restrict__ amax_out,
+                                                          float* __restrict__ scale_out,
+                                                          float* __restrict__ inv_out,
+                                                          uint32_t* __restrict__ flags_out) {
+    const int lane = threadIdx.x & 63;
+    const uint32_t n_waves = gridDim.x * kWaves;
+    for (uint32_t item = blockIdx.x * kWaves + (threadIdx.x >> 6); item < n_items; item += n_waves) {
+        uint32_t lo = 0, hi = n_tensors;            // the last tensor whose first item is <= item
+        while (hi - lo > 1) {
+            const uint32_t mid = (lo + hi) >> 1;
+            if (tensors[mid].item_begin <= item) lo = mid; else hi = mid;
         }
-        scale_out[t * n_fmts + f] = scale;
-        inv_out[t * n_fmts + f] = inv;
+        const RowTensor T = tensors[lo];
+        const int64_t row0 = (int64_t)(item - T.item_begin) * T.rows_per_item;
+        const int64_t row1 = row0 + T.rows_per_item < T.n_rows ? row0 + T.rows_per_item : T.n_rows;
+        const int32_t i0 = T.causal_rows > 0 ? (int32_t)(row0 % T.causal_rows) : 0;   // row0's index in its matrix
+        int L = 64;                                  // lanes per row
+        if (T.aligned) {
+            const int nv = T.row_len / kVec;
+            while (L > 1 && (L >> 1) >= nv) L >>= 1;
+        }
+        const int G = 64 / L, sub = lane / L, sl = lane - sub * L;
+        for (int64_t rb = row0; rb < row1; rb += G) {
+            const int64_t rho = rb + sub;
+            const bool live = rho < row1;
+            int32_t len = T.row_len;
+            if (T.causal_rows > 0) {
+                const int32_t i = (int32_t)(((int64_t)i0 + (rho - row0)) % T.causal_rows);
+                int64_t l = (int64_t)i + 1 + ((int64_t)T.row_len - T.causal_rows);
+                len = (int32_t)(l < 0 ? 0 : (l > T.row_len ? T.row_len : l));
+            }
+            uint32_t m = 0;
+            if (live && T.aligned) {
+                const int nvr = (len + kVec - 1) / kVec;
+                const int tail = len - (nvr - 1) * kVec;
+                const gptr128_t p = reinterpret_cast<gptr128_t>((gptr16_t)T.x + rho * T.row_len);
+                int v = sl;
+                for (; v + 3 * L < nvr - 1; v += 4 * L) {      // four whole vectors in flight
+                    const u32x4 a = load128<true>(p + v), b = load128<true>(p + v + L);
+                    const u32x4 c = load128<true>(p + v + 2 * L), d = load128<true>(p + v + 3 * L);
+                    m = max_words(max_words(max_words(max_words(m, a), b), c), d);
+                }
+                for (; v < nvr; v += L) {
+                    u32x4 a = load128<true>(p + v);
+                    if (v == nvr - 1 && tail < kVec) a = keep_leading(a, tail);
+                    m = max_words(m, a);
+                }
+            } else if (live) {
+                const gptr16_t p = (gptr16_t)T.x + rho * T.row_len;
+                for (int32_t j = sl; j < len; j += L) {
+                    const uint32_t h = (uint32_t)p[j] & 0x7FFFu;
+                    m = m > h ? m : h;
+                }
+            }
+            for (int o = 1; o < L; o <<= 1) {              // L is the same for the whole wave
+                const uint32_t w = (uint32_t)__shfl_xor((int)m, o);
+                m = m > w ? m : w;
+            }
+            if (live && sl == 0) {
+                const int64_t o = (int64_t)T.out_row + rho;
+                write_scales(m, n_fmts, fmt0, fmt1, &amax_out[o], &scale_out[o * n_fmts], &inv_out[o * n_fmts]);
+                if (m >= 0x7F80u) atomicOr(&flags_out[lo], 1u);
+            }
+        }
     }
 }
 
@@ -635,7 +972,12 @@ __global__ __launch_bounds__(kWG) void fake_quant_kernel(const uint16_t* __restr
 
 typedef void (*sens_fn_t)(const ResolvedUnit*, const ChunkRef*, uint32_t, float*);
 
-sens_fn_t sens_variant(int n_fmts, int fmt0, int fmt1) {
+sens_fn_t sens_variant(int n_fmts, int fmt0, int fmt1, int rows) {
+    if (rows) {
+        if (n_fmts == 1) return fmt0 == 0 ? sens_rows_kernel<1, 0, 0> : sens_rows_kernel<1, 1, 1>;
+        if (fmt0 == 0) return fmt1 == 0 ? sens_rows_kernel<2, 0, 0> : sens_rows_kernel<2, 0, 1>;
+        return fmt1 == 0 ? sens_rows_kernel<2, 1, 0> : sens_rows_kernel<2, 1, 1>;
+    }
     if (n_fmts == 1) return fmt0 == 0 ? sens_kernel<1, 0, 0> : sens_kernel<1, 1, 1>;
     if (fmt0 == 0) return fmt1 == 0 ? sens_kernel<2, 0, 0> : sens_kernel<2, 0, 1>;
     return fmt1 == 0 ? sens_kernel<2, 1, 0> : sens_kernel<2, 1, 1>;
@@ -650,38 +992,56 @@ int resident_blocks(const void* fn, int cus) {
 
 }  // namespace
 
-int sens_resident_blocks(int n_fmts, int fmt0, int fmt1, int cus) {
-    return resident_blocks((const void*)sens_variant(n_fmts, fmt0, fmt1), cus);
+int sens_resident_blocks(int n_fmts, int fmt0, int fmt1, int rows, int cus) {
+    return resident_blocks((const void*)sens_variant(n_fmts, fmt0, fmt1, rows), cus);
 }
 
 typedef void (*sens_w_fn_t)(const WGroup*, uint32_t, uint32_t, const ResolvedUnit*, const uint32_t*, float*);
 
-static sens_w_fn_t sens_w_variant(int n_fmts, int fmt0, int fmt1) {
-    if (n_fmts == 1) return fmt0 == 0 ? sens_w_kernel<1, 0, 0> : sens_w_kernel<1, 1, 1>;
-    if (fmt0 == 0) return fmt1 == 0 ? sens_w_kernel<2, 0, 0> : sens_w_kernel<2, 0, 1>;
-    return fmt1 == 0 ? sens_w_kernel<2, 1, 0> : sens_w_kernel<2, 1, 1>;
+template <bool ROWS>
+static sens_w_fn_t sens_w_variant_of(int n_fmts, int fmt0, int fmt1) {
+    if (n_fmts == 1) return fmt0 == 0 ? sens_w_kernel<1, 0, 0, ROWS> : sens_w_kernel<1, 1, 1, ROWS>;
+    if (fmt0 == 0) return fmt1 == 0 ? sens_w_kernel<2, 0, 0, ROWS> : sens_w_kernel<2, 0, 1, ROWS>;
+    return fmt1 == 0 ? sens_w_kernel<2, 1, 0, ROWS> : sens_w_kernel<2, 1, 1, ROWS>;
+}
+static sens_w_fn_t sens_w_variant(int n_fmts, int fmt0, int fmt1, int rows) {
+    return rows ? sens_w_variant_of<true>(n_fmts, fmt0, fmt1) : sens_w_variant_of<false>(n_fmts, fmt0, fmt1);
 }
 
-int sens_w_resident_blocks(int n_fmts, int fmt0, int fmt1, int cus) {
-    return resident_blocks((const void*)sens_w_variant(n_fmts, fmt0, fmt1), cus);
+int sens_w_resident_blocks(int n_fmts, int fmt0, int fmt1, int rows, int cus) {
+    return resident_blocks((const void*)sens_w_variant(n_fmts, fmt0, fmt1, rows), cus);
 }
 
 hipError_t launch_sens_w(const WGroup* d_groups, uint32_t n_groups, uint32_t n_items,
                          const ResolvedUnit* d_runits, const uint32_t* d_chunk_begin, int n_fmts, int fmt0,
-                         int fmt1, float* d_partials, int grid, hipStream_t stream) {
-    hipLaunchKernelGGL(sens_w_variant(n_fmts, fmt0, fmt1), dim3(grid), dim3(kWG), 0, stream, d_groups,
+                         int fmt1, int rows, float* d_partials, int grid, hipStream_t stream) {
+    hipLaunchKernelGGL(sens_w_variant(n_fmts, fmt0, fmt1, rows), dim3(grid), dim3(kWG), 0, stream, d_groups,
                        n_groups, n_items, d_runits, d_chunk_begin, d_partials);
     return hipGetLastError();
 }
 
 int absmax_resident_blocks(int cus) { return resident_blocks((const void*)absmax_kernel, cus); }
+int absmax_rows_resident_blocks(int cus) { return resident_blocks((const void*)absmax_rows_kernel, cus); }
+
+hipError_t launch_absmax_rows(const RowTensor* d_tensors, uint32_t n_tensors, uint32_t n_items,
+                              int n_fmts, int fmt0, int fmt1, float* d_amax, float* d_scale,
+                              float* d_inv, uint32_t* d_flags, int grid, hipStream_t stream) {
+    hipLaunchKernelGGL(zero_u32_kernel, dim3((n_tensors + kWG - 1) / kWG), dim3(kWG), 0, stream, d_flags,
+                       n_tensors);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || n_items == 0) return e;
+    hipLaunchKernelGGL(absmax_rows_kernel, dim3(grid), dim3(kWG), 0, stream, d_tensors, n_tensors, n_items,
+                       n_fmts, fmt0, fmt1, d_amax, d_scale, d_inv, d_flags);
+    return hipGetLastError();
+}
 
 hipError_t launch_prepare(const WorkUnit* d_units, const uint32_t* d_chunk_begin,
                           const UnitSchedule* d_schedule, uint32_t n_units, uint32_t n_chunks,
-                          int n_fmts, ResolvedUnit* d_runits, ChunkRef* d_map, hipStream_t stream) {
+                          int n_fmts, int row_tables, ResolvedUnit* d_runits, ChunkRef* d_map,
+                          hipStream_t stream) {
     const uint32_t n = n_units > n_chunks ? n_units : n_chunks;
     hipLaunchKernelGGL(prepare_kernel, dim3((n + kWG - 1) / kWG), dim3(kWG), 0, stream, d_units,
-                       d_chunk_begin, d_schedule, n_units, n_chunks, n_fmts, d_runits, d_map);
+                       d_chunk_begin, d_schedule, n_units, n_chunks, n_fmts, row_tables, d_runits, d_map);
     return hipGetLastError();
 }
 
@@ -715,9 +1075,9 @@ hipError_t launch_fake_quant(const uint16_t* d_x, int64_t n, float scale, float 
 }
 
 hipError_t launch_sens(const ResolvedUnit* d_runits, const ChunkRef* d_map, uint32_t n_chunks,
-                       int n_fmts, int fmt0, int fmt1, float* d_partials, int grid,
+                       int n_fmts, int fmt0, int fmt1, int rows, float* d_partials, int grid,
                        hipStream_t stream) {
-    hipLaunchKernelGGL(sens_variant(n_fmts, fmt0, fmt1), dim3(grid), dim3(kWG), 0, stream, d_runits,
+    hipLaunchKernelGGL(sens_variant(n_fmts, fmt0, fmt1, rows), dim3(grid), dim3(kWG), 0, stream, d_runits,
                        d_map, n_chunks, d_partials);
     return hipGetLastError();
 }

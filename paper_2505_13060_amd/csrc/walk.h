@@ -15,6 +15,13 @@
 //       influence the result; e differs from lane to lane
 //   void partial(int64_t e, int jlo, int jhi)
 //       elements x[e + j], jlo <= j < jhi, to be fetched one by one
+//   void begin_dense(int64_t e0, int le)
+//       a dense chunk starts: the vectors this thread is about to be given (by full and partial,
+//       one after the other) start at elements e0 + le, e0 + le + kWG*kVec, e0 + le + 2*kWG*kVec, ...
+//       A context that needs the row of every vector follows them with a RowCursor.
+//   void set_row(int64_t row)
+//       causal chunks: the vectors that follow, until the next call, lie in row `row` of the unit
+//       (matrix index * rows + row index)
 // Element indices are relative to the unit's first element.
 #pragma once
 
@@ -30,6 +37,32 @@ namespace ampsens {
 
 constexpr int kUnroll = 4;           // independent 128-bit loads per stream in flight per lane
 
+// Row of every vector of a thread's strided walk over a [rows, row_len] array, without a
+// division per vector: one division where the walk starts, then additions.  row_len == 0 means
+// the array is one row.  Vectors must not straddle rows (row_len a multiple of kVec, walk
+// starting on a vector boundary of the array).
+struct RowCursor {
+    int32_t row, col, drow, dcol, len;
+    // The walk starts at element e0 + le (e0 common to the workgroup, 0 <= le < 2^16) and moves
+    // `stride` (< 2^30) elements per step.
+    AMPSENS_HD void begin(int64_t e0, int le, int32_t stride, int32_t row_len) {
+        len = row_len;
+        if (row_len <= 0) { row = col = drow = dcol = 0; return; }
+        const int64_t r0 = e0 / row_len;
+        const uint32_t off = (uint32_t)(e0 - r0 * row_len) + (uint32_t)le;   // < 2^30 + 2^16
+        const uint32_t q = off / (uint32_t)row_len;
+        row = (int32_t)r0 + (int32_t)q;
+        col = (int32_t)(off - q * (uint32_t)row_len);
+        drow = stride / row_len;
+        dcol = stride % row_len;
+    }
+    AMPSENS_HD void advance() {
+        col += dcol;
+        row += drow;
+        if (col >= len && len > 0) { col -= len; ++row; }
+    }
+};
+
 // True when every vector of dense chunk `chunk_local` is whole and aligned.
 AMPSENS_HD bool dense_chunk_interior(int64_t n, uint32_t head, bool scalar, uint32_t chunk_local) {
     const int64_t v0 = (int64_t)chunk_local * kChunkVecs;
@@ -42,6 +75,7 @@ AMPSENS_HD void walk_dense_chunk(int64_t n, uint32_t head, bool scalar, uint32_t
     const int64_t nvec = (n + head + (kVec - 1)) / kVec;
     const int64_t v0 = (int64_t)chunk_local * kChunkVecs;
     int64_t v1 = v0 + kChunkVecs;
+    ctx.begin_dense(v0 * kVec - head, tid * kVec);
     if (dense_chunk_interior(n, head, scalar, chunk_local)) {
         const int64_t eu = v0 * kVec - head;
 #pragma unroll
@@ -107,6 +141,7 @@ AMPSENS_HD void walk_causal_chunk(int32_t rows, int32_t cols, bool scalar, uint3
                 if (e0 >= li) continue;
                 const int jhi = (li - e0 < kVec) ? (li - e0) : kVec;
                 const int64_t e = mat_base + (int64_t)i * cols + e0;
+                ctx.set_row((int64_t)mat * rows + i);
                 if (!scalar && jhi == kVec) ctx.template full<1>(e, 0, 0);
                 else ctx.partial(e, 0, jhi);
             }
@@ -139,6 +174,7 @@ AMPSENS_HD void walk_causal_chunk_aligned(int32_t rows, int32_t cols, uint32_t c
         const int32_t nv_row = (li + kVec - 1) / kVec;
         const int tail = li - (nv_row - 1) * kVec;              // 1..8 when the row has elements
         const int64_t e_row = ((int64_t)mat * rows + (i < rows ? i : 0)) * cols;
+        ctx.set_row((int64_t)mat * rows + (i < rows ? i : 0));
         for (int32_t v0 = 0; v0 < nv_band; v0 += kStep * kUnroll) {
             const int32_t v = v0 + (lane / kBandRows);
             int count = nv_row > v ? (nv_row - v + kStep - 1) / kStep : 0;

@@ -7,13 +7,14 @@ tensors allocated once; every number is produced by libampsens' kernels.
 import numpy as np
 import torch
 
-from . import (amp_absmax_scale, amp_absmax_workspace_bytes, amp_sens_bgemm,
+from . import (ROWS_OPERAND0, ROWS_OPERAND1, amp_absmax_rows_workspace_bytes, amp_absmax_scale,
+               amp_absmax_scale_rows, amp_absmax_workspace_bytes, amp_sens_bgemm,
                amp_sens_bgemm_workspace_bytes, amp_sens_linear, amp_sens_linear_workspace_bytes,
                bgemm_desc, causal, dense, linear_desc, tensor)
 
 
-def _layout(lay):
-    return dense(lay[1]) if lay[0] == "dense" else causal(lay[1], lay[2], lay[3])
+def _layout(lay, cols=0):
+    return dense(lay[1], cols) if lay[0] == "dense" else causal(lay[1], lay[2], lay[3])
 
 
 def _row(t, i):
@@ -100,3 +101,117 @@ class SensPass:
         return dict(amax=self.d_amax.cpu().numpy(), scale=self.d_scale.cpu().numpy(),
                     inv=self.d_inv.cpu().numpy(), flags=self.d_flags.cpu().numpy(),
                     linear=lin_ops, bgemm=bg_ops)
+
+
+class RowSensPass:
+    """The same pass with one scale per row where asked for: per token for the activations of the
+    linears (x_rows), per output channel for their weights (w_rows), per row of the BGEMM
+    operands (bgemm_rows; a dense operand's row is its last dimension).  Operands left at one
+    scale per tensor go through amp_absmax_scale as in SensPass."""
+
+    def __init__(self, workload, device, x_rows=True, w_rows=True, bgemm_rows=True):
+        self.w, self.device, self.fmts = workload, device, list(workload.fmts)
+        nf = len(self.fmts)
+        f32 = dict(device=device, dtype=torch.float32)
+        per_tensor, per_row = [], []                 # (key, Tensor)
+        for k, op in enumerate(workload.linears):
+            rows = int(op.row_offsets[-1])
+            (per_row if x_rows else per_tensor).append((("lin", k, 0), tensor(op.x, dense(rows * op.C, op.C))))
+            (per_row if w_rows else per_tensor).append((("lin", k, 1), tensor(op.w, dense(op.K * op.C, op.C))))
+        for k, op in enumerate(workload.bgemms):
+            for side, (x, lay) in enumerate(((op.x0, op.lay0), (op.x1, op.lay1))):
+                t = tensor(x, _layout(lay, x.shape[-1]), op.R)
+                (per_row if bgemm_rows else per_tensor).append((("bg", k, side), t))
+        self.t_tensors = [t for _, t in per_tensor]
+        self.r_tensors = [t for _, t in per_row]
+        nt = max(len(self.t_tensors), 1)
+        self.d_amax = torch.zeros(nt, **f32)
+        self.d_scale = torch.zeros(nt, nf, **f32)
+        self.d_inv = torch.zeros(nt, nf, **f32)
+        self.d_flags = torch.zeros(nt, device=device, dtype=torch.int32)
+        ws_rows, n_rows = amp_absmax_rows_workspace_bytes(self.r_tensors)
+        self.n_rows = n_rows
+        self.r_amax = torch.zeros(max(n_rows, 1), **f32)
+        self.r_scale = torch.zeros(max(n_rows, 1), nf, **f32)
+        self.r_inv = torch.zeros(max(n_rows, 1), nf, **f32)
+        self.r_flags = torch.zeros(max(len(self.r_tensors), 1), device=device, dtype=torch.int32)
+        # where each operand's scales start
+        self.where = {}
+        for i, (key, _) in enumerate(per_tensor):
+            self.where[key] = ("tensor", i)
+        base = 0
+        for i, (key, t) in enumerate(per_row):
+            _, rows = amp_absmax_rows_workspace_bytes([t])
+            self.where[key] = ("rows", base, rows, i)
+            base += rows
+
+        def scales(key):
+            w = self.where[key]
+            if w[0] == "tensor":
+                return self.d_scale[w[1]], self.d_inv[w[1]], 0
+            return self.r_scale[w[1]:], self.r_inv[w[1]:], 1
+
+        self.lin_desc, self.bg_desc = [], []
+        for k, op in enumerate(workload.linears):
+            uniform = np.array_equal(op.row_offsets, np.arange(op.R + 1) * (op.row_offsets[1] if op.R else 0))
+            xs, xi, xr = scales(("lin", k, 0))
+            ws_, wi, wr = scales(("lin", k, 1))
+            self.lin_desc.append(linear_desc(
+                op.x, op.dx, op.w, op.dw, op.C, op.K, op.R, xs, xi, ws_, wi,
+                tokens=int(op.row_offsets[1]) if (uniform and op.R) else 0,
+                sample_row_offsets=None if uniform else op.row_offsets,
+                scale_rows=(ROWS_OPERAND0 if xr else 0) | (ROWS_OPERAND1 if wr else 0)))
+        for k, op in enumerate(workload.bgemms):
+            s0, i0, r0 = scales(("bg", k, 0))
+            s1, i1, r1 = scales(("bg", k, 1))
+            self.bg_desc.append(bgemm_desc(op.x0, op.dx0, _layout(op.lay0, op.x0.shape[-1]), op.x1, op.dx1,
+                                           _layout(op.lay1, op.x1.shape[-1]), op.R, s0, i0, s1, i1,
+                                           scale_rows=(ROWS_OPERAND0 if r0 else 0) | (ROWS_OPERAND1 if r1 else 0)))
+        self.lin_R = [op.R for op in workload.linears]
+        self.bg_R = [op.R for op in workload.bgemms]
+        self.d_lin_out = torch.zeros(max(sum(self.lin_R), 1), nf, 4, **f32)
+        self.d_bg_out = torch.zeros(max(sum(self.bg_R), 1), nf, 4, **f32)
+
+        def ws(nbytes):
+            return torch.empty(max(nbytes, 256), device=device, dtype=torch.uint8)
+
+        self.ws_abs = ws(amp_absmax_workspace_bytes(self.t_tensors))
+        self.ws_rows = ws(ws_rows)
+        self.ws_lin = ws(amp_sens_linear_workspace_bytes(self.lin_desc, nf))
+        self.ws_bg = ws(amp_sens_bgemm_workspace_bytes(self.bg_desc, nf))
+
+    def absmax(self, stream=None):
+        if self.t_tensors:
+            amp_absmax_scale(self.t_tensors, self.fmts, self.d_amax, self.d_scale, self.d_inv, self.d_flags,
+                             self.ws_abs, stream)
+        if self.r_tensors:
+            amp_absmax_scale_rows(self.r_tensors, self.fmts, self.r_amax, self.r_scale, self.r_inv,
+                                  self.r_flags, self.ws_rows, stream)
+
+    def sens(self, stream=None):
+        if self.lin_desc:
+            amp_sens_linear(self.lin_desc, self.fmts, self.d_lin_out, self.ws_lin, stream)
+        if self.bg_desc:
+            amp_sens_bgemm(self.bg_desc, self.fmts, self.d_bg_out, self.ws_bg, stream)
+
+    def run(self, stream=None):
+        self.absmax(stream)
+        self.sens(stream)
+
+    def results(self):
+        torch.cuda.synchronize(self.device)
+        lin = self.d_lin_out.cpu().numpy()
+        bg = self.d_bg_out.cpu().numpy()
+        lin_ops, bg_ops, o = [], [], 0
+        for R in self.lin_R:
+            lin_ops.append(lin[o:o + R])
+            o += R
+        o = 0
+        for R in self.bg_R:
+            bg_ops.append(bg[o:o + R])
+            o += R
+        return dict(amax=self.d_amax.cpu().numpy(), scale=self.d_scale.cpu().numpy(),
+                    inv=self.d_inv.cpu().numpy(), flags=self.d_flags.cpu().numpy(),
+                    row_amax=self.r_amax.cpu().numpy(), row_scale=self.r_scale.cpu().numpy(),
+                    row_inv=self.r_inv.cpu().numpy(), row_flags=self.r_flags.cpu().numpy(),
+                    where=dict(self.where), linear=lin_ops, bgemm=bg_ops)

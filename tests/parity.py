@@ -101,3 +101,75 @@ def check_workload(workload, res):
         check_linear(op, k, res, workload.fmts)
     for k, op in enumerate(workload.bgemms):
         check_bgemm(op, k, len(workload.linears), res, workload.fmts)
+
+
+# ---- one scale per row (RowSensPass) ---------------------------------------------------------------
+
+def _operand_scales(res, key, x_bits, n_rows, row_len, fmts, causal_rows, what):
+    """Checks the library's scales of one operand bit for bit against the oracle and returns, per
+    format, (scale[n_rows], inv[n_rows]); a per-tensor operand is broadcast to its rows."""
+    w = res["where"][key]
+    out = []
+    if w[0] == "tensor":
+        causal = None if causal_rows is None else (n_rows // causal_rows, causal_rows, row_len)
+        for sc, iv in check_scales(res, w[1], x_bits, fmts, causal, what):
+            out.append((np.full(n_rows, sc, dtype=np.float32), np.full(n_rows, iv, dtype=np.float32)))
+        return out
+    _, base, rows, ti = w
+    assert rows == n_rows, (what, rows, n_rows)
+    flags = 0
+    for fi, f in enumerate(fmts):
+        am, sc, iv, fl = oracle.absmax_scale_rows(x_bits, n_rows, row_len, f, causal_rows=causal_rows)
+        flags |= fl
+        assert np.array_equal(bits32(res["row_amax"][base:base + n_rows]), bits32(am)), what
+        assert np.array_equal(bits32(res["row_scale"][base:base + n_rows, fi]), bits32(sc)), (what, fi)
+        assert np.array_equal(bits32(res["row_inv"][base:base + n_rows, fi]), bits32(iv)), (what, fi)
+        out.append((sc, iv))
+    assert res["row_flags"][ti] == flags, what
+    return out
+
+
+def check_workload_rows(workload, res):
+    fmts = workload.fmts
+    for k, op in enumerate(workload.linears):
+        x, dx, w, dw = (to_bits(t).reshape(-1) for t in (op.x, op.dx, op.w, op.dw))
+        rows = int(op.row_offsets[-1])
+        sx = _operand_scales(res, ("lin", k, 0), x, rows, op.C, fmts, None, op.name + ".x")
+        sw = _operand_scales(res, ("lin", k, 1), w, op.K, op.C, fmts, None, op.name + ".w")
+        got = res["linear"][k]
+        for fi, f in enumerate(fmts):
+            for r in range(op.R):
+                r0, r1 = int(op.row_offsets[r]), int(op.row_offsets[r + 1])
+                Ex, Ax = oracle.sens_operand_rows(x[r0 * op.C:r1 * op.C], dx[r0 * op.C:r1 * op.C], r1 - r0, op.C,
+                                                  sx[fi][0][r0:r1], sx[fi][1][r0:r1], f)
+                n = op.K * op.C
+                Ew, Aw = oracle.sens_operand_rows(w, dw[r * n:(r + 1) * n], op.K, op.C, sw[fi][0], sw[fi][1], f)
+                tag = "%s r=%d fmt=%d" % (op.name, r, f)
+                assert_sum_close(got[r, fi, 1], Ax, 0.0, tag + " A_X")
+                assert_sum_close(got[r, fi, 3], Aw, 0.0, tag + " A_W")
+                assert_sum_close(got[r, fi, 0], Ex, E_FLOOR * Ax, tag + " E_X")
+                assert_sum_close(got[r, fi, 2], Ew, E_FLOOR * Aw, tag + " E_W")
+    for k, op in enumerate(workload.bgemms):
+        got = res["bgemm"][k]
+        sides = []
+        for side, (xt, dxt, lay) in enumerate(((op.x0, op.dx0, op.lay0), (op.x1, op.dx1, op.lay1))):
+            xb, db = to_bits(xt).reshape(-1), to_bits(dxt).reshape(-1)
+            row_len = xt.shape[-1]
+            causal_rows = lay[2] if lay[0] == "causal" else None
+            n_rows = xb.size // row_len
+            sc = _operand_scales(res, ("bg", k, side), xb, n_rows, row_len, fmts, causal_rows,
+                                 "%s.x%d" % (op.name, side))
+            sides.append((xb, db, row_len, causal_rows, n_rows // op.R, sc))
+        for fi, f in enumerate(fmts):
+            for r in range(op.R):
+                vals = []
+                for xb, db, row_len, causal_rows, per, sc in sides:
+                    a, b = r * per, (r + 1) * per
+                    vals.append(oracle.sens_operand_rows(xb[a * row_len:b * row_len], db[a * row_len:b * row_len],
+                                                         per, row_len, sc[fi][0][a:b], sc[fi][1][a:b], f,
+                                                         causal_rows=causal_rows))
+                tag = "%s r=%d fmt=%d" % (op.name, r, f)
+                assert_sum_close(got[r, fi, 1], vals[0][1], 0.0, tag + " A_0")
+                assert_sum_close(got[r, fi, 3], vals[1][1], 0.0, tag + " A_1")
+                assert_sum_close(got[r, fi, 0], vals[0][0], E_FLOOR * vals[0][1], tag + " E_0")
+                assert_sum_close(got[r, fi, 2], vals[1][0], E_FLOOR * vals[1][1], tag + " E_1")

@@ -127,6 +127,83 @@ def test_kernel_walk_covers_every_element_once(lay, xo, dxo, mul):
     assert nch.value >= 1
 
 
+ROW_REPLAY_CASES = [
+    # (layout, row length, x offset, dx offset, batch_mul): dense [n / row_len, row_len] or causal rows
+    (("dense", 4096 * 24), 4096, 0, 0, 1), (("dense", 11008 * 7), 11008, 0, 0, 1), (("dense", 128 * 700), 128, 0, 0, 1),
+    (("dense", 8 * 5000), 8, 0, 0, 1), (("dense", 1408 * 50), 1408, 0, 0, 1), (("dense", 28672 * 3), 28672, 0, 0, 1),
+    (("dense", 40 * 1000), 40, 0, 0, 2), (("dense", 32768 * 2), 32768, 0, 0, 1), (("dense", 65536 * 2), 65536, 0, 0, 1),
+    (("dense", 100 * 333), 100, 0, 0, 1),                     # row length not a multiple of 8: element path
+    (("dense", 128 * 300), 128, 6, 6, 1),                     # misaligned buffer: element path
+    (("dense", 4096 * 9), 4096, 0, 8, 1),                     # x and xdot misaligned against each other
+    (("causal", 3, 64, 64), 64, 0, 0, 1), (("causal", 1, 37, 48), 48, 0, 0, 2), (("causal", 2, 520, 512), 512, 0, 0, 1),
+    (("causal", 2, 16, 72), 72, 4, 4, 1), (("causal", 1, 200, 1024), 1024, 0, 0, 1),
+]
+
+
+@pytest.mark.parametrize("lay,row_len,xo,dxo,mul", ROW_REPLAY_CASES)
+def test_kernel_walk_tracks_the_row_of_every_vector(lay, row_len, xo, dxo, mul):
+    """Units with one scale per row: the replay of the kernels' index code also follows the row of
+    every vector the way the device context does (one division per chunk, then additions; or the
+    row named by the causal walker) and compares it with element index / row length."""
+    L = amp.lib()
+    L.ampsens_debug_replay_unit_rows.restype = C.c_int64
+    L.ampsens_debug_replay_unit_rows.argtypes = [C.c_uint64, C.c_uint64, C.c_void_p, C.c_int64, C.c_int64,
+                                                 C.c_void_p, C.c_int64, C.POINTER(C.c_uint64)]
+    if lay[0] == "dense":
+        layout = amp.dense(lay[1])
+        span = lay[1] * mul
+        want = np.ones(span, dtype=np.int32)
+    else:
+        _, b, r, c = lay
+        layout = amp.causal(b, r, c)
+        span = b * r * c * mul
+        i = np.arange(r)[:, None]
+        j = np.arange(c)[None, :]
+        want = np.broadcast_to((j <= i + (c - r)).astype(np.int32), (b * mul, r, c)).reshape(-1).copy()
+    counts = np.zeros(span, dtype=np.int32)
+    nch = C.c_uint64()
+    bad = L.ampsens_debug_replay_unit_rows(0x10000 + xo, 0x90000 + dxo, C.byref(layout), mul, row_len,
+                                           counts.ctypes.data_as(C.c_void_p), span, C.byref(nch))
+    assert bad == 0
+    assert np.array_equal(counts, want)
+
+
+def test_row_scale_descriptors_are_validated():
+    L = amp.lib()
+    n = C.c_size_t()
+    rows = C.c_int64()
+    d = amp.linear_desc(None, None, None, None, 64, 32, 2, None, None, None, None, tokens=5, scale_rows=3)
+    d.x = d.dx = d.w = d.dw = 4096
+    d.x_scale = d.x_inv = d.w_scale = d.w_inv = 4096
+    assert L.amp_sens_linear_workspace_bytes(C.byref(d), 1, 2, C.byref(n)) == amp.OK
+    d.scale_rows = 4
+    assert L.amp_sens_linear_workspace_bytes(C.byref(d), 1, 2, C.byref(n)) == amp.ERR_INVALID_ARG
+    # a dense BGEMM operand with one scale per row must say its row length, and it must divide the block
+    b = amp.bgemm_desc(None, None, amp.dense(4 * 64 * 16), None, None, amp.dense(4 * 64 * 16, 16), 2,
+                       None, None, None, None, scale_rows=amp.ROWS_OPERAND1)
+    b.x0 = b.dx0 = b.x1 = b.dx1 = 4096
+    b.scale0 = b.inv0 = b.scale1 = b.inv1 = 4096
+    assert L.amp_sens_bgemm_workspace_bytes(C.byref(b), 1, 2, C.byref(n)) == amp.OK
+    b.scale_rows = amp.ROWS_OPERAND0
+    assert L.amp_sens_bgemm_workspace_bytes(C.byref(b), 1, 2, C.byref(n)) == amp.ERR_INVALID_ARG
+    b.layout0 = amp.dense(4 * 64 * 16, 48)                     # 4096 % 48 != 0
+    assert L.amp_sens_bgemm_workspace_bytes(C.byref(b), 1, 2, C.byref(n)) == amp.ERR_INVALID_ARG
+    # rows of an absmax call
+    t = amp.Tensor(4096, amp.dense(1000 * 128, 128), 3)
+    assert L.amp_absmax_rows_workspace_bytes(C.byref(t), 1, C.byref(n), C.byref(rows)) == amp.OK
+    assert rows.value == 3000 and n.value == 256
+    t = amp.Tensor(4096, amp.causal(2, 40, 64), 3)
+    assert L.amp_absmax_rows_workspace_bytes(C.byref(t), 1, C.byref(n), C.byref(rows)) == amp.OK
+    assert rows.value == 240
+    t = amp.Tensor(4096, amp.dense(1000), 1)                   # no row length
+    assert L.amp_absmax_rows_workspace_bytes(C.byref(t), 1, C.byref(n), C.byref(rows)) == amp.ERR_INVALID_ARG
+    fm = (C.c_int * 2)(0, 1)
+    t = amp.Tensor(4096, amp.dense(1024, 128), 1)
+    assert L.amp_absmax_scale_rows(C.byref(t), 1, fm, 2, 256, 256, 256, 256, 4096, 0, None) == amp.ERR_WORKSPACE_TOO_SMALL
+    assert L.amp_absmax_scale_rows(C.byref(t), 1, fm, 2, 256, 256, 256, None, 4096, 256, None) == amp.ERR_INVALID_ARG
+    assert L.amp_absmax_scale_rows(None, 0, fm, 2, None, None, None, None, None, 0, None) == amp.OK
+
+
 @pytest.mark.parametrize("shapes", [
     [(4, 256, 1024, 1024)],                                   # config 0
     [(16, 2048, 4096, 4096), (16, 2048, 4096, 11008)],        # two linears of the 7B block

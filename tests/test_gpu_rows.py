@@ -1,0 +1,218 @@
+"""GPU parity tests for one scale per row (per-token activations, per-channel weights, rows of
+BGEMM operands): row amax and scales bit-exact, sums within 1e-4 of the oracle's per-row
+routines (tests/parity.py).  Every test prints what it is about to run before touching the GPU."""
+import ctypes as C
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2505_13060_amd as amp
+from paper_2505_13060_amd import workloads as wl
+from paper_2505_13060_amd.pipeline import RowSensPass, SensPass
+from helpers import f32_to_bf16_bits
+import parity
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def say(msg):
+    print("[gpu-test] " + msg, flush=True)
+    sys.stdout.flush()
+
+
+def bf(bits, *shape):
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(torch.bfloat16).view(*shape)
+
+
+def to_device(workload):
+    for op in workload.linears:
+        op.x, op.dx, op.w, op.dw = (t.to(DEV) for t in (op.x, op.dx, op.w, op.dw))
+    for op in workload.bgemms:
+        op.x0, op.dx0, op.x1, op.dx1 = (t.to(DEV) for t in (op.x0, op.dx0, op.x1, op.dx1))
+    return workload
+
+
+def run_rows(workload, **modes):
+    say("rows %s: %s, %d linears, %d bgemms, %.1f M pairs" %
+        (modes, workload.name, len(workload.linears), len(workload.bgemms), workload.pairs() / 1e6))
+    to_device(workload)
+    p = RowSensPass(workload, DEV, **modes)
+    p.run()
+    res = p.results()
+    parity.check_workload_rows(workload, res)
+    return p, res
+
+
+def _mk(rng, n, sigma):
+    return f32_to_bf16_bits((rng.standard_normal(n) * sigma).astype(np.float32))
+
+
+@pytest.mark.parametrize("rows,row_len,off", [(700, 128, 0), (37, 11008, 0), (333, 100, 0), (300, 128, 6),
+                                              (5000, 8, 0), (3, 28672, 0), (1, 40, 0), (129, 4096, 0), (64, 24, 0)])
+def test_row_absmax_bit_exact_dense(rows, row_len, off):
+    rng = np.random.default_rng(rows * 7 + row_len)
+    x = f32_to_bf16_bits((rng.standard_normal((rows, row_len)) * np.exp(rng.normal(0, 2, (rows, 1)))).astype(np.float32))
+    x[rows // 2] = 0                                         # an all-zero row: scale 1
+    flat = x.reshape(-1)
+    buf = torch.zeros(flat.size + 8, dtype=torch.int16, device=DEV)
+    buf[off // 2: off // 2 + flat.size] = torch.from_numpy(flat.view(np.int16)).to(DEV)
+    view = buf[off // 2:]
+    fmts = [amp.E4M3, amp.E5M2]
+    t = [amp.tensor(view, amp.dense(rows * row_len, row_len))]
+    ws_bytes, n_rows = amp.amp_absmax_rows_workspace_bytes(t)
+    assert n_rows == rows
+    say("row absmax [%d, %d] offset %d" % (rows, row_len, off))
+    d_amax = torch.zeros(rows, device=DEV)
+    d_scale = torch.zeros(rows, 2, device=DEV)
+    d_inv = torch.zeros(rows, 2, device=DEV)
+    d_flags = torch.full((1,), 7, dtype=torch.int32, device=DEV)
+    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=DEV)
+    amp.amp_absmax_scale_rows(t, fmts, d_amax, d_scale, d_inv, d_flags, ws)
+    torch.cuda.synchronize()
+    assert int(d_flags[0]) == 0
+    for fi, f in enumerate(fmts):
+        am, sc, iv, fl = oracle.absmax_scale_rows(flat, rows, row_len, f)
+        assert np.array_equal(parity.bits32(d_amax.cpu().numpy()), parity.bits32(am))
+        assert np.array_equal(parity.bits32(d_scale[:, fi].cpu().numpy()), parity.bits32(sc))
+        assert np.array_equal(parity.bits32(d_inv[:, fi].cpu().numpy()), parity.bits32(iv))
+
+
+def test_row_absmax_causal_rows_many_tensors_and_flags():
+    rng = np.random.default_rng(5)
+    tensors, host = [], []
+    for (b, r, c, samples) in [(2, 37, 48, 2), (1, 48, 24, 1), (3, 64, 64, 2), (1, 520, 512, 1), (2, 16, 72, 3)]:
+        x = _mk(rng, samples * b * r * c, 0.5)
+        i = np.arange(r)[:, None]
+        j = np.arange(c)[None, :]
+        outside = np.broadcast_to(j > i + (c - r), (samples * b, r, c)).reshape(-1)
+        x[outside] = 0x7FC0                                  # NaN outside the operand: no effect
+        tensors.append((x, b, r, c, samples))
+    # a dense tensor with one Inf (flag), and an empty one
+    xin = _mk(rng, 50 * 64, 1.0)
+    xin[64 * 7 + 3] = 0x7F80
+    dev = [torch.from_numpy(x.view(np.int16)).to(DEV) for (x, *_r) in tensors] + [torch.from_numpy(xin.view(np.int16)).to(DEV)]
+    descs = [amp.tensor(d, amp.causal(b, r, c), s) for d, (x, b, r, c, s) in zip(dev, tensors)]
+    descs.append(amp.tensor(dev[-1], amp.dense(50 * 64, 64)))
+    descs.append(amp.tensor(None, amp.dense(0, 64)))
+    ws_bytes, n_rows = amp.amp_absmax_rows_workspace_bytes(descs)
+    want_rows = sum(s * b * r for (x, b, r, c, s) in tensors) + 50
+    assert n_rows == want_rows
+    say("row absmax, %d tensors, %d rows" % (len(descs), n_rows))
+    fmts = [amp.E5M2]
+    d_amax = torch.zeros(n_rows, device=DEV)
+    d_scale = torch.zeros(n_rows, 1, device=DEV)
+    d_inv = torch.zeros(n_rows, 1, device=DEV)
+    d_flags = torch.full((len(descs),), 9, dtype=torch.int32, device=DEV)
+    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=DEV)
+    amp.amp_absmax_scale_rows(descs, fmts, d_amax, d_scale, d_inv, d_flags, ws)
+    torch.cuda.synchronize()
+    flags = d_flags.cpu().numpy()
+    assert list(flags) == [0, 0, 0, 0, 0, 1, 0]
+    base = 0
+    am_g, sc_g, iv_g = d_amax.cpu().numpy(), d_scale.cpu().numpy()[:, 0], d_inv.cpu().numpy()[:, 0]
+    for (x, b, r, c, s) in tensors:
+        n = s * b * r
+        am, sc, iv, fl = oracle.absmax_scale_rows(x, n, c, amp.E5M2, causal_rows=r)
+        assert fl == 0
+        assert np.array_equal(parity.bits32(am_g[base:base + n]), parity.bits32(am))
+        assert np.array_equal(parity.bits32(sc_g[base:base + n]), parity.bits32(sc))
+        assert np.array_equal(parity.bits32(iv_g[base:base + n]), parity.bits32(iv))
+        base += n
+    am, sc, iv, fl = oracle.absmax_scale_rows(xin, 50, 64, amp.E5M2)
+    assert fl == 1
+    ok = np.arange(50) != 7
+    assert np.array_equal(parity.bits32(am_g[base:base + 50])[ok], parity.bits32(am)[ok])
+    assert np.isinf(am_g[base + 7])
+
+
+def test_rows_config0_full():
+    run_rows(wl.config0("cpu"))
+
+
+def test_rows_config1_reduced_block_all_rows():
+    run_rows(wl.config1("cpu", R=3, S=200, hidden=520, ffn=1384, H=4, D=64))
+
+
+@pytest.mark.parametrize("modes", [dict(x_rows=True, w_rows=False, bgemm_rows=False),
+                                   dict(x_rows=False, w_rows=True, bgemm_rows=False),
+                                   dict(x_rows=False, w_rows=False, bgemm_rows=True)])
+def test_rows_mixed_with_per_tensor_operands(modes):
+    run_rows(wl.config1("cpu", R=2, S=136, hidden=256, ffn=520, H=2, D=64), **modes)
+
+
+def test_rows_config3_reduced_single_format():
+    run_rows(wl.config3("cpu", R=2, S=264, hidden=512, ffn=1800, Hq=8, Hkv=2, D=64))
+
+
+def test_rows_config4_reduced_ragged_many_small():
+    run_rows(wl.config4("cpu", R=5, experts=6, C=512, K=176, tok_lo=1, tok_hi=40, n_bgemm=4, S=72, H=2, D=32))
+
+
+def test_rows_weight_kernel_on_and_off():
+    L = amp.lib()
+    for (R, tokens, Cd, K) in [(11, 40, 520, 190), (3, 16, 1024, 100), (2, 64, 4096, 24), (9, 24, 40, 2500)]:
+        w = wl.Workload("wk_rows", [amp.E4M3, amp.E5M2],
+                        [wl._linear("lin", 555 + R, R, tokens, Cd, K, "cpu", outliers=2)])
+        outs = []
+        for on in (0, 1):
+            say("weight kernel %s with row scales: R=%d W=%dx%d" % ("on" if on else "off", R, K, Cd))
+            L.ampsens_debug_set_w_kernel(C.c_int(on))
+            try:
+                p, res = run_rows(w)
+            finally:
+                L.ampsens_debug_set_w_kernel(C.c_int(1))
+            outs.append(res["linear"][0].copy())
+        assert np.allclose(outs[0], outs[1], rtol=2e-6, atol=0)
+
+
+def test_rows_odd_row_lengths_misalignment_and_causal_shapes():
+    rng = np.random.default_rng(123)
+    lin, bg = [], []
+    # C not a multiple of 8 (element path), empty and one-token samples
+    off = np.array([0, 0, 1, 1, 40], dtype=np.int64)
+    Cd, K, R = 52, 9, 4
+    lin.append(wl.LinearOp("odd_C", bf(_mk(rng, 40 * Cd, 1.0), 40, Cd), bf(_mk(rng, 40 * Cd, 1e-3), 40, Cd),
+                           bf(_mk(rng, K * Cd, 0.02), K, Cd), bf(_mk(rng, R * K * Cd, 1e-3), R, K, Cd), R, Cd, K, off))
+    # short rows: several rows per vector step
+    Cd, K, R = 8, 300, 2
+    lin.append(wl.LinearOp("C8", bf(_mk(rng, 2 * 50 * Cd, 1.0), 100, Cd), bf(_mk(rng, 100 * Cd, 1e-3), 100, Cd),
+                           bf(_mk(rng, K * Cd, 0.02), K, Cd), bf(_mk(rng, R * K * Cd, 1e-3), R, K, Cd), R, Cd, K,
+                           np.array([0, 50, 100], dtype=np.int64)))
+    for (H, S, S2, D) in [(2, 37, 48, 24), (1, 48, 24, 8), (3, 33, 33, 40), (2, 16, 16, 16), (1, 136, 136, 64), (2, 40, 64, 12)]:
+        R = 2
+        p, dp = _mk(rng, R * H * S * S2, 0.3), _mk(rng, R * H * S * S2, 1e-3)
+        i = np.arange(S)[:, None]
+        j = np.arange(S2)[None, :]
+        outside = np.broadcast_to(j > i + (S2 - S), (R * H, S, S2)).reshape(-1)
+        p[outside] = 0x7FC0
+        dp[outside] = 0xFFC0
+        v, dv = _mk(rng, R * H * S2 * D, 1.0), _mk(rng, R * H * S2 * D, 1e-3)
+        bg.append(wl.BgemmOp("odd_causal_%dx%d" % (S, S2), bf(p, R, H, S, S2), bf(dp, R, H, S, S2), ("causal", H, S, S2),
+                             bf(v, R, H, S2, D), bf(dv, R, H, S2, D), ("dense", H * S2 * D), R))
+    run_rows(wl.Workload("edge_rows", [amp.E4M3, amp.E5M2], lin, bg))
+
+
+def test_rows_with_equal_rows_reproduce_the_per_tensor_pass():
+    """If every row of an operand has the same amax, the per-row pass must give the per-tensor sums."""
+    w = wl.config1("cpu", R=2, S=64, hidden=128, ffn=256, H=2, D=32)
+    peak = f32_to_bf16_bits(np.array([4096.0], dtype=np.float32)).view(np.int16)[0]
+    for op in w.linears:
+        op.x.view(torch.int16)[:, 0] = int(peak)
+        op.w.view(torch.int16)[:, 0] = int(peak)
+    to_device(w)
+    say("rows vs per-tensor on equal-amax rows")
+    a = RowSensPass(w, DEV, bgemm_rows=False)
+    a.run()
+    ra = a.results()
+    b = SensPass(w, DEV)
+    b.run()
+    rb = b.results()
+    for k in range(len(w.linears)):
+        assert np.allclose(ra["linear"][k], rb["linear"][k], rtol=3e-6, atol=0), w.linears[k].name
+    for k in range(len(w.bgemms)):
+        assert np.array_equal(ra["bgemm"][k], rb["bgemm"][k])
