@@ -112,6 +112,8 @@ def host_tail(workload, res, n_blocks, amp):
 # ---- CPU baseline: the oracle on a bounded sample --------------------------------------------
 
 def cpu_baseline(workload, target_seconds=15.0):
+    """The oracle's per-tensor routine on a bounded sample (the per-row routine does the same
+    arithmetic per element; the baseline is quoted for the headline mode)."""
     import oracle
     from paper_2505_13060_amd.workloads import to_bits
     threads = max(1, min(16, os.cpu_count() or 1))
@@ -173,6 +175,9 @@ def main():
     ap.add_argument("--steps", type=int, default=32)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="config2")
+    ap.add_argument("--scales", choices=["tensor", "rows"], default="tensor",
+                    help="scale granularity: one per tensor (headline) or one per row (per token / per "
+                         "output channel / per row of a BGEMM operand)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -187,7 +192,7 @@ def main():
         sys.exit(3)
 
     import paper_2505_13060_amd as amp
-    from paper_2505_13060_amd.pipeline import SensPass
+    from paper_2505_13060_amd.pipeline import RowSensPass, SensPass
     dev = "cuda:0"
     torch.cuda.set_device(0)
     log("generating %s on %s" % (args.workload, torch.cuda.get_device_name(0)))
@@ -196,7 +201,9 @@ def main():
     torch.cuda.synchronize()
     pairs = workload.pairs()
     log("%.1f M pairs per step (%.2f GB), generated in %.1f s" % (pairs / 1e6, pairs * 4 / 1e9, time.perf_counter() - t0))
-    p = SensPass(workload, dev)
+    p = SensPass(workload, dev) if args.scales == "tensor" else RowSensPass(workload, dev)
+    if args.scales == "rows":
+        label += "; one scale per row"
     abs_elems = 0
     for op in workload.linears:
         abs_elems += int(op.row_offsets[-1]) * op.C + op.K * op.C
@@ -243,6 +250,10 @@ def main():
                  "sens_kernel (BGEMM operands)"],
              2: ["sens_kernel (linears)", "sens_kernel (BGEMM operands)"],
              1: ["sens_kernel"]}.get(launches_per_step, ["launch %d" % i for i in range(launches_per_step)])
+    if args.scales == "rows" and launches_per_step == 4:
+        names = ["sens_w_kernel, per-channel scales (weights of the linears)",
+                 "sens_wrows_kernel (activations of the linears, rows of 512+ elements)",
+                 "sens_wrows_kernel (causal BGEMM operands)", "sens_rows_kernel (BGEMM operands with short rows)"]
     launch_detail = []
     per_ms = ms.reshape(args.steps, launches_per_step).mean(axis=0)
     per_pairs = lp.reshape(args.steps, launches_per_step)[0].astype(np.float64)

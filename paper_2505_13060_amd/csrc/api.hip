@@ -66,6 +66,7 @@ struct WorkTable {
     std::vector<WorkUnit> units;
     std::vector<uint32_t> chunk_begin;
     std::vector<uint32_t> group;                  // units with the same non-zero id share their x
+    std::vector<uint64_t> unit_pairs;             // elements of each unit that belong to its operand
     uint64_t n_chunks = 0;
     uint64_t n_pairs = 0;                         // elements that belong to the operands
     bool any_rows = false;                        // some unit has one scale per row
@@ -103,6 +104,7 @@ struct WorkTable {
                 valid += (uint64_t)(len < 0 ? 0 : (len > L.cols ? L.cols : len));
             }
             n_pairs += valid * (uint64_t)batch;
+            unit_pairs.push_back(valid * (uint64_t)batch);
         } else {
             const int64_t n = L.n_elems * batch_mul;
             u.n = n;
@@ -113,12 +115,14 @@ struct WorkTable {
                 if (row_len < 0 || row_len > kMaxDim || n % row_len != 0) return AMP_ERR_INVALID_ARG;
                 if (n / row_len > 0x7FFFFFFFll) return AMP_ERR_TOO_LARGE;
                 u.cols = (int32_t)row_len;
+                u.rows = (int32_t)(n / row_len);
                 // rows must be made of whole vectors for the vector path
                 if (row_len % kVec != 0 || u.head != 0) { u.flags |= kUnitScalar; u.head = 0; }
             }
             u.chunks_per_mat = 1;
             chunks = unit_chunks_dense(n, u.head);
             n_pairs += (uint64_t)n;
+            unit_pairs.push_back((uint64_t)n);
         }
         chunk_begin.push_back((uint32_t)n_chunks);
         group.push_back(group_id);
@@ -148,20 +152,36 @@ struct WorkTable {
         return (u + 1 < units.size() ? chunk_begin[u + 1] : n_chunks) - chunk_begin[u];
     }
 
-    // How a call is split between the two streaming kernels.
+    // Which streaming kernel takes a unit: 0 = one scale per tensor; 1 = one scale per row with
+    // rows long enough that a wave's 512 contiguous elements meet at most two of them, or an
+    // aligned causal unit (scales in scalar registers / once per band); 2 = any other unit with
+    // row scales (short rows, rows not made of whole vectors).
+    static int unit_class(const WorkUnit& u) {
+        if (!(u.flags & kUnitRowScale)) return 0;
+        if (u.flags & kUnitScalar) return 2;
+        if (u.flags & kUnitCausal) return 1;
+        return u.cols >= kVec * 64 ? 1 : 2;
+    }
+
+    // How a call is split between the kernels.
     struct Plan {
-        std::vector<UnitSchedule> schedule;       // positions of the chunks the streaming kernel takes
-        std::vector<WGroup> wgroups;              // work of the weight kernel
-        uint64_t n_positions = 0;                 // streaming kernel
-        uint64_t n_items = 0;                     // weight kernel
-        uint64_t w_pairs = 0;                     // element pairs the weight kernel covers
-        uint64_t w_bytes = 0;                     // bytes it is defined to read: x once per batch, xdot per member
+        std::vector<UnitSchedule> schedule;       // positions of the chunks the streaming kernels take
+        std::vector<WGroup> wgroups;              // work of the weight kernel: groups with one scale per
+                                                  // tensor first, then those with row scales; item_begin
+                                                  // counts from the first item of the group's launch
+        uint64_t class_pos[4] = {0, 0, 0, 0};     // streaming kernel of class c: positions [class_pos[c], class_pos[c+1])
+        uint64_t class_pairs[3] = {0, 0, 0};
+        uint64_t n_positions = 0;
+        size_t w_groups[2] = {0, 0};              // weight kernel launch v: groups, items, pairs, bytes
+        uint64_t w_items[2] = {0, 0};
+        uint64_t w_pairs[2] = {0, 0};             // element pairs the launch covers
+        uint64_t w_bytes[2] = {0, 0};             // bytes it is defined to read: x once per batch, xdot per member
     };
 
-    // Units stay in call order, except that the members of a group (same group id, equal chunk
-    // counts, at most 65535 of them) are interleaved block by block.  With use_w, a group whose
-    // members are whole-vector aligned and evenly spaced in the unit list hands its whole chunks to
-    // the weight kernel; the ragged last chunk stays with the streaming kernel.
+    // Units stay in call order inside their class, except that the members of a group (same group
+    // id, equal chunk counts, at most 65535 of them) are interleaved block by block.  With use_w, a
+    // group whose members are whole-vector aligned and evenly spaced in the unit list hands its
+    // whole chunks to the weight kernel; the ragged last chunk stays with the streaming kernel.
     Plan plan(uint32_t block, bool use_w) const {
         Plan P;
         P.schedule.resize(units.size());
@@ -169,48 +189,56 @@ struct WorkTable {
         for (size_t u = 0; u < units.size(); ++u)
             if (group[u] != 0) by_group[group[u]].push_back(u);
         std::vector<char> done(units.size(), 0);
-        for (size_t u = 0; u < units.size(); ++u) {
-            if (done[u]) continue;
-            std::vector<size_t> members(1, u);
-            if (group[u] != 0)
-                for (size_t v : by_group[group[u]])
-                    if (v > u && !done[v] && chunks_of(v) == chunks_of(u) && members.size() < 65535)
-                        members.push_back(v);
-            uint32_t skip = 0;
-            if (use_w && members.size() >= 2) {
-                bool ok = true;
-                const size_t stride = members[1] - members[0];
-                for (size_t m = 0; m < members.size() && ok; ++m) {
-                    const WorkUnit& w = units[members[m]];
-                    ok = w.flags == units[u].flags && (w.flags & (kUnitCausal | kUnitScalar)) == 0 &&
-                         w.head == 0 && w.x == units[u].x && w.n == units[u].n &&
-                         w.scale == units[u].scale && w.inv == units[u].inv && w.cols == units[u].cols &&
-                         members[m] == u + m * stride;
+        for (int cls = 0; cls < 3; ++cls) {
+            P.class_pos[cls] = P.n_positions;
+            for (size_t u = 0; u < units.size(); ++u) {
+                if (done[u] || unit_class(units[u]) != cls) continue;
+                std::vector<size_t> members(1, u);
+                if (group[u] != 0)
+                    for (size_t v : by_group[group[u]])
+                        if (v > u && !done[v] && chunks_of(v) == chunks_of(u) && members.size() < 65535 &&
+                            unit_class(units[v]) == cls)
+                            members.push_back(v);
+                uint32_t skip = 0;
+                if (use_w && members.size() >= 2) {
+                    bool ok = true;
+                    const size_t stride = members[1] - members[0];
+                    for (size_t m = 0; m < members.size() && ok; ++m) {
+                        const WorkUnit& w = units[members[m]];
+                        ok = w.flags == units[u].flags && (w.flags & (kUnitCausal | kUnitScalar)) == 0 &&
+                             w.head == 0 && w.x == units[u].x && w.n == units[u].n &&
+                             w.scale == units[u].scale && w.inv == units[u].inv && w.cols == units[u].cols &&
+                             members[m] == u + m * stride;
+                    }
+                    const uint64_t whole = (uint64_t)units[u].n / ((uint64_t)kChunkVecs * kVec);
+                    if (ok && whole > 0) {
+                        const int v = cls == 0 ? 0 : 1;
+                        skip = (uint32_t)whole;
+                        WGroup G;
+                        std::memset(&G, 0, sizeof(G));
+                        G.first_unit = (uint32_t)u;
+                        G.unit_stride = (uint32_t)stride;
+                        G.members = (uint32_t)members.size();
+                        G.chunks = skip;
+                        G.item_begin = (uint32_t)P.w_items[v];
+                        P.wgroups.push_back(G);
+                        P.w_groups[v] += 1;
+                        P.w_items[v] += whole * ((members.size() + kWBatch - 1) / kWBatch);
+                        P.w_pairs[v] += whole * (uint64_t)kChunkVecs * kVec * members.size();
+                        P.w_bytes[v] += whole * (uint64_t)kChunkVecs * kVec * 2 *
+                                        (members.size() + (members.size() + kWBatch - 1) / kWBatch);
+                    }
                 }
-                const uint64_t whole = (uint64_t)units[u].n / ((uint64_t)kChunkVecs * kVec);
-                if (ok && whole > 0) {
-                    skip = (uint32_t)whole;
-                    WGroup G;
-                    std::memset(&G, 0, sizeof(G));
-                    G.first_unit = (uint32_t)u;
-                    G.unit_stride = (uint32_t)stride;
-                    G.members = (uint32_t)members.size();
-                    G.chunks = skip;
-                    G.item_begin = (uint32_t)P.n_items;
-                    P.wgroups.push_back(G);
-                    P.n_items += whole * ((members.size() + kWBatch - 1) / kWBatch);
-                    P.w_pairs += whole * (uint64_t)kChunkVecs * kVec * members.size();
-                    P.w_bytes += whole * (uint64_t)kChunkVecs * kVec * 2 *
-                                 (members.size() + (members.size() + kWBatch - 1) / kWBatch);
+                for (size_t m = 0; m < members.size(); ++m) {
+                    P.schedule[members[m]] = UnitSchedule{(uint32_t)P.n_positions, (uint16_t)members.size(),
+                                                          (uint16_t)m, block, skip};
+                    done[members[m]] = 1;
+                    P.class_pairs[cls] += unit_pairs[members[m]] - (uint64_t)skip * kChunkVecs * kVec;
                 }
+                P.n_positions += (chunks_of(u) - skip) * members.size();
             }
-            for (size_t m = 0; m < members.size(); ++m) {
-                P.schedule[members[m]] = UnitSchedule{(uint32_t)P.n_positions, (uint16_t)members.size(),
-                                                      (uint16_t)m, block, skip};
-                done[members[m]] = 1;
-            }
-            P.n_positions += (chunks_of(u) - skip) * members.size();
         }
+        P.class_pos[3] = P.n_positions;
         return P;
     }
 };
@@ -250,7 +278,7 @@ int persistent_grid(uint64_t n_chunks, int resident) {
 
 int sens_grid(uint64_t n_chunks, int n_fmts, int f0, int f1, int rows) {
     static std::mutex mu;
-    static int cached[64][2][2][2][2];
+    static int cached[64][2][2][2][3];
     const int dev = device_index();
     int resident;
     if (dev < 0) {
@@ -364,8 +392,7 @@ amp_status_t run_sens(const WorkTable& t, const amp_fp8_format_t* fmts, int n_fm
     float* d_partials = (float*)(ws + L.partials);
     const UnitSchedule* d_sch = (const UnitSchedule*)(ws + t.schedule_offset());
     const WGroup* d_groups = (const WGroup*)(ws + t.groups_offset());
-    const int rows = t.any_rows ? 1 : 0;
-    AMP_HIP(launch_prepare(d_units, d_cb, d_sch, n_units, n_chunks, n_fmts, rows, d_runits, d_map, stream));
+    AMP_HIP(launch_prepare(d_units, d_cb, d_sch, n_units, n_chunks, n_fmts, d_runits, d_map, stream));
     auto timed_begin = [&](uint64_t pairs, uint64_t bytes) -> hipError_t {
         if (g_profile.used >= (int)g_profile.start.size()) return hipSuccess;
         g_profile.pairs[g_profile.used] = pairs;
@@ -376,17 +403,26 @@ amp_status_t run_sens(const WorkTable& t, const amp_fp8_format_t* fmts, int n_fm
         if (g_profile.used >= (int)g_profile.start.size()) return hipSuccess;
         return hipEventRecord(g_profile.stop[g_profile.used++], stream);
     };
-    if (plan.n_items > 0) {
-        const int grid = persistent_grid(plan.n_items, sens_w_grid(n_fmts, f0, f1, rows));
-        AMP_HIP(timed_begin(plan.w_pairs, plan.w_bytes));
-        AMP_HIP(launch_sens_w(d_groups, (uint32_t)plan.wgroups.size(), (uint32_t)plan.n_items, d_runits, d_cb,
-                              n_fmts, f0, f1, rows, d_partials, grid, stream));
-        AMP_HIP(timed_end());
+    // weight kernel: groups with one scale per tensor, then groups with one per output channel
+    size_t g0 = 0;
+    for (int v = 0; v < 2; ++v) {
+        if (plan.w_items[v] > 0) {
+            const int grid = persistent_grid(plan.w_items[v], sens_w_grid(n_fmts, f0, f1, v));
+            AMP_HIP(timed_begin(plan.w_pairs[v], plan.w_bytes[v]));
+            AMP_HIP(launch_sens_w(d_groups + g0, (uint32_t)plan.w_groups[v], (uint32_t)plan.w_items[v], d_runits,
+                                  d_cb, n_fmts, f0, f1, v, d_partials, grid, stream));
+            AMP_HIP(timed_end());
+        }
+        g0 += plan.w_groups[v];
     }
-    if (plan.n_positions > 0) {
-        const int grid = sens_grid(plan.n_positions, n_fmts, f0, f1, rows);
-        AMP_HIP(timed_begin(t.n_pairs - plan.w_pairs, (t.n_pairs - plan.w_pairs) * 4));
-        AMP_HIP(launch_sens(d_runits, d_map, (uint32_t)plan.n_positions, n_fmts, f0, f1, rows, d_partials, grid, stream));
+    // streaming kernels, one launch per class of units
+    for (int cls = 0; cls < 3; ++cls) {
+        const uint64_t n_pos = plan.class_pos[cls + 1] - plan.class_pos[cls];
+        if (n_pos == 0) continue;
+        const int grid = sens_grid(n_pos, n_fmts, f0, f1, cls);
+        AMP_HIP(timed_begin(plan.class_pairs[cls], plan.class_pairs[cls] * 4));
+        AMP_HIP(launch_sens(d_runits, d_map + plan.class_pos[cls], (uint32_t)n_pos, n_fmts, f0, f1, cls, d_partials,
+                            grid, stream));
         AMP_HIP(timed_end());
     }
     AMP_HIP(launch_sens_finalize(d_runits, d_cb, n_units, n_fmts, d_partials, d_out, stream));
@@ -523,6 +559,7 @@ WsLayout absmax_layout(const WorkTable& t) { return ws_layout(t, (size_t)kWaves 
 // memory span in elements); returns the number of accesses that fell outside [0, span), plus
 // the number of "full" vectors that were not 16-byte aligned.
 struct ReplayCtx {
+    static constexpr bool kRollDense = false;
     int32_t* counts;
     int64_t span;
     uintptr_t addr;          // byte address the unit would have
@@ -617,7 +654,7 @@ amp_status_t amp_absmax_scale(const amp_tensor_t* tensors, int n_tensors, const 
     ChunkRef* d_map = (ChunkRef*)(ws + L.map);
     uint32_t* d_partial_max = (uint32_t*)(ws + L.partials);
     const UnitSchedule* d_sch = (const UnitSchedule*)(ws + t.schedule_offset());
-    AMP_HIP(launch_prepare(d_units, d_cb, d_sch, n_units, n_chunks, 0, 0, d_runits, d_map, stream));
+    AMP_HIP(launch_prepare(d_units, d_cb, d_sch, n_units, n_chunks, 0, d_runits, d_map, stream));
     if (n_chunks > 0)
         AMP_HIP(launch_absmax(d_runits, d_map, n_chunks, d_partial_max, absmax_grid(n_chunks), stream));
     AMP_HIP(launch_absmax_finalize(d_cb, d_partial_max, n_tensors, n_fmts, (int)fmts[0],
@@ -652,8 +689,13 @@ amp_status_t build_absmax_rows(const amp_tensor_t* tensors, int n_tensors, RowPl
         R.row_len = (int32_t)row_len;
         R.causal_rows = T.layout.causal ? (int32_t)T.layout.rows : 0;
         R.aligned = ((uintptr_t)T.data % 16 == 0 && row_len % kVec == 0) ? 1u : 0u;
-        // about 8192 elements per work item, a whole number of rows
-        const int64_t per = row_len > 0 ? (8192 / row_len > 0 ? 8192 / row_len : 1) : 1;
+        // about 16384 elements per work item: a whole number of the row groups a wave handles at once
+        int64_t per = 1;
+        if (row_len > 0) {
+            const int64_t group = R.aligned ? 64 / absmax_row_lanes((int32_t)row_len, T.layout.causal != 0) : 1;
+            per = 16384 / row_len > 0 ? 16384 / row_len : 1;
+            per = (per + group - 1) / group * group;
+        }
         R.rows_per_item = (uint32_t)per;
         if (P->n_rows + (uint64_t)n_rows > 0xFFFFFFFFull) return AMP_ERR_TOO_LARGE;
         R.out_row = (uint32_t)P->n_rows;
@@ -844,7 +886,12 @@ int64_t ampsens_debug_check_linear_schedule(const amp_linear_desc_t* ops, int n_
     // the weight kernel's items: every (member, whole chunk) of a group exactly once, in bounds
     std::vector<uint32_t> covered(t.units.size(), 0);
     uint64_t items = 0;
+    size_t gi = 0;
     for (const WGroup& G : plan.wgroups) {
+        if (gi++ == plan.w_groups[0]) {                        // the second launch counts from 0 again
+            if (items != plan.w_items[0]) ++bad;
+            items = 0;
+        }
         if (G.item_begin != items) ++bad;
         items += (uint64_t)G.chunks * ((G.members + kWBatch - 1) / kWBatch);
         for (uint32_t m = 0; m < G.members; ++m) {
@@ -854,7 +901,7 @@ int64_t ampsens_debug_check_linear_schedule(const amp_linear_desc_t* ops, int n_
             if ((uint64_t)G.chunks * kChunkVecs * kVec > (uint64_t)t.units[u].n) ++bad;
         }
     }
-    if (items != plan.n_items) ++bad;
+    if (items != plan.w_items[plan.w_groups[1] > 0 ? 1 : 0]) ++bad;
     for (size_t u = 0; u < t.units.size(); ++u)
         if (covered[u] != sch[u].skip) ++bad;
     if (n_chunks_out) *n_chunks_out = t.n_chunks;

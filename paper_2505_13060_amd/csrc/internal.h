@@ -34,7 +34,8 @@ enum : uint32_t {
                                      // with ordinary caching; everything else streams non-temporally
     kUnitRowScale = 8u,              // one scale per row: scale / inv point at [rows][n_fmts] tables whose
                                      // first row is the unit's first row; dense units keep the row
-                                     // length in `cols`, causal units use their own rows and cols
+                                     // length in `cols` and their number of rows in `rows`, causal
+                                     // units use their own rows and cols
 };
 
 struct alignas(16) WorkUnit {        // 64 bytes
@@ -65,13 +66,13 @@ struct alignas(16) ResolvedUnit {    // 64 bytes
     uint32_t out;
     uint32_t chunks_per_mat;
     union {
-        struct {                     // calls with one scale per tensor everywhere: the values
+        struct {                     // one scale per tensor: the values
             float inv[kMaxFormats];
             float scale[kMaxFormats];
         };
-        struct {                     // calls in which some unit has a scale per row: [rows][n_fmts]
-            const float* row_inv;    // tables (a per-tensor unit of such a call is a one-row table
-            const float* row_scale;  // with row length 0 = "every element is in row 0")
+        struct {                     // kUnitRowScale: [rows][n_fmts] tables, first row = the unit's first
+            const float* row_inv;
+            const float* row_scale;
         };
     };
 };
@@ -134,16 +135,16 @@ inline uint32_t causal_chunks_per_mat(int64_t rows) {
 // ---- launchers (kernels.hip) ---------------------------------------------------------------
 // All enqueue on `stream` and return the launch error, never synchronise.
 // Persistent-grid size for the streaming kernels on the current device (resident workgroups).
-// `rows`: the variant that reads its scales from row tables.
-int sens_resident_blocks(int n_fmts, int fmt0, int fmt1, int rows, int cus);
+// cls: the class of units the variant is for: 0 = one scale per tensor; 1 = row scales, rows of at
+// least 512 elements or aligned causal rows; 2 = row scales, any other shape.
+int sens_resident_blocks(int n_fmts, int fmt0, int fmt1, int cls, int cus);
 int absmax_resident_blocks(int cus);
 int absmax_rows_resident_blocks(int cus);
 
-// row_tables != 0: keep the scale pointers (row tables) instead of resolving them to values.
+// Units with kUnitRowScale keep their scale pointers (row tables); the others get values.
 hipError_t launch_prepare(const WorkUnit* d_units, const uint32_t* d_chunk_begin,
                           const UnitSchedule* d_schedule, uint32_t n_units, uint32_t n_chunks,
-                          int n_fmts, int row_tables, ResolvedUnit* d_runits, ChunkRef* d_map,
-                          hipStream_t stream);
+                          int n_fmts, ResolvedUnit* d_runits, ChunkRef* d_map, hipStream_t stream);
 hipError_t launch_absmax(const ResolvedUnit* d_runits, const ChunkRef* d_map, uint32_t n_chunks,
                          uint32_t* d_partial_max, int grid, hipStream_t stream);
 hipError_t launch_absmax_finalize(const uint32_t* d_chunk_begin, const uint32_t* d_partial_max,
@@ -175,6 +176,16 @@ struct alignas(16) RowTensor {       // 48 bytes
     uint32_t reserved[2];
 };
 static_assert(sizeof(RowTensor) == 48, "RowTensor layout");
+// Lanes of a wave that share one row in the per-row absmax: a power of two, at most 64, chosen so
+// that a lane has about four vectors of its row to fetch; causal rows (whose valid length varies
+// from one vector to the whole row) take 8 lanes, i.e. 8 neighbouring rows per wave step.
+inline __host__ __device__ int absmax_row_lanes(int32_t row_len, bool causal) {
+    const int nv = row_len / kVec;
+    int L = 64;
+    while (L > 1 && (L >> 1) * 4 >= nv) L >>= 1;
+    if (causal && L > 8) L = 8;
+    return L;
+}
 hipError_t launch_absmax_rows(const RowTensor* d_tensors, uint32_t n_tensors, uint32_t n_items,
                               int n_fmts, int fmt0, int fmt1, float* d_amax, float* d_scale,
                               float* d_inv, uint32_t* d_flags, int grid, hipStream_t stream);

@@ -137,7 +137,6 @@ __global__ __launch_bounds__(kWG) void prepare_kernel(const WorkUnit* __restrict
                                                       const uint32_t* __restrict__ chunk_begin,
                                                       const UnitSchedule* __restrict__ schedule,
                                                       uint32_t n_units, uint32_t n_chunks, int n_fmts,
-                                                      int row_tables,
                                                       ResolvedUnit* __restrict__ runits,
                                                       ChunkRef* __restrict__ map) {
     const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -146,7 +145,7 @@ __global__ __launch_bounds__(kWG) void prepare_kernel(const WorkUnit* __restrict
         ResolvedUnit r;
         r.x = u.x; r.dx = u.dx; r.n = u.n; r.rows = u.rows; r.cols = u.cols; r.flags = u.flags;
         r.head = u.head; r.out = u.out; r.chunks_per_mat = u.chunks_per_mat;
-        if (row_tables) {
+        if (u.flags & kUnitRowScale) {
             r.row_inv = u.inv;
             r.row_scale = u.scale;
         } else {
@@ -202,6 +201,7 @@ __device__ __forceinline__ void one_format(const float (&xv)[4], const float (&g
 
 template <int NF, int F0, int F1>
 struct SensCtx {
+    static constexpr bool kRollDense = false;
     gptr16_t x;
     gptr16_t g;
     bool keep_x;                                   // x is re-read soon: ordinary caching
@@ -300,9 +300,10 @@ struct SensCtx {
 //   causal: the walker names the row of the vectors that follow, its scales are fetched once;
 //   dense, rows not made of whole vectors: element by element, one division per element (slow,
 //       only for odd row lengths or misaligned buffers).
-// A unit of such a call that has one scale for the whole tensor is a table of one row.
+// Only units with row scales reach this context; it is the general one (any row length).
 template <int NF, int F0, int F1>
 struct SensRowCtx {
+    static constexpr bool kRollDense = false;
     enum Mode { kRow, kCursor, kElem };
     gptr16_t x;
     gptr16_t g;
@@ -340,14 +341,8 @@ struct SensRowCtx {
 #pragma unroll
         for (int f = 0; f < NF; ++f) { E[f] = 0.0f; pk[f] = 0; inv[f] = 1.0f; scale[f] = 1.0f; }
         A = 0.0f;
-        if (!(u.flags & kUnitRowScale)) {
-            mode = kRow;
-            if (u.row_inv != nullptr && u.row_scale != nullptr) load_row(0u, inv, scale);
-        } else if (u.flags & kUnitCausal) {
-            mode = kRow;
-        } else {
-            mode = (u.flags & kUnitScalar) ? kElem : kCursor;
-        }
+        if (u.flags & kUnitCausal) mode = kRow;
+        else mode = (u.flags & kUnitScalar) ? kElem : kCursor;
     }
     __device__ __forceinline__ void begin_dense(int64_t e0, int le) {
         if (mode == kCursor) cur.begin(e0, le, kWG * kVec, row_len);
@@ -474,6 +469,158 @@ struct SensRowCtx {
     }
 };
 
+// Row scales for units whose rows hold at least 512 elements (or aligned causal units): the 64
+// lanes of a wave cover 512 contiguous elements per vector step, so a step meets at most two rows.
+// The wave follows its own position with a cursor in scalar registers and fetches the scales of
+// those rows through the scalar cache; steps that lie inside one row (all of them when the row
+// length is a multiple of 512) use them as scalar operands, the others select per lane.  Causal
+// units: a lane stays in one row per band and fetches that row's scales once.
+template <int NF, int F0, int F1>
+struct SensWaveRowCtx {
+    static constexpr bool kRollDense = true;
+    gptr16_t x;
+    gptr16_t g;
+    bool keep_x;
+    gptrf_t ri;
+    gptrf_t rs;
+    int32_t row_len, last_row;
+    bool causal;
+    int lane;
+    RowCursor cur;                                 // of the wave's first lane; uniform over the wave
+    float inv[NF], scale[NF];                      // causal: of the lane's current row
+    float E[NF];
+    float A;
+    int pk[NF];
+
+    __device__ __forceinline__ void init(const ResolvedUnit& u) {
+        x = (gptr16_t)u.x;
+        g = (gptr16_t)u.dx;
+        keep_x = (u.flags & kUnitKeepX) != 0;
+        ri = (gptrf_t)u.row_inv;
+        rs = (gptrf_t)u.row_scale;
+        row_len = u.cols;
+        causal = (u.flags & kUnitCausal) != 0;
+        last_row = causal ? 0 : u.rows - 1;
+        lane = threadIdx.x & 63;
+#pragma unroll
+        for (int f = 0; f < NF; ++f) { E[f] = 0.0f; pk[f] = 0; inv[f] = 1.0f; scale[f] = 1.0f; }
+        A = 0.0f;
+    }
+    template <class Row>
+    __device__ __forceinline__ void load_row(Row row, float (&iv)[NF], float (&sc)[NF]) const {
+#pragma unroll
+        for (int f = 0; f < NF; ++f) {
+            iv[f] = ri[row * NF + f];
+            sc[f] = rs[row * NF + f];
+        }
+    }
+    __device__ __forceinline__ void begin_dense(int64_t e0, int le) {
+        cur.begin(e0, __builtin_amdgcn_readfirstlane(le - lane * kVec), kWG * kVec, row_len);
+        cur.row = __builtin_amdgcn_readfirstlane(cur.row);
+        cur.col = __builtin_amdgcn_readfirstlane(cur.col);
+    }
+    __device__ __forceinline__ void set_row(int64_t row) { load_row(row, inv, scale); }
+
+    __device__ __forceinline__ void quad(uint32_t xw0, uint32_t xw1, uint32_t gw0, uint32_t gw1,
+                                         const float (&iv)[NF], const float (&sc)[NF]) {
+        const float xv[4] = {bf16_lo(xw0), bf16_hi(xw0), bf16_lo(xw1), bf16_hi(xw1)};
+        const float gv[4] = {bf16_lo(gw0), bf16_hi(gw0), bf16_lo(gw1), bf16_hi(gw1)};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float a = gv[j] * xv[j];
+            A = fmaf(a, a, A);
+        }
+        one_format<F0>(xv, gv, iv[0], sc[0], E[0], pk[0]);
+        if constexpr (NF > 1) one_format<F1>(xv, gv, iv[1], sc[1], E[1], pk[1]);
+    }
+    __device__ __forceinline__ void vec(const u32x4& xv, const u32x4& gv, const float (&iv)[NF],
+                                        const float (&sc)[NF]) {
+        quad(xv.x, xv.y, gv.x, gv.y, iv, sc);
+        quad(xv.z, xv.w, gv.z, gv.w, iv, sc);
+    }
+
+    template <int U>
+    __device__ __forceinline__ void full(int64_t eu, int le, int64_t stride) {
+        const gptr128_t bx = reinterpret_cast<gptr128_t>(x + eu);
+        const gptr128_t bg = reinterpret_cast<gptr128_t>(g + eu);
+        const int lv = le / kVec;
+        const int64_t sv = stride / kVec;
+        u32x4 xr[U], gr[U];
+        if (keep_x) {
+#pragma unroll
+            for (int k = 0; k < U; ++k) xr[k] = load128<false>(bx + k * sv + lv);
+        } else {
+#pragma unroll
+            for (int k = 0; k < U; ++k) xr[k] = load128<true>(bx + k * sv + lv);
+        }
+#pragma unroll
+        for (int k = 0; k < U; ++k) gr[k] = load128<true>(bg + k * sv + lv);
+        // rows of the wave's U steps
+        int32_t row_a[U], rem[U];
+#pragma unroll
+        for (int k = 0; k < U; ++k) {
+            row_a[k] = cur.row;
+            rem[k] = row_len - cur.col;                // elements of row_a left from the wave's first lane on
+            cur.advance();
+        }
+#pragma unroll
+        for (int k = 0; k < U; ++k) {
+            float iv[NF], sc[NF];
+            load_row((uint32_t)row_a[k], iv, sc);      // uniform: scalar loads
+            if (rem[k] >= 64 * kVec) {                 // the whole step lies in one row: scalar operands
+                vec(xr[k], gr[k], iv, sc);
+            } else {
+                float ib[NF], sb[NF];
+                load_row((uint32_t)(row_a[k] < last_row ? row_a[k] + 1 : last_row), ib, sb);
+                const bool second = lane * kVec >= rem[k];
+#pragma unroll
+                for (int f = 0; f < NF; ++f) {
+                    ib[f] = second ? ib[f] : iv[f];
+                    sb[f] = second ? sb[f] : sc[f];
+                }
+                vec(xr[k], gr[k], ib, sb);
+            }
+        }
+    }
+
+    template <int U>
+    __device__ __forceinline__ void full_masked(int64_t e, int stride, int count, int tail) {
+        const gptr128_t px = reinterpret_cast<gptr128_t>(x + e);
+        const gptr128_t pg = reinterpret_cast<gptr128_t>(g + e);
+        const int sv = stride / kVec;
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+        u32x4 xr[U], gr[U];
+#pragma unroll
+        for (int k = 0; k < U; ++k) {
+            xr[k] = k < count ? load128<true>(px + k * sv) : zero;
+            gr[k] = k < count ? load128<true>(pg + k * sv) : zero;
+        }
+        if (tail < kVec) {
+#pragma unroll
+            for (int k = 0; k < U; ++k)
+                if (k == count - 1) { xr[k] = keep_leading(xr[k], tail); gr[k] = keep_leading(gr[k], tail); }
+        }
+#pragma unroll
+        for (int k = 0; k < U; ++k)
+            if (k < count) vec(xr[k], gr[k], inv, scale);
+    }
+
+    // Not reached for the units this context is given (rows of whole vectors, aligned causal
+    // rows); kept correct: the element's row by division, or the row the causal walker named.
+    __device__ __forceinline__ void partial(int64_t e, int jlo, int jhi) {
+        const u32x4 xv = gather8(x, e, jlo, jhi);
+        const u32x4 gv = gather8(g, e, jlo, jhi);
+        float iv[NF], sc[NF];
+        if (!causal && row_len > 0) {
+            load_row((e + jlo) / row_len, iv, sc);
+        } else {
+#pragma unroll
+            for (int f = 0; f < NF; ++f) { iv[f] = inv[f]; sc[f] = scale[f]; }
+        }
+        vec(xv, gv, iv, sc);
+    }
+};
+
 template <class Ctx, int NF>
 __device__ __forceinline__ void sens_body(const ResolvedUnit* __restrict__ runits,
                                           const ChunkRef* __restrict__ map, uint32_t n_chunks,
@@ -514,6 +661,16 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
                                                    const ChunkRef* __restrict__ map,
                                                    uint32_t n_chunks, float* __restrict__ partials) {
     sens_body<SensCtx<NF, F0, F1>, NF>(runits, map, n_chunks, partials);
+}
+
+#ifndef AMPSENS_WROWS_WAVES
+#define AMPSENS_WROWS_WAVES 6
+#endif
+template <int NF, int F0, int F1>
+__global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(AMPSENS_WROWS_WAVES, AMPSENS_WROWS_WAVES))) void sens_wrows_kernel(const ResolvedUnit* __restrict__ runits,
+                                                        const ChunkRef* __restrict__ map,
+                                                        uint32_t n_chunks, float* __restrict__ partials) {
+    sens_body<SensWaveRowCtx<NF, F0, F1>, NF>(runits, map, n_chunks, partials);
 }
 
 #ifndef AMPSENS_ROWS_WAVES
@@ -565,8 +722,8 @@ __global__ __launch_bounds__(kWG) void sens_w_kernel(const WGroup* __restrict__ 
 #pragma unroll
         for (int f = 0; f < NF; ++f) {
             if constexpr (ROWS) {
-                inv[f] = u0.row_inv[f];             // a table of one row unless the unit has row scales
-                scale[f] = u0.row_scale[f];
+                inv[f] = 1.0f;                      // fetched per vector below
+                scale[f] = 1.0f;
             } else {
                 inv[f] = u0.inv[f];
                 scale[f] = u0.scale[f];
@@ -583,21 +740,18 @@ __global__ __launch_bounds__(kWG) void sens_w_kernel(const WGroup* __restrict__ 
         const gptr128_t px = reinterpret_cast<gptr128_t>((gptr16_t)u0.x + base);
         int pk = 0;
         RowCursor cur;
-        const bool by_row = ROWS && (u0.flags & kUnitRowScale) != 0;
-        if constexpr (ROWS) cur.begin(base, tid * kVec, kWG * kVec, by_row ? u0.cols : 0);
+        if constexpr (ROWS) cur.begin(base, tid * kVec, kWG * kVec, u0.cols);
 #pragma unroll 1
         for (int s = 0; s < kChunkVecs / kWG; ++s) {
             const int v = s * kWG + tid;
             const u32x4 xw = load128<false>(px + v);
             if constexpr (ROWS) {
-                if (by_row) {
 #pragma unroll
-                    for (int f = 0; f < NF; ++f) {
-                        inv[f] = ((gptrf_t)u0.row_inv)[(uint32_t)cur.row * NF + f];
-                        scale[f] = ((gptrf_t)u0.row_scale)[(uint32_t)cur.row * NF + f];
-                    }
-                    cur.advance();
+                for (int f = 0; f < NF; ++f) {
+                    inv[f] = ((gptrf_t)u0.row_inv)[(uint32_t)cur.row * NF + f];
+                    scale[f] = ((gptrf_t)u0.row_scale)[(uint32_t)cur.row * NF + f];
                 }
+                cur.advance();
             }
             u32x4 gr[kWLoad];
 #pragma unroll
@@ -716,6 +870,7 @@ __global__ __launch_bounds__(kWG) void sens_finalize_kernel(const ResolvedUnit* 
 // ---- absmax ---------------------------------------------------------------------------------
 
 struct AbsmaxCtx {
+    static constexpr bool kRollDense = false;
     gptr16_t x;
     uint32_t m;                                     // running max of (bits & 0x7FFF)
 
@@ -836,9 +991,9 @@ __global__ __launch_bounds__(kFinThreads) void absmax_finalize_kernel(const uint
 
 // ---- absmax and scales per row ----------------------------------------------------------------
 // A wave owns a run of consecutive rows of one tensor.  Rows made of whole, aligned vectors are
-// read with 128-bit loads by min(64, next power of two >= vectors per row) lanes each, so that
-// short rows (128 elements = 16 lanes) still fill the wave with 4 rows at a time; other rows are
-// read element by element.  Every row is reduced inside its lane group and written by one lane:
+// read with 128-bit loads by a group of lanes sized so that every lane has about four vectors to
+// fetch (a 128-element row: 4 lanes, 16 rows per wave step); other rows are read element by
+// element by the whole wave.  Every row is reduced inside its lane group and written by one lane:
 // no partials, no second kernel.  flags must be zero before the launch.
 __device__ __forceinline__ uint32_t max_words(uint32_t m, const u32x4& v) {
     const uint32_t w[4] = {v.x, v.y, v.z, v.w};
@@ -875,11 +1030,7 @@ __global__ __launch_bounds__(kWG) void absmax_rows_kernel(const RowTensor* __res
         const int64_t row0 = (int64_t)(item - T.item_begin) * T.rows_per_item;
         const int64_t row1 = row0 + T.rows_per_item < T.n_rows ? row0 + T.rows_per_item : T.n_rows;
         const int32_t i0 = T.causal_rows > 0 ? (int32_t)(row0 % T.causal_rows) : 0;   // row0's index in its matrix
-        int L = 64;                                  // lanes per row
-        if (T.aligned) {
-            const int nv = T.row_len / kVec;
-            while (L > 1 && (L >> 1) >= nv) L >>= 1;
-        }
+        const int L = T.aligned ? absmax_row_lanes(T.row_len, T.causal_rows > 0) : 64;   // lanes per row
         const int G = 64 / L, sub = lane / L, sl = lane - sub * L;
         for (int64_t rb = row0; rb < row1; rb += G) {
             const int64_t rho = rb + sub;
@@ -972,8 +1123,13 @@ __global__ __launch_bounds__(kWG) void fake_quant_kernel(const uint16_t* __restr
 
 typedef void (*sens_fn_t)(const ResolvedUnit*, const ChunkRef*, uint32_t, float*);
 
-sens_fn_t sens_variant(int n_fmts, int fmt0, int fmt1, int rows) {
-    if (rows) {
+sens_fn_t sens_variant(int n_fmts, int fmt0, int fmt1, int cls) {
+    if (cls == 1) {
+        if (n_fmts == 1) return fmt0 == 0 ? sens_wrows_kernel<1, 0, 0> : sens_wrows_kernel<1, 1, 1>;
+        if (fmt0 == 0) return fmt1 == 0 ? sens_wrows_kernel<2, 0, 0> : sens_wrows_kernel<2, 0, 1>;
+        return fmt1 == 0 ? sens_wrows_kernel<2, 1, 0> : sens_wrows_kernel<2, 1, 1>;
+    }
+    if (cls == 2) {
         if (n_fmts == 1) return fmt0 == 0 ? sens_rows_kernel<1, 0, 0> : sens_rows_kernel<1, 1, 1>;
         if (fmt0 == 0) return fmt1 == 0 ? sens_rows_kernel<2, 0, 0> : sens_rows_kernel<2, 0, 1>;
         return fmt1 == 0 ? sens_rows_kernel<2, 1, 0> : sens_rows_kernel<2, 1, 1>;
@@ -1037,11 +1193,10 @@ hipError_t launch_absmax_rows(const RowTensor* d_tensors, uint32_t n_tensors, ui
 
 hipError_t launch_prepare(const WorkUnit* d_units, const uint32_t* d_chunk_begin,
                           const UnitSchedule* d_schedule, uint32_t n_units, uint32_t n_chunks,
-                          int n_fmts, int row_tables, ResolvedUnit* d_runits, ChunkRef* d_map,
-                          hipStream_t stream) {
+                          int n_fmts, ResolvedUnit* d_runits, ChunkRef* d_map, hipStream_t stream) {
     const uint32_t n = n_units > n_chunks ? n_units : n_chunks;
     hipLaunchKernelGGL(prepare_kernel, dim3((n + kWG - 1) / kWG), dim3(kWG), 0, stream, d_units,
-                       d_chunk_begin, d_schedule, n_units, n_chunks, n_fmts, row_tables, d_runits, d_map);
+                       d_chunk_begin, d_schedule, n_units, n_chunks, n_fmts, d_runits, d_map);
     return hipGetLastError();
 }
 

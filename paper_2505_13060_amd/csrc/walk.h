@@ -19,6 +19,8 @@
 //       a dense chunk starts: the vectors this thread is about to be given (by full and partial,
 //       one after the other) start at elements e0 + le, e0 + le + kWG*kVec, e0 + le + 2*kWG*kVec, ...
 //       A context that needs the row of every vector follows them with a RowCursor.
+//   static constexpr bool kRollDense
+//       true: the walk over a whole dense chunk stays a loop instead of being unrolled
 //   void set_row(int64_t row)
 //       causal chunks: the vectors that follow, until the next call, lie in row `row` of the unit
 //       (matrix index * rows + row index)
@@ -78,9 +80,15 @@ AMPSENS_HD void walk_dense_chunk(int64_t n, uint32_t head, bool scalar, uint32_t
     ctx.begin_dense(v0 * kVec - head, tid * kVec);
     if (dense_chunk_interior(n, head, scalar, chunk_local)) {
         const int64_t eu = v0 * kVec - head;
+        if constexpr (Ctx::kRollDense) {               // the context's code per group is large: keep one copy
+#pragma unroll 1
+            for (int k = 0; k < kChunkVecs / kWG; k += kUnroll)
+                ctx.template full<kUnroll>(eu + (int64_t)k * kWG * kVec, tid * kVec, (int64_t)kWG * kVec);
+        } else {
 #pragma unroll
-        for (int k = 0; k < kChunkVecs / kWG; k += kUnroll)
-            ctx.template full<kUnroll>(eu + (int64_t)k * kWG * kVec, tid * kVec, (int64_t)kWG * kVec);
+            for (int k = 0; k < kChunkVecs / kWG; k += kUnroll)
+                ctx.template full<kUnroll>(eu + (int64_t)k * kWG * kVec, tid * kVec, (int64_t)kWG * kVec);
+        }
         return;
     }
     if (v1 > nvec) v1 = nvec;
