@@ -84,20 +84,23 @@ def host_tail(workload, res, n_blocks, amp):
     else:
         groups = [[n] for n in names]           # J = L special case
     rng = np.random.default_rng(2002)
+    # the same resident tensors stand for every block of the sweep; a seeded per-block factor stands
+    # in for the depth dependence of the gradients' magnitude.  d_{j,p} is linear in the layers' loss
+    # MSE, so each group's table is built once and scaled per block.
+    depth = np.exp(rng.normal(0.0, 0.7, n_blocks))
+    tables = []
+    for g in groups:
+        lm = np.zeros((len(g), nf + 1))
+        lg = np.zeros((len(g), nf + 1))
+        for i, n in enumerate(g):
+            lm[i, 1:] = layer[n][2]                               # measured first-order loss MSE
+            lg[i, 1:] = 0.5 * macs[n]                             # FP8 halves the MAC time
+        tables.append(amp.amp_group_tables(lm, lg))
     n_choices, gains, mses = [], [], []
     for b in range(n_blocks):
-        # the same resident tensors stand for every block of the sweep; a seeded per-block factor
-        # stands in for the depth dependence of the gradients' magnitude
-        depth = float(np.exp(rng.normal(0.0, 0.7)))
-        for g in groups:
-            lm = np.zeros((len(g), nf + 1))
-            lg = np.zeros((len(g), nf + 1))
-            for i, n in enumerate(g):
-                lm[i, 1:] = layer[n][2] * depth                   # measured first-order loss MSE
-                lg[i, 1:] = 0.5 * macs[n]                         # FP8 halves the MAC time
-            d, c = amp.amp_group_tables(lm, lg)
+        for d, c in tables:
             n_choices.append(d.size)
-            mses.append(d)
+            mses.append(d * depth[b])
             gains.append(c)
     total = sum(float(m.max()) for m in mses)
     budget = 1e-3 * total
