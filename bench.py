@@ -176,7 +176,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=32)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="config2")
     ap.add_argument("--scales", choices=["tensor", "rows"], default="tensor",
                     help="scale granularity: one per tensor (headline) or one per row (per token / per "

@@ -293,11 +293,23 @@ def test_workspace_too_small_is_reported_on_gpu_box_too():
 # configuration bench.py times; the oracle recomputes sampled (op, operand, sample) units in full
 # ---------------------------------------------------------------------------------------------
 
-def test_config1_full_size_sampled_units():
-    say("config1 at full size: generating 13.9 GB on the GPU")
-    w = wl.config1(DEV)
+FULL_SIZE = {
+    # which (op, sample) units the oracle recomputes: activations, weights, K, P, V
+    "config1": dict(make=lambda: wl.config1(DEV), x=(("q_proj", 3), ("down_proj", 0)),
+                    w=(("gate_proj", 5), ("o_proj", 7)), k=7, p=1, v=6),
+    # the benchmark's workload: R = 16, i.e. two batches of 8 samples for the weight kernel
+    "config2_block": dict(make=lambda: wl.config2_block(DEV, 5), x=(("k_proj", 11),),
+                          w=(("up_proj", 13), ("v_proj", 2)), k=15, p=9, v=None),
+}
+
+
+@pytest.mark.parametrize("which", ["config1", "config2_block"])
+def test_full_size_sampled_units(which):
+    plan = FULL_SIZE[which]
+    say("%s at full size: generating on the GPU" % which)
+    w = plan["make"]()
     torch.cuda.synchronize()
-    say("config1 at full size: %.1f M pairs; running the pass" % (w.pairs() / 1e6))
+    say("%s at full size: %.1f M pairs; running the pass" % (which, w.pairs() / 1e6))
     p = SensPass(w, DEV)
     p.run()
     res = p.results()
@@ -313,7 +325,7 @@ def test_config1_full_size_sampled_units():
             parity.assert_sum_close(got4[fi, col], E[0], parity.E_FLOOR * A[0], tag + " E fmt=%d" % f)
 
     # activations of q_proj, sample 3; down_proj, sample 0
-    for name, r in (("q_proj", 3), ("down_proj", 0)):
+    for name, r in plan["x"]:
         k, op = lin[name]
         say("  %s X sample %d" % (name, r))
         sc = parity.check_scales(res, 2 * k, wl.to_bits(op.x).reshape(-1), fmts, None, name + ".x")
@@ -321,7 +333,7 @@ def test_config1_full_size_sampled_units():
         xb, gb = wl.to_bits(op.x[rows]).reshape(-1), wl.to_bits(op.dx[rows]).reshape(-1)
         check_unit("%s.X r=%d" % (name, r), res["linear"][k][r], 0, xb, gb, xb.size, sc)
     # weights of gate_proj with the gradient of sample 5; o_proj with sample 7
-    for name, r in (("gate_proj", 5), ("o_proj", 7)):
+    for name, r in plan["w"]:
         k, op = lin[name]
         say("  %s W sample %d" % (name, r))
         wb = wl.to_bits(op.w).reshape(-1)
@@ -329,20 +341,24 @@ def test_config1_full_size_sampled_units():
         check_unit("%s.W r=%d" % (name, r), res["linear"][k][r], 2, wb, wl.to_bits(op.dw[r]).reshape(-1), wb.size, sc)
     # K of QK^T, sample 7 (dense); P of PV, sample 1 (causal); V of PV, sample 6
     k, op = bg["qk_matmul"]
-    say("  qk_matmul K sample 7")
+    r = plan["k"]
+    say("  qk_matmul K sample %d" % r)
     sc = parity.check_scales(res, 2 * nl + 2 * k + 1, wl.to_bits(op.x1).reshape(-1), fmts, None, "K")
-    kb = wl.to_bits(op.x1[7]).reshape(-1)
-    check_unit("K r=7", res["bgemm"][k][7], 2, kb, wl.to_bits(op.dx1[7]).reshape(-1), kb.size, sc)
+    kb = wl.to_bits(op.x1[r]).reshape(-1)
+    check_unit("K r=%d" % r, res["bgemm"][k][r], 2, kb, wl.to_bits(op.dx1[r]).reshape(-1), kb.size, sc)
     k, op = bg["av_matmul"]
     _, H, S, S2 = op.lay0
-    say("  av_matmul P (causal %dx%dx%d) sample 1" % (H, S, S2))
+    r = plan["p"]
+    say("  av_matmul P (causal %dx%dx%d) sample %d" % (H, S, S2, r))
     sc = parity.check_scales(res, 2 * nl + 2 * k, wl.to_bits(op.x0).reshape(-1), fmts, (op.R * H, S, S2), "P")
-    check_unit("P r=1", res["bgemm"][k][1], 0, wl.to_bits(op.x0[1]).reshape(-1), wl.to_bits(op.dx0[1]).reshape(-1),
+    check_unit("P r=%d" % r, res["bgemm"][k][r], 0, wl.to_bits(op.x0[r]).reshape(-1), wl.to_bits(op.dx0[r]).reshape(-1),
                0, sc, causal=(H, S, S2))
-    say("  av_matmul V sample 6")
-    sc = parity.check_scales(res, 2 * nl + 2 * k + 1, wl.to_bits(op.x1).reshape(-1), fmts, None, "V")
-    vb = wl.to_bits(op.x1[6]).reshape(-1)
-    check_unit("V r=6", res["bgemm"][k][6], 2, vb, wl.to_bits(op.dx1[6]).reshape(-1), vb.size, sc)
+    if plan["v"] is not None:
+        r = plan["v"]
+        say("  av_matmul V sample %d" % r)
+        sc = parity.check_scales(res, 2 * nl + 2 * k + 1, wl.to_bits(op.x1).reshape(-1), fmts, None, "V")
+        vb = wl.to_bits(op.x1[r]).reshape(-1)
+        check_unit("V r=%d" % r, res["bgemm"][k][r], 2, vb, wl.to_bits(op.dx1[r]).reshape(-1), vb.size, sc)
     # properties that hold at any size: A does not depend on the format; every sum is finite, positive
     for arr in res["linear"] + res["bgemm"]:
         assert np.all(np.isfinite(arr)) and np.all(arr > 0)
