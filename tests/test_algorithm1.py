@@ -1,0 +1,165 @@
+"""The paper's Algorithm 1 assembled from the library's host calls (paper_2505_13060_amd/algorithm1.py):
+tables, budget tau^2 E[g^2], selection, decoding; checked on synthetic statistics against what
+eq. (ip) and Sec. 2.2-2.3 fix.  The GPU test runs the whole procedure on a small random model."""
+import itertools
+import os
+import sys
+
+import numpy as np
+import pytest
+
+sys.path.insert(0, os.path.dirname(__file__))
+
+import oracle
+import paper_2505_13060_amd as amp
+from paper_2505_13060_amd import algorithm1 as a1
+
+FMTS = [amp.E4M3, amp.E5M2]
+NAMES = ["q_proj", "k_proj", "v_proj", "qk", "pv", "o_proj", "gate_proj", "up_proj", "down_proj"]
+LLAMA_EDGES = [("in", "q_proj"), ("in", "k_proj"), ("in", "v_proj"), ("q_proj", "qk"), ("k_proj", "qk"),
+               ("qk", "pv"), ("v_proj", "pv"), ("pv", "o_proj"), ("o_proj", "gate_proj"), ("o_proj", "up_proj"),
+               ("gate_proj", "mul"), ("up_proj", "mul"), ("mul", "down_proj")]    # mul: SiLU(gate) * up
+VERTICES = ["in"] + NAMES + ["mul"]
+
+
+def fake_sums(seed, R=4):
+    rng = np.random.default_rng(seed)
+    sums = {}
+    for n in NAMES:
+        A0, A1 = rng.uniform(0.5, 2.0, R), rng.uniform(0.5, 2.0, R)
+        s = np.zeros((R, 2, 4), dtype=np.float32)
+        for f, ratio in enumerate((0.43 / 768, 0.43 / 192)):
+            s[:, f, 0], s[:, f, 1] = A0 * ratio * rng.uniform(0.8, 1.2, R), A0
+            s[:, f, 2], s[:, f, 3] = A1 * ratio * rng.uniform(0.8, 1.2, R), A1
+        sums[n] = s
+    return sums
+
+
+def shapes():
+    ops = {n: dict(kind="linear", N=64, C=128, K=128) for n in NAMES}
+    ops["gate_proj"] = ops["up_proj"] = dict(kind="linear", N=64, C=128, K=352)
+    ops["down_proj"] = dict(kind="linear", N=64, C=352, K=128)
+    ops["qk"] = dict(kind="bgemm", N=4 * 64, C=32, K=64)
+    ops["pv"] = dict(kind="bgemm", N=4 * 64, C=64, K=32)
+    return ops
+
+
+def test_partition_of_a_llama_layer_is_the_papers_figure():
+    groups = a1.partition(VERTICES, LLAMA_EDGES, quantizable=NAMES)
+    assert [sorted(g) for g in groups] == [sorted(["q_proj", "k_proj", "v_proj", "qk", "pv"]), ["o_proj"],
+                                           ["gate_proj", "up_proj"], ["down_proj"]]
+
+
+def test_loss_mse_of_a_layer_follows_sec_2_2():
+    sums = fake_sums(1)
+    model = a1.layer_loss_mse(sums, FMTS, "model")
+    meas = a1.layer_loss_mse(sums, FMTS, "measured")
+    for n, s in sums.items():
+        s64 = s.astype(np.float64)
+        s_l = np.mean(s64[:, 0, 1] + s64[:, 0, 3])                        # eq. (sensl)
+        assert model[n][0] == pytest.approx(s_l / 768.0, rel=1e-12)        # alpha of 3 mantissa bits
+        assert model[n][1] == pytest.approx(s_l / 192.0, rel=1e-12)
+        assert meas[n][1] == pytest.approx(np.mean(s64[:, 1, 0] + s64[:, 1, 2]), rel=1e-12)
+
+
+def test_gains_follow_sec_2_3():
+    g = a1.theoretical_gains(shapes(), 2, "time", delta=0.5)
+    assert g["gate_proj"][0] == 64 * 128 * 352 * 0.5 and g["gate_proj"][1] == g["gate_proj"][0]
+    assert g["qk"][0] == 4 * 64 * 32 * 32 * 0.5                            # N C^2 delta for a BGEMM
+    m = a1.theoretical_gains(shapes(), 2, "memory", delta=1.0)
+    assert m["down_proj"][0] == 352 * 128 and m["pv"][0] == 0.0
+
+
+def test_selection_against_enumeration_and_the_budget_end_points():
+    sums = fake_sums(2)
+    groups = a1.partition(VERTICES, LLAMA_EDGES, quantizable=NAMES)
+    gains = a1.theoretical_gains(shapes(), 2, "time")
+    mean_g2 = 4.0
+    mse = a1.layer_loss_mse(sums, FMTS)
+    n_choices, G, D = a1.build_tables(groups, mse, gains)
+    assert list(n_choices) == [3 ** 5, 3, 9, 3]
+    # tau = 0: everything stays at high precision; a huge tau: every op takes an FP8 format
+    cfg, info = a1.select(sums, mean_g2, 0.0, groups, gains, FMTS)
+    assert all(v is None for v in cfg.values()) and info["total_gain"] == 0.0
+    cfg, info = a1.select(sums, mean_g2, 1e3, groups, gains, FMTS)
+    assert all(v is not None for v in cfg.values())
+    assert info["total_gain"] == pytest.approx(sum(g[0] for g in gains.values()), rel=1e-12)
+    # in between: the optimum of eq. (ip) by brute force over per-op formats (the objective and the
+    # constraint are additive over ops, so the groups do not restrict the optimum here)
+    tau = 0.035
+    cfg, info = a1.select(sums, mean_g2, tau, groups, gains, FMTS)
+    budget = tau ** 2 * mean_g2
+    best = 0.0
+    for combo in itertools.product(range(3), repeat=len(NAMES)):
+        d = sum(mse[n][c - 1] for n, c in zip(NAMES, combo) if c)
+        if d <= budget:
+            best = max(best, sum(gains[n][c - 1] for n, c in zip(NAMES, combo) if c))
+    assert 0.0 < best < sum(g[0] for g in gains.values())
+    assert info["total_gain"] == pytest.approx(best, rel=1e-12)
+    assert info["total_mse"] <= budget
+    # the decoded configuration reproduces the reported totals
+    got_gain = sum(gains[n][FMTS.index(f)] for n, f in cfg.items() if f is not None)
+    got_mse = sum(mse[n][FMTS.index(f)] for n, f in cfg.items() if f is not None)
+    assert got_gain == pytest.approx(info["total_gain"], rel=1e-12)
+    assert got_mse == pytest.approx(info["total_mse"], rel=1e-12)
+
+
+def test_curve_is_monotone_and_ip_dominates_the_ordered_baselines():
+    sums = fake_sums(3)
+    groups = a1.partition(VERTICES, LLAMA_EDGES, quantizable=NAMES)
+    gains = a1.theoretical_gains(shapes(), 2, "time")
+    taus = np.linspace(0.0, 0.05, 21)
+    ip = a1.tradeoff_curve(sums, 1.0, taus, groups, gains, FMTS)
+    prefix = a1.tradeoff_curve(sums, 1.0, taus, groups, gains, FMTS, strategy="prefix")
+    rng = np.random.default_rng(0)
+    rand = a1.tradeoff_curve(sums, 1.0, taus, groups, gains, FMTS, strategy="ordered",
+                             order=rng.permutation(len(groups)).astype(np.int32))
+    g = [r[1] for r in ip]
+    assert all(b >= a for a, b in zip(g, g[1:]))                          # more budget never hurts
+    for (t, gi, di), (_, gp, dp), (_, gr, dr) in zip(ip, prefix, rand):
+        assert di <= t * t + 1e-18 and dp <= t * t + 1e-18 and dr <= t * t + 1e-18
+        assert gi >= gp - 1e-9 and gi >= gr - 1e-9
+
+
+@pytest.mark.gpu
+def test_gpu_algorithm1_on_a_small_model():
+    import torch
+    from tiny_model import TinyLlama
+    dev = "cuda:0"
+    m = TinyLlama(vocab=256, d=128, heads=4, ffn=352, layers=2).to(torch.bfloat16).to(dev)
+
+    def setter(fn):
+        m.mm = fn
+
+    def tokens(seed):
+        g = torch.Generator().manual_seed(seed)
+        return torch.randint(0, 256, (97,), generator=g).to(dev)
+
+    print("[gpu-test] Algorithm 1 on a 2-layer model, 4 samples", flush=True)
+    sums, mean_g2, ops = a1.calibrate(m, [tokens(s) for s in range(4)], lambda mod, t: mod.loss(t), FMTS, dev,
+                                      bgemm_setter=setter)
+    assert len(sums) == 19 and mean_g2 > 0
+    names = list(sums)
+    # per block the groups of the paper's figure; the head on its own
+    groups = []
+    for b in range(2):
+        pre = "blocks.%d." % b
+        groups += [[pre + n for n in ("q_proj", "k_proj", "v_proj", "qk", "pv")], [pre + "o_proj"],
+                   [pre + "gate_proj", pre + "up_proj"], [pre + "down_proj"]]
+    groups.append(["head"])
+    assert sorted(sum(groups, [])) == sorted(names)
+    gains = a1.theoretical_gains(ops, 2, "time")
+    full = sum(g[0] for g in gains.values())
+    prev = -1.0
+    for tau in (0.0, 1e-3, 1e-2, 1e-1, 10.0):
+        cfg, info = a1.select(sums, mean_g2, tau, groups, gains, FMTS)
+        assert info["total_mse"] <= info["budget"] * (1 + 1e-12)
+        assert info["total_gain"] >= prev
+        prev = info["total_gain"]
+    assert prev == pytest.approx(full, rel=1e-12)                          # tau = 10: everything in FP8
+    cfg0, info0 = a1.select(sums, mean_g2, 0.0, groups, gains, FMTS)
+    assert info0["total_gain"] == 0.0
+    # the model statistic (s alpha) and the measured one order the formats the same way: E4M3 costs less
+    for n in names:
+        assert a1.layer_loss_mse(sums, FMTS, "model")[n][0] < a1.layer_loss_mse(sums, FMTS, "model")[n][1]
+        assert a1.layer_loss_mse(sums, FMTS, "measured")[n][0] < a1.layer_loss_mse(sums, FMTS, "measured")[n][1]
