@@ -701,7 +701,13 @@ amp_status_t build_absmax_rows(const amp_tensor_t* tensors, int n_tensors, RowPl
         R.out_row = (uint32_t)P->n_rows;
         R.item_begin = (uint32_t)P->n_items;
         P->n_rows += (uint64_t)n_rows;
-        P->n_items += ((uint64_t)n_rows + per - 1) / per;
+        if (T.layout.causal && n_rows > 0) {
+            const uint64_t bands = ((uint64_t)T.layout.rows + kBandRows - 1) / kBandRows;
+            R.items_per_mat = (uint32_t)((bands + 1) / 2);
+            P->n_items += (uint64_t)(n_rows / T.layout.rows) * R.items_per_mat;
+        } else {
+            P->n_items += ((uint64_t)n_rows + per - 1) / per;
+        }
         if (P->n_items > kMaxChunks) return AMP_ERR_TOO_LARGE;
         P->tensors.push_back(R);
     }

@@ -173,7 +173,9 @@ struct alignas(16) RowTensor {       // 48 bytes
     uint32_t item_begin;             // first work item of this tensor
     uint32_t rows_per_item;
     uint32_t aligned;                // rows start on 16-byte boundaries and row_len % 8 == 0
-    uint32_t reserved[2];
+    uint32_t items_per_mat;          // causal: a work item is a band of 8 rows from the top of a matrix and
+                                     // its mirror from the bottom (equal work per item); 0 otherwise
+    uint32_t reserved;
 };
 static_assert(sizeof(RowTensor) == 48, "RowTensor layout");
 // Lanes of a wave that share one row in the per-row absmax: a power of two, at most 64, chosen so

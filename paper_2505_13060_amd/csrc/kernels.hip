@@ -1027,52 +1027,67 @@ __global__ __launch_bounds__(kWG) void absmax_rows_kernel(const RowTensor* __res
             if (tensors[mid].item_begin <= item) lo = mid; else hi = mid;
         }
         const RowTensor T = tensors[lo];
-        const int64_t row0 = (int64_t)(item - T.item_begin) * T.rows_per_item;
-        const int64_t row1 = row0 + T.rows_per_item < T.n_rows ? row0 + T.rows_per_item : T.n_rows;
-        const int32_t i0 = T.causal_rows > 0 ? (int32_t)(row0 % T.causal_rows) : 0;   // row0's index in its matrix
         const int L = T.aligned ? absmax_row_lanes(T.row_len, T.causal_rows > 0) : 64;   // lanes per row
         const int G = 64 / L, sub = lane / L, sl = lane - sub * L;
-        for (int64_t rb = row0; rb < row1; rb += G) {
-            const int64_t rho = rb + sub;
-            const bool live = rho < row1;
-            int32_t len = T.row_len;
-            if (T.causal_rows > 0) {
-                const int32_t i = (int32_t)(((int64_t)i0 + (rho - row0)) % T.causal_rows);
-                int64_t l = (int64_t)i + 1 + ((int64_t)T.row_len - T.causal_rows);
-                len = (int32_t)(l < 0 ? 0 : (l > T.row_len ? T.row_len : l));
-            }
-            uint32_t m = 0;
-            if (live && T.aligned) {
-                const int nvr = (len + kVec - 1) / kVec;
-                const int tail = len - (nvr - 1) * kVec;
-                const gptr128_t p = reinterpret_cast<gptr128_t>((gptr16_t)T.x + rho * T.row_len);
-                int v = sl;
-                for (; v + 3 * L < nvr - 1; v += 4 * L) {      // four whole vectors in flight
-                    const u32x4 a = load128<true>(p + v), b = load128<true>(p + v + L);
-                    const u32x4 c = load128<true>(p + v + 2 * L), d = load128<true>(p + v + 3 * L);
-                    m = max_words(max_words(max_words(max_words(m, a), b), c), d);
+        // rows [row0, row1) of the tensor; i0 = index of row0 inside its matrix (causal)
+        auto run = [&](int64_t row0, int64_t row1, int32_t i0) {
+            for (int64_t rb = row0; rb < row1; rb += G) {
+                const int64_t rho = rb + sub;
+                const bool live = rho < row1;
+                int32_t len = T.row_len;
+                if (T.causal_rows > 0) {
+                    const int32_t i = (int32_t)(((int64_t)i0 + (rho - row0)) % T.causal_rows);
+                    int64_t l = (int64_t)i + 1 + ((int64_t)T.row_len - T.causal_rows);
+                    len = (int32_t)(l < 0 ? 0 : (l > T.row_len ? T.row_len : l));
                 }
-                for (; v < nvr; v += L) {
-                    u32x4 a = load128<true>(p + v);
-                    if (v == nvr - 1 && tail < kVec) a = keep_leading(a, tail);
-                    m = max_words(m, a);
+                uint32_t m = 0;
+                if (live && T.aligned) {
+                    const int nvr = (len + kVec - 1) / kVec;
+                    const int tail = len - (nvr - 1) * kVec;
+                    const gptr128_t p = reinterpret_cast<gptr128_t>((gptr16_t)T.x + rho * T.row_len);
+                    const int nwhole = tail < kVec ? nvr - 1 : nvr;   // vectors that need no masking
+                    int v = sl;
+                    for (; v + 3 * L < nwhole; v += 4 * L) {       // four whole vectors in flight
+                        const u32x4 a = load128<true>(p + v), b = load128<true>(p + v + L);
+                        const u32x4 c = load128<true>(p + v + 2 * L), d = load128<true>(p + v + 3 * L);
+                        m = max_words(max_words(max_words(max_words(m, a), b), c), d);
+                    }
+                    for (; v < nvr; v += L) {
+                        u32x4 a = load128<true>(p + v);
+                        if (v == nvr - 1 && tail < kVec) a = keep_leading(a, tail);
+                        m = max_words(m, a);
+                    }
+                } else if (live) {
+                    const gptr16_t p = (gptr16_t)T.x + rho * T.row_len;
+                    for (int32_t j = sl; j < len; j += L) {
+                        const uint32_t h = (uint32_t)p[j] & 0x7FFFu;
+                        m = m > h ? m : h;
+                    }
                 }
-            } else if (live) {
-                const gptr16_t p = (gptr16_t)T.x + rho * T.row_len;
-                for (int32_t j = sl; j < len; j += L) {
-                    const uint32_t h = (uint32_t)p[j] & 0x7FFFu;
-                    m = m > h ? m : h;
+                for (int o = 1; o < L; o <<= 1) {              // L is the same for the whole wave
+                    const uint32_t w = (uint32_t)__shfl_xor((int)m, o);
+                    m = m > w ? m : w;
+                }
+                if (live && sl == 0) {
+                    const int64_t o = (int64_t)T.out_row + rho;
+                    write_scales(m, n_fmts, fmt0, fmt1, &amax_out[o], &scale_out[o * n_fmts], &inv_out[o * n_fmts]);
+                    if (m >= 0x7F80u) atomicOr(&flags_out[lo], 1u);
                 }
             }
-            for (int o = 1; o < L; o <<= 1) {              // L is the same for the whole wave
-                const uint32_t w = (uint32_t)__shfl_xor((int)m, o);
-                m = m > w ? m : w;
-            }
-            if (live && sl == 0) {
-                const int64_t o = (int64_t)T.out_row + rho;
-                write_scales(m, n_fmts, fmt0, fmt1, &amax_out[o], &scale_out[o * n_fmts], &inv_out[o * n_fmts]);
-                if (m >= 0x7F80u) atomicOr(&flags_out[lo], 1u);
-            }
+        };
+        const uint32_t rel = item - T.item_begin;
+        if (T.items_per_mat > 0) {
+            const int64_t mat = rel / T.items_per_mat;
+            const int32_t slot = (int32_t)(rel % T.items_per_mat);
+            const int32_t mirror = (T.causal_rows + kBandRows - 1) / kBandRows - 1 - slot;
+            const int64_t base = mat * T.causal_rows;
+            const int32_t a0 = slot * kBandRows, b0 = mirror * kBandRows;
+            run(base + a0, base + (a0 + kBandRows < T.causal_rows ? a0 + kBandRows : T.causal_rows), a0);
+            if (mirror > slot)
+                run(base + b0, base + (b0 + kBandRows < T.causal_rows ? b0 + kBandRows : T.causal_rows), b0);
+        } else {
+            const int64_t row0 = (int64_t)rel * T.rows_per_item;
+            run(row0, row0 + T.rows_per_item < T.n_rows ? row0 + T.rows_per_item : T.n_rows, 0);
         }
     }
 }
