@@ -256,7 +256,8 @@ def main():
     if args.scales == "rows" and launches_per_step == 4:
         names = ["sens_w_kernel, per-channel scales (weights of the linears)",
                  "sens_wrows_kernel (activations of the linears, rows of 512+ elements)",
-                 "sens_wrows_kernel (causal BGEMM operands)", "sens_rows_kernel (BGEMM operands with short rows)"]
+                 "sens_wrows_kernel (causal BGEMM operands)",
+                 "sens_wrows_kernel, short-row variant (BGEMM operands with rows of 128)"]
     launch_detail = []
     per_ms = ms.reshape(args.steps, launches_per_step).mean(axis=0)
     per_pairs = lp.reshape(args.steps, launches_per_step)[0].astype(np.float64)

@@ -154,13 +154,14 @@ struct WorkTable {
 
     // Which streaming kernel takes a unit: 0 = one scale per tensor; 1 = one scale per row with
     // rows long enough that a wave's 512 contiguous elements meet at most two of them, or an
-    // aligned causal unit (scales in scalar registers / once per band); 2 = any other unit with
-    // row scales (short rows, rows not made of whole vectors).
+    // aligned causal unit; 3 = short rows of a power-of-two length (a wave step covers whole rows);
+    // 2 = any other unit with row scales (other short rows, rows not made of whole vectors).
     static int unit_class(const WorkUnit& u) {
         if (!(u.flags & kUnitRowScale)) return 0;
         if (u.flags & kUnitScalar) return 2;
         if (u.flags & kUnitCausal) return 1;
-        return u.cols >= kVec * 64 ? 1 : 2;
+        if (u.cols >= kVec * 64) return 1;
+        return (u.cols & (u.cols - 1)) == 0 ? 3 : 2;        // a power of two (>= 8): whole rows per wave step
     }
 
     // How a call is split between the kernels.
@@ -169,8 +170,8 @@ struct WorkTable {
         std::vector<WGroup> wgroups;              // work of the weight kernel: groups with one scale per
                                                   // tensor first, then those with row scales; item_begin
                                                   // counts from the first item of the group's launch
-        uint64_t class_pos[4] = {0, 0, 0, 0};     // streaming kernel of class c: positions [class_pos[c], class_pos[c+1])
-        uint64_t class_pairs[3] = {0, 0, 0};
+        uint64_t class_pos[5] = {0, 0, 0, 0, 0};     // streaming kernel of class c: positions [class_pos[c], class_pos[c+1])
+        uint64_t class_pairs[4] = {0, 0, 0, 0};
         uint64_t n_positions = 0;
         size_t w_groups[2] = {0, 0};              // weight kernel launch v: groups, items, pairs, bytes
         uint64_t w_items[2] = {0, 0};
@@ -189,7 +190,7 @@ struct WorkTable {
         for (size_t u = 0; u < units.size(); ++u)
             if (group[u] != 0) by_group[group[u]].push_back(u);
         std::vector<char> done(units.size(), 0);
-        for (int cls = 0; cls < 3; ++cls) {
+        for (int cls = 0; cls < 4; ++cls) {
             P.class_pos[cls] = P.n_positions;
             for (size_t u = 0; u < units.size(); ++u) {
                 if (done[u] || unit_class(units[u]) != cls) continue;
@@ -238,7 +239,7 @@ struct WorkTable {
                 P.n_positions += (chunks_of(u) - skip) * members.size();
             }
         }
-        P.class_pos[3] = P.n_positions;
+        P.class_pos[4] = P.n_positions;
         return P;
     }
 };
@@ -278,7 +279,7 @@ int persistent_grid(uint64_t n_chunks, int resident) {
 
 int sens_grid(uint64_t n_chunks, int n_fmts, int f0, int f1, int rows) {
     static std::mutex mu;
-    static int cached[64][2][2][2][3];
+    static int cached[64][2][2][2][4];
     const int dev = device_index();
     int resident;
     if (dev < 0) {
@@ -416,7 +417,7 @@ amp_status_t run_sens(const WorkTable& t, const amp_fp8_format_t* fmts, int n_fm
         g0 += plan.w_groups[v];
     }
     // streaming kernels, one launch per class of units
-    for (int cls = 0; cls < 3; ++cls) {
+    for (int cls = 0; cls < 4; ++cls) {
         const uint64_t n_pos = plan.class_pos[cls + 1] - plan.class_pos[cls];
         if (n_pos == 0) continue;
         const int grid = sens_grid(n_pos, n_fmts, f0, f1, cls);
@@ -567,16 +568,24 @@ struct ReplayCtx {
     // row tracking as a context with one scale per row would do it; row_len 0 = no check
     int32_t row_len = 0;
     bool cursor_mode = false, have_row = false;
+    bool wave_mode = false;                         // track the wave's first lane only (see wave_lane_row)
+    int32_t last_row = 0;
+    int lane = 0;
     RowCursor cur;
     int64_t row = 0;
     __host__ __device__ void begin_dense(int64_t e0, int le) {
-        if (row_len > 0 && cursor_mode) cur.begin(e0, le, kWG * kVec, row_len);
+        if (row_len > 0 && cursor_mode) cur.begin(e0, wave_mode ? le - lane * kVec : le, kWG * kVec, row_len);
     }
     __host__ __device__ void set_row(int64_t r) { row = r; have_row = true; }
     // a vector that starts at element s is about to be consumed
     __host__ __device__ void vector_row(int64_t s) {
         if (row_len <= 0) return;
-        if (cursor_mode) {
+        if (cursor_mode && wave_mode) {
+            if (wave_lane_row(cur, last_row, wave_sub_shift(row_len), lane) != s / row_len ||
+                s % row_len + kVec > row_len)
+                ++bad;
+            cur.advance();
+        } else if (cursor_mode) {
             if (cur.row != s / row_len || cur.col != s % row_len || cur.col + kVec > row_len) ++bad;
             cur.advance();
         } else if (!have_row || s / row_len != row || s % row_len + kVec > row_len) {
@@ -947,6 +956,9 @@ int64_t ampsens_debug_replay_unit_rows(uint64_t x_addr, uint64_t dx_addr, const 
                 ctx.row_len = u.cols;
                 ctx.cursor_mode = !(u.flags & kUnitCausal) && !(u.flags & kUnitScalar);
                 if (!(u.flags & kUnitCausal) && (u.flags & kUnitScalar)) ctx.row_len = 0;   // divides per element
+                ctx.wave_mode = ctx.cursor_mode && WorkTable::unit_class(u) != 2;
+                ctx.last_row = u.rows - 1;
+                ctx.lane = tid & 63;
             }
             walk_chunk(u, c, tid, ctx);
             bad += ctx.bad;

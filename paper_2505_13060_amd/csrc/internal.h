@@ -136,7 +136,8 @@ inline uint32_t causal_chunks_per_mat(int64_t rows) {
 // All enqueue on `stream` and return the launch error, never synchronise.
 // Persistent-grid size for the streaming kernels on the current device (resident workgroups).
 // cls: the class of units the variant is for: 0 = one scale per tensor; 1 = row scales, rows of at
-// least 512 elements or aligned causal rows; 2 = row scales, any other shape.
+// least 512 elements or aligned causal rows; 2 = row scales, any other shape; 3 = row scales, rows
+// of a power-of-two length below 512.
 int sens_resident_blocks(int n_fmts, int fmt0, int fmt1, int cls, int cus);
 int absmax_resident_blocks(int cus);
 int absmax_rows_resident_blocks(int cus);

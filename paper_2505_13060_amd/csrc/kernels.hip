@@ -469,13 +469,14 @@ struct SensRowCtx {
     }
 };
 
-// Row scales for units whose rows hold at least 512 elements (or aligned causal units): the 64
-// lanes of a wave cover 512 contiguous elements per vector step, so a step meets at most two rows.
+// Row scales for units whose rows hold at least 512 elements (or a power of two below that, or
+// aligned causal units): the 64 lanes of a wave cover 512 contiguous elements per vector step, so a
+// step meets at most two long rows, or a whole number of short ones.
 // The wave follows its own position with a cursor in scalar registers and fetches the scales of
 // those rows through the scalar cache; steps that lie inside one row (all of them when the row
 // length is a multiple of 512) use them as scalar operands, the others select per lane.  Causal
 // units: a lane stays in one row per band and fetches that row's scales once.
-template <int NF, int F0, int F1>
+template <int NF, int F0, int F1, bool SHORT>
 struct SensWaveRowCtx {
     static constexpr bool kRollDense = true;
     gptr16_t x;
@@ -484,6 +485,7 @@ struct SensWaveRowCtx {
     gptrf_t ri;
     gptrf_t rs;
     int32_t row_len, last_row;
+    int sub_shift;                                 // >= 0: rows of 8 << sub_shift < 512 elements
     bool causal;
     int lane;
     RowCursor cur;                                 // of the wave's first lane; uniform over the wave
@@ -501,6 +503,8 @@ struct SensWaveRowCtx {
         row_len = u.cols;
         causal = (u.flags & kUnitCausal) != 0;
         last_row = causal ? 0 : u.rows - 1;
+        sub_shift = -1;
+        if (!causal) sub_shift = wave_sub_shift(row_len);
         lane = threadIdx.x & 63;
 #pragma unroll
         for (int f = 0; f < NF; ++f) { E[f] = 0.0f; pk[f] = 0; inv[f] = 1.0f; scale[f] = 1.0f; }
@@ -562,6 +566,17 @@ struct SensWaveRowCtx {
             row_a[k] = cur.row;
             rem[k] = row_len - cur.col;                // elements of row_a left from the wave's first lane on
             cur.advance();
+        }
+        if constexpr (SHORT) {
+            // short rows (8 << sub_shift elements, a divisor of 512): a step covers whole rows, the
+            // lane's row is the wave's first row plus lane >> sub_shift
+#pragma unroll
+            for (int k = 0; k < U; ++k) {
+                float iv[NF], sc[NF];
+                load_row((uint32_t)(row_a[k] + (lane >> sub_shift)), iv, sc);     // = wave_lane_row
+                vec(xr[k], gr[k], iv, sc);
+            }
+            return;
         }
 #pragma unroll
         for (int k = 0; k < U; ++k) {
@@ -666,11 +681,11 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
 #ifndef AMPSENS_WROWS_WAVES
 #define AMPSENS_WROWS_WAVES 6
 #endif
-template <int NF, int F0, int F1>
+template <int NF, int F0, int F1, bool SHORT>
 __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(AMPSENS_WROWS_WAVES, AMPSENS_WROWS_WAVES))) void sens_wrows_kernel(const ResolvedUnit* __restrict__ runits,
                                                         const ChunkRef* __restrict__ map,
                                                         uint32_t n_chunks, float* __restrict__ partials) {
-    sens_body<SensWaveRowCtx<NF, F0, F1>, NF>(runits, map, n_chunks, partials);
+    sens_body<SensWaveRowCtx<NF, F0, F1, SHORT>, NF>(runits, map, n_chunks, partials);
 }
 
 #ifndef AMPSENS_ROWS_WAVES
@@ -1140,9 +1155,14 @@ typedef void (*sens_fn_t)(const ResolvedUnit*, const ChunkRef*, uint32_t, float*
 
 sens_fn_t sens_variant(int n_fmts, int fmt0, int fmt1, int cls) {
     if (cls == 1) {
-        if (n_fmts == 1) return fmt0 == 0 ? sens_wrows_kernel<1, 0, 0> : sens_wrows_kernel<1, 1, 1>;
-        if (fmt0 == 0) return fmt1 == 0 ? sens_wrows_kernel<2, 0, 0> : sens_wrows_kernel<2, 0, 1>;
-        return fmt1 == 0 ? sens_wrows_kernel<2, 1, 0> : sens_wrows_kernel<2, 1, 1>;
+        if (n_fmts == 1) return fmt0 == 0 ? sens_wrows_kernel<1, 0, 0, false> : sens_wrows_kernel<1, 1, 1, false>;
+        if (fmt0 == 0) return fmt1 == 0 ? sens_wrows_kernel<2, 0, 0, false> : sens_wrows_kernel<2, 0, 1, false>;
+        return fmt1 == 0 ? sens_wrows_kernel<2, 1, 0, false> : sens_wrows_kernel<2, 1, 1, false>;
+    }
+    if (cls == 3) {
+        if (n_fmts == 1) return fmt0 == 0 ? sens_wrows_kernel<1, 0, 0, true> : sens_wrows_kernel<1, 1, 1, true>;
+        if (fmt0 == 0) return fmt1 == 0 ? sens_wrows_kernel<2, 0, 0, true> : sens_wrows_kernel<2, 0, 1, true>;
+        return fmt1 == 0 ? sens_wrows_kernel<2, 1, 0, true> : sens_wrows_kernel<2, 1, 1, true>;
     }
     if (cls == 2) {
         if (n_fmts == 1) return fmt0 == 0 ? sens_rows_kernel<1, 0, 0> : sens_rows_kernel<1, 1, 1>;

@@ -37,6 +37,16 @@ namespace ampsens {
 #define AMPSENS_HD __host__ __device__ inline
 #endif
 
+// Row of a lane's vector when only the wave's first lane is tracked (cursor `cur` of that lane):
+// the 64 lanes cover 512 contiguous elements.  Rows of at least 512 elements: the step meets row
+// cur.row and, from the lane on that passes the row's end, the next row.  Shorter rows whose length
+// is a power of two (sub_shift = log2(row_len / 8)): the step covers whole rows.
+AMPSENS_HD int wave_sub_shift(int32_t row_len) {
+    if (row_len >= 64 * kVec) return -1;
+    int s = 0;
+    while ((kVec << (s + 1)) <= row_len) ++s;
+    return s;
+}
 constexpr int kUnroll = 4;           // independent 128-bit loads per stream in flight per lane
 
 // Row of every vector of a thread's strided walk over a [rows, row_len] array, without a
@@ -69,6 +79,12 @@ struct RowCursor {
 AMPSENS_HD bool dense_chunk_interior(int64_t n, uint32_t head, bool scalar, uint32_t chunk_local) {
     const int64_t v0 = (int64_t)chunk_local * kChunkVecs;
     return !scalar && (v0 * kVec >= (int64_t)head) && ((v0 + kChunkVecs) * kVec - head <= n);
+}
+
+AMPSENS_HD int32_t wave_lane_row(const RowCursor& cur, int32_t last_row, int sub_shift, int lane) {
+    if (sub_shift >= 0) return cur.row + (lane >> sub_shift);
+    if (lane * kVec < cur.len - cur.col) return cur.row;
+    return cur.row < last_row ? cur.row + 1 : last_row;
 }
 
 template <class Ctx>

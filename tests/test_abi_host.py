@@ -132,6 +132,8 @@ ROW_REPLAY_CASES = [
     (("dense", 4096 * 24), 4096, 0, 0, 1), (("dense", 11008 * 7), 11008, 0, 0, 1), (("dense", 128 * 700), 128, 0, 0, 1),
     (("dense", 8 * 5000), 8, 0, 0, 1), (("dense", 1408 * 50), 1408, 0, 0, 1), (("dense", 28672 * 3), 28672, 0, 0, 1),
     (("dense", 40 * 1000), 40, 0, 0, 2), (("dense", 32768 * 2), 32768, 0, 0, 1), (("dense", 65536 * 2), 65536, 0, 0, 1),
+    (("dense", 256 * 400), 256, 0, 0, 1), (("dense", 64 * 3000), 64, 0, 0, 1), (("dense", 16 * 9000), 16, 0, 0, 1),
+    (("dense", 520 * 130), 520, 0, 0, 1), (("dense", 1000 * 70), 1000, 0, 0, 1), (("dense", 48 * 1500), 48, 0, 0, 1),
     (("dense", 100 * 333), 100, 0, 0, 1),                     # row length not a multiple of 8: element path
     (("dense", 128 * 300), 128, 6, 6, 1),                     # misaligned buffer: element path
     (("dense", 4096 * 9), 4096, 0, 8, 1),                     # x and xdot misaligned against each other
