@@ -89,6 +89,14 @@ def absmax_scale(x, fmt, causal=None):
     return np.float32(am.value), np.float32(sc.value), np.float32(iv.value), fl.value
 
 
+def scale_pow2(amax_bits, fmt):
+    """(scale, inv) float32: the smallest power of two s with amax / s <= FMAX, and 1 / s."""
+    sc, iv = C.c_float(), C.c_float()
+    rc = lib().orc_scale_pow2(C.c_uint16(int(amax_bits)), int(fmt), C.byref(sc), C.byref(iv))
+    assert rc == 0
+    return np.float32(sc.value), np.float32(iv.value)
+
+
 def fake_quant_fp8(x, scale, inv, fmt, want_dequant=True):
     x = _u16(x)
     codes = np.empty(x.size, dtype=np.uint8)

@@ -252,6 +252,28 @@ int orc_absmax_scale(const uint16_t* x, int64_t n, int causal, int64_t batch, in
     return 0;
 }
 
+// Power-of-two scales (a scale policy the paper leaves open, common for FP8 hardware with
+// exponent-only scale factors): the smallest power of two s with amax / s <= FMAX, and inv = 1 / s,
+// both exact.  amax == 0, or an inv that is not a finite fp32 number, gives scale = inv = 1.
+// amax_bits: bf16 pattern of amax (sign ignored).
+int orc_scale_pow2(uint16_t amax_bits, int fmt, float* scale_out, float* inv_out) {
+    Fmt f;
+    if (!fmt_of(fmt, &f)) return 1;
+    double a = std::fabs((double)bf16_val(amax_bits));
+    *scale_out = 1.0f;
+    *inv_out = 1.0f;
+    if (a == 0.0 || !(a <= std::numeric_limits<double>::max())) return 0;
+    int k = (int)std::ceil(std::log2(a / f.fmax));
+    // log2 in floating point may be off by one ulp at exact powers of two: settle k exactly
+    while (std::ldexp(f.fmax, k) < a) ++k;
+    while (std::ldexp(f.fmax, k - 1) >= a) --k;
+    double s = std::ldexp(1.0, k), inv = std::ldexp(1.0, -k);
+    if ((double)(float)inv != inv || std::isinf((float)inv) || (double)(float)s != s || (float)s == 0.0f) return 0;
+    *scale_out = (float)s;
+    *inv_out = (float)inv;
+    return 0;
+}
+
 // ---- fake quantisation -----------------------------------------------------------------
 
 int orc_fake_quant_fp8(const uint16_t* x, int64_t n, float scale, float inv, int fmt,

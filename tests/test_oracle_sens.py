@@ -349,3 +349,59 @@ def test_rows_scale_removes_the_error_a_loud_row_causes_in_quiet_rows():
     assert Ar == pytest.approx(At[0], rel=1e-14)
     assert Er <= 3 * oracle.alpha(3) * Ar
     assert Et[0] > 20 * Er
+
+
+# ---- power-of-two scales ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("fmt", [oracle.E4M3, oracle.E5M2])
+def test_pow2_scale_is_the_smallest_power_of_two_that_fits(fmt):
+    from fractions import Fraction
+    fmax = Fraction(int(FMAX[fmt]))
+    pats = np.concatenate([np.arange(1, 0x7F80, 37, dtype=np.uint16),           # spread over all magnitudes
+                           np.array([1, 2, 0x007F, 0x0080, 0x0081, 0x7F7F], dtype=np.uint16)])
+    # amax = FMAX * 2^k exactly, and its bf16 neighbours
+    exact = f32_to_bf16_bits(np.array([FMAX[fmt] * 2.0 ** k for k in range(-100, 100, 7)], dtype=np.float32))
+    pats = np.concatenate([pats, exact, exact + 1, exact - 1]).astype(np.uint16)
+    vals = bf16_bits_to_f64(pats)
+    for h, v in zip(pats, vals):
+        sc, iv = oracle.scale_pow2(h, fmt)
+        a = Fraction(float(v))
+        s = Fraction(float(sc))
+        if sc == 1.0 and iv == 1.0 and not (a / 1 <= fmax and a * 2 > fmax):
+            # fallback: only where 1 / s is not an fp32 number
+            k_true = 0
+            while fmax * Fraction(2) ** k_true < a:
+                k_true += 1
+            while fmax * Fraction(2) ** (k_true - 1) >= a:
+                k_true -= 1
+            assert k_true < -126 or k_true > 127, (h, v)
+            continue
+        assert s.numerator == 1 or s.denominator == 1                             # a power of two ...
+        assert (s.numerator & (s.numerator - 1)) == 0 and (s.denominator & (s.denominator - 1)) == 0
+        assert a / s <= fmax and a / (s / 2) > fmax                                # ... the smallest that fits
+        assert Fraction(float(iv)) * s == 1
+    assert oracle.scale_pow2(0, fmt) == (1.0, 1.0)
+    sc, iv = oracle.scale_pow2(f32_to_bf16_bits(np.array([FMAX[fmt] * 4], dtype=np.float32))[0], fmt)
+    assert (sc, iv) == (4.0, 0.25)
+
+
+@pytest.mark.parametrize("fmt", [oracle.E4M3, oracle.E5M2])
+def test_pow2_scale_commutes_with_the_cast(fmt):
+    """At a power-of-two scale s the cast of x is the cast of x / s at scale 1, so E(x; s) = s^2 E(x / s; 1)
+    exactly, and values on the grid times s have zero error."""
+    rng = np.random.default_rng(21)
+    x = rand_bf16(rng, 4000, 3.0)
+    g = f32_to_bf16_bits(np.ones(4000, dtype=np.float32))
+    am = np.abs(bf16_bits_to_f64(x)).max()
+    amax_bits = f32_to_bf16_bits(np.array([am], dtype=np.float32))[0]
+    sc, iv = oracle.scale_pow2(amax_bits, fmt)
+    assert sc != 1.0
+    xs = f32_to_bf16_bits((bf16_bits_to_f64(x) * float(iv)).astype(np.float32))    # exact: power of two
+    E, A = oracle.sens_operand(x, g, 1, x.size, sc, iv, fmt)
+    E1, A1 = oracle.sens_operand(xs, g, 1, x.size, 1.0, 1.0, fmt)
+    assert E[0] == pytest.approx(float(sc) ** 2 * E1[0], rel=1e-15)
+    codes, deq = oracle.fake_quant_fp8(x, sc, iv, fmt)
+    on_grid = f32_to_bf16_bits(deq)
+    assert np.array_equal(bf16_bits_to_f64(on_grid), deq.astype(np.float64))        # FP8 values times 2^k are bf16
+    E0, _ = oracle.sens_operand(on_grid, g, 1, x.size, sc, iv, fmt)
+    assert E0[0] == 0.0
