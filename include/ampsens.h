@@ -84,6 +84,13 @@ typedef enum amp_fp8_format {
  * samples (X: rows_total rows; W: K rows shared by the samples; BGEMM: R * rows-per-sample rows),
  * as amp_absmax_scale_rows writes them.  Fast path: row_len a multiple of 8 and 16-byte aligned
  * buffers; anything else is computed element by element. */
+/* Scale rule.  Or-ed into a format passed to amp_absmax_scale / amp_absmax_scale_rows: the scale
+ * is the smallest power of two s with amax / s <= FMAX_f and the reciprocal is 1 / s, both exact
+ * (exponent-only scale factors), instead of amax / FMAX_f and FMAX_f / amax.  amax == 0, a
+ * non-finite amax, or an s whose reciprocal is not an fp32 number give scale = inv = 1.  The
+ * sensitivity calls take scales as inputs and accept plain formats only. */
+#define AMP_SCALE_POW2 0x100
+
 #define AMP_ROWS_OPERAND0 1          /* X of a linear layer / X0 of a BGEMM */
 #define AMP_ROWS_OPERAND1 2          /* W of a linear layer / X1 of a BGEMM */
 

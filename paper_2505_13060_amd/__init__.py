@@ -15,6 +15,7 @@ from . import build as _build
 E4M3 = 0
 E5M2 = 1
 MAX_FORMATS = 2
+SCALE_POW2 = 0x100         # or-ed into a format for the absmax calls: power-of-two scales
 ROWS_OPERAND0 = 1          # one scale per row of X (linear) / X0 (BGEMM)
 ROWS_OPERAND1 = 2          # one scale per row of W (linear) / X1 (BGEMM)
 

@@ -34,11 +34,12 @@ constexpr uint64_t kMaxChunks = 0x7FFFFFFFull;
 
 bool fmt_ok(int f) { return f == AMP_FP8_E4M3 || f == AMP_FP8_E5M2; }
 
-amp_status_t check_fmts(const amp_fp8_format_t* fmts, int n_fmts) {
+// scale_flags: AMP_SCALE_POW2 may be or-ed into the formats (the absmax calls).
+amp_status_t check_fmts(const amp_fp8_format_t* fmts, int n_fmts, bool scale_flags = false) {
     if (n_fmts < 1 || n_fmts > AMP_MAX_FORMATS) return AMP_ERR_BAD_FORMAT;
     if (!fmts) return AMP_ERR_INVALID_ARG;
     for (int f = 0; f < n_fmts; ++f)
-        if (!fmt_ok((int)fmts[f])) return AMP_ERR_BAD_FORMAT;
+        if (!fmt_ok(scale_flags ? ((int)fmts[f] & ~AMP_SCALE_POW2) : (int)fmts[f])) return AMP_ERR_BAD_FORMAT;
     return AMP_OK;
 }
 
@@ -640,7 +641,7 @@ amp_status_t amp_absmax_scale(const amp_tensor_t* tensors, int n_tensors, const 
                               int n_fmts, float* d_amax, float* d_scale, float* d_inv,
                               uint32_t* d_flags, void* workspace, size_t workspace_bytes,
                               void* stream_) {
-    amp_status_t st = check_fmts(fmts, n_fmts);
+    amp_status_t st = check_fmts(fmts, n_fmts, true);
     if (st != AMP_OK) return st;
     WorkTable t;
     st = build_absmax(tensors, n_tensors, &t);
@@ -738,7 +739,7 @@ amp_status_t amp_absmax_rows_workspace_bytes(const amp_tensor_t* tensors, int n_
 amp_status_t amp_absmax_scale_rows(const amp_tensor_t* tensors, int n_tensors, const amp_fp8_format_t* fmts,
                                    int n_fmts, float* d_amax, float* d_scale, float* d_inv, uint32_t* d_flags,
                                    void* workspace, size_t workspace_bytes, void* stream_) {
-    amp_status_t st = check_fmts(fmts, n_fmts);
+    amp_status_t st = check_fmts(fmts, n_fmts, true);
     if (st != AMP_OK) return st;
     RowPlan P;
     st = build_absmax_rows(tensors, n_tensors, &P);

@@ -958,15 +958,30 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
 
 __device__ __forceinline__ float fmax_of(int fmt) { return fmt == 0 ? 448.0f : 57344.0f; }
 
-// amax (as the maximum of bits & 0x7FFF) -> amax, flag, and the scales of every format.
+// amax (as the maximum of bits & 0x7FFF) -> amax and the scales of every format.  A format code
+// with kScalePow2 set asks for the smallest power of two s with amax / s <= FMAX and inv = 1 / s
+// (both exact) instead of amax / FMAX and FMAX / amax.
+constexpr int kScalePow2 = 0x100;
 __device__ __forceinline__ void write_scales(uint32_t bits, int n_fmts, int fmt0, int fmt1, float* amax_out,
                                              float* scale_out, float* inv_out) {
     const float amax = __uint_as_float(bits << 16);
     *amax_out = amax;
     for (int f = 0; f < n_fmts; ++f) {
-        const float fm = fmax_of(f == 0 ? fmt0 : fmt1);
+        const int code = f == 0 ? fmt0 : fmt1;
+        const float fm = fmax_of(code & 0xFF);
         float scale = 1.0f, inv = 1.0f;
-        if (amax != 0.0f) {
+        if (code & kScalePow2) {
+            // FMAX = 1.75 * 2^eF; amax = m * 2^e with m in [1, 2): k = e - eF, one more if m > 1.75
+            const int e_field = (int)(bits >> 7) & 0xFF;                // bf16 exponent field
+            if (e_field != 0 && e_field != 0xFF) {
+                const int k = e_field - 127 - ((code & 0xFF) == 0 ? 8 : 15) + ((bits & 0x7Fu) > 96u ? 1 : 0);
+                if (k >= -127 && k <= 127) {
+                    scale = k >= -126 ? __uint_as_float((uint32_t)(k + 127) << 23)
+                                      : __uint_as_float(1u << (k + 149));
+                    inv = __uint_as_float((uint32_t)(127 - k) << 23);
+                }
+            }
+        } else if (amax != 0.0f) {
             scale = amax / fm;                      // correctly rounded fp32 divisions
             inv = fm / amax;
             if (__builtin_isinf(inv)) { scale = 1.0f; inv = 1.0f; }

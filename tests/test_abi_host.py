@@ -48,6 +48,12 @@ def test_argument_validation_without_a_gpu():
     assert L.amp_fake_quant_fp8(8, 16, 1.0, 1.0, 7, 8, None, None) == amp.ERR_BAD_FORMAT
     assert L.amp_absmax_scale(None, 0, fm, 3, None, None, None, None, None, 0, None) == amp.ERR_BAD_FORMAT
     assert L.amp_sens_linear(None, 0, (C.c_int * 1)(5), 1, None, None, 0, None) == amp.ERR_BAD_FORMAT
+    # the power-of-two scale flag belongs to the absmax calls only
+    pw = (C.c_int * 2)(0 | amp.SCALE_POW2, 1 | amp.SCALE_POW2)
+    assert L.amp_absmax_scale(None, 0, pw, 2, None, None, None, None, None, 0, None) == amp.OK
+    assert L.amp_absmax_scale_rows(None, 0, pw, 2, None, None, None, None, None, 0, None) == amp.OK
+    assert L.amp_sens_linear(None, 0, pw, 2, None, None, 0, None) == amp.ERR_BAD_FORMAT
+    assert L.amp_absmax_scale(None, 0, (C.c_int * 1)(2 | amp.SCALE_POW2), 1, None, None, None, None, None, 0, None) == amp.ERR_BAD_FORMAT
     # nothing to do is fine and launches nothing
     assert L.amp_fake_quant_fp8(None, 0, 1.0, 1.0, 0, None, None, None) == amp.OK
     assert L.amp_absmax_scale(None, 0, fm, 2, None, None, None, None, None, 0, None) == amp.OK

@@ -216,3 +216,80 @@ def test_rows_with_equal_rows_reproduce_the_per_tensor_pass():
         assert np.allclose(ra["linear"][k], rb["linear"][k], rtol=3e-6, atol=0), w.linears[k].name
     for k in range(len(w.bgemms)):
         assert np.array_equal(ra["bgemm"][k], rb["bgemm"][k])
+
+
+def test_power_of_two_scales_per_tensor_and_per_row_bit_exact():
+    """AMP_SCALE_POW2: the smallest power of two that fits amax into the format, against the oracle, for
+    magnitudes over the whole bf16 range including amax = FMAX * 2^k exactly and its neighbours; then the
+    sums at those scales against the oracle."""
+    rng = np.random.default_rng(77)
+    rows, row_len = 600, 64
+    x = f32_to_bf16_bits((rng.standard_normal((rows, row_len)) * np.exp(rng.uniform(-80, 80, (rows, 1)))).astype(np.float32))
+    exact = f32_to_bf16_bits(np.array([448.0 * 2.0 ** k for k in range(-60, 60)], dtype=np.float32))
+    for i, h in enumerate(exact):                              # rows whose amax is FMAX * 2^k, one step above, one below
+        x[3 * i] = 0
+        x[3 * i, 5] = h
+        x[3 * i + 1] = 0
+        x[3 * i + 1, 7] = h + 1
+        x[3 * i + 2] = 0
+        x[3 * i + 2, 9] = h - 1
+    x[590] = 0                                                 # amax = 0
+    x[591] = 1                                                 # the smallest subnormal: no fp32 reciprocal
+    flat = x.reshape(-1)
+    d = torch.from_numpy(flat.view(np.int16)).to(DEV)
+    fmts = [amp.E4M3 | amp.SCALE_POW2, amp.E5M2 | amp.SCALE_POW2]
+    t = [amp.tensor(d, amp.dense(rows * row_len, row_len))]
+    ws_bytes, n_rows = amp.amp_absmax_rows_workspace_bytes(t)
+    say("power-of-two scales, %d rows" % n_rows)
+    d_amax = torch.zeros(rows, device=DEV)
+    d_scale = torch.zeros(rows, 2, device=DEV)
+    d_inv = torch.zeros(rows, 2, device=DEV)
+    d_flags = torch.zeros(1, dtype=torch.int32, device=DEV)
+    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=DEV)
+    amp.amp_absmax_scale_rows(t, fmts, d_amax, d_scale, d_inv, d_flags, ws)
+    torch.cuda.synchronize()
+    am = d_amax.cpu().numpy()
+    am_bits = (parity.bits32(am) >> 16).astype(np.uint16)
+    assert np.array_equal(am_bits, (flat.reshape(rows, row_len) & 0x7FFF).max(axis=1))
+    for fi, f in enumerate([amp.E4M3, amp.E5M2]):
+        want = [oracle.scale_pow2(h, f) for h in am_bits]
+        assert np.array_equal(parity.bits32(d_scale[:, fi].cpu().numpy()), parity.bits32(np.array([w[0] for w in want])))
+        assert np.array_equal(parity.bits32(d_inv[:, fi].cpu().numpy()), parity.bits32(np.array([w[1] for w in want])))
+    # per tensor, several tensors in one call
+    tens = [amp.tensor(d[i * row_len:], amp.dense(row_len * 10)) for i in (0, 3, 30, 300, 590)]
+    ws2 = torch.empty(max(amp.amp_absmax_workspace_bytes(tens), 256), dtype=torch.uint8, device=DEV)
+    a2 = torch.zeros(5, device=DEV)
+    s2 = torch.zeros(5, 2, device=DEV)
+    i2 = torch.zeros(5, 2, device=DEV)
+    f2 = torch.zeros(5, dtype=torch.int32, device=DEV)
+    amp.amp_absmax_scale(tens, fmts, a2, s2, i2, f2, ws2)
+    torch.cuda.synchronize()
+    for j, i in enumerate((0, 3, 30, 300, 590)):
+        h = int((flat[i * row_len:(i + 10) * row_len] & 0x7FFF).max())
+        for fi, f in enumerate([amp.E4M3, amp.E5M2]):
+            sc, iv = oracle.scale_pow2(h, f)
+            assert parity.bits32(s2[j, fi].cpu().numpy()) == parity.bits32(sc)
+            assert parity.bits32(i2[j, fi].cpu().numpy()) == parity.bits32(iv)
+    # the sums at power-of-two row scales (magnitudes that keep the fp32 sums finite)
+    x2 = f32_to_bf16_bits((rng.standard_normal((rows, row_len)) * np.exp(rng.uniform(-8, 8, (rows, 1)))).astype(np.float32)).reshape(-1)
+    g = f32_to_bf16_bits((rng.standard_normal(rows * row_len) * 1e-2).astype(np.float32))
+    dx2 = torch.from_numpy(x2.view(np.int16)).to(DEV)
+    dg = torch.from_numpy(g.view(np.int16)).to(DEV)
+    t2 = [amp.tensor(dx2, amp.dense(rows * row_len, row_len))]
+    amp.amp_absmax_scale_rows(t2, fmts, d_amax, d_scale, d_inv, d_flags, ws)
+    desc = [amp.bgemm_desc(dx2, dg, amp.dense(rows * row_len, row_len), dx2, dg, amp.dense(rows * row_len, row_len), 1,
+                           d_scale, d_inv, d_scale, d_inv, scale_rows=amp.ROWS_OPERAND0 | amp.ROWS_OPERAND1)]
+    out = torch.zeros(1, 2, 4, device=DEV)
+    ws3 = torch.empty(max(amp.amp_sens_bgemm_workspace_bytes(desc, 2), 256), dtype=torch.uint8, device=DEV)
+    amp.amp_sens_bgemm(desc, [amp.E4M3, amp.E5M2], out, ws3)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()[0]
+    for fi, f in enumerate([amp.E4M3, amp.E5M2]):
+        sc = d_scale[:, fi].cpu().numpy()
+        iv = d_inv[:, fi].cpu().numpy()
+        assert np.all(np.log2(sc) == np.round(np.log2(sc)))
+        E, A = oracle.sens_operand_rows(x2, g, rows, row_len, sc, iv, f)
+        parity.assert_sum_close(got[fi, 1], A, 0.0, "A pow2 fmt=%d" % f)
+        parity.assert_sum_close(got[fi, 0], E, parity.E_FLOOR * A, "E pow2 fmt=%d" % f)
+        parity.assert_sum_close(got[fi, 3], A, 0.0, "A1 pow2 fmt=%d" % f)
+        parity.assert_sum_close(got[fi, 2], E, parity.E_FLOOR * A, "E1 pow2 fmt=%d" % f)
