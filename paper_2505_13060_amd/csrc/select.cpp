@@ -8,8 +8,10 @@
 // it drops (i) every partial that another one dominates and (ii) every partial whose upper
 // bound -- its gain plus the LP relaxation of the remaining groups under the remaining
 // budget, evaluated on the groups' upper convex hulls -- cannot reach the best complete
-// configuration found so far.  Both rules keep at least one optimal configuration, so the
-// result is exact.
+// configuration found so far.  The best complete configuration known is kept tight by completing
+// every kept partial greedily along the hulls (the LP walk without its fractional last edge), so
+// the gap between bound and incumbent is one hull edge and few partials survive.  Both rules keep
+// at least one optimal configuration, so the result is exact.
 #include "../../include/ampsens.h"
 
 #include <algorithm>
@@ -29,22 +31,67 @@ struct Segment {            // one edge of a group's upper convex hull
     double dd, dg;          // increments, dd > 0, dg > 0
 };
 
-// LP relaxation of groups j..J-1 as a concave piecewise-linear function of the budget:
-// start from every group's cheapest choice, then take hull edges in order of decreasing slope.
-struct Tail {
-    double base_d = 0, base_g = 0;
-    std::vector<double> cum_d, cum_g;    // prefix sums over edges sorted by slope, starting at 0
-    double bound(double budget) const {  // -inf when even the cheapest choices do not fit
-        double room = budget - base_d;
-        if (room < 0) return -std::numeric_limits<double>::infinity();
-        // last k with cum_d[k] <= room
-        size_t k = std::upper_bound(cum_d.begin(), cum_d.end(), room) - cum_d.begin() - 1;
-        double g = base_g + cum_g[k];
-        if (k + 1 < cum_d.size()) {
-            double dd = cum_d[k + 1] - cum_d[k];
-            g += (cum_g[k + 1] - cum_g[k]) * ((room - cum_d[k]) / dd);
+// LP relaxation of the groups not yet decided, as a concave piecewise-linear function of the
+// budget: start from every such group's cheapest choice, then take hull edges in order of
+// decreasing slope.  All hull edges are sorted by slope once; two Fenwick trees over that order
+// hold the increments of the edges whose group is still undecided, so that "walk the edges until
+// the budget is used up" is a descent of the tree and dropping a group is a point update.
+struct Relaxation {
+    std::vector<Segment> edges;          // sorted by decreasing slope
+    std::vector<int32_t> group;          // owner of each edge
+    std::vector<double> fd, fg;          // Fenwick trees (1-based) over dd and dg of live edges
+    double base_d = 0, base_g = 0;       // cheapest choices of the undecided groups
+    size_t top = 1;                      // largest power of two <= edges.size()
+
+    // Rebuilt from the live edges whenever a group leaves (linear time): sums of live edges only,
+    // no residue of removed ones.
+    void build() {
+        const size_t n = edges.size();
+        fd.assign(n + 1, 0.0);
+        fg.assign(n + 1, 0.0);
+        for (size_t i = 1; i <= n; ++i) {
+            if (live[i - 1]) { fd[i] += edges[i - 1].dd; fg[i] += edges[i - 1].dg; }
+            const size_t up = i + (i & (~i + 1));
+            if (up <= n) { fd[up] += fd[i]; fg[up] += fg[i]; }
+        }
+        top = 1;
+        while (top * 2 <= n) top *= 2;
+    }
+    // Greedy walk over the live edges while they fit into `room` (>= 0).  Returns the gain of the
+    // whole edges taken; *frac receives the gain of the fraction of the next live edge that still fits.
+    double walk(double room, double* frac) const {
+        size_t pos = 0;
+        double used = 0, g = 0;
+        const size_t n = edges.size();
+        for (size_t step = n ? top : 0; step > 0; step >>= 1) {
+            const size_t nxt = pos + step;
+            if (nxt <= n && used + fd[nxt] <= room) { pos = nxt; used += fd[nxt]; g += fg[nxt]; }
+        }
+        // the next live edge after position pos (removed edges carry nothing)
+        if (frac) {
+            *frac = 0.0;
+            size_t k = pos;
+            while (k < n && !live[k]) ++k;
+            if (k < n) *frac = edges[k].dg * ((room - used) / edges[k].dd);
         }
         return g;
+    }
+    std::vector<char> live;
+    // upper bound: -inf when even the cheapest choices do not fit
+    double bound(double budget) const {
+        const double room = budget - base_d;
+        if (room < 0) return -std::numeric_limits<double>::infinity();
+        double frac;
+        const double g = walk(room, &frac);
+        return base_g + g + frac;
+    }
+    // The same walk without the fractional last edge.  Edges are taken in order of decreasing slope
+    // and the slopes along one group's hull decrease, so the edges taken from a group are a prefix of
+    // its hull: this is the gain of a real configuration that fits.
+    double integral(double budget) const {
+        const double room = budget - base_d;
+        if (room < 0) return -std::numeric_limits<double>::infinity();
+        return base_g + walk(room, nullptr);
     }
 };
 
@@ -142,10 +189,11 @@ amp_status_t amp_select_subgraphs(int J, const int32_t* n_choices, const double*
         off += (size_t)n_choices[j];
     }
 
-    // 2. LP-relaxation tails.
-    std::vector<Tail> tails(J + 1);
+    // 2. LP relaxation over all groups; groups leave it as the search decides them.
+    Relaxation rest;
     {
-        std::vector<std::vector<Segment>> hull(J);
+        struct Tagged { Segment s; int32_t j; int32_t k; };
+        std::vector<Tagged> all;
         for (int j = 0; j < J; ++j) {
             // upper convex hull of the (d, g) points, which are sorted by d with increasing g
             std::vector<Choice> h;
@@ -160,53 +208,59 @@ amp_status_t amp_select_subgraphs(int J, const int32_t* n_choices, const double*
                 h.push_back(ch);
             }
             for (size_t k = 1; k < h.size(); ++k)
-                hull[j].push_back(Segment{h[k].d - h[k - 1].d, h[k].g - h[k - 1].g});
+                all.push_back(Tagged{Segment{h[k].d - h[k - 1].d, h[k].g - h[k - 1].g}, j, (int32_t)k});
+            rest.base_d += groups[j].front().d;
+            rest.base_g += groups[j].front().g;
         }
-        std::vector<Segment> pool;
-        tails[J].cum_d = {0.0};
-        tails[J].cum_g = {0.0};
-        for (int j = J - 1; j >= 0; --j) {
-            for (const Segment& s : hull[j]) pool.push_back(s);
-            std::sort(pool.begin(), pool.end(), [](const Segment& a, const Segment& b) {
-                return a.dg * b.dd > b.dg * a.dd;               // slope a > slope b
-            });
-            Tail& t = tails[j];
-            t.base_d = tails[j + 1].base_d + groups[j].front().d;
-            t.base_g = tails[j + 1].base_g + groups[j].front().g;
-            t.cum_d.assign(1, 0.0);
-            t.cum_g.assign(1, 0.0);
-            for (const Segment& s : pool) {
-                t.cum_d.push_back(t.cum_d.back() + s.dd);
-                t.cum_g.push_back(t.cum_g.back() + s.dg);
-            }
-        }
+        // decreasing slope; among equal slopes a group's edges keep their hull order
+        std::stable_sort(all.begin(), all.end(), [](const Tagged& a, const Tagged& b) {
+            const double l = a.s.dg * b.s.dd, r = b.s.dg * a.s.dd;
+            if (l != r) return l > r;
+            if (a.j != b.j) return a.j < b.j;
+            return a.k < b.k;
+        });
+        for (const Tagged& t : all) { rest.edges.push_back(t.s); rest.group.push_back(t.j); }
+        rest.live.assign(rest.edges.size(), 1);
+        rest.build();
     }
+    // cheapest choices of groups j..J-1
+    std::vector<double> suffix_d(J + 1, 0.0), suffix_g(J + 1, 0.0);
+    for (int j = J - 1; j >= 0; --j) {
+        suffix_d[j] = suffix_d[j + 1] + groups[j].front().d;
+        suffix_g[j] = suffix_g[j + 1] + groups[j].front().g;
+    }
+    rest.base_d = suffix_d[0];
+    rest.base_g = suffix_g[0];
+    std::vector<std::vector<size_t>> edges_of(J);
+    for (size_t i = 0; i < rest.group.size(); ++i) edges_of[rest.group[i]].push_back(i);
     if (J == 0) {
         if (mse_budget < 0) return AMP_ERR_INFEASIBLE;
         if (total_gain) *total_gain = 0.0;
         if (total_mse) *total_mse = 0.0;
         return AMP_OK;
     }
-    if (tails[0].base_d > mse_budget) return AMP_ERR_INFEASIBLE;
+    if (rest.base_d > mse_budget) return AMP_ERR_INFEASIBLE;
 
     // 3. Stage-wise search with dominance and bound pruning.
     const double ninf = -std::numeric_limits<double>::infinity();
-    double incumbent = tails[0].base_g;             // all-cheapest configuration is feasible
+    double incumbent = rest.integral(mse_budget);   // greedy configuration along the hulls: fits
     auto slack = [](double v) { return 1e-12 * (std::fabs(v) + 1.0); };
     std::vector<std::vector<State>> stages(J + 1);
     stages[0].push_back(State{0.0, 0.0, -1, -1});
     std::vector<State> cand;
     for (int j = 0; j < J; ++j) {
         cand.clear();
-        const Tail& rest = tails[j + 1];
+        // group j is decided in this stage: take it out of the relaxation
+        for (size_t i : edges_of[j]) rest.live[i] = 0;
+        rest.build();
+        rest.base_d = suffix_d[j + 1];
+        rest.base_g = suffix_g[j + 1];
         for (int32_t s = 0; s < (int32_t)stages[j].size(); ++s) {
             const State& st = stages[j][s];
             for (int32_t p = 0; p < (int32_t)groups[j].size(); ++p) {
                 const double d = st.d + groups[j][p].d;
                 if (d + rest.base_d > mse_budget) break;         // choices are sorted by mse
                 const double g = st.g + groups[j][p].g;
-                const double done = g + rest.base_g;             // complete with the cheapest choices
-                if (done > incumbent) incumbent = done;
                 cand.push_back(State{d, g, s, p});
             }
         }
@@ -221,8 +275,11 @@ amp_status_t amp_select_subgraphs(int J, const int32_t* n_choices, const double*
         for (const State& c : cand) {
             if (!(c.g > best)) continue;                          // dominated
             best = c.g;
-            const double ub = c.g + rest.bound(mse_budget - c.d);
+            const double room = mse_budget - c.d;
+            const double ub = c.g + rest.bound(room);
             if (ub < incumbent - slack(incumbent)) continue;      // cannot reach the incumbent
+            const double lb = c.g + rest.integral(room);          // a configuration that completes c
+            if (lb > incumbent) incumbent = lb;
             next.push_back(c);
         }
         if (next.empty()) return AMP_ERR_INFEASIBLE;              // cannot happen once base fits

@@ -333,6 +333,78 @@ def test_select_matches_oracle_pareto_on_block_structured_instances(blocks, frac
     check_against(amp.amp_select_subgraphs(n_choices, gain, mse, budget), n_choices, gain, mse, budget, want_g)
 
 
+def lp_bound(n_choices, gain, mse, budget):
+    """Upper bound of eq. (ip): its LP relaxation, by sorting the edges of every group's upper convex
+    hull by slope (plain numpy, independent of the library)."""
+    off = offsets(n_choices)
+    base_d = base_g = 0.0
+    edges = []
+    for o, k in zip(off, n_choices):
+        pts = sorted(zip(mse[o:o + k], gain[o:o + k]))
+        keep = []
+        best = -np.inf
+        for d, g in pts:                                       # non-dominated, by increasing mse
+            if g > best:
+                keep.append((d, g))
+                best = g
+        hull = []
+        for p in keep:
+            while len(hull) >= 2 and (hull[-1][1] - hull[-2][1]) * (p[0] - hull[-2][0]) <= \
+                    (p[1] - hull[-2][1]) * (hull[-1][0] - hull[-2][0]):
+                hull.pop()
+            hull.append(p)
+        base_d += hull[0][0]
+        base_g += hull[0][1]
+        edges += [(b[0] - a[0], b[1] - a[1]) for a, b in zip(hull, hull[1:])]
+    edges.sort(key=lambda e: -e[1] / e[0])
+    room, g = budget - base_d, base_g
+    greedy = base_g
+    for dd, dg in edges:
+        if dd <= room:
+            room -= dd
+            g += dg
+            greedy = g
+        else:
+            g += dg * room / dd
+            break
+    return g, greedy
+
+
+@pytest.mark.parametrize("blocks,sizes,frac", [(80, (5, 1, 2, 1), 0.1), (80, (1,) * 9, 0.02), (16, (1,) * 88, 0.1),
+                                               (16, (1,) * 88, 0.5)])
+def test_select_on_model_sized_instances_is_fast_and_within_the_lp_bound(blocks, sizes, frac):
+    """70B-sized partitions and the 1408 single-layer groups of the ragged configuration: the optimum lies
+    between the greedy walk along the hulls and the LP bound, which differ by one hull edge."""
+    import time
+    rng = np.random.default_rng(blocks + len(sizes))
+    n_choices, gains, mses = [], [], []
+    for _ in range(blocks):
+        depth = np.exp(rng.normal(0, 0.7))
+        for L in sizes:
+            lm = np.zeros((L, 3))
+            lg = np.zeros((L, 3))
+            lm[:, 1] = rng.uniform(0.5, 2, L) * depth / 768
+            lm[:, 2] = lm[:, 1] * 4 * rng.uniform(0.8, 1.2, L)
+            lg[:, 1:] = rng.uniform(1, 10, L)[:, None]
+            d, c = amp.amp_group_tables(lm, lg)
+            n_choices.append(d.size)
+            mses.append(d)
+            gains.append(c)
+    n_choices = np.array(n_choices, dtype=np.int32)
+    gain, mse = np.concatenate(gains), np.concatenate(mses)
+    budget = frac * sum(m.max() for m in mses)
+    t0 = time.perf_counter()
+    choice, tg, td = amp.amp_select_subgraphs(n_choices, gain, mse, budget)
+    dt = time.perf_counter() - t0
+    off = offsets(n_choices)
+    assert td <= budget and mse[off + choice].sum() == pytest.approx(td, rel=1e-12)
+    assert gain[off + choice].sum() == pytest.approx(tg, rel=1e-12)
+    ub, greedy = lp_bound(n_choices, gain, mse, budget)
+    assert greedy * (1 - 1e-12) <= tg <= ub * (1 + 1e-12)
+    assert ub - tg <= 10.0 + 1e-9                              # one hull edge gains at most 10 here
+    assert dt < 2.0
+
+
 def test_select_invariances_and_errors():
     rng = np.random.default_rng(77)
     n_choices, gain, mse, budget = llama_like_instance(rng, 3, 0.1)
