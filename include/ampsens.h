@@ -275,7 +275,10 @@ amp_status_t amp_select_ordered(int J, const int32_t* n_choices, const double* g
  * before and after the kernel, until n launches have been recorded.  An amp_sens_linear call
  * launches the weight kernel (W read once per batch of samples) if it has whole weight chunks for
  * it, then the streaming kernel for everything else; an amp_sens_bgemm call launches the streaming
- * kernel.  amp_profile_read waits for the recorded events, writes the elapsed milliseconds of each
+ * kernel.  Operands with one scale per row have kernels of their own: a call then launches up to two
+ * weight kernels (per-tensor, per-channel) and up to four streaming kernels (one scale per tensor;
+ * long or causal rows; short power-of-two rows; other shapes), in that order, each only if it has
+ * work.  amp_profile_read waits for the recorded events, writes the elapsed milliseconds of each
  * launch to ms[0..*n_launches) and, if not NULL, to pairs[] the number of element pairs the
  * launch covered and to bytes[] the operand bytes it is defined to read (4 per pair for the
  * streaming kernel; for the weight kernel 2 per pair plus W's bytes once per batch of samples)
