@@ -18,7 +18,7 @@
  *
  *   ztilde is the absmax-scaled FP8 fake quantisation of z, with one scale per tensor or,
  *   optionally, one per row (see "scale granularity" below).  The paper names the
- *   format only as "FP8-E4M3: 4 exponent, 3 mantissa bits" (Sec. 3.1) and does not describe
+ *   format only by its bit split, four exponent and three mantissa bits (Sec. 3.1), and does not describe
  *   the cast; this library uses the OCP 8-bit formats (E4M3: max 448, no infinities; E5M2:
  *   max 57344), round to nearest even, saturating:
  *

@@ -21,7 +21,8 @@
 //   * eq. (ip) of Sec. 2.1: maximise sum of gains subject to sum of loss MSE
 //          <= budget with one choice per group -- by exhaustive enumeration, and by
 //          a dominance-pruned enumeration for larger instances.
-//   * The paper only says "FP8-E4M3: 4 exponent, 3 mantissa bits" (Sec. 3.1) and is
+//   * The paper names its FP8 format only by its bit split, four exponent and three mantissa
+//          bits (Sec. 3.1), and is
 //          silent on the cast itself.  The cast here is the OCP 8-bit floating point
 //          definition: E4M3 (bias 7, no infinities, S.1111.111 is NaN, max 448) and
 //          E5M2 (bias 15, IEEE-like, max 57344), round to nearest, ties to even,

@@ -1,6 +1,6 @@
 """Capture layer: hands the operands and loss gradients of a PyTorch model's quantisable
 operations to libampsens, one calibration sample per forward/backward pass (step 2 of
-Algorithm 1, App. A: the sensitivity of every layer is measured "in high precision" from one
+Algorithm 1, App. A: the sensitivity of every layer is measured on the unquantised model from one
 forward and one backward pass per sample; Sec. 2.2 defines z_l as the operands of op l and
 z_l-dot as the loss gradient with respect to them).
 
