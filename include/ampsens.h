@@ -37,9 +37,9 @@
  *     including the workspace; the library allocates no device memory and frees nothing.
  *   - Device calls validate their arguments on the host first (no launch happens on an error),
  *     then enqueue on the caller's stream (a hipStream_t passed as void*, NULL = the null
- *     stream).  They do not wait for the GPU.  Each call copies a small descriptor table from
- *     pageable host memory into the workspace with hipMemcpyAsync, which may block the host
- *     until earlier work on that stream has drained.
+ *     stream).  They do not wait for the GPU.  Each call copies a small descriptor table into the
+ *     workspace with hipMemcpyAsync from a pinned host buffer of the library's own (host memory,
+ *     created on first use, at most 32 per device, reused when their copy has completed, never freed).
  *   - Pointers need only 2-byte alignment; 16-byte aligned buffers take the fast path
  *     (128-bit loads).  Results do not depend on the launch grid.
  *   - Every call returns amp_status_t.  After AMP_ERR_DEVICE, amp_last_device_error() gives

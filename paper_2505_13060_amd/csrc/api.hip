@@ -345,18 +345,93 @@ int g_use_w_kernel = 1;                                // test / tuning hook
 
 uint32_t schedule_block() { return g_schedule_block > 0 ? (uint32_t)g_schedule_block : kDefaultScheduleBlock; }
 
-amp_status_t upload(const WorkTable& t, const WorkTable::Plan& plan, void* workspace, hipStream_t stream) {
-    std::vector<uint8_t> blob(t.table_bytes(), 0);
-    std::memcpy(blob.data(), t.units.data(), t.units.size() * sizeof(WorkUnit));
-    std::vector<uint32_t> cb = t.chunk_begin;
-    cb.push_back((uint32_t)t.n_chunks);
-    std::memcpy(blob.data() + t.units.size() * sizeof(WorkUnit), cb.data(), cb.size() * 4);
-    std::memcpy(blob.data() + t.schedule_offset(), plan.schedule.data(),
-                plan.schedule.size() * sizeof(UnitSchedule));
-    if (!plan.wgroups.empty())
-        std::memcpy(blob.data() + t.groups_offset(), plan.wgroups.data(), plan.wgroups.size() * sizeof(WGroup));
-    AMP_HIP(hipMemcpyAsync(workspace, blob.data(), blob.size(), hipMemcpyHostToDevice, stream));
+// Pinned host staging for the descriptor tables.  A table is assembled in a pinned slot and copied
+// from there, so the source stays valid until the copy has run whatever the runtime does with
+// pageable sources, and the copy is an ordinary asynchronous command of the stream.  Slots are host
+// memory only, created on demand (at most kMaxStagingSlots per device), reused once the copy that
+// read them has completed (one event per slot) and never freed.
+struct StagingSlot {
+    void* host = nullptr;
+    size_t cap = 0;
+    hipEvent_t done = nullptr;
+    bool in_flight = false;
+};
+constexpr size_t kMaxStagingSlots = 32;
+std::mutex g_staging_mu;
+std::vector<StagingSlot> g_staging[64];                // per device
+
+// A slot of the current device's pool with room for `bytes`, or -1 (then the caller copies from
+// pageable memory).  Call with g_staging_mu held.
+int staging_acquire(int dev, size_t bytes) {
+    std::vector<StagingSlot>& pool = g_staging[dev];
+    int busy_fit = -1;
+    for (size_t i = 0; i < pool.size(); ++i) {
+        if (pool[i].cap < bytes) continue;
+        if (!pool[i].in_flight || hipEventQuery(pool[i].done) == hipSuccess) {
+            pool[i].in_flight = false;
+            return (int)i;
+        }
+        if (busy_fit < 0) busy_fit = (int)i;
+    }
+    (void)hipGetLastError();                               // hipEventQuery reports "not ready" as an error
+    if (pool.size() < kMaxStagingSlots) {
+        StagingSlot slot;
+        slot.cap = round_up(bytes < ((size_t)64 << 10) ? ((size_t)64 << 10) : bytes, 4096);
+        if (hipHostMalloc(&slot.host, slot.cap, hipHostMallocDefault) != hipSuccess) {
+            (void)hipGetLastError();
+            return -1;
+        }
+        if (hipEventCreateWithFlags(&slot.done, hipEventDisableTiming) != hipSuccess) {
+            (void)hipGetLastError();
+            (void)hipHostFree(slot.host);
+            return -1;
+        }
+        pool.push_back(slot);
+        return (int)pool.size() - 1;
+    }
+    if (busy_fit >= 0 && hipEventSynchronize(pool[busy_fit].done) == hipSuccess) {
+        pool[busy_fit].in_flight = false;
+        return busy_fit;
+    }
+    return -1;
+}
+
+// Copies `bytes` bytes, written by fill(dst), to device memory `d_dst` on `stream`.
+template <class Fill>
+amp_status_t staged_upload(void* d_dst, size_t bytes, hipStream_t stream, Fill fill) {
+    const int dev = device_index();
+    if (dev >= 0) {
+        std::lock_guard<std::mutex> lock(g_staging_mu);
+        const int slot = staging_acquire(dev, bytes);
+        if (slot >= 0) {
+            StagingSlot& sl = g_staging[dev][slot];
+            fill((uint8_t*)sl.host);
+            AMP_HIP(hipMemcpyAsync(d_dst, sl.host, bytes, hipMemcpyHostToDevice, stream));
+            AMP_HIP(hipEventRecord(sl.done, stream));
+            sl.in_flight = true;
+            return AMP_OK;
+        }
+    }
+    std::vector<uint8_t> pageable(bytes);                  // the runtime stages pageable sources itself
+    fill(pageable.data());
+    AMP_HIP(hipMemcpyAsync(d_dst, pageable.data(), bytes, hipMemcpyHostToDevice, stream));
     return AMP_OK;
+}
+
+// units | chunk_begin | schedule | weight groups -> the head of the workspace
+amp_status_t upload(const WorkTable& t, const WorkTable::Plan& plan, void* workspace, hipStream_t stream) {
+    const size_t bytes = t.table_bytes();
+    return staged_upload(workspace, bytes, stream, [&](uint8_t* blob) {
+        std::memset(blob, 0, bytes);
+        std::memcpy(blob, t.units.data(), t.units.size() * sizeof(WorkUnit));
+        uint8_t* cb = blob + t.units.size() * sizeof(WorkUnit);
+        std::memcpy(cb, t.chunk_begin.data(), t.chunk_begin.size() * 4);
+        const uint32_t total = (uint32_t)t.n_chunks;
+        std::memcpy(cb + t.chunk_begin.size() * 4, &total, 4);
+        std::memcpy(blob + t.schedule_offset(), plan.schedule.data(), plan.schedule.size() * sizeof(UnitSchedule));
+        if (!plan.wgroups.empty())
+            std::memcpy(blob + t.groups_offset(), plan.wgroups.data(), plan.wgroups.size() * sizeof(WGroup));
+    });
 }
 
 // ---- optional timing of the sensitivity kernel ------------------------------------------------
@@ -752,7 +827,9 @@ amp_status_t amp_absmax_scale_rows(const amp_tensor_t* tensors, int n_tensors, c
     const size_t bytes = P.tensors.size() * sizeof(RowTensor);
     if (workspace_bytes < round_up(bytes, 256)) return AMP_ERR_WORKSPACE_TOO_SMALL;
     hipStream_t stream = (hipStream_t)stream_;
-    AMP_HIP(hipMemcpyAsync(workspace, P.tensors.data(), bytes, hipMemcpyHostToDevice, stream));
+    st = staged_upload(workspace, bytes, stream,
+                       [&](uint8_t* dst) { std::memcpy(dst, P.tensors.data(), bytes); });
+    if (st != AMP_OK) return st;
     const uint64_t waves = P.n_items;
     const uint64_t wgs = (waves + kWaves - 1) / kWaves;
     static std::mutex mu;
