@@ -389,3 +389,44 @@ def test_weight_kernel_and_streaming_kernel_agree():
             outs.append(res["linear"][0].copy())
         L.ampsens_debug_set_w_kernel(C.c_int(1))
         assert np.allclose(outs[0], outs[1], rtol=2e-6, atol=0)
+
+
+def test_tensor_with_more_than_2_to_31_elements():
+    """Element indices beyond 32 bits: one dense operand of 2^31 + 2^20 + 4104 elements made of a repeated
+    2^20-element pattern.  Every whole repetition covers the same chunks relative to its start, so its
+    per-chunk fp32 partials are those of the pattern and the sums must be (repetitions) x the pattern's sums
+    plus the tail's, which the oracle computes."""
+    period, reps, tail = 1 << 20, 2049, 4104
+    n = period * reps + tail
+    rng = np.random.default_rng(2031)
+    xp = f32_to_bf16_bits(rng.standard_normal(period).astype(np.float32))
+    gp = f32_to_bf16_bits((rng.standard_normal(period) * 1e-3).astype(np.float32))
+    xp[12345] = f32_to_bf16_bits(np.array([300.0], dtype=np.float32))[0]          # the amax
+    say("one operand of %d elements (%.1f GB with its gradient)" % (n, n * 4 / 1e9))
+    xd = torch.from_numpy(xp.view(np.int16)).to(DEV)
+    gd = torch.from_numpy(gp.view(np.int16)).to(DEV)
+    x = torch.cat([xd.repeat(reps), xd[:tail]])
+    g = torch.cat([gd.repeat(reps), gd[:tail]])
+    small = torch.zeros(8, dtype=torch.int16, device=DEV)
+    fmts = [amp.E4M3, amp.E5M2]
+    tens = [amp.tensor(x, amp.dense(n))]
+    ws = torch.empty(max(amp.amp_absmax_workspace_bytes(tens), 256), dtype=torch.uint8, device=DEV)
+    am = torch.zeros(1, device=DEV)
+    sc = torch.zeros(1, 2, device=DEV)
+    iv = torch.zeros(1, 2, device=DEV)
+    fl = torch.zeros(1, dtype=torch.int32, device=DEV)
+    amp.amp_absmax_scale(tens, fmts, am, sc, iv, fl, ws)
+    desc = [amp.bgemm_desc(x, g, amp.dense(n), small, small, amp.dense(8), 1, sc[0], iv[0], sc[0], iv[0])]
+    out = torch.zeros(1, 2, 4, device=DEV)
+    ws2 = torch.empty(max(amp.amp_sens_bgemm_workspace_bytes(desc, 2), 256), dtype=torch.uint8, device=DEV)
+    amp.amp_sens_bgemm(desc, fmts, out, ws2)
+    torch.cuda.synchronize()
+    assert float(am[0]) == 300.0 and int(fl[0]) == 0
+    got = out.cpu().numpy()[0]
+    for fi, f in enumerate(fmts):
+        a0, s0, i0, _ = oracle.absmax_scale(xp, f)
+        assert parity.bits32(sc[0, fi].cpu().numpy()) == parity.bits32(s0)
+        Ep, Ap = oracle.sens_operand(xp, gp, 1, period, s0, i0, f)
+        Et, At = oracle.sens_operand(xp[:tail], gp[:tail], 1, tail, s0, i0, f)
+        parity.assert_sum_close(got[fi, 1], reps * Ap[0] + At[0], 0.0, "A fmt=%d" % f)
+        parity.assert_sum_close(got[fi, 0], reps * Ep[0] + Et[0], 0.0, "E fmt=%d" % f)
