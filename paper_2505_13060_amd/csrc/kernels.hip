@@ -884,15 +884,21 @@ __global__ __launch_bounds__(kWG) void sens_finalize_kernel(const ResolvedUnit* 
 
 // ---- absmax ---------------------------------------------------------------------------------
 
+typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
+
 struct AbsmaxCtx {
     static constexpr bool kRollDense = false;
     gptr16_t x;
-    uint32_t m;                                     // running max of (bits & 0x7FFF)
+    uint32_t m;                                     // two running maxima of (bits & 0x7FFF), one per half
 
+    // both elements of a word at once: clear the signs, packed 16-bit maximum
     __device__ __forceinline__ void word(uint32_t w) {
-        const uint32_t lo = w & 0x7FFFu, hi = (w >> 16) & 0x7FFFu;
-        m = m > lo ? m : lo;
-        m = m > hi ? m : hi;
+        const u16x2 a = __builtin_bit_cast(u16x2, m), b = __builtin_bit_cast(u16x2, w & 0x7FFF7FFFu);
+        m = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(a, b));
+    }
+    __device__ __forceinline__ uint32_t result() const {
+        const uint32_t lo = m & 0xFFFFu, hi = m >> 16;
+        return lo > hi ? lo : hi;
     }
     __device__ __forceinline__ void vec(const u32x4& v) { word(v.x); word(v.y); word(v.z); word(v.w); }
     __device__ __forceinline__ void begin_dense(int64_t, int) {}
@@ -949,7 +955,7 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
         ctx.x = (gptr16_t)u.x;
         ctx.m = 0;
         walk_chunk(u, local, tid, ctx);
-        const uint32_t m = wave_max(ctx.m);
+        const uint32_t m = wave_max(ctx.result());
         if ((tid & 63) == 0) partial_max[(size_t)slot_id * kWaves + (tid >> 6)] = m;
         if (!more) break;
         c = cn;
