@@ -40,6 +40,8 @@
  *     stream).  They do not wait for the GPU.  Each call copies a small descriptor table into the
  *     workspace with hipMemcpyAsync from a pinned host buffer of the library's own (host memory,
  *     created on first use, at most 32 per device, reused when their copy has completed, never freed).
+ *     Only when all 32 are still in flight does a call wait for the oldest copy; only when pinned
+ *     memory cannot be had does it copy from pageable memory and wait for that copy.
  *   - Pointers need only 2-byte alignment; 16-byte aligned buffers take the fast path
  *     (128-bit loads).  Results do not depend on the launch grid.
  *   - Every call returns amp_status_t.  After AMP_ERR_DEVICE, amp_last_device_error() gives

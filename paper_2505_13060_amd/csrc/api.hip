@@ -58,6 +58,15 @@ amp_status_t check_layout(const amp_layout_t& L) {
     return AMP_OK;
 }
 
+// Entries of one [rows, cols] matrix that belong to the operand: row i owns its first
+// i + 1 + (cols - rows) columns, clipped to [0, cols] (the diagonal ends at the last column).
+uint64_t causal_valid(int64_t rows, int64_t cols) {
+    if (rows <= 0 || cols <= 0) return 0;
+    const uint64_t r = (uint64_t)rows, c = (uint64_t)cols;
+    if (cols >= rows) return r * (c - r + 1) + r * (r - 1) / 2;      // lengths c-r+1 .. c
+    return c * (c + 1) / 2;                                          // the last c rows: lengths 1 .. c
+}
+
 int64_t layout_span(const amp_layout_t& L) {
     return L.causal ? L.batch * L.rows * L.cols : L.n_elems;
 }
@@ -99,11 +108,7 @@ struct WorkTable {
             u.chunks_per_mat = (L.rows > 0 && L.cols > 0) ? causal_chunks_per_mat(L.rows) : 0;
             chunks = (uint64_t)batch * u.chunks_per_mat;
             if (chunks == 0) u.chunks_per_mat = 1;         // never divide by zero on the device
-            uint64_t valid = 0;
-            for (int64_t i = 0; i < L.rows; ++i) {
-                int64_t len = i + 1 + (L.cols - L.rows);
-                valid += (uint64_t)(len < 0 ? 0 : (len > L.cols ? L.cols : len));
-            }
+            const uint64_t valid = causal_valid(L.rows, L.cols);
             n_pairs += valid * (uint64_t)batch;
             unit_pairs.push_back(valid * (uint64_t)batch);
         } else {
@@ -412,9 +417,12 @@ amp_status_t staged_upload(void* d_dst, size_t bytes, hipStream_t stream, Fill f
             return AMP_OK;
         }
     }
-    std::vector<uint8_t> pageable(bytes);                  // the runtime stages pageable sources itself
+    // No pinned slot (the pool is full and busy, or pinned memory ran out): copy from pageable
+    // memory and wait, so the source outlives the copy.  The only place a device call blocks.
+    std::vector<uint8_t> pageable(bytes);
     fill(pageable.data());
     AMP_HIP(hipMemcpyAsync(d_dst, pageable.data(), bytes, hipMemcpyHostToDevice, stream));
+    AMP_HIP(hipStreamSynchronize(stream));
     return AMP_OK;
 }
 
