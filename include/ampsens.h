@@ -211,6 +211,19 @@ amp_status_t amp_sens_bgemm(const amp_bgemm_desc_t* ops /* host array */, int n_
                             const amp_fp8_format_t* fmts /* host */, int n_fmts, float* d_out,
                             void* workspace, size_t workspace_bytes, void* stream);
 
+/* Linear layers and BGEMMs of one call (a whole transformer block, or a whole model): the same sums,
+ * bit for bit, as amp_sens_linear followed by amp_sens_bgemm, with one descriptor table, one set-up
+ * and one finalisation for all of them, and the BGEMM operands streamed by the same launch as the
+ * activations.  d_out holds the linear layers' block first ([sum of R over the linears][n_fmts][4],
+ * laid out as above) and the BGEMMs' block right behind it.  Either array may be empty. */
+amp_status_t amp_sens_block_workspace_bytes(const amp_linear_desc_t* linears, int n_linears,
+                                            const amp_bgemm_desc_t* bgemms, int n_bgemms, int n_fmts,
+                                            size_t* bytes);
+amp_status_t amp_sens_block(const amp_linear_desc_t* linears /* host array */, int n_linears,
+                            const amp_bgemm_desc_t* bgemms /* host array */, int n_bgemms,
+                            const amp_fp8_format_t* fmts /* host */, int n_fmts, float* d_out,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---- step 4 (host): epilogue of Sec. 2.2 -------------------------------------------------
  * sums: HOST copy of one op's block of d_out, [R][n_fmts][4].
  *   *s_layer       = (1/R) sum_r (A_op0^r + A_op1^r)                 (eq. (sensl))
@@ -277,14 +290,16 @@ amp_status_t amp_select_ordered(int J, const int32_t* n_choices, const double* g
  * before and after the kernel, until n launches have been recorded.  An amp_sens_linear call
  * launches the weight kernel (W read once per batch of samples) if it has whole weight chunks for
  * it, then the streaming kernel for everything else; an amp_sens_bgemm call launches the streaming
- * kernel.  Operands with one scale per row have kernels of their own: a call then launches up to two
+ * kernel; an amp_sens_block call launches what amp_sens_linear would, with the BGEMM operands in the
+ * streaming launches.  Operands with one scale per row have kernels of their own: a call then launches up to two
  * weight kernels (per-tensor, per-channel) and up to four streaming kernels (one scale per tensor;
  * long or causal rows; short power-of-two rows; other shapes), in that order, each only if it has
  * work.  amp_profile_read waits for the recorded events, writes the elapsed milliseconds of each
  * launch to ms[0..*n_launches) and, if not NULL, to pairs[] the number of element pairs the
  * launch covered and to bytes[] the operand bytes it is defined to read (4 per pair for the
  * streaming kernel; for the weight kernel 2 per pair plus W's bytes once per batch of samples)
- * (host arrays; capacity must be >= the n given to enable), and resets the count.  amp_profile_enable(0) destroys the events.  Not thread-safe; meant for benchmarks. */
+ * (host arrays; capacity must be >= the n given to enable), and resets the count.
+ * amp_profile_enable(0) destroys the events.  Not thread-safe; meant for benchmarks. */
 amp_status_t amp_profile_enable(int max_launches);
 amp_status_t amp_profile_read(float* ms, uint64_t* pairs, uint64_t* bytes, int capacity, int* n_launches);
 

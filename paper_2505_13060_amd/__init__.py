@@ -85,6 +85,10 @@ def lib():
                                          C.c_void_p, C.c_size_t, C.c_void_p]
             getattr(L, name + "_workspace_bytes").argtypes = [C.c_void_p, C.c_int, C.c_int,
                                                               C.POINTER(C.c_size_t)]
+        L.amp_sens_block.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p,
+                                     C.c_void_p, C.c_size_t, C.c_void_p]
+        L.amp_sens_block_workspace_bytes.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int,
+                                                     C.POINTER(C.c_size_t)]
         _lib = L
     return _lib
 
@@ -221,6 +225,23 @@ def amp_sens_bgemm(ops, fmts, d_out, workspace, stream=None):
     _check(lib().amp_sens_bgemm(_array(BgemmDesc, ops), len(ops), f, nf, _ptr(d_out),
                                 _ptr(workspace), workspace.numel() * workspace.element_size(),
                                 _stream(stream)), "amp_sens_bgemm")
+
+
+def amp_sens_block_workspace_bytes(linears, bgemms, n_fmts):
+    n = C.c_size_t()
+    _check(lib().amp_sens_block_workspace_bytes(_array(LinearDesc, linears), len(linears),
+                                                _array(BgemmDesc, bgemms), len(bgemms), int(n_fmts),
+                                                C.byref(n)), "amp_sens_block_workspace_bytes")
+    return n.value
+
+
+def amp_sens_block(linears, bgemms, fmts, d_out, workspace, stream=None):
+    """Linears and BGEMMs in one call; d_out [sum R of the linears + sum R of the BGEMMs, n_fmts, 4]."""
+    f, nf = _fmts(fmts)
+    _check(lib().amp_sens_block(_array(LinearDesc, linears), len(linears), _array(BgemmDesc, bgemms),
+                                len(bgemms), f, nf, _ptr(d_out), _ptr(workspace),
+                                workspace.numel() * workspace.element_size(), _stream(stream)),
+           "amp_sens_block")
 
 
 def amp_alpha(mantissa_bits):

@@ -184,7 +184,7 @@ def _ops_of(samples, fmts):
 
 def _run(workload, device):
     from .pipeline import SensPass                              # loads the library: fails loudly without it
-    p = SensPass(workload, device)
+    p = SensPass(workload, device, one_call=True)
     p.run()
     res = p.results()
     if res["flags"].any():

@@ -514,10 +514,12 @@ amp_status_t run_sens(const WorkTable& t, const amp_fp8_format_t* fmts, int n_fm
     return AMP_OK;
 }
 
-amp_status_t build_linear(const amp_linear_desc_t* ops, int n_ops, int n_fmts, WorkTable* t) {
+// out_base (in / out): samples of the ops already in the table; this call's sums start there in d_out.
+amp_status_t build_linear(const amp_linear_desc_t* ops, int n_ops, int n_fmts, WorkTable* t,
+                          uint64_t* out_base = nullptr) {
     if (n_ops < 0 || (n_ops > 0 && !ops)) return AMP_ERR_INVALID_ARG;
     if (n_fmts < 1 || n_fmts > AMP_MAX_FORMATS) return AMP_ERR_BAD_FORMAT;
-    uint64_t base = 0;
+    uint64_t base = out_base ? *out_base : 0;
     for (int k = 0; k < n_ops; ++k) {
         const amp_linear_desc_t& op = ops[k];
         if (op.R < 0 || op.C < 0 || op.K < 0 || op.tokens < 0) return AMP_ERR_INVALID_ARG;
@@ -558,6 +560,7 @@ amp_status_t build_linear(const amp_linear_desc_t* ops, int n_ops, int n_fmts, W
         }
         base += (uint64_t)op.R;
     }
+    if (out_base) *out_base = base;
     return AMP_OK;
 }
 
@@ -576,10 +579,11 @@ amp_status_t row_geometry(const amp_layout_t& L, int64_t* row_len, int64_t* rows
     return AMP_OK;
 }
 
-amp_status_t build_bgemm(const amp_bgemm_desc_t* ops, int n_ops, int n_fmts, WorkTable* t) {
+amp_status_t build_bgemm(const amp_bgemm_desc_t* ops, int n_ops, int n_fmts, WorkTable* t,
+                         uint64_t* out_base = nullptr) {
     if (n_ops < 0 || (n_ops > 0 && !ops)) return AMP_ERR_INVALID_ARG;
     if (n_fmts < 1 || n_fmts > AMP_MAX_FORMATS) return AMP_ERR_BAD_FORMAT;
-    uint64_t base = 0;
+    uint64_t base = out_base ? *out_base : 0;
     for (int k = 0; k < n_ops; ++k) {
         const amp_bgemm_desc_t& op = ops[k];
         if (op.R < 0) return AMP_ERR_INVALID_ARG;
@@ -617,6 +621,7 @@ amp_status_t build_bgemm(const amp_bgemm_desc_t* ops, int n_ops, int n_fmts, Wor
         }
         base += (uint64_t)op.R;
     }
+    if (out_base) *out_base = base;
     return AMP_OK;
 }
 
@@ -908,6 +913,34 @@ amp_status_t amp_sens_bgemm(const amp_bgemm_desc_t* ops, int n_ops, const amp_fp
     if (st != AMP_OK) return st;
     WorkTable t;
     st = build_bgemm(ops, n_ops, n_fmts, &t);
+    if (st != AMP_OK) return st;
+    return run_sens(t, fmts, n_fmts, d_out, workspace, workspace_bytes, stream);
+}
+
+amp_status_t amp_sens_block_workspace_bytes(const amp_linear_desc_t* linears, int n_linears,
+                                            const amp_bgemm_desc_t* bgemms, int n_bgemms, int n_fmts,
+                                            size_t* bytes) {
+    if (!bytes) return AMP_ERR_INVALID_ARG;
+    WorkTable t;
+    uint64_t base = 0;
+    amp_status_t st = build_linear(linears, n_linears, n_fmts, &t, &base);
+    if (st != AMP_OK) return st;
+    st = build_bgemm(bgemms, n_bgemms, n_fmts, &t, &base);
+    if (st != AMP_OK) return st;
+    *bytes = sens_layout(t, n_fmts).total;
+    return AMP_OK;
+}
+
+amp_status_t amp_sens_block(const amp_linear_desc_t* linears, int n_linears, const amp_bgemm_desc_t* bgemms,
+                            int n_bgemms, const amp_fp8_format_t* fmts, int n_fmts, float* d_out,
+                            void* workspace, size_t workspace_bytes, void* stream) {
+    amp_status_t st = check_fmts(fmts, n_fmts);
+    if (st != AMP_OK) return st;
+    WorkTable t;
+    uint64_t base = 0;
+    st = build_linear(linears, n_linears, n_fmts, &t, &base);
+    if (st != AMP_OK) return st;
+    st = build_bgemm(bgemms, n_bgemms, n_fmts, &t, &base);
     if (st != AMP_OK) return st;
     return run_sens(t, fmts, n_fmts, d_out, workspace, workspace_bytes, stream);
 }

@@ -9,8 +9,9 @@ import torch
 
 from . import (ROWS_OPERAND0, ROWS_OPERAND1, amp_absmax_rows_workspace_bytes, amp_absmax_scale,
                amp_absmax_scale_rows, amp_absmax_workspace_bytes, amp_sens_bgemm,
-               amp_sens_bgemm_workspace_bytes, amp_sens_linear, amp_sens_linear_workspace_bytes,
-               bgemm_desc, causal, dense, linear_desc, tensor)
+               amp_sens_bgemm_workspace_bytes, amp_sens_block, amp_sens_block_workspace_bytes,
+               amp_sens_linear, amp_sens_linear_workspace_bytes, bgemm_desc, causal, dense, linear_desc,
+               tensor)
 
 
 def _layout(lay, cols=0):
@@ -22,9 +23,12 @@ def _row(t, i):
 
 
 class SensPass:
-    """Holds descriptors, outputs and workspaces for one Workload resident on `device`."""
+    """Holds descriptors, outputs and workspaces for one Workload resident on `device`.
+    one_call: linears and BGEMMs go through amp_sens_block (one table, one set-up, one streaming
+    launch for activations and BGEMM operands) instead of amp_sens_linear + amp_sens_bgemm."""
 
-    def __init__(self, workload, device):
+    def __init__(self, workload, device, one_call=False):
+        self.one_call = one_call
         self.w = workload
         self.device = device
         self.fmts = list(workload.fmts)
@@ -60,21 +64,29 @@ class SensPass:
                                            self.d_scale[t0 + 1], self.d_inv[t0 + 1]))
         self.lin_R = [op.R for op in workload.linears]
         self.bg_R = [op.R for op in workload.bgemms]
-        self.d_lin_out = torch.zeros(max(sum(self.lin_R), 1), nf, 4, **f32)
-        self.d_bg_out = torch.zeros(max(sum(self.bg_R), 1), nf, 4, **f32)
+        nlr, nbr = sum(self.lin_R), sum(self.bg_R)
+        self.d_out = torch.zeros(max(nlr + nbr, 1), nf, 4, **f32)      # the linears' block, then the BGEMMs'
+        self.d_lin_out = self.d_out[:nlr]
+        self.d_bg_out = self.d_out[nlr:nlr + nbr]
 
         def ws(nbytes):
             return torch.empty(max(nbytes, 256), device=device, dtype=torch.uint8)
 
         self.ws_abs = ws(amp_absmax_workspace_bytes(self.tensors))
-        self.ws_lin = ws(amp_sens_linear_workspace_bytes(self.lin_desc, nf))
-        self.ws_bg = ws(amp_sens_bgemm_workspace_bytes(self.bg_desc, nf))
+        if one_call:
+            self.ws_block = ws(amp_sens_block_workspace_bytes(self.lin_desc, self.bg_desc, nf))
+        else:
+            self.ws_lin = ws(amp_sens_linear_workspace_bytes(self.lin_desc, nf))
+            self.ws_bg = ws(amp_sens_bgemm_workspace_bytes(self.bg_desc, nf))
 
     def absmax(self, stream=None):
         amp_absmax_scale(self.tensors, self.fmts, self.d_amax, self.d_scale, self.d_inv, self.d_flags,
                          self.ws_abs, stream)
 
     def sens(self, stream=None):
+        if self.one_call:
+            amp_sens_block(self.lin_desc, self.bg_desc, self.fmts, self.d_out, self.ws_block, stream)
+            return
         if self.lin_desc:
             amp_sens_linear(self.lin_desc, self.fmts, self.d_lin_out, self.ws_lin, stream)
         if self.bg_desc:
@@ -109,7 +121,8 @@ class RowSensPass:
     operands (bgemm_rows; a dense operand's row is its last dimension).  Operands left at one
     scale per tensor go through amp_absmax_scale as in SensPass."""
 
-    def __init__(self, workload, device, x_rows=True, w_rows=True, bgemm_rows=True):
+    def __init__(self, workload, device, x_rows=True, w_rows=True, bgemm_rows=True, one_call=False):
+        self.one_call = one_call
         self.w, self.device, self.fmts = workload, device, list(workload.fmts)
         nf = len(self.fmts)
         f32 = dict(device=device, dtype=torch.float32)
@@ -169,16 +182,21 @@ class RowSensPass:
                                            scale_rows=(ROWS_OPERAND0 if r0 else 0) | (ROWS_OPERAND1 if r1 else 0)))
         self.lin_R = [op.R for op in workload.linears]
         self.bg_R = [op.R for op in workload.bgemms]
-        self.d_lin_out = torch.zeros(max(sum(self.lin_R), 1), nf, 4, **f32)
-        self.d_bg_out = torch.zeros(max(sum(self.bg_R), 1), nf, 4, **f32)
+        nlr, nbr = sum(self.lin_R), sum(self.bg_R)
+        self.d_out = torch.zeros(max(nlr + nbr, 1), nf, 4, **f32)
+        self.d_lin_out = self.d_out[:nlr]
+        self.d_bg_out = self.d_out[nlr:nlr + nbr]
 
         def ws(nbytes):
             return torch.empty(max(nbytes, 256), device=device, dtype=torch.uint8)
 
         self.ws_abs = ws(amp_absmax_workspace_bytes(self.t_tensors))
         self.ws_rows = ws(ws_rows)
-        self.ws_lin = ws(amp_sens_linear_workspace_bytes(self.lin_desc, nf))
-        self.ws_bg = ws(amp_sens_bgemm_workspace_bytes(self.bg_desc, nf))
+        if one_call:
+            self.ws_block = ws(amp_sens_block_workspace_bytes(self.lin_desc, self.bg_desc, nf))
+        else:
+            self.ws_lin = ws(amp_sens_linear_workspace_bytes(self.lin_desc, nf))
+            self.ws_bg = ws(amp_sens_bgemm_workspace_bytes(self.bg_desc, nf))
 
     def absmax(self, stream=None):
         if self.t_tensors:
@@ -189,6 +207,9 @@ class RowSensPass:
                                   self.r_flags, self.ws_rows, stream)
 
     def sens(self, stream=None):
+        if self.one_call:
+            amp_sens_block(self.lin_desc, self.bg_desc, self.fmts, self.d_out, self.ws_block, stream)
+            return
         if self.lin_desc:
             amp_sens_linear(self.lin_desc, self.fmts, self.d_lin_out, self.ws_lin, stream)
         if self.bg_desc:

@@ -90,6 +90,40 @@ def test_argument_validation_without_a_gpu():
     assert n.value == 512 + 256 + 256 + 256
 
 
+def test_block_call_is_validated_like_its_two_halves():
+    """amp_sens_block: the workspace holds one table for all units; a bad descriptor on either side,
+    a bad format or a short workspace is refused before any launch; nothing to do is not an error."""
+    L = amp.lib()
+    n, nl, nb = C.c_size_t(), C.c_size_t(), C.c_size_t()
+    d = amp.linear_desc(None, None, None, None, 64, 32, 2, None, None, None, None, tokens=5)
+    d.x = d.dx = d.w = d.dw = 4096
+    d.x_scale = d.x_inv = d.w_scale = d.w_inv = 4096
+    b = amp.bgemm_desc(None, None, amp.dense(4 * 64 * 16), None, None, amp.causal(4, 64, 64), 3,
+                       None, None, None, None)
+    b.x0 = b.dx0 = b.x1 = b.dx1 = 4096
+    b.scale0 = b.inv0 = b.scale1 = b.inv1 = 4096
+    assert L.amp_sens_block_workspace_bytes(C.byref(d), 1, C.byref(b), 1, 2, C.byref(n)) == amp.OK
+    assert L.amp_sens_linear_workspace_bytes(C.byref(d), 1, 2, C.byref(nl)) == amp.OK
+    assert L.amp_sens_bgemm_workspace_bytes(C.byref(b), 1, 2, C.byref(nb)) == amp.OK
+    assert max(nl.value, nb.value) < n.value <= nl.value + nb.value
+    assert L.amp_sens_block_workspace_bytes(C.byref(d), 1, None, 0, 2, C.byref(n)) == amp.OK and n.value == nl.value
+    assert L.amp_sens_block_workspace_bytes(None, 0, C.byref(b), 1, 2, C.byref(n)) == amp.OK and n.value == nb.value
+    assert L.amp_sens_block_workspace_bytes(None, 1, C.byref(b), 1, 2, C.byref(n)) == amp.ERR_INVALID_ARG
+    assert L.amp_sens_block_workspace_bytes(C.byref(d), 1, C.byref(b), 1, 3, C.byref(n)) == amp.ERR_BAD_FORMAT
+    fm = (C.c_int * 2)(amp.E4M3, amp.E5M2)
+    bad = (C.c_int * 2)(amp.E4M3, 7)
+    assert L.amp_sens_block(None, 0, None, 0, fm, 2, None, None, 0, None) == amp.OK
+    assert L.amp_sens_block(C.byref(d), 1, C.byref(b), 1, bad, 2, 4096, 4096, 1 << 20, None) == amp.ERR_BAD_FORMAT
+    assert L.amp_sens_block_workspace_bytes(C.byref(d), 1, C.byref(b), 1, 2, C.byref(n)) == amp.OK
+    assert L.amp_sens_block(C.byref(d), 1, C.byref(b), 1, fm, 2, 4096, 4096, n.value - 1, None) == amp.ERR_WORKSPACE_TOO_SMALL
+    assert L.amp_sens_block(C.byref(d), 1, C.byref(b), 1, fm, 2, None, 4096, n.value, None) == amp.ERR_INVALID_ARG
+    b.R = -1
+    assert L.amp_sens_block(C.byref(d), 1, C.byref(b), 1, fm, 2, 4096, 4096, n.value, None) == amp.ERR_INVALID_ARG
+    b.R = 3
+    d.scale_rows = 4
+    assert L.amp_sens_block(C.byref(d), 1, C.byref(b), 1, fm, 2, 4096, 4096, n.value, None) == amp.ERR_INVALID_ARG
+
+
 REPLAY_CASES = [
     # (layout, x offset in bytes from a 16-byte boundary, dx offset, batch_mul)
     (("dense", 1), 0, 0, 1), (("dense", 7), 0, 0, 1), (("dense", 8), 0, 0, 1),

@@ -316,7 +316,7 @@ def test_full_size_sampled_units(which):
     w = plan["make"]()
     torch.cuda.synchronize()
     say("%s at full size: %.1f M pairs; running the pass" % (which, w.pairs() / 1e6))
-    p = SensPass(w, DEV)
+    p = SensPass(w, DEV, one_call=True)                 # the launch configuration bench.py times
     p.run()
     res = p.results()
     fmts = w.fmts
@@ -377,6 +377,34 @@ def test_full_size_sampled_units(which):
     if len(fmts) == 2:
         for arr in res["linear"] + res["bgemm"]:
             assert np.all(arr[:, 0, 0] < arr[:, 1, 0]) and np.all(arr[:, 0, 2] < arr[:, 1, 2])
+
+
+@pytest.mark.parametrize("which", ["config1", "config4", "only_linears", "only_bgemms"])
+def test_one_call_for_linears_and_bgemms(which):
+    """amp_sens_block (one table, one set-up, BGEMM operands in the activations' launch) against the
+    oracle, and bit for bit against amp_sens_linear + amp_sens_bgemm on the same inputs."""
+    if which == "config4":
+        w = wl.config4("cpu", R=5, experts=6, C=512, K=176, tok_lo=1, tok_hi=40, n_bgemm=4, S=72, H=2, D=32)
+    else:
+        w = wl.config1("cpu", R=3, S=200, hidden=520, ffn=1384, H=4, D=64)
+    if which == "only_linears":
+        w.bgemms = []
+    if which == "only_bgemms":
+        w.linears = []
+    to_device(w)
+    say("one call, %s: %d linears, %d bgemms" % (which, len(w.linears), len(w.bgemms)))
+    one = SensPass(w, DEV, one_call=True)
+    one.run()
+    res_one = one.results()
+    parity.check_workload(w, res_one)
+    say("two calls, %s" % which)
+    two = SensPass(w, DEV)
+    two.run()
+    res_two = two.results()
+    for key in ("linear", "bgemm"):
+        assert len(res_one[key]) == len(res_two[key])
+        for a, b in zip(res_one[key], res_two[key]):
+            assert np.array_equal(parity.bits32(a), parity.bits32(b))
 
 
 def test_weight_kernel_and_streaming_kernel_agree():

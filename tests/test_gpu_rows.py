@@ -145,6 +145,16 @@ def test_rows_mixed_with_per_tensor_operands(modes):
     run_rows(wl.config1("cpu", R=2, S=136, hidden=256, ffn=520, H=2, D=64), **modes)
 
 
+def test_rows_one_call_for_linears_and_bgemms():
+    """Row scales through amp_sens_block: four classes of units in one call."""
+    w = wl.config1("cpu", R=3, S=200, hidden=520, ffn=1384, H=4, D=64)
+    p_one, res_one = run_rows(w, one_call=True)
+    p_two, res_two = run_rows(w)
+    for key in ("linear", "bgemm"):
+        for a, b in zip(res_one[key], res_two[key]):
+            assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+
+
 def test_rows_config3_reduced_single_format():
     run_rows(wl.config3("cpu", R=2, S=264, hidden=512, ffn=1800, Hq=8, Hkv=2, D=64))
 
