@@ -379,6 +379,63 @@ def test_full_size_sampled_units(which):
             assert np.all(arr[:, 0, 0] < arr[:, 1, 0]) and np.all(arr[:, 0, 2] < arr[:, 1, 2])
 
 
+def test_config2_block_at_full_size_every_unit():
+    """One whole block of the benchmark's workload in the benchmark's launch configuration: every
+    (op, operand, sample, format) sum against the oracle, and every scale bit for bit.  The oracle's
+    routine is single-threaded; the units are fanned over host threads (ctypes releases the GIL)."""
+    import os
+    from concurrent.futures import ThreadPoolExecutor
+    say("config2 block 17 at full size: generating on the GPU")
+    w = wl.config2_block(DEV, 17)
+    torch.cuda.synchronize()
+    say("running the pass over %.1f M pairs" % (w.pairs() / 1e6))
+    p = SensPass(w, DEV, one_call=True)
+    p.run()
+    res = p.results()
+    fmts = w.fmts
+    nl = len(w.linears)
+    units = []                                   # (tag, got [nf, 2] = (E, A) per format, x, dx, n, causal, scales)
+    for k, op in enumerate(w.linears):
+        say("  %s: copying to the host, scales" % op.name)
+        x, dx, wt, dw = wl.to_bits(op.x), wl.to_bits(op.dx), wl.to_bits(op.w).reshape(-1), wl.to_bits(op.dw)
+        sx = parity.check_scales(res, 2 * k, x.reshape(-1), fmts, None, op.name + ".x")
+        sw = parity.check_scales(res, 2 * k + 1, wt, fmts, None, op.name + ".w")
+        for r in range(op.R):
+            rows = slice(int(op.row_offsets[r]), int(op.row_offsets[r + 1]))
+            xb, gb = x[rows].reshape(-1), dx[rows].reshape(-1)
+            units.append(("%s.X r=%d" % (op.name, r), res["linear"][k][r][:, 0:2], xb, gb, xb.size, None, sx))
+            units.append(("%s.W r=%d" % (op.name, r), res["linear"][k][r][:, 2:4], wt, dw[r].reshape(-1), wt.size,
+                          None, sw))
+    for k, op in enumerate(w.bgemms):
+        say("  %s: copying to the host, scales" % op.name)
+        for side, (xt, dxt, lay) in enumerate(((op.x0, op.dx0, op.lay0), (op.x1, op.dx1, op.lay1))):
+            x, dx = wl.to_bits(xt), wl.to_bits(dxt)
+            c = None if lay[0] == "dense" else (lay[1], lay[2], lay[3])
+            sc = parity.check_scales(res, 2 * nl + 2 * k + side, x.reshape(-1), fmts,
+                                     None if c is None else (c[0] * op.R, c[1], c[2]),
+                                     "%s.x%d" % (op.name, side))
+            for r in range(op.R):
+                xb, gb = x[r].reshape(-1), dx[r].reshape(-1)
+                units.append(("%s.x%d r=%d" % (op.name, side, r), res["bgemm"][k][r][:, 2 * side:2 * side + 2], xb, gb,
+                              xb.size if c is None else 0, c, sc))
+
+    def one(u):
+        tag, got, xb, gb, n, c, sc = u
+        for fi, f in enumerate(fmts):
+            E, A = oracle.sens_operand(xb, gb, 1, n, sc[fi][0], sc[fi][1], f, causal=c)
+            parity.assert_sum_close(got[fi, 1], A[0], 0.0, tag + " A fmt=%d" % f)
+            parity.assert_sum_close(got[fi, 0], E[0], parity.E_FLOOR * A[0], tag + " E fmt=%d" % f)
+        return tag
+
+    threads = max(1, min(16, os.cpu_count() or 1))
+    say("  %d units on %d host threads" % (len(units), threads))
+    with ThreadPoolExecutor(threads) as ex:
+        for i, tag in enumerate(ex.map(one, units)):
+            if i % 32 == 31:
+                say("  ... %d units match, last %s" % (i + 1, tag))
+    assert len(units) == 16 * (2 * nl + 2 * len(w.bgemms))
+
+
 @pytest.mark.parametrize("which", ["config1", "config4", "only_linears", "only_bgemms"])
 def test_one_call_for_linears_and_bgemms(which):
     """amp_sens_block (one table, one set-up, BGEMM operands in the activations' launch) against the
