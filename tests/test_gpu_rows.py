@@ -155,6 +155,67 @@ def test_rows_one_call_for_linears_and_bgemms():
             assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
 
 
+def test_rows_config2_block_at_full_size_every_unit():
+    """One whole block of the benchmark's workload with one scale per row on every operand (per token,
+    per output channel, per row of the BGEMM operands), in the launch configuration
+    `bench.py --scales rows` times: every row's scales bit for bit and every (op, operand, sample,
+    format) sum against the oracle, fanned over host threads."""
+    import os
+    from concurrent.futures import ThreadPoolExecutor
+    say("rows, config2 block 23 at full size: generating on the GPU")
+    w = wl.config2_block(DEV, 23)
+    torch.cuda.synchronize()
+    p = RowSensPass(w, DEV, one_call=True)
+    p.run()
+    res = p.results()
+    fmts = w.fmts
+    units = []                  # (tag, got [nf, 2], x, dx, n_rows, row_len, causal_rows, scales of those rows)
+    for k, op in enumerate(w.linears):
+        say("  %s: copying to the host, scales of every row" % op.name)
+        x, dx, wt, dw = (wl.to_bits(t).reshape(-1) for t in (op.x, op.dx, op.w, op.dw))
+        rows = int(op.row_offsets[-1])
+        sx = parity._operand_scales(res, ("lin", k, 0), x, rows, op.C, fmts, None, op.name + ".x")
+        sw = parity._operand_scales(res, ("lin", k, 1), wt, op.K, op.C, fmts, None, op.name + ".w")
+        n = op.K * op.C
+        for r in range(op.R):
+            r0, r1 = int(op.row_offsets[r]), int(op.row_offsets[r + 1])
+            units.append(("%s.X r=%d" % (op.name, r), res["linear"][k][r][:, 0:2], x[r0 * op.C:r1 * op.C],
+                          dx[r0 * op.C:r1 * op.C], r1 - r0, op.C, None, [(a[r0:r1], b[r0:r1]) for a, b in sx]))
+            units.append(("%s.W r=%d" % (op.name, r), res["linear"][k][r][:, 2:4], wt, dw[r * n:(r + 1) * n],
+                          op.K, op.C, None, sw))
+    for k, op in enumerate(w.bgemms):
+        for side, (xt, dxt, lay) in enumerate(((op.x0, op.dx0, op.lay0), (op.x1, op.dx1, op.lay1))):
+            say("  %s operand %d: copying to the host, scales of every row" % (op.name, side))
+            xb, db = wl.to_bits(xt).reshape(-1), wl.to_bits(dxt).reshape(-1)
+            row_len = xt.shape[-1]
+            causal_rows = lay[2] if lay[0] == "causal" else None
+            n_rows = xb.size // row_len
+            sc = parity._operand_scales(res, ("bg", k, side), xb, n_rows, row_len, fmts, causal_rows,
+                                        "%s.x%d" % (op.name, side))
+            per = n_rows // op.R
+            for r in range(op.R):
+                a, b = r * per, (r + 1) * per
+                units.append(("%s.x%d r=%d" % (op.name, side, r), res["bgemm"][k][r][:, 2 * side:2 * side + 2],
+                              xb[a * row_len:b * row_len], db[a * row_len:b * row_len], per, row_len, causal_rows,
+                              [(s_[a:b], i_[a:b]) for s_, i_ in sc]))
+
+    def one(u):
+        tag, got, xb, gb, n_rows, row_len, causal_rows, sc = u
+        for fi, f in enumerate(fmts):
+            E, A = oracle.sens_operand_rows(xb, gb, n_rows, row_len, sc[fi][0], sc[fi][1], f, causal_rows=causal_rows)
+            parity.assert_sum_close(got[fi, 1], A, 0.0, tag + " A fmt=%d" % f)
+            parity.assert_sum_close(got[fi, 0], E, parity.E_FLOOR * A, tag + " E fmt=%d" % f)
+        return tag
+
+    threads = max(1, min(16, os.cpu_count() or 1))
+    say("  %d units on %d host threads" % (len(units), threads))
+    with ThreadPoolExecutor(threads) as ex:
+        for i, tag in enumerate(ex.map(one, units)):
+            if i % 32 == 31:
+                say("  ... %d units match, last %s" % (i + 1, tag))
+    assert len(units) == 16 * 2 * (len(w.linears) + len(w.bgemms))
+
+
 def test_rows_config3_reduced_single_format():
     run_rows(wl.config3("cpu", R=2, S=264, hidden=512, ffn=1800, Hq=8, Hkv=2, D=64))
 
