@@ -671,8 +671,13 @@ __device__ __forceinline__ void sens_body(const ResolvedUnit* __restrict__ runit
     }
 }
 
+// 7 waves per SIMD (72 VGPRs): at 8 (64 VGPRs) the compiler cannot keep a group's eight loads in
+// flight and issues them one or two at a time between the arithmetic.
+#ifndef AMPSENS_SENS_WAVES
+#define AMPSENS_SENS_WAVES 7
+#endif
 template <int NF, int F0, int F1>
-__global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) void sens_kernel(const ResolvedUnit* __restrict__ runits,
+__global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(AMPSENS_SENS_WAVES, AMPSENS_SENS_WAVES))) void sens_kernel(const ResolvedUnit* __restrict__ runits,
                                                    const ChunkRef* __restrict__ map,
                                                    uint32_t n_chunks, float* __restrict__ partials) {
     sens_body<SensCtx<NF, F0, F1>, NF>(runits, map, n_chunks, partials);
