@@ -97,8 +97,8 @@ class SensPass:
         self.absmax(stream)
         self.sens(stream)
 
-    def results(self):
-        """Synchronise and copy the small outputs to the host."""
+    def results(self, scales=True):
+        """Synchronise and copy the small outputs to the host (scales=False: the sums and flags only)."""
         torch.cuda.synchronize(self.device)
         lin = self.d_lin_out.cpu().numpy()
         bg = self.d_bg_out.cpu().numpy()
@@ -110,9 +110,11 @@ class SensPass:
         for R in self.bg_R:
             bg_ops.append(bg[o:o + R])
             o += R
-        return dict(amax=self.d_amax.cpu().numpy(), scale=self.d_scale.cpu().numpy(),
-                    inv=self.d_inv.cpu().numpy(), flags=self.d_flags.cpu().numpy(),
-                    linear=lin_ops, bgemm=bg_ops)
+        out = dict(flags=self.d_flags.cpu().numpy(), linear=lin_ops, bgemm=bg_ops)
+        if scales:
+            out.update(amax=self.d_amax.cpu().numpy(), scale=self.d_scale.cpu().numpy(),
+                       inv=self.d_inv.cpu().numpy())
+        return out
 
 
 class RowSensPass:
@@ -219,7 +221,8 @@ class RowSensPass:
         self.absmax(stream)
         self.sens(stream)
 
-    def results(self):
+    def results(self, scales=True):
+        """scales=False leaves the per-row scale tables (12–20 bytes per row) on the device."""
         torch.cuda.synchronize(self.device)
         lin = self.d_lin_out.cpu().numpy()
         bg = self.d_bg_out.cpu().numpy()
@@ -231,8 +234,10 @@ class RowSensPass:
         for R in self.bg_R:
             bg_ops.append(bg[o:o + R])
             o += R
-        return dict(amax=self.d_amax.cpu().numpy(), scale=self.d_scale.cpu().numpy(),
-                    inv=self.d_inv.cpu().numpy(), flags=self.d_flags.cpu().numpy(),
-                    row_amax=self.r_amax.cpu().numpy(), row_scale=self.r_scale.cpu().numpy(),
-                    row_inv=self.r_inv.cpu().numpy(), row_flags=self.r_flags.cpu().numpy(),
-                    where=dict(self.where), linear=lin_ops, bgemm=bg_ops)
+        out = dict(flags=self.d_flags.cpu().numpy(), row_flags=self.r_flags.cpu().numpy(),
+                   where=dict(self.where), linear=lin_ops, bgemm=bg_ops)
+        if scales:
+            out.update(amax=self.d_amax.cpu().numpy(), scale=self.d_scale.cpu().numpy(),
+                       inv=self.d_inv.cpu().numpy(), row_amax=self.r_amax.cpu().numpy(),
+                       row_scale=self.r_scale.cpu().numpy(), row_inv=self.r_inv.cpu().numpy())
+        return out
