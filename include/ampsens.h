@@ -72,7 +72,11 @@ typedef enum amp_status {
 
 typedef enum amp_fp8_format {
     AMP_FP8_E4M3 = 0,                /* OCP E4M3: bias 7, max 448, S.1111.111 = NaN, m_f = 3 */
-    AMP_FP8_E5M2 = 1                 /* OCP E5M2: bias 15, max 57344, IEEE-like, m_f = 2 */
+    AMP_FP8_E5M2 = 1,                /* OCP E5M2: bias 15, max 57344, IEEE-like, m_f = 2 */
+    AMP_FP8_FORMAT_INT_RANGE_ = 0x7FFFFFFF   /* not a format: gives the type the range of int, so that a
+                                                format or-ed with a flag (AMP_SCALE_POW2), or an invalid
+                                                value on its way to AMP_ERR_BAD_FORMAT, is a valid value
+                                                of the type in C++ as well */
 } amp_fp8_format_t;
 
 #define AMP_MAX_FORMATS 2
