@@ -157,18 +157,25 @@ def cpu_baseline(workload, target_seconds=15.0):
 
 
 def measured_traffic(kernel_label, workload_name):
-    """HBM bytes per launch of the named kernel from the committed rocprofv3 counter summary
+    """HBM bytes per launch of the named kernel from the committed rocprofv3 counter summaries
     (FETCH_SIZE and WRITE_SIZE runs of this same command, scaled by a plain copy of known size);
-    None if no summary covers the workload."""
-    kernel = (kernel_label or "").split(" ")[0]
-    path = os.path.join(ROOT, "profiles", "sens_kernels_%s_block.md" % workload_name)
+    None if no summary under profiles/ covers the kernel on this workload."""
+    kernel = (kernel_label or "").split(" ")[0].rstrip(",")
     tag = "traffic_bytes_per_launch(%s, %s) =" % (kernel, workload_name)
+    folder = os.path.join(ROOT, "profiles")
     try:
-        for line in open(path):
-            if line.startswith(tag):
-                return float(line.split("=")[1])
+        names = sorted(os.listdir(folder))
     except OSError:
-        pass
+        return None
+    for name in names:
+        if not name.endswith(".md"):
+            continue
+        try:
+            for line in open(os.path.join(folder, name)):
+                if line.startswith(tag):
+                    return float(line.split("=")[1])
+        except OSError:
+            pass
     return None
 
 
