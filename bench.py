@@ -188,6 +188,10 @@ def main():
     ap.add_argument("--scales", choices=["tensor", "rows"], default="tensor",
                     help="scale granularity: one per tensor (headline) or one per row (per token / per "
                          "output channel / per row of a BGEMM operand)")
+    ap.add_argument("--settle", type=float, default=6.0,
+                    help="seconds to leave the GPU idle between generating the inputs and the warm-up: for a "
+                         "few seconds after a process has freed tens of GB of device memory every kernel on "
+                         "the device streams about 3 %% slower")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -228,6 +232,9 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    if args.settle > 0:
+        torch.cuda.synchronize()
+        time.sleep(args.settle)
     for _ in range(args.warmup):
         p.run()
     # the warm-up ends like the timed region does: read-back, epilogue, selection (the first
@@ -324,7 +331,7 @@ def main():
                    "bytes_per_step": abs_bytes_step},
         "select": tail,
         "timed_region": {"device_ms": (t_dev - t0) * 1e3, "host_enqueue_ms": (t_enq - t0) * 1e3,
-                         "host_tail_ms": (t1 - t_dev) * 1e3},
+                         "host_tail_ms": (t1 - t_dev) * 1e3, "idle_before_warmup_s": args.settle},
     }
     if not args.no_cpu_baseline:
         log("timing the CPU oracle on a bounded sample")
