@@ -20,6 +20,8 @@
 #include "internal.h"
 #include "walk.h"
 
+#include <type_traits>
+
 #ifndef AMPSENS_W_LOAD
 #define AMPSENS_W_LOAD 8
 #endif
@@ -761,6 +763,11 @@ __global__ __launch_bounds__(kWG) void sens_w_kernel(const WGroup* __restrict__ 
         int pk = 0;
         RowCursor cur;
         if constexpr (ROWS) cur.begin(base, tid * kVec, kWG * kVec, u0.cols);
+        // A full batch (the usual case) gets a copy of the loop without the per-member tests, so that
+        // the compiler can wait for the gradient loads one by one instead of for all of them.
+        auto steps = [&](auto full_batch) {
+        constexpr bool kFull = decltype(full_batch)::value;
+        const int nbe = kFull ? kWBatch : nb;
 #pragma unroll 1
         for (int s = 0; s < kChunkVecs / kWG; ++s) {
             const int v = s * kWG + tid;
@@ -776,7 +783,7 @@ __global__ __launch_bounds__(kWG) void sens_w_kernel(const WGroup* __restrict__ 
             u32x4 gr[kWLoad];
 #pragma unroll
             for (int k = 0; k < kWLoad; ++k)
-                if (k < nb) gr[k] = load128<true>(reinterpret_cast<gptr128_t>(gp[k] + base) + v);
+                if (k < nbe) gr[k] = load128<true>(reinterpret_cast<gptr128_t>(gp[k] + base) + v);
             // x and the quantisation error of every format, once
             const uint32_t w4[4] = {xw.x, xw.y, xw.z, xw.w};
             float xv[kVec], ev[NF][kVec];
@@ -810,10 +817,10 @@ __global__ __launch_bounds__(kWG) void sens_w_kernel(const WGroup* __restrict__ 
 #pragma unroll
                 for (int kk = 0; kk < kWLoad; ++kk) {
                     const int k = k0 + kk;
-                    if (k < nb) {
+                    if (k < nbe) {
                         const uint32_t g4[4] = {gr[kk].x, gr[kk].y, gr[kk].z, gr[kk].w};
                         // the slot is free: fetch the gradient of sample k + kWLoad into it
-                        if (k + kWLoad < kWBatch && k + kWLoad < nb)
+                        if (k + kWLoad < kWBatch && k + kWLoad < nbe)
                             gr[kk] = load128<true>(reinterpret_cast<gptr128_t>(gp[(k + kWLoad) % kWBatch] + base) + v);
 #pragma unroll
                         for (int i = 0; i < 4; ++i) {
@@ -832,6 +839,8 @@ __global__ __launch_bounds__(kWG) void sens_w_kernel(const WGroup* __restrict__ 
                 }
             }
         }
+        };
+        if (nb == kWBatch) steps(std::true_type{}); else steps(std::false_type{});
 #pragma unroll
         for (int k = 0; k < kWBatch; ++k) {
             if (k < nb) {
