@@ -1,63 +1,55 @@
 """TEST INFRASTRUCTURE.  Plain Python statements of the host-side steps that sit next to the hot
-path: the partition of a computation DAG into sequential sub-graphs (Appendix B, Algorithm 2 of
-the paper) taken step by step in the paper's order, and the Prefix / Random baseline strategies
-of Sec. 3.1.  Imported by tests only; shares nothing with the library.
+path: the partition of a computation DAG into sequential sub-graphs (Appendix B of the paper) and
+the Prefix / Random baseline strategies of Sec. 3.1.  Imported by tests only; shares nothing with
+the library.
 
-Readings of Algorithm 2 where the printed listing is loose:
-  * "Run BFS and denote the longest path from the start to each vertex": a longest path needs the
-    vertices in topological order, so path lengths are computed that way.
-  * The frontier A is a set; the vertices picked for expansion in one sweep are those that were in
-    A when the sweep began (the listing mutates A while iterating over it); next[v'] is added
-    vertex by vertex.
+The partition is written from what a sequential sub-graph is (Sec. 2.3.1 and Appendix B: a region
+with a single entry and a single exit, so that everything before it is finished when it starts and
+everything after it waits for its last vertex), not from the appendix's listing: a vertex closes a
+group iff every path from the start vertex to the sink passes through it, which is decided here by
+brute force (take the vertex out and see whether the sink can still be reached); every other vertex
+belongs to the first closing vertex it leads to.
 """
 
 
-def longest_paths(n, edges):
-    succ = [[] for _ in range(n)]
-    indeg = [0] * n
-    for a, b in edges:
-        succ[a].append(b)
-        indeg[b] += 1
-    start = [v for v in range(n) if indeg[v] == 0]
-    assert len(start) == 1
-    order, plen = [start[0]], [0] * n
-    deg = list(indeg)
-    for v in order:
+def _reachable(succ, src, banned=None):
+    """Vertices reachable from src (src included) without stepping on `banned`."""
+    seen = {src}
+    stack = [src]
+    while stack:
+        v = stack.pop()
         for w in succ[v]:
-            plen[w] = max(plen[w], plen[v] + 1)
-            deg[w] -= 1
-            if deg[w] == 0:
-                order.append(w)
-    assert len(order) == n, "cycle"
-    return start[0], succ, plen
+            if w != banned and w not in seen:
+                seen.add(w)
+                stack.append(w)
+    return seen
 
 
 def partition_sequential(n, edges, quantizable=None):
-    """Returns the list of groups (lists of vertices, quantisable ones only, in no particular order)."""
-    start, succ, plen = longest_paths(n, edges)
-    ends = [v for v in range(n) if not succ[v]]
-    assert len(ends) == 1
-    end = ends[0]
-    groups = []
-    v = start
-    while v != end:
-        group = set()
-        cur_len = plen[v] + 1
-        frontier = set(succ[v])
-        while len(frontier) > 1:
-            for w in sorted(frontier):                       # the sweep's snapshot of A
-                if plen[w] <= cur_len:
-                    frontier.discard(w)
-                    group.add(w)
-                    frontier.update(succ[w])
-            cur_len += 1
-        v = frontier.pop()
-        group.add(v)
-        if quantizable is not None:
-            group = {w for w in group if quantizable[w]}
-        if group:
-            groups.append(sorted(group))
-    return groups
+    """Returns the list of groups (sorted lists of vertices, quantisable ones only) in execution order."""
+    succ = [[] for _ in range(n)]
+    has_pred = [False] * n
+    for a, b in edges:
+        succ[a].append(b)
+        has_pred[b] = True
+    starts = [v for v in range(n) if not has_pred[v]]
+    sinks = [v for v in range(n) if not succ[v]]
+    assert len(starts) == 1 and len(sinks) == 1
+    start, sink = starts[0], sinks[0]
+    reach = [_reachable(succ, v) for v in range(n)]
+    # closing vertices: without them the sink is cut off from the start (the sink itself is one)
+    closing = [v for v in range(n)
+               if v != start and (v == sink or sink not in _reachable(succ, start, banned=v))]
+    # every path meets all of them, so they are totally ordered: c comes before c' iff c leads to c'
+    closing.sort(key=lambda c: sum(1 for c2 in closing if c2 in reach[c]), reverse=True)
+    groups = [[] for _ in closing]
+    for v in range(n):
+        if v == start:
+            continue
+        first = next(i for i, c in enumerate(closing) if c in reach[v])
+        if quantizable is None or quantizable[v]:
+            groups[first].append(v)
+    return [sorted(g) for g in groups if g]
 
 
 def select_ordered(n_choices, gain, mse, budget, order=None):

@@ -1,6 +1,7 @@
 """Host-side rows next to the hot path: partition into sequential sub-graphs (Appendix B), gain
 formulas (Sec. 2.3.2, 2.3.3) and the Prefix / Random baselines (Sec. 3.1).  The library's C++
-(dominator-tree formulation) is compared with a step-by-step Python statement of Algorithm 2, and
+(dominator-tree formulation) is compared with a brute-force Python statement of what a sequential
+sub-graph is (take a vertex out; if the sink is cut off from the start, the vertex closes a group), and
 both are pinned to the partition the paper shows for a Llama-3 layer."""
 import numpy as np
 import pytest
@@ -93,7 +94,7 @@ def random_dag(rng, n):
 
 
 @pytest.mark.parametrize("seed", range(60))
-def test_partition_matches_algorithm_2_on_random_dags(seed):
+def test_partition_matches_the_brute_force_definition_on_random_dags(seed):
     rng = np.random.default_rng(seed)
     n = int(rng.integers(2, 40))
     edges = random_dag(rng, n)
