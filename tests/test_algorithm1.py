@@ -121,6 +121,63 @@ def test_curve_is_monotone_and_ip_dominates_the_ordered_baselines():
         assert gi >= gp - 1e-9 and gi >= gr - 1e-9
 
 
+def check_selection_against_oracle(sums, mean_g2, groups, gains, names):
+    # the same sums through the oracle's epilogue and enumeration: layer loss MSE, group tables
+    # (column p = base-(F+1) digits of p, first layer least significant, written out here), the
+    # optimum of eq. (ip) and the per-op formats it stands for
+    F = len(FMTS) + 1
+    for statistic in ("measured", "model"):
+        d_layer = {}
+        for n in names:
+            s64 = np.asarray(sums[n], dtype=np.float64)
+            if statistic == "model":
+                s_l = oracle.layer_sensitivity(s64[:, 0, 1], s64[:, 0, 3])
+                d_layer[n] = [s_l * oracle.alpha(oracle.fp8_mantissa_bits(f)) for f in FMTS]
+            else:
+                d_layer[n] = [float(np.mean(s64[:, fi, 0] + s64[:, fi, 2])) for fi in range(len(FMTS))]
+            got = a1.layer_loss_mse(sums, FMTS, statistic)[n]
+            assert np.allclose(got, d_layer[n], rtol=1e-12, atol=0.0), (statistic, n)
+        n_choices, G, D = [], [], []
+        for g in groups:
+            n_choices.append(F ** len(g))
+            for digits in itertools.product(range(F), repeat=len(g)):       # last layer fastest ...
+                digits = digits[::-1]                                        # ... so reverse: layer 0 fastest
+                D.append(sum(0.0 if dg == 0 else d_layer[n][dg - 1] for n, dg in zip(g, digits)))
+                G.append(sum(0.0 if dg == 0 else gains[n][dg - 1] for n, dg in zip(g, digits)))
+        # thresholds placed inside the range of this model's statistics so that the selection is mixed
+        total = sum(max(d_layer[n]) for n in names)
+        mixed = 0
+        for frac in (0.03, 0.06, 0.12, 0.2, 0.7):
+            tau = float(np.sqrt(frac * total / mean_g2))
+            cfg, info = a1.select(sums, mean_g2, tau, groups, gains, FMTS, statistic=statistic)
+            rc, choice, tg, td = oracle.select_pareto(n_choices, G, D, info["budget"])
+            assert rc == 0
+            assert info["total_gain"] == pytest.approx(tg, rel=1e-9), (statistic, frac)
+            assert info["total_mse"] <= info["budget"] * (1 + 1e-12)
+            # what decode() says the chosen columns mean, priced with the oracle-side per-layer numbers
+            cfg_gain = sum(gains[n][FMTS.index(f)] for n, f in cfg.items() if f is not None)
+            cfg_mse = sum(d_layer[n][FMTS.index(f)] for n, f in cfg.items() if f is not None)
+            assert cfg_gain == pytest.approx(tg, rel=1e-9) and cfg_mse <= info["budget"] * (1 + 1e-9)
+            if np.array_equal(choice, info["choice"]):
+                want_cfg = {}
+                for g, pcol in zip(groups, choice):
+                    for i, n in enumerate(g):
+                        dg = (int(pcol) // F ** i) % F
+                        want_cfg[n] = None if dg == 0 else FMTS[dg - 1]
+                assert dict(cfg) == want_cfg
+                assert info["total_mse"] == pytest.approx(td, rel=1e-9)
+            kinds = set(cfg.values())
+            mixed += len(kinds) > 1
+        assert mixed >= 2, "the thresholds did not produce mixed configurations"
+
+
+def test_selection_matches_the_oracle_on_synthetic_sums():
+    sums = fake_sums(7)
+    groups = a1.partition(VERTICES, LLAMA_EDGES, quantizable=NAMES)
+    gains = a1.theoretical_gains(shapes(), 2, "time")
+    check_selection_against_oracle(sums, 1.0, groups, gains, NAMES)
+
+
 @pytest.mark.gpu
 def test_gpu_algorithm1_on_a_small_model():
     import torch
@@ -159,6 +216,7 @@ def test_gpu_algorithm1_on_a_small_model():
     assert prev == pytest.approx(full, rel=1e-12)                          # tau = 10: everything in FP8
     cfg0, info0 = a1.select(sums, mean_g2, 0.0, groups, gains, FMTS)
     assert info0["total_gain"] == 0.0
+    check_selection_against_oracle(sums, mean_g2, groups, gains, names)
     # the model statistic (s alpha) and the measured one order the formats the same way: E4M3 costs less
     for n in names:
         assert a1.layer_loss_mse(sums, FMTS, "model")[n][0] < a1.layer_loss_mse(sums, FMTS, "model")[n][1]
