@@ -37,11 +37,14 @@
  *     including the workspace; the library allocates no device memory and frees nothing.
  *   - Device calls validate their arguments on the host first (no launch happens on an error),
  *     then enqueue on the caller's stream (a hipStream_t passed as void*, NULL = the null
- *     stream).  They do not wait for the GPU.  Each call copies a small descriptor table into the
- *     workspace with hipMemcpyAsync from a pinned host buffer of the library's own (host memory,
- *     created on first use, at most 32 per device, reused when their copy has completed, never freed).
- *     Only when all 32 are still in flight does a call wait for the oldest copy; only when pinned
- *     memory cannot be had does it copy from pageable memory and wait for that copy.
+ *     stream).  They launch kernels and nothing else: no device or pinned memory is allocated or
+ *     freed, no copy engine is used, nothing waits for the GPU, and nothing of the host arguments
+ *     is referenced after the call returns (the small descriptor table of a call travels to the
+ *     head of the workspace as kernel arguments, 3840 bytes per launch).  Such calls may be
+ *     recorded into a HIP graph by stream capture.
+ *   - Every device call is a set-up (host work per op, the table, the chunk map) followed by a run
+ *     (kernel launches only).  Callers that repeat a call on the same buffers keep the set-up:
+ *     amp_*_setup fills a caller-owned amp_plan_t, amp_run replays it (see "plans" below).
  *   - Pointers need only 2-byte alignment; 16-byte aligned buffers take the fast path
  *     (128-bit loads).  Results do not depend on the launch grid.
  *   - Every call returns amp_status_t.  After AMP_ERR_DEVICE, amp_last_device_error() gives
@@ -237,6 +240,12 @@ amp_status_t amp_sens_block(const amp_linear_desc_t* linears /* host array */, i
 amp_status_t amp_layer_loss_mse(const float* sums, int R, const amp_fp8_format_t* fmts, int n_fmts,
                                 double* s_layer, double* d_model, double* d_measured);
 
+/* The loss-MSE budget of eq. (ip) (Sec. 2.1): tau^2 E[g^2], with tau < 1 the threshold on the
+ * normalised RMSE and E[g^2] the mean of the squared losses g^r of the n calibration samples
+ * (host array; NaN for n < 1). */
+double amp_loss_second_moment(const double* losses, int n);
+double amp_mse_budget(double tau, double mean_g2);
+
 /* alpha_f = 2^(-2 m)/12 for a float format with m mantissa bits (Sec. 2.2). */
 double amp_alpha(int mantissa_bits);
 
@@ -288,22 +297,59 @@ amp_status_t amp_select_ordered(int J, const int32_t* n_choices, const double* g
                                 double mse_budget, const int32_t* order, int32_t* choice,
                                 double* total_gain, double* total_mse);
 
+/* ---- plans: set-up once, run many times -----------------------------------------------------------
+ * The calibration loop of the paper's Algorithm 1 (step "sensitivity calibration") visits the same
+ * operand buffers sample after sample; the set-up of a call depends on pointers and shapes only.
+ * amp_*_setup does everything the one-shot call of the same name does except the pass itself, on
+ * `stream`, and records what a run needs in *plan (plain data, caller-owned, may be copied; it
+ * holds the workspace and output pointers given here).  amp_run enqueues the pass: it reads the
+ * scales (sensitivity pass) or the operands (absmax) as they are when it executes, so an absmax
+ * run followed by a sensitivity run on the same stream is one calibration step.  The workspace
+ * must stay untouched between the set-up and the last run, runs of one plan must not overlap, and
+ * a run must be ordered after the set-up (same stream, or an event).  A call without work gives a
+ * plan whose run does nothing.  amp_sens_block_setup takes the flags below.
+ * amp_plan_limit_grid caps the number of workgroups of the plan's persistent grids (0 = as many as
+ * are resident), e.g. to leave compute units to a concurrent forward pass; results do not change. */
+typedef struct amp_plan { uint64_t opaque[64]; } amp_plan_t;
+
+#define AMP_PLAN_STREAM_WEIGHTS 1u   /* read W with every sample's gradient instead of once per batch of
+                                        8 resident gradients (same sums, bit for bit) */
+#define AMP_PLAN_INTERLEAVE(n) ((uint32_t)((n) & 0xFF) << 8)   /* tuning: chunks of one reader of a shared W
+                                        that sit next to each other in the schedule (0 = default 8) */
+
+amp_status_t amp_absmax_scale_setup(const amp_tensor_t* tensors /* host array */, int n_tensors,
+                                    const amp_fp8_format_t* fmts /* host */, int n_fmts,
+                                    float* d_amax, float* d_scale, float* d_inv, uint32_t* d_flags,
+                                    void* workspace, size_t workspace_bytes, void* stream, amp_plan_t* plan);
+amp_status_t amp_absmax_scale_rows_setup(const amp_tensor_t* tensors /* host array */, int n_tensors,
+                                         const amp_fp8_format_t* fmts /* host */, int n_fmts,
+                                         float* d_amax, float* d_scale, float* d_inv, uint32_t* d_flags,
+                                         void* workspace, size_t workspace_bytes, void* stream,
+                                         amp_plan_t* plan);
+amp_status_t amp_sens_block_setup(const amp_linear_desc_t* linears /* host array */, int n_linears,
+                                  const amp_bgemm_desc_t* bgemms /* host array */, int n_bgemms,
+                                  const amp_fp8_format_t* fmts /* host */, int n_fmts, float* d_out,
+                                  void* workspace, size_t workspace_bytes, uint32_t flags, void* stream,
+                                  amp_plan_t* plan);
+amp_status_t amp_plan_limit_grid(amp_plan_t* plan, int max_workgroups);
+amp_status_t amp_run(const amp_plan_t* plan, void* stream);
+
 /* ---- optional kernel timing ---------------------------------------------------------------
  * amp_profile_enable(n > 0) creates n pairs of HIP events on the current device; from then on
- * every launch of a fused sensitivity kernel records one pair on the call's stream, immediately
- * before and after the kernel, until n launches have been recorded.  An amp_sens_linear call
- * launches the weight kernel (W read once per batch of samples) if it has whole weight chunks for
- * it, then the streaming kernel for everything else; an amp_sens_bgemm call launches the streaming
- * kernel; an amp_sens_block call launches what amp_sens_linear would, with the BGEMM operands in the
- * streaming launches.  Operands with one scale per row have kernels of their own: a call then launches up to two
- * weight kernels (per-tensor, per-channel) and up to four streaming kernels (one scale per tensor;
- * long or causal rows; short power-of-two rows; other shapes), in that order, each only if it has
- * work.  amp_profile_read waits for the recorded events, writes the elapsed milliseconds of each
+ * every launch of a fused sensitivity kernel records one pair on the run's stream, immediately
+ * before and after the kernel, until n launches have been recorded.  A sensitivity run launches
+ * the weight kernel (W read once per batch of samples) if it has whole weight chunks for it, then
+ * the streaming kernel for everything else (activations, BGEMM operands, ragged ends).  Operands
+ * with one scale per row have kernels of their own: a run then launches up to two weight kernels
+ * (per-tensor, per-channel) and up to four streaming kernels (one scale per tensor; long or
+ * causal rows; short power-of-two rows; other shapes), in that order, each only if it has work.
+ * amp_profile_read waits for the recorded events, writes the elapsed milliseconds of each
  * launch to ms[0..*n_launches) and, if not NULL, to pairs[] the number of element pairs the
  * launch covered and to bytes[] the operand bytes it is defined to read (4 per pair for the
  * streaming kernel; for the weight kernel 2 per pair plus W's bytes once per batch of samples)
  * (host arrays; capacity must be >= the n given to enable), and resets the count.
- * amp_profile_enable(0) destroys the events.  Not thread-safe; meant for benchmarks. */
+ * amp_profile_enable(0) destroys the events.  Meant for benchmarks: do not enable it around a
+ * stream capture, and do not call enable / read while runs are being enqueued from other threads. */
 amp_status_t amp_profile_enable(int max_launches);
 amp_status_t amp_profile_read(float* ms, uint64_t* pairs, uint64_t* bytes, int capacity, int* n_launches);
 

@@ -18,6 +18,12 @@ MAX_FORMATS = 2
 SCALE_POW2 = 0x100         # or-ed into a format for the absmax calls: power-of-two scales
 ROWS_OPERAND0 = 1          # one scale per row of X (linear) / X0 (BGEMM)
 ROWS_OPERAND1 = 2          # one scale per row of W (linear) / X1 (BGEMM)
+PLAN_STREAM_WEIGHTS = 1    # amp_sens_block_setup flag: read W with every sample's gradient
+
+
+def plan_interleave(n):
+    """amp_sens_block_setup flag: chunks of one reader of a shared W next to each other in the schedule."""
+    return (int(n) & 0xFF) << 8
 
 OK, ERR_INVALID_ARG, ERR_BAD_FORMAT, ERR_WORKSPACE_TOO_SMALL, ERR_NONFINITE_INPUT, ERR_DEVICE, \
     ERR_INFEASIBLE, ERR_TOO_LARGE = range(8)
@@ -30,6 +36,11 @@ class AmpError(RuntimeError):
         if status == ERR_DEVICE:
             msg += " (hipError_t %d)" % lib().amp_last_device_error()
         super().__init__("%s: %s" % (where, msg))
+
+
+class Plan(C.Structure):
+    """amp_plan_t: what a run needs, filled by the *_setup calls; keeps the tensors it points into alive."""
+    _fields_ = [("opaque", C.c_uint64 * 64)]
 
 
 class Layout(C.Structure):
@@ -89,6 +100,15 @@ def lib():
                                      C.c_void_p, C.c_size_t, C.c_void_p]
         L.amp_sens_block_workspace_bytes.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int,
                                                      C.POINTER(C.c_size_t)]
+        setup_tail = [C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(Plan)]
+        for name in ("amp_absmax_scale_setup", "amp_absmax_scale_rows_setup"):
+            getattr(L, name).argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p,
+                                         C.c_void_p, C.c_void_p] + setup_tail
+        L.amp_sens_block_setup.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_int,
+                                           C.c_void_p, C.c_void_p, C.c_size_t, C.c_uint32, C.c_void_p,
+                                           C.POINTER(Plan)]
+        L.amp_plan_limit_grid.argtypes = [C.POINTER(Plan), C.c_int]
+        L.amp_run.argtypes = [C.POINTER(Plan), C.c_void_p]
         _lib = L
     return _lib
 
@@ -242,6 +262,66 @@ def amp_sens_block(linears, bgemms, fmts, d_out, workspace, stream=None):
                                 len(bgemms), f, nf, _ptr(d_out), _ptr(workspace),
                                 workspace.numel() * workspace.element_size(), _stream(stream)),
            "amp_sens_block")
+
+
+def amp_absmax_scale_setup(tensors, fmts, d_amax, d_scale, d_inv, d_flags, workspace, stream=None):
+    """The set-up half of amp_absmax_scale; returns the Plan for amp_run."""
+    f, nf = _fmts(fmts)
+    plan = Plan()
+    _check(lib().amp_absmax_scale_setup(_array(Tensor, tensors), len(tensors), f, nf, _ptr(d_amax), _ptr(d_scale),
+                                        _ptr(d_inv), _ptr(d_flags), _ptr(workspace),
+                                        workspace.numel() * workspace.element_size(), _stream(stream),
+                                        C.byref(plan)), "amp_absmax_scale_setup")
+    plan._keep = (tensors, d_amax, d_scale, d_inv, d_flags, workspace)
+    return plan
+
+
+def amp_absmax_scale_rows_setup(tensors, fmts, d_amax, d_scale, d_inv, d_flags, workspace, stream=None):
+    f, nf = _fmts(fmts)
+    plan = Plan()
+    _check(lib().amp_absmax_scale_rows_setup(_array(Tensor, tensors), len(tensors), f, nf, _ptr(d_amax),
+                                             _ptr(d_scale), _ptr(d_inv), _ptr(d_flags), _ptr(workspace),
+                                             workspace.numel() * workspace.element_size(), _stream(stream),
+                                             C.byref(plan)), "amp_absmax_scale_rows_setup")
+    plan._keep = (tensors, d_amax, d_scale, d_inv, d_flags, workspace)
+    return plan
+
+
+def amp_sens_block_setup(linears, bgemms, fmts, d_out, workspace, flags=0, stream=None):
+    """The set-up half of amp_sens_block (flags: PLAN_STREAM_WEIGHTS, plan_interleave(n)); returns the Plan."""
+    f, nf = _fmts(fmts)
+    plan = Plan()
+    _check(lib().amp_sens_block_setup(_array(LinearDesc, linears), len(linears), _array(BgemmDesc, bgemms),
+                                      len(bgemms), f, nf, _ptr(d_out), _ptr(workspace),
+                                      workspace.numel() * workspace.element_size(), int(flags), _stream(stream),
+                                      C.byref(plan)), "amp_sens_block_setup")
+    plan._keep = (linears, bgemms, d_out, workspace)
+    return plan
+
+
+def amp_plan_limit_grid(plan, max_workgroups):
+    _check(lib().amp_plan_limit_grid(C.byref(plan), int(max_workgroups)), "amp_plan_limit_grid")
+
+
+def amp_run(plan, stream=None):
+    _check(lib().amp_run(C.byref(plan), _stream(stream)), "amp_run")
+
+
+def amp_loss_second_moment(losses):
+    """E[g^2] over the samples' losses."""
+    losses = np.ascontiguousarray(losses, dtype=np.float64)
+    f = lib().amp_loss_second_moment
+    f.restype = C.c_double
+    f.argtypes = [C.c_void_p, C.c_int]
+    return f(losses.ctypes.data_as(C.c_void_p), int(losses.size))
+
+
+def amp_mse_budget(tau, mean_g2):
+    """tau^2 E[g^2], the loss-MSE budget of eq. (ip)."""
+    f = lib().amp_mse_budget
+    f.restype = C.c_double
+    f.argtypes = [C.c_double, C.c_double]
+    return f(float(tau), float(mean_g2))
 
 
 def amp_alpha(mantissa_bits):

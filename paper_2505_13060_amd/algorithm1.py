@@ -14,7 +14,7 @@ from collections import OrderedDict
 
 import numpy as np
 
-from . import (amp_group_tables, amp_layer_loss_mse, amp_memory_gain, amp_partition_sequential,
+from . import (amp_group_tables, amp_layer_loss_mse, amp_memory_gain, amp_mse_budget, amp_partition_sequential,
                amp_select_ordered, amp_select_subgraphs, amp_time_gain_macs)
 
 
@@ -95,7 +95,7 @@ def select(sums, mean_g2, tau, groups, gains, fmts, statistic="measured", strate
     order as the baselines of Sec. 3.1 do.  Returns (config {op: format or None}, info)."""
     mse = layer_loss_mse(sums, fmts, statistic)
     n_choices, G, D = build_tables(groups, mse, gains)
-    budget = float(tau) ** 2 * float(mean_g2)
+    budget = amp_mse_budget(tau, mean_g2)
     if strategy == "ip":
         choice, total_gain, total_mse = amp_select_subgraphs(n_choices, G, D, budget)
     else:
@@ -111,7 +111,7 @@ def tradeoff_curve(sums, mean_g2, taus, groups, gains, fmts, statistic="measured
     n_choices, G, D = build_tables(groups, mse, gains)
     rows = []
     for tau in taus:
-        budget = float(tau) ** 2 * float(mean_g2)
+        budget = amp_mse_budget(tau, mean_g2)
         if strategy == "ip":
             _, tg, td = amp_select_subgraphs(n_choices, G, D, budget)
         else:

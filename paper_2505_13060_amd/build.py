@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libampsens.so")
 SOURCES = ["kernels.hip", "api.hip", "select.cpp", "graph.cpp"]
-HEADERS = ["internal.h", "walk.h", os.path.join("..", "..", "include", "ampsens.h")]
+HEADERS = ["internal.h", "walk.h", "table.h", os.path.join("..", "..", "include", "ampsens.h")]
 
 # -ffp-contract=off: the multiply that decides an FP8 code must not fuse with anything; wanted
 #   fusions are written as fmaf.

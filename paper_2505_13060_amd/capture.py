@@ -24,6 +24,7 @@ from collections import OrderedDict
 import numpy as np
 import torch
 
+from . import amp_loss_second_moment
 from . import workloads as wl
 
 
@@ -217,7 +218,7 @@ class ResidentSink:
     def finalize(self):
         """{op name: float32 sums [R, n_fmts, 4] = (E_0, A_0, E_1, A_1)}, E[g^2]."""
         out, self.raw = _run(self.workload(), self.device)
-        return out, float(np.mean(np.square(self.losses)))
+        return out, amp_loss_second_moment(self.losses)
 
 
 class StreamSink:
@@ -238,4 +239,4 @@ class StreamSink:
 
     def finalize(self):
         return (OrderedDict((n, np.stack(v)) for n, v in self.sums.items()),
-                float(np.mean(np.square(self.losses))))
+                amp_loss_second_moment(self.losses))

@@ -142,10 +142,18 @@ int sens_resident_blocks(int n_fmts, int fmt0, int fmt1, int cls, int cus);
 int absmax_resident_blocks(int cus);
 int absmax_rows_resident_blocks(int cus);
 
-// Units with kUnitRowScale keep their scale pointers (row tables); the others get values.
+// Host memory -> device memory through kernel arguments, one launch per piece; d_dst is 16-byte
+// aligned and has room for `bytes` rounded up to 16.  The source is read before the call returns.
+struct TablePiece { uint4 w[240]; };                   // 3840 bytes: fits the kernel-argument segment
+hipError_t launch_table_write(const void* host_src, size_t bytes, void* d_dst, hipStream_t stream);
+// Once per set-up: unit records for the streaming kernels (scales not yet filled in) and the chunk map.
 hipError_t launch_prepare(const WorkUnit* d_units, const uint32_t* d_chunk_begin,
                           const UnitSchedule* d_schedule, uint32_t n_units, uint32_t n_chunks,
-                          int n_fmts, ResolvedUnit* d_runits, ChunkRef* d_map, hipStream_t stream);
+                          ResolvedUnit* d_runits, ChunkRef* d_map, hipStream_t stream);
+// Every run: units with one scale per tensor get the values their scale pointers hold now; units
+// with kUnitRowScale keep their table pointers.
+hipError_t launch_resolve(const WorkUnit* d_units, uint32_t n_units, int n_fmts, ResolvedUnit* d_runits,
+                          hipStream_t stream);
 hipError_t launch_absmax(const ResolvedUnit* d_runits, const ChunkRef* d_map, uint32_t n_chunks,
                          uint32_t* d_partial_max, int grid, hipStream_t stream);
 hipError_t launch_absmax_finalize(const uint32_t* d_chunk_begin, const uint32_t* d_partial_max,

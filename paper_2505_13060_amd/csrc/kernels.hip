@@ -20,6 +20,7 @@
 #include "internal.h"
 #include "walk.h"
 
+#include <cstring>
 #include <type_traits>
 
 #ifndef AMPSENS_W_LOAD
@@ -133,12 +134,22 @@ __device__ __forceinline__ u32x4 keep_leading(u32x4 v, int tail) {
     return r;
 }
 
-// ---- prepare: resolve scales, build the chunk map ---------------------------------------------
+// ---- descriptor tables arrive as kernel arguments ------------------------------------------------
+// A call's table (a few KB to a few hundred KB of unit records) is cut into pieces that travel as
+// the by-value argument of this kernel: no staging buffer, no copy engine, nothing that outlives
+// the call on the host, and a launch that a HIP graph can hold by value.
+__global__ __launch_bounds__(kWG) void table_write_kernel(TablePiece piece, uint4* __restrict__ dst,
+                                                          uint32_t n_words) {
+    for (uint32_t i = threadIdx.x; i < n_words; i += kWG) dst[i] = piece.w[i];
+}
 
+// ---- prepare: the static part of a call (once per set-up) ----------------------------------------
+// Unit records in the form the streaming kernels read, and the chunk map: for every schedule
+// position its unit, its index inside that unit and its partial slot, so that no kernel searches.
 __global__ __launch_bounds__(kWG) void prepare_kernel(const WorkUnit* __restrict__ units,
                                                       const uint32_t* __restrict__ chunk_begin,
                                                       const UnitSchedule* __restrict__ schedule,
-                                                      uint32_t n_units, uint32_t n_chunks, int n_fmts,
+                                                      uint32_t n_units, uint32_t n_chunks,
                                                       ResolvedUnit* __restrict__ runits,
                                                       ChunkRef* __restrict__ map) {
     const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -151,11 +162,7 @@ __global__ __launch_bounds__(kWG) void prepare_kernel(const WorkUnit* __restrict
             r.row_inv = u.inv;
             r.row_scale = u.scale;
         } else {
-            for (int f = 0; f < kMaxFormats; ++f) {
-                const bool have = f < n_fmts && u.inv != nullptr && u.scale != nullptr;
-                r.inv[f] = have ? u.inv[f] : 1.0f;
-                r.scale[f] = have ? u.scale[f] : 1.0f;
-            }
+            for (int f = 0; f < kMaxFormats; ++f) { r.inv[f] = 1.0f; r.scale[f] = 1.0f; }
         }
         runits[i] = r;
     }
@@ -170,6 +177,22 @@ __global__ __launch_bounds__(kWG) void prepare_kernel(const WorkUnit* __restrict
         if (ref.local >= sch.skip)
             map[schedule_position(sch, ref.local - sch.skip,
                                   chunk_begin[ui + 1] - chunk_begin[ui] - sch.skip)] = ref;
+    }
+}
+
+// ---- resolve: the scales of a run (every run) ------------------------------------------------------
+// Units with one scale per tensor get the values their scale pointers hold now (an absmax run on
+// the same stream may just have written them); units with row scales keep their table pointers.
+__global__ __launch_bounds__(kWG) void resolve_kernel(const WorkUnit* __restrict__ units, uint32_t n_units,
+                                                      int n_fmts, ResolvedUnit* __restrict__ runits) {
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_units) return;
+    const WorkUnit u = units[i];
+    if (u.flags & kUnitRowScale) return;
+    for (int f = 0; f < kMaxFormats; ++f) {
+        const bool have = f < n_fmts && u.inv != nullptr && u.scale != nullptr;
+        runits[i].inv[f] = have ? u.inv[f] : 1.0f;
+        runits[i].scale[f] = have ? u.scale[f] : 1.0f;
     }
 }
 
@@ -723,8 +746,11 @@ __global__ __launch_bounds__(kWG) void sens_w_kernel(const WGroup* __restrict__ 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     for (uint32_t item = blockIdx.x; item < n_items; item += gridDim.x) {
-        uint32_t gi = 0;
-        while (gi + 1 < n_groups && groups[gi + 1].item_begin <= item) ++gi;
+        uint32_t gi = 0, ghi = n_groups;                        // the last group whose first item is <= item
+        while (ghi - gi > 1) {
+            const uint32_t mid = (gi + ghi) >> 1;
+            if (groups[mid].item_begin <= item) gi = mid; else ghi = mid;
+        }
         const WGroup G = groups[gi];
         const uint32_t batches = (G.members + kWBatch - 1) / kWBatch;
         const uint32_t rel = item - G.item_begin;
@@ -1261,12 +1287,35 @@ hipError_t launch_absmax_rows(const RowTensor* d_tensors, uint32_t n_tensors, ui
     return hipGetLastError();
 }
 
+hipError_t launch_table_write(const void* host_src, size_t bytes, void* d_dst, hipStream_t stream) {
+    const uint8_t* src = (const uint8_t*)host_src;
+    uint8_t* dst = (uint8_t*)d_dst;
+    TablePiece piece;
+    for (size_t off = 0; off < bytes; off += sizeof(TablePiece)) {
+        const size_t n = bytes - off < sizeof(TablePiece) ? bytes - off : sizeof(TablePiece);
+        std::memcpy(&piece, src + off, n);
+        if (n % 16) std::memset((uint8_t*)&piece + n, 0, 16 - n % 16);
+        hipLaunchKernelGGL(table_write_kernel, dim3(1), dim3(kWG), 0, stream, piece, (uint4*)(dst + off),
+                           (uint32_t)((n + 15) / 16));
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
 hipError_t launch_prepare(const WorkUnit* d_units, const uint32_t* d_chunk_begin,
                           const UnitSchedule* d_schedule, uint32_t n_units, uint32_t n_chunks,
-                          int n_fmts, ResolvedUnit* d_runits, ChunkRef* d_map, hipStream_t stream) {
+                          ResolvedUnit* d_runits, ChunkRef* d_map, hipStream_t stream) {
     const uint32_t n = n_units > n_chunks ? n_units : n_chunks;
     hipLaunchKernelGGL(prepare_kernel, dim3((n + kWG - 1) / kWG), dim3(kWG), 0, stream, d_units,
-                       d_chunk_begin, d_schedule, n_units, n_chunks, n_fmts, d_runits, d_map);
+                       d_chunk_begin, d_schedule, n_units, n_chunks, d_runits, d_map);
+    return hipGetLastError();
+}
+
+hipError_t launch_resolve(const WorkUnit* d_units, uint32_t n_units, int n_fmts, ResolvedUnit* d_runits,
+                          hipStream_t stream) {
+    hipLaunchKernelGGL(resolve_kernel, dim3((n_units + kWG - 1) / kWG), dim3(kWG), 0, stream, d_units, n_units,
+                       n_fmts, d_runits);
     return hipGetLastError();
 }
 

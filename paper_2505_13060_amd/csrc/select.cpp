@@ -134,6 +134,15 @@ amp_status_t amp_layer_loss_mse(const float* sums, int R, const amp_fp8_format_t
     return AMP_OK;
 }
 
+double amp_loss_second_moment(const double* losses, int n) {
+    if (n < 1 || !losses) return std::numeric_limits<double>::quiet_NaN();
+    double s = 0.0;
+    for (int r = 0; r < n; ++r) s += losses[r] * losses[r];
+    return s / (double)n;
+}
+
+double amp_mse_budget(double tau, double mean_g2) { return tau * tau * mean_g2; }
+
 amp_status_t amp_group_tables(int n_layers, int F, const double* layer_mse, const double* layer_gain,
                               double* d, double* c) {
     if (n_layers < 0 || F < 1 || !d || !c) return AMP_ERR_INVALID_ARG;

@@ -8,10 +8,11 @@ import numpy as np
 import torch
 
 from . import (ROWS_OPERAND0, ROWS_OPERAND1, amp_absmax_rows_workspace_bytes, amp_absmax_scale,
-               amp_absmax_scale_rows, amp_absmax_workspace_bytes, amp_sens_bgemm,
-               amp_sens_bgemm_workspace_bytes, amp_sens_block, amp_sens_block_workspace_bytes,
-               amp_sens_linear, amp_sens_linear_workspace_bytes, bgemm_desc, causal, dense, linear_desc,
-               tensor)
+               amp_absmax_scale_rows, amp_absmax_scale_rows_setup, amp_absmax_scale_setup,
+               amp_absmax_workspace_bytes, amp_plan_limit_grid, amp_run, amp_sens_bgemm,
+               amp_sens_bgemm_workspace_bytes, amp_sens_block, amp_sens_block_setup,
+               amp_sens_block_workspace_bytes, amp_sens_linear, amp_sens_linear_workspace_bytes, bgemm_desc,
+               causal, dense, linear_desc, tensor)
 
 
 def _layout(lay, cols=0):
@@ -25,9 +26,14 @@ def _row(t, i):
 class SensPass:
     """Holds descriptors, outputs and workspaces for one Workload resident on `device`.
     one_call: linears and BGEMMs go through amp_sens_block (one table, one set-up, one streaming
-    launch for activations and BGEMM operands) instead of amp_sens_linear + amp_sens_bgemm."""
+    launch for activations and BGEMM operands) instead of amp_sens_linear + amp_sens_bgemm.
+    plan: the set-up of both calls (absmax, sensitivity block) is done once, here, on the current
+    stream, and run() only replays the plans (kernel launches only); flags go to
+    amp_sens_block_setup, grid_limit to amp_plan_limit_grid."""
 
-    def __init__(self, workload, device, one_call=False):
+    def __init__(self, workload, device, one_call=False, plan=False, flags=0, grid_limit=0):
+        self.plan = plan or flags != 0 or grid_limit != 0
+        one_call = one_call or self.plan
         self.one_call = one_call
         self.w = workload
         self.device = device
@@ -78,12 +84,28 @@ class SensPass:
         else:
             self.ws_lin = ws(amp_sens_linear_workspace_bytes(self.lin_desc, nf))
             self.ws_bg = ws(amp_sens_bgemm_workspace_bytes(self.bg_desc, nf))
+        if self.plan:
+            self.abs_plan = amp_absmax_scale_setup(self.tensors, self.fmts, self.d_amax, self.d_scale, self.d_inv,
+                                                   self.d_flags, self.ws_abs)
+            self.sens_plan = amp_sens_block_setup(self.lin_desc, self.bg_desc, self.fmts, self.d_out,
+                                                  self.ws_block, flags)
+            self.limit_grid(grid_limit)
+
+    def limit_grid(self, max_workgroups):
+        amp_plan_limit_grid(self.abs_plan, max_workgroups)
+        amp_plan_limit_grid(self.sens_plan, max_workgroups)
 
     def absmax(self, stream=None):
+        if self.plan:
+            amp_run(self.abs_plan, stream)
+            return
         amp_absmax_scale(self.tensors, self.fmts, self.d_amax, self.d_scale, self.d_inv, self.d_flags,
                          self.ws_abs, stream)
 
     def sens(self, stream=None):
+        if self.plan:
+            amp_run(self.sens_plan, stream)
+            return
         if self.one_call:
             amp_sens_block(self.lin_desc, self.bg_desc, self.fmts, self.d_out, self.ws_block, stream)
             return
@@ -123,7 +145,10 @@ class RowSensPass:
     operands (bgemm_rows; a dense operand's row is its last dimension).  Operands left at one
     scale per tensor go through amp_absmax_scale as in SensPass."""
 
-    def __init__(self, workload, device, x_rows=True, w_rows=True, bgemm_rows=True, one_call=False):
+    def __init__(self, workload, device, x_rows=True, w_rows=True, bgemm_rows=True, one_call=False, plan=False,
+                 flags=0):
+        self.plan = plan or flags != 0
+        one_call = one_call or self.plan
         self.one_call = one_call
         self.w, self.device, self.fmts = workload, device, list(workload.fmts)
         nf = len(self.fmts)
@@ -199,8 +224,19 @@ class RowSensPass:
         else:
             self.ws_lin = ws(amp_sens_linear_workspace_bytes(self.lin_desc, nf))
             self.ws_bg = ws(amp_sens_bgemm_workspace_bytes(self.bg_desc, nf))
+        if self.plan:
+            self.abs_plan = amp_absmax_scale_setup(self.t_tensors, self.fmts, self.d_amax, self.d_scale, self.d_inv,
+                                                   self.d_flags, self.ws_abs)
+            self.rows_plan = amp_absmax_scale_rows_setup(self.r_tensors, self.fmts, self.r_amax, self.r_scale,
+                                                         self.r_inv, self.r_flags, self.ws_rows)
+            self.sens_plan = amp_sens_block_setup(self.lin_desc, self.bg_desc, self.fmts, self.d_out,
+                                                  self.ws_block, flags)
 
     def absmax(self, stream=None):
+        if self.plan:
+            amp_run(self.abs_plan, stream)
+            amp_run(self.rows_plan, stream)
+            return
         if self.t_tensors:
             amp_absmax_scale(self.t_tensors, self.fmts, self.d_amax, self.d_scale, self.d_inv, self.d_flags,
                              self.ws_abs, stream)
@@ -209,6 +245,9 @@ class RowSensPass:
                                   self.r_flags, self.ws_rows, stream)
 
     def sens(self, stream=None):
+        if self.plan:
+            amp_run(self.sens_plan, stream)
+            return
         if self.one_call:
             amp_sens_block(self.lin_desc, self.bg_desc, self.fmts, self.d_out, self.ws_block, stream)
             return

@@ -16,8 +16,10 @@ int sens_resident_blocks(int, int, int, int, int cus) { return 8 * cus; }
 int absmax_resident_blocks(int cus) { return 8 * cus; }
 int absmax_rows_resident_blocks(int cus) { return 8 * cus; }
 int sens_w_resident_blocks(int, int, int, int, int cus) { return 4 * cus; }
-hipError_t launch_prepare(const WorkUnit*, const uint32_t*, const UnitSchedule*, uint32_t, uint32_t, int,
+hipError_t launch_table_write(const void*, size_t, void*, hipStream_t) { std::abort(); }
+hipError_t launch_prepare(const WorkUnit*, const uint32_t*, const UnitSchedule*, uint32_t, uint32_t,
                           ResolvedUnit*, ChunkRef*, hipStream_t) { std::abort(); }
+hipError_t launch_resolve(const WorkUnit*, uint32_t, int, ResolvedUnit*, hipStream_t) { std::abort(); }
 hipError_t launch_absmax(const ResolvedUnit*, const ChunkRef*, uint32_t, uint32_t*, int, hipStream_t) { std::abort(); }
 hipError_t launch_absmax_finalize(const uint32_t*, const uint32_t*, int, int, int, int, float*, float*, float*,
                                   uint32_t*, hipStream_t) { std::abort(); }
@@ -32,10 +34,11 @@ hipError_t launch_sens_finalize(const ResolvedUnit*, const uint32_t*, uint32_t, 
 }  // namespace ampsens
 
 extern "C" {
-int64_t ampsens_debug_check_linear_schedule(const amp_linear_desc_t*, int, int, uint64_t*, uint64_t*);
-int64_t ampsens_debug_replay_unit(uint64_t, uint64_t, const amp_layout_t*, int64_t, int32_t*, int64_t, uint64_t*);
-int64_t ampsens_debug_replay_unit_rows(uint64_t, uint64_t, const amp_layout_t*, int64_t, int64_t, int32_t*, int64_t,
-                                       uint64_t*);
+// tests/host_hooks.cpp, compiled along
+int64_t hooks_check_linear_schedule(const amp_linear_desc_t*, int, int, int, int, uint64_t*, uint64_t*);
+int64_t hooks_replay_unit(uint64_t, uint64_t, const amp_layout_t*, int64_t, int32_t*, int64_t, uint64_t*);
+int64_t hooks_replay_unit_rows(uint64_t, uint64_t, const amp_layout_t*, int64_t, int64_t, int32_t*, int64_t,
+                               uint64_t*);
 }
 
 static int failures = 0;
@@ -72,7 +75,7 @@ int main() {
         const amp_status_t st = amp_sens_linear_workspace_bytes(lin.data(), n_ops, nf, &bytes);
         CHECK(st == AMP_OK);
         uint64_t chunks = 0, inter = 0;
-        CHECK(ampsens_debug_check_linear_schedule(lin.data(), n_ops, nf, &chunks, &inter) == 0);
+        CHECK(hooks_check_linear_schedule(lin.data(), n_ops, nf, (int)uni(0, 9), (int)uni(0, 1), &chunks, &inter) == 0);
         std::vector<amp_bgemm_desc_t> bg((size_t)uni(0, 4));
         for (amp_bgemm_desc_t& b : bg) {
             std::memset(&b, 0, sizeof(b));
@@ -91,6 +94,25 @@ int main() {
         size_t b3 = 0; int64_t rows = 0;
         CHECK(amp_absmax_workspace_bytes(ts.data(), (int)ts.size(), &b3) == AMP_OK);
         CHECK(amp_absmax_rows_workspace_bytes(ts.data(), (int)ts.size(), &b3, &rows) == AMP_OK);
+    }
+
+    // plans: every error path of the set-up calls answers on the host, and a plan that was never set up does not run
+    {
+        amp_plan_t plan;
+        std::memset(&plan, 0xAB, sizeof(plan));
+        CHECK(amp_run(&plan, nullptr) == AMP_ERR_INVALID_ARG);
+        CHECK(amp_run(nullptr, nullptr) == AMP_ERR_INVALID_ARG);
+        const amp_fp8_format_t fm[2] = {AMP_FP8_E4M3, AMP_FP8_E5M2};
+        CHECK(amp_sens_block_setup(nullptr, 0, nullptr, 0, fm, 2, nullptr, nullptr, 0, 0u, nullptr, nullptr) == AMP_ERR_INVALID_ARG);
+        CHECK(amp_sens_block_setup(nullptr, 0, nullptr, 0, fm, 2, nullptr, nullptr, 0, 2u, nullptr, &plan) == AMP_ERR_INVALID_ARG);
+        CHECK(amp_run(&plan, nullptr) == AMP_ERR_INVALID_ARG);
+        CHECK(amp_sens_block_setup(nullptr, 0, nullptr, 0, fm, 2, nullptr, nullptr, 0, 0u, nullptr, &plan) == AMP_OK);
+        CHECK(amp_run(&plan, nullptr) == AMP_OK);                       // nothing to do, nothing launched
+        CHECK(amp_plan_limit_grid(&plan, 7) == AMP_OK && amp_plan_limit_grid(&plan, -1) == AMP_ERR_INVALID_ARG);
+        CHECK(amp_absmax_scale_setup(nullptr, 0, fm, 2, nullptr, nullptr, nullptr, nullptr, nullptr, 0, nullptr, &plan) == AMP_OK);
+        CHECK(amp_run(&plan, nullptr) == AMP_OK);
+        CHECK(amp_absmax_scale_rows_setup(nullptr, 0, fm, 3, nullptr, nullptr, nullptr, nullptr, nullptr, 0, nullptr, &plan) == AMP_ERR_BAD_FORMAT);
+        CHECK(amp_run(&plan, nullptr) == AMP_ERR_INVALID_ARG);
     }
 
     // the walk replay: every element of a unit exactly once, no access outside it
@@ -112,8 +134,8 @@ int main() {
         const uint64_t addr = 0x40000000ull + 2 * (uint64_t)uni(0, 7);
         std::vector<int32_t> counts((size_t)span, 0);
         uint64_t nch = 0;
-        const int64_t bad = row_len ? ampsens_debug_replay_unit_rows(addr, addr, &L, 1, row_len, counts.data(), span, &nch)
-                                    : ampsens_debug_replay_unit(addr, addr, &L, 1, counts.data(), span, &nch);
+        const int64_t bad = row_len ? hooks_replay_unit_rows(addr, addr, &L, 1, row_len, counts.data(), span, &nch)
+                                    : hooks_replay_unit(addr, addr, &L, 1, counts.data(), span, &nch);
         CHECK(bad == 0);
         if (!causal)
             for (int64_t e = 0; e < span; ++e) if (counts[(size_t)e] != 1) { CHECK(counts[(size_t)e] == 1); break; }

@@ -11,6 +11,7 @@ import pytest
 
 import oracle
 import paper_2505_13060_amd as amp
+from conftest import host_hooks
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -32,12 +33,32 @@ def test_library_exports_every_declared_symbol():
     assert L.amp_status_string(amp.ERR_INFEASIBLE).decode().startswith("no configuration")
 
 
+def test_product_library_exports_no_test_hooks():
+    """Replay and schedule checks live in tests/host_hooks.cpp; the product ABI is the header, nothing more."""
+    import subprocess
+    out = subprocess.run(["nm", "-D", "--defined-only", amp._build.LIB], capture_output=True, text=True, check=True).stdout
+    names = [line.split()[-1] for line in out.splitlines() if line.strip()]
+    assert not [n for n in names if "debug" in n or n.startswith("hooks_")]
+    exported = sorted(n for n in names if n.startswith("amp_"))
+    assert exported == declared_symbols(), set(exported) ^ set(declared_symbols())
+
+
+def test_budget_of_eq_ip():
+    losses = np.array([0.5, -2.0, 3.0, 1.25])
+    m = amp.amp_loss_second_moment(losses)
+    assert m == pytest.approx((0.25 + 4.0 + 9.0 + 1.5625) / 4, rel=1e-15)
+    assert amp.amp_mse_budget(0.01, m) == pytest.approx(1e-4 * m, rel=1e-15)
+    assert amp.amp_mse_budget(0.0, m) == 0.0
+    assert np.isnan(amp.amp_loss_second_moment(np.zeros(0)))
+
+
 def test_struct_sizes_match_header():
     # natural C layout of the header's structs
     assert C.sizeof(amp.Layout) == 40
     assert C.sizeof(amp.Tensor) == 56
     assert C.sizeof(amp.LinearDesc) == 104
     assert C.sizeof(amp.BgemmDesc) == 152
+    assert C.sizeof(amp.Plan) == 512
 
 
 def test_argument_validation_without_a_gpu():
@@ -143,10 +164,7 @@ REPLAY_CASES = [
 
 @pytest.mark.parametrize("lay,xo,dxo,mul", REPLAY_CASES)
 def test_kernel_walk_covers_every_element_once(lay, xo, dxo, mul):
-    L = amp.lib()
-    L.ampsens_debug_replay_unit.restype = C.c_int64
-    L.ampsens_debug_replay_unit.argtypes = [C.c_uint64, C.c_uint64, C.c_void_p, C.c_int64,
-                                            C.c_void_p, C.c_int64, C.POINTER(C.c_uint64)]
+    L = host_hooks()
     if lay[0] == "dense":
         layout = amp.dense(lay[1])
         span = lay[1] * mul
@@ -160,7 +178,7 @@ def test_kernel_walk_covers_every_element_once(lay, xo, dxo, mul):
         want = np.broadcast_to((j <= i + (c - r)).astype(np.int32), (b * mul, r, c)).reshape(-1).copy()
     counts = np.zeros(span, dtype=np.int32)
     nch = C.c_uint64()
-    bad = L.ampsens_debug_replay_unit(0x10000 + xo, 0x90000 + dxo, C.byref(layout), mul,
+    bad = L.hooks_replay_unit(0x10000 + xo, 0x90000 + dxo, C.byref(layout), mul,
                                       counts.ctypes.data_as(C.c_void_p), span, C.byref(nch))
     assert bad == 0
     assert np.array_equal(counts, want)
@@ -187,10 +205,7 @@ def test_kernel_walk_tracks_the_row_of_every_vector(lay, row_len, xo, dxo, mul):
     """Units with one scale per row: the replay of the kernels' index code also follows the row of
     every vector the way the device context does (one division per chunk, then additions; or the
     row named by the causal walker) and compares it with element index / row length."""
-    L = amp.lib()
-    L.ampsens_debug_replay_unit_rows.restype = C.c_int64
-    L.ampsens_debug_replay_unit_rows.argtypes = [C.c_uint64, C.c_uint64, C.c_void_p, C.c_int64, C.c_int64,
-                                                 C.c_void_p, C.c_int64, C.POINTER(C.c_uint64)]
+    L = host_hooks()
     if lay[0] == "dense":
         layout = amp.dense(lay[1])
         span = lay[1] * mul
@@ -204,7 +219,7 @@ def test_kernel_walk_tracks_the_row_of_every_vector(lay, row_len, xo, dxo, mul):
         want = np.broadcast_to((j <= i + (c - r)).astype(np.int32), (b * mul, r, c)).reshape(-1).copy()
     counts = np.zeros(span, dtype=np.int32)
     nch = C.c_uint64()
-    bad = L.ampsens_debug_replay_unit_rows(0x10000 + xo, 0x90000 + dxo, C.byref(layout), mul, row_len,
+    bad = L.hooks_replay_unit_rows(0x10000 + xo, 0x90000 + dxo, C.byref(layout), mul, row_len,
                                            counts.ctypes.data_as(C.c_void_p), span, C.byref(nch))
     assert bad == 0
     assert np.array_equal(counts, want)
@@ -255,10 +270,7 @@ def test_row_scale_descriptors_are_validated():
 def test_schedule_is_a_permutation_of_the_chunks(shapes):
     """Weight units of one op (same W, one gradient per sample) are interleaved in the schedule;
     whatever the shapes, every chunk must get exactly one position."""
-    L = amp.lib()
-    L.ampsens_debug_check_linear_schedule.restype = C.c_int64
-    L.ampsens_debug_check_linear_schedule.argtypes = [C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_uint64),
-                                                      C.POINTER(C.c_uint64)]
+    L = host_hooks()
     descs = []
     base = 0x100000
     for (R, tokens, Cd, K) in shapes:
@@ -270,7 +282,8 @@ def test_schedule_is_a_permutation_of_the_chunks(shapes):
         descs.append(d)
     arr = (amp.LinearDesc * len(descs))(*descs)
     n, inter = C.c_uint64(), C.c_uint64()
-    assert L.ampsens_debug_check_linear_schedule(arr, len(descs), 2, C.byref(n), C.byref(inter)) == 0
+    for block, use_w in ((0, 1), (0, 0), (1, 1), (3, 0), (5, 1)):
+        assert L.hooks_check_linear_schedule(arr, len(descs), 2, block, use_w, C.byref(n), C.byref(inter)) == 0
     assert n.value >= len(descs)
     if shapes[0][0] > 1 and shapes[0][2] * shapes[0][3] % 8 == 0:
         assert inter.value > 0

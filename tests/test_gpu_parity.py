@@ -188,18 +188,24 @@ def test_single_format_e5m2_and_format_order():
 
 def test_results_do_not_depend_on_grid_and_repeat_bit_identically():
     w = to_device(wl.config1("cpu", R=2, S=136, hidden=256, ffn=520, H=2, D=64))
-    say("determinism: grid caps 0 (default), 1, 7, 64")
-    p = SensPass(w, DEV)
-    L = amp.lib()
+    say("determinism: one-shot calls, then a plan with grid limits 0 (default), 1, 7, 64 and schedule blocks")
     outs = []
-    for cap in (0, 0, 1, 7, 64):
-        L.ampsens_debug_set_grid_cap(C.c_int(cap))
-        p.d_lin_out.zero_()
-        p.d_bg_out.zero_()
+
+    def take(p):
+        p.d_out.zero_()
         p.run()
         r = p.results()
         outs.append((np.concatenate(r["linear"]).copy(), np.concatenate(r["bgemm"]).copy(), r["scale"].copy()))
-    L.ampsens_debug_set_grid_cap(C.c_int(0))
+
+    take(SensPass(w, DEV))                                 # amp_sens_linear + amp_sens_bgemm
+    take(SensPass(w, DEV, one_call=True))                  # amp_sens_block
+    p = SensPass(w, DEV, plan=True)                        # set-up once, amp_run per pass
+    for cap in (0, 0, 1, 7, 64):
+        p.limit_grid(cap)
+        take(p)
+    for block in (1, 3, 8):
+        take(SensPass(w, DEV, flags=amp.plan_interleave(block)))
+    take(SensPass(w, DEV, flags=amp.PLAN_STREAM_WEIGHTS, grid_limit=5))
     for o in outs[1:]:
         for a, b in zip(outs[0], o):
             assert np.array_equal(parity.bits32(a), parity.bits32(b))
@@ -465,10 +471,9 @@ def test_one_call_for_linears_and_bgemms(which):
 
 
 def test_weight_kernel_and_streaming_kernel_agree():
-    """Weights go through the kernel that reads W once per batch of 8 samples; with the test hook off
+    """Weights go through the kernel that reads W once per batch of 8 samples; with AMP_PLAN_STREAM_WEIGHTS
     they go through the streaming kernel.  Both must match the oracle, for sample counts that are not
     multiples of the batch and weights with a ragged last chunk or an unaligned gradient."""
-    L = amp.lib()
     for (R, tokens, Cd, K) in [(11, 40, 520, 190), (3, 16, 1024, 100), (9, 8, 333, 301), (2, 64, 4096, 24)]:
         w = wl.Workload("wk", [amp.E4M3, amp.E5M2],
                         [wl._linear("lin", 777 + R, R, tokens, Cd, K, "cpu", outliers=2)])
@@ -476,13 +481,11 @@ def test_weight_kernel_and_streaming_kernel_agree():
         outs = []
         for on in (0, 1):
             say("weight kernel %s: R=%d W=%dx%d (%d elements)" % ("on" if on else "off", R, K, Cd, K * Cd))
-            L.ampsens_debug_set_w_kernel(C.c_int(on))
-            p = SensPass(w, DEV)
+            p = SensPass(w, DEV, plan=True, flags=0 if on else amp.PLAN_STREAM_WEIGHTS)
             p.run()
             res = p.results()
             parity.check_workload(w, res)
             outs.append(res["linear"][0].copy())
-        L.ampsens_debug_set_w_kernel(C.c_int(1))
         assert np.allclose(outs[0], outs[1], rtol=2e-6, atol=0)
 
 

@@ -225,18 +225,13 @@ def test_rows_config4_reduced_ragged_many_small():
 
 
 def test_rows_weight_kernel_on_and_off():
-    L = amp.lib()
     for (R, tokens, Cd, K) in [(11, 40, 520, 190), (3, 16, 1024, 100), (2, 64, 4096, 24), (9, 24, 40, 2500)]:
         w = wl.Workload("wk_rows", [amp.E4M3, amp.E5M2],
                         [wl._linear("lin", 555 + R, R, tokens, Cd, K, "cpu", outliers=2)])
         outs = []
         for on in (0, 1):
             say("weight kernel %s with row scales: R=%d W=%dx%d" % ("on" if on else "off", R, K, Cd))
-            L.ampsens_debug_set_w_kernel(C.c_int(on))
-            try:
-                p, res = run_rows(w)
-            finally:
-                L.ampsens_debug_set_w_kernel(C.c_int(1))
+            p, res = run_rows(w, plan=True, flags=0 if on else amp.PLAN_STREAM_WEIGHTS)
             outs.append(res["linear"][0].copy())
         assert np.allclose(outs[0], outs[1], rtol=2e-6, atol=0)
 

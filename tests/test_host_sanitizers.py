@@ -20,7 +20,7 @@ def test_host_code_is_clean_under_asan_and_ubsan(tmp_path):
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument",
            "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
            "-Xarch_host", "-fno-sanitize-recover=undefined",
-           "-x", "hip", os.path.join(ROOT, "tests", "host_sanitize.cpp"),
+           "-x", "hip", os.path.join(ROOT, "tests", "host_sanitize.cpp"), os.path.join(ROOT, "tests", "host_hooks.cpp"),
            os.path.join(csrc, "api.hip"), os.path.join(csrc, "select.cpp"), os.path.join(csrc, "graph.cpp"),
            "-o", exe]
     build = subprocess.run(cmd, capture_output=True, text=True)
