@@ -33,48 +33,65 @@ struct Segment {            // one edge of a group's upper convex hull
 
 // LP relaxation of the groups not yet decided, as a concave piecewise-linear function of the
 // budget: start from every such group's cheapest choice, then take hull edges in order of
-// decreasing slope.  All hull edges are sorted by slope once; two Fenwick trees over that order
-// hold the increments of the edges whose group is still undecided, so that "walk the edges until
-// the budget is used up" is a descent of the tree and dropping a group is a point update.
+// decreasing slope.  All hull edges are sorted by slope once; a segment tree over that order holds
+// the increments of the edges whose group is still undecided, so that "walk the edges until the
+// budget is used up" is one descent of the tree and dropping an edge is one leaf-to-root update.
+// Inner nodes are always recomputed from their children, so removed edges leave no rounding residue.
 struct Relaxation {
     std::vector<Segment> edges;          // sorted by decreasing slope
     std::vector<int32_t> group;          // owner of each edge
-    std::vector<double> fd, fg;          // Fenwick trees (1-based) over dd and dg of live edges
+    std::vector<double> td, tg;          // segment tree over dd and dg of live edges: node p has children
+                                         // 2p and 2p + 1, leaf of edge i is leaves + i
+    size_t leaves = 1;                   // a power of two >= edges.size()
     double base_d = 0, base_g = 0;       // cheapest choices of the undecided groups
-    size_t top = 1;                      // largest power of two <= edges.size()
 
-    // Rebuilt from the live edges whenever a group leaves (linear time): sums of live edges only,
-    // no residue of removed ones.
     void build() {
         const size_t n = edges.size();
-        fd.assign(n + 1, 0.0);
-        fg.assign(n + 1, 0.0);
-        for (size_t i = 1; i <= n; ++i) {
-            if (live[i - 1]) { fd[i] += edges[i - 1].dd; fg[i] += edges[i - 1].dg; }
-            const size_t up = i + (i & (~i + 1));
-            if (up <= n) { fd[up] += fd[i]; fg[up] += fg[i]; }
-        }
-        top = 1;
-        while (top * 2 <= n) top *= 2;
+        leaves = 1;
+        while (leaves < n) leaves *= 2;
+        td.assign(2 * leaves, 0.0);
+        tg.assign(2 * leaves, 0.0);
+        for (size_t i = 0; i < n; ++i)
+            if (live[i]) { td[leaves + i] = edges[i].dd; tg[leaves + i] = edges[i].dg; }
+        for (size_t p = leaves - 1; p >= 1; --p) { td[p] = td[2 * p] + td[2 * p + 1]; tg[p] = tg[2 * p] + tg[2 * p + 1]; }
     }
-    // Greedy walk over the live edges while they fit into `room` (>= 0).  Returns the gain of the
-    // whole edges taken; *frac receives the gain of the fraction of the next live edge that still fits.
+    void remove(size_t i) {
+        live[i] = 0;
+        size_t p = leaves + i;
+        td[p] = 0.0;
+        tg[p] = 0.0;
+        for (p >>= 1; p >= 1; p >>= 1) { td[p] = td[2 * p] + td[2 * p + 1]; tg[p] = tg[2 * p] + tg[2 * p + 1]; }
+    }
+    // Greedy walk over the live edges, in order, while they fit into `room` (>= 0): the longest
+    // prefix whose increments fit.  Returns the gain of the whole edges taken; *frac receives the
+    // gain of the fraction of the next live edge that still fits.
     double walk(double room, double* frac) const {
-        size_t pos = 0;
+        if (frac) *frac = 0.0;
+        if (edges.empty()) return 0.0;
+        if (td[1] <= room) return tg[1];                       // everything fits
+        size_t p = 1;
         double used = 0, g = 0;
-        const size_t n = edges.size();
-        for (size_t step = n ? top : 0; step > 0; step >>= 1) {
-            const size_t nxt = pos + step;
-            if (nxt <= n && used + fd[nxt] <= room) { pos = nxt; used += fd[nxt]; g += fg[nxt]; }
+        while (p < leaves) {
+            const size_t l = 2 * p;
+            if (used + td[l] <= room) { used += td[l]; g += tg[l]; p = l + 1; }   // the left half fits: go on in the right
+            else p = l;
         }
-        // the next live edge after position pos (removed edges carry nothing)
-        if (frac) {
-            *frac = 0.0;
-            size_t k = pos;
-            while (k < n && !live[k]) ++k;
-            if (k < n) *frac = edges[k].dg * ((room - used) / edges[k].dd);
-        }
+        // p is the leaf of the first edge that does not fit (removed edges weigh nothing and always fit)
+        if (used + td[p] <= room) { used += td[p]; g += tg[p]; }
+        else if (frac) *frac = tg[p] * ((room - used) / td[p]);
         return g;
+    }
+    // Index of the first live edge that the greedy walk cannot take whole, edges.size() if all fit.
+    size_t first_unfit(double room) const {
+        if (edges.empty() || td[1] <= room) return edges.size();
+        size_t p = 1;
+        double used = 0;
+        while (p < leaves) {
+            const size_t l = 2 * p;
+            if (used + td[l] <= room) { used += td[l]; p = l + 1; }
+            else p = l;
+        }
+        return used + td[p] <= room ? edges.size() : p - leaves;
     }
     std::vector<char> live;
     // upper bound: -inf when even the cheapest choices do not fit
@@ -232,16 +249,39 @@ amp_status_t amp_select_subgraphs(int J, const int32_t* n_choices, const double*
         rest.live.assign(rest.edges.size(), 1);
         rest.build();
     }
-    // cheapest choices of groups j..J-1
+    std::vector<std::vector<size_t>> edges_of(J);
+    for (size_t i = 0; i < rest.group.size(); ++i) edges_of[rest.group[i]].push_back(i);
+    // Order in which the search decides the groups (any order is exact).  The LP optimum takes all hull
+    // edges steeper than the slope of the edge at which the budget runs out; a group whose edges are all
+    // far from that slope has one choice that survives the bound, a group with an edge near it has
+    // several.  Deciding the clear-cut groups first keeps the list of partial configurations short
+    // until the last stages.
+    std::vector<int32_t> order(J);
+    for (int j = 0; j < J; ++j) order[j] = j;
+    {
+        double base = 0.0;
+        for (int j = 0; j < J; ++j) base += groups[j].front().d;
+        rest.base_d = base;
+        const size_t brk = mse_budget >= base ? rest.first_unfit(mse_budget - base) : rest.edges.size();
+        if (brk < rest.edges.size()) {
+            const double lam = std::log(rest.edges[brk].dg / rest.edges[brk].dd);
+            std::vector<double> clear(J, std::numeric_limits<double>::infinity());
+            for (int j = 0; j < J; ++j)
+                for (size_t i : edges_of[j]) {
+                    const double dist = std::fabs(std::log(rest.edges[i].dg / rest.edges[i].dd) - lam);
+                    if (dist < clear[j]) clear[j] = dist;
+                }
+            std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return clear[a] > clear[b]; });
+        }
+    }
+    // cheapest choices of the groups decided at stages t..J-1
     std::vector<double> suffix_d(J + 1, 0.0), suffix_g(J + 1, 0.0);
-    for (int j = J - 1; j >= 0; --j) {
-        suffix_d[j] = suffix_d[j + 1] + groups[j].front().d;
-        suffix_g[j] = suffix_g[j + 1] + groups[j].front().g;
+    for (int t = J - 1; t >= 0; --t) {
+        suffix_d[t] = suffix_d[t + 1] + groups[order[t]].front().d;
+        suffix_g[t] = suffix_g[t + 1] + groups[order[t]].front().g;
     }
     rest.base_d = suffix_d[0];
     rest.base_g = suffix_g[0];
-    std::vector<std::vector<size_t>> edges_of(J);
-    for (size_t i = 0; i < rest.group.size(); ++i) edges_of[rest.group[i]].push_back(i);
     if (J == 0) {
         if (mse_budget < 0) return AMP_ERR_INFEASIBLE;
         if (total_gain) *total_gain = 0.0;
@@ -257,15 +297,15 @@ amp_status_t amp_select_subgraphs(int J, const int32_t* n_choices, const double*
     std::vector<std::vector<State>> stages(J + 1);
     stages[0].push_back(State{0.0, 0.0, -1, -1});
     std::vector<State> cand;
-    for (int j = 0; j < J; ++j) {
+    for (int t = 0; t < J; ++t) {
+        const int j = order[t];
         cand.clear();
         // group j is decided in this stage: take it out of the relaxation
-        for (size_t i : edges_of[j]) rest.live[i] = 0;
-        rest.build();
-        rest.base_d = suffix_d[j + 1];
-        rest.base_g = suffix_g[j + 1];
-        for (int32_t s = 0; s < (int32_t)stages[j].size(); ++s) {
-            const State& st = stages[j][s];
+        for (size_t i : edges_of[j]) rest.remove(i);
+        rest.base_d = suffix_d[t + 1];
+        rest.base_g = suffix_g[t + 1];
+        for (int32_t s = 0; s < (int32_t)stages[t].size(); ++s) {
+            const State& st = stages[t][s];
             for (int32_t p = 0; p < (int32_t)groups[j].size(); ++p) {
                 const double d = st.d + groups[j][p].d;
                 if (d + rest.base_d > mse_budget) break;         // choices are sorted by mse
@@ -280,7 +320,7 @@ amp_status_t amp_select_subgraphs(int J, const int32_t* n_choices, const double*
             return a.pick < b.pick;
         });
         double best = ninf;
-        std::vector<State>& next = stages[j + 1];
+        std::vector<State>& next = stages[t + 1];
         for (const State& c : cand) {
             if (!(c.g > best)) continue;                          // dominated
             best = c.g;
@@ -302,9 +342,9 @@ amp_status_t amp_select_subgraphs(int J, const int32_t* n_choices, const double*
     if (total_gain) *total_gain = last[bi].g;
     if (total_mse) *total_mse = last[bi].d;
     int32_t s = bi;
-    for (int j = J; j >= 1; --j) {
-        choice[j - 1] = groups[j - 1][stages[j][s].pick].idx;
-        s = stages[j][s].parent;
+    for (int t = J; t >= 1; --t) {
+        choice[order[t - 1]] = groups[order[t - 1]][stages[t][s].pick].idx;
+        s = stages[t][s].parent;
     }
     return AMP_OK;
 }
