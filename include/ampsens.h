@@ -231,6 +231,23 @@ amp_status_t amp_sens_block(const amp_linear_desc_t* linears /* host array */, i
                             const amp_fp8_format_t* fmts /* host */, int n_fmts, float* d_out,
                             void* workspace, size_t workspace_bytes, void* stream);
 
+/* amp_sens_block for callers that cannot allocate (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc) and have no workspace at hand: the same pass, the same
+ * sums bit for bit, with the workspace in a device array of AMP_STATIC_WORKSPACE_BYTES that is part
+ * of the library's code object (every GPU the library runs on holds it until the process ends).
+ * Calls whose amp_sens_block_workspace_bytes exceed it return AMP_ERR_WORKSPACE_TOO_SMALL before
+ * anything is launched (16 MiB covers one Llama-7B-shaped block at S = 2048 with 16 resident
+ * samples).  The call allocates and frees nothing on the device or in pinned memory and does not
+ * wait for the GPU.  All calls on a GPU share that GPU's array: two calls that overlap in time on
+ * one GPU (different streams, or different host threads without ordering) race; calls on one
+ * stream, or ordered by events, are safe.  Nothing in the array needs clearing between calls: every
+ * word a pass reads has been written earlier in the same pass. */
+#define AMP_STATIC_WORKSPACE_BYTES (16u << 20)
+amp_status_t amp_sens_block_static(const amp_linear_desc_t* linears /* host array */, int n_linears,
+                                   const amp_bgemm_desc_t* bgemms /* host array */, int n_bgemms,
+                                   const amp_fp8_format_t* fmts /* host */, int n_fmts, float* d_out,
+                                   void* stream);
+
 /* ---- step 4 (host): epilogue of Sec. 2.2 -------------------------------------------------
  * sums: HOST copy of one op's block of d_out, [R][n_fmts][4].
  *   *s_layer       = (1/R) sum_r (A_op0^r + A_op1^r)                 (eq. (sensl))

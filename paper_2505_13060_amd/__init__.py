@@ -107,6 +107,8 @@ def lib():
         L.amp_sens_block_setup.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_int,
                                            C.c_void_p, C.c_void_p, C.c_size_t, C.c_uint32, C.c_void_p,
                                            C.POINTER(Plan)]
+        L.amp_sens_block_static.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_int,
+                                            C.c_void_p, C.c_void_p]
         L.amp_plan_limit_grid.argtypes = [C.POINTER(Plan), C.c_int]
         L.amp_run.argtypes = [C.POINTER(Plan), C.c_void_p]
         _lib = L
@@ -262,6 +264,16 @@ def amp_sens_block(linears, bgemms, fmts, d_out, workspace, stream=None):
                                 len(bgemms), f, nf, _ptr(d_out), _ptr(workspace),
                                 workspace.numel() * workspace.element_size(), _stream(stream)),
            "amp_sens_block")
+
+
+STATIC_WORKSPACE_BYTES = 16 << 20
+
+
+def amp_sens_block_static(linears, bgemms, fmts, d_out, stream=None):
+    """amp_sens_block with the library's own fixed device array as workspace (no allocation anywhere)."""
+    f, nf = _fmts(fmts)
+    _check(lib().amp_sens_block_static(_array(LinearDesc, linears), len(linears), _array(BgemmDesc, bgemms),
+                                       len(bgemms), f, nf, _ptr(d_out), _stream(stream)), "amp_sens_block_static")
 
 
 def amp_absmax_scale_setup(tensors, fmts, d_amax, d_scale, d_inv, d_flags, workspace, stream=None):

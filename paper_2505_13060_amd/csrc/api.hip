@@ -326,6 +326,29 @@ amp_status_t run_plan(const PlanData& P, hipStream_t stream) {
     return AMP_ERR_INVALID_ARG;
 }
 
+// ---- the workspace of the entry point that allocates nothing -------------------------------------
+// A file-scope device array stands in for the caller's workspace.  Its name is a host-side handle,
+// not a device address: the address is looked up once per device (every GPU that loads the library
+// holds its own copy of the array) and only that pointer is ever handed to a kernel.
+constexpr size_t kStaticScratchBytes = (size_t)AMP_STATIC_WORKSPACE_BYTES;
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[kStaticScratchBytes];
+
+amp_status_t static_scratch(void** out) {
+    static std::mutex mu;
+    static void* ptr[64];
+    const int dev = device_index();
+    if (dev < 0) return device_error(hipErrorInvalidDevice);
+    std::lock_guard<std::mutex> lock(mu);
+    if (ptr[dev] == nullptr) {
+        void* p = nullptr;
+        AMP_HIP(hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch)));
+        if (p == nullptr || (uintptr_t)p % 256) return device_error(hipErrorInvalidSymbol);
+        ptr[dev] = p;
+    }
+    *out = ptr[dev];
+    return AMP_OK;
+}
+
 amp_status_t build_block(const amp_linear_desc_t* linears, int n_linears, const amp_bgemm_desc_t* bgemms,
                          int n_bgemms, int n_fmts, WorkTable* t) {
     uint64_t base = 0;
@@ -496,6 +519,25 @@ amp_status_t amp_sens_block(const amp_linear_desc_t* linears, int n_linears, con
                                            workspace_bytes, 0u, stream, &plan);
     if (st != AMP_OK) return st;
     return amp_run(&plan, stream);
+}
+
+amp_status_t amp_sens_block_static(const amp_linear_desc_t* linears, int n_linears, const amp_bgemm_desc_t* bgemms,
+                                   int n_bgemms, const amp_fp8_format_t* fmts, int n_fmts, float* d_out,
+                                   void* stream) {
+    amp_status_t st = check_fmts(fmts, n_fmts);
+    if (st != AMP_OK) return st;
+    WorkTable t;
+    st = build_block(linears, n_linears, bgemms, n_bgemms, n_fmts, &t);
+    if (st != AMP_OK) return st;
+    if (t.units.empty()) return AMP_OK;
+    if (sens_layout(t, n_fmts).total > kStaticScratchBytes) return AMP_ERR_WORKSPACE_TOO_SMALL;
+    void* ws = nullptr;
+    st = static_scratch(&ws);
+    if (st != AMP_OK) return st;
+    PlanData P;
+    st = sens_setup(t, fmts, n_fmts, d_out, ws, kStaticScratchBytes, 0u, (hipStream_t)stream, &P);
+    if (st != AMP_OK) return st;
+    return run_plan(P, (hipStream_t)stream);
 }
 
 // ---- plans ------------------------------------------------------------------------------------------
