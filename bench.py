@@ -214,9 +214,11 @@ def main():
     ap.add_argument("--calls", choices=["oneshot", "plan"], default="oneshot",
                     help="oneshot: every step's calls do their own set-up (headline); plan: set-up once per "
                          "block outside the timed region, steps replay the plans with amp_run")
-    ap.add_argument("--scales", choices=["tensor", "rows"], default="tensor",
+    ap.add_argument("--scales", choices=["tensor", "rows", "rows-single-read"], default="tensor",
                     help="scale granularity: one per tensor (headline) or one per row (per token / per "
-                         "output channel / per row of a BGEMM operand)")
+                         "output channel / per row of a BGEMM operand); rows-single-read: the sensitivity "
+                         "pass computes the row scales of the activations and BGEMM operands itself, "
+                         "every row is fetched once")
     ap.add_argument("--settle", type=float, default=6.0,
                     help="seconds to leave the GPU idle between generating the inputs and the warm-up: for a "
                          "few seconds after a process has freed tens of GB of device memory every kernel on "
@@ -249,19 +251,22 @@ def main():
         # linears and BGEMMs of the block in one call: one table, one set-up, one streaming launch
         plan = args.calls == "plan"
         passes.append(SensPass(workload, dev, one_call=True, plan=plan) if args.scales == "tensor"
-                      else RowSensPass(workload, dev, one_call=True, plan=plan))
+                      else RowSensPass(workload, dev, one_call=True, plan=plan,
+                                       single_read=args.scales == "rows-single-read"))
     torch.cuda.synchronize()
     workload = workloads[0]
     pairs = workload.pairs()
     log("%.1f M pairs per step (%.2f GB), generated in %.1f s" % (pairs / 1e6, pairs * 4 / 1e9, time.perf_counter() - t0))
-    if args.scales == "rows":
-        label += "; one scale per row"
+    if args.scales != "tensor":
+        label += "; one scale per row" + (", computed by the sensitivity pass (single read)" if args.scales != "rows" else "")
     label += "; steps rotate over %d distinct resident block(s)" % n_blocks
+    # elements the absmax passes of a step read: every operand once, except those whose row scales
+    # the sensitivity pass computes itself
     abs_elems = 0
     for op in workload.linears:
-        abs_elems += int(op.row_offsets[-1]) * op.C + op.K * op.C
+        abs_elems += op.K * op.C + (0 if args.scales == "rows-single-read" else int(op.row_offsets[-1]) * op.C)
     for op in workload.bgemms:
-        abs_elems += op.pairs()
+        abs_elems += 0 if args.scales == "rows-single-read" else op.pairs()
 
     if args.calibrate_copy:
         src = torch.ones(1 << 28, device=dev, dtype=torch.float32)       # 1 GiB
@@ -321,6 +326,10 @@ def main():
         names = ["sens_w_kernel, per-channel scales (weights of the linears)",
                  "sens_wrows_kernel (activations of the linears, causal BGEMM operands)",
                  "sens_wrows_kernel, short-row variant (BGEMM operands with rows of 128)"]
+    if args.scales == "rows-single-read" and launches_per_step == 3:
+        names = ["sens_w_kernel, per-channel scales (weights of the linears)",
+                 "sens_fused_rows_kernel (activations of the linears, causal BGEMM operands: absmax, scales and sums in one read)",
+                 "sens_fused_rows_kernel, short-row variant (BGEMM operands with rows of 128)"]
     launch_detail = []
     per_ms = ms.reshape(args.steps, launches_per_step).mean(axis=0)
     per_min = ms.reshape(args.steps, launches_per_step).min(axis=0)

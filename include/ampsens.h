@@ -97,11 +97,25 @@ typedef enum amp_fp8_format {
  * is the smallest power of two s with amax / s <= FMAX_f and the reciprocal is 1 / s, both exact
  * (exponent-only scale factors), instead of amax / FMAX_f and FMAX_f / amax.  amax == 0, a
  * non-finite amax, or an s whose reciprocal is not an fp32 number give scale = inv = 1.  The
- * sensitivity calls take scales as inputs and accept plain formats only. */
+ * sensitivity calls take scales as inputs; they accept the flag too, and use it only for operands
+ * whose row scales they compute themselves (AMP_ROWS_COMPUTE0 / 1 below). */
 #define AMP_SCALE_POW2 0x100
 
 #define AMP_ROWS_OPERAND0 1          /* X of a linear layer / X0 of a BGEMM */
 #define AMP_ROWS_OPERAND1 2          /* W of a linear layer / X1 of a BGEMM */
+/* Single-read variant: the sensitivity pass itself finds each row's absmax, derives the scales with
+ * the arithmetic of amp_absmax_scale_rows (the rule, amax / FMAX or power of two, is taken from the
+ * formats passed to the sensitivity call, which may carry AMP_SCALE_POW2 for this purpose) and casts the
+ * row with them: every row is fetched once, kept in registers while it is reduced, and its
+ * gradient streamed against it.  The operand's scale / reciprocal tables are then OUTPUTS of the
+ * pass (same [rows][n_fmts] layout), no absmax call is needed for it, and no amax or non-finite
+ * flag is produced (a NaN or Inf in a row shows in that sample's sums).  Requires rows made of whole
+ * 16-byte vectors (row length a multiple of 8, 16-byte aligned buffers) of at most 32768 elements;
+ * anything else is AMP_ERR_INVALID_ARG (use the two-pass form).  For a linear layer only the
+ * activations can be computed this way: the weight is shared by the samples and small next to its R
+ * gradients, its table comes from amp_absmax_scale_rows. */
+#define AMP_ROWS_COMPUTE0 4          /* operand 0: one scale per row, computed by the pass */
+#define AMP_ROWS_COMPUTE1 8          /* operand 1 of a BGEMM, likewise */
 
 /* Shape of one sample's block of an operand.
  * causal == 0: n_elems consecutive elements (batch/rows/cols ignored).

@@ -18,6 +18,8 @@ MAX_FORMATS = 2
 SCALE_POW2 = 0x100         # or-ed into a format for the absmax calls: power-of-two scales
 ROWS_OPERAND0 = 1          # one scale per row of X (linear) / X0 (BGEMM)
 ROWS_OPERAND1 = 2          # one scale per row of W (linear) / X1 (BGEMM)
+ROWS_COMPUTE0 = 4          # operand 0: one scale per row, computed by the sensitivity pass itself (single read)
+ROWS_COMPUTE1 = 8          # operand 1 of a BGEMM, likewise
 PLAN_STREAM_WEIGHTS = 1    # amp_sens_block_setup flag: read W with every sample's gradient
 
 

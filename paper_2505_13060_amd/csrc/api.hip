@@ -65,7 +65,7 @@ int persistent_grid(uint64_t n_chunks, int resident, int limit) {
 
 int sens_resident(int n_fmts, int f0, int f1, int cls) {
     static std::mutex mu;
-    static int cached[64][2][2][2][4];
+    static int cached[64][2][2][2][kSensClasses];
     const int dev = device_index();
     if (dev < 0) return sens_resident_blocks(n_fmts, f0, f1, cls, device_cus());
     std::lock_guard<std::mutex> lock(mu);
@@ -109,7 +109,7 @@ struct PlanData {
     float* d_out;
     uint32_t w_groups[2], w_items[2];
     uint64_t w_pairs[2], w_bytes[2];
-    uint64_t class_pos[5], class_pairs[4];
+    uint64_t class_pos[kSensClasses + 1], class_pairs[kSensClasses];
     // absmax, per tensor and per row
     float *d_amax, *d_scale, *d_inv;
     uint32_t* d_flags;
@@ -172,8 +172,8 @@ amp_status_t sens_setup(const WorkTable& t, const amp_fp8_format_t* fmts, int n_
         P->w_pairs[v] = plan.w_pairs[v];
         P->w_bytes[v] = plan.w_bytes[v];
     }
-    for (int c = 0; c < 5; ++c) P->class_pos[c] = plan.class_pos[c];
-    for (int c = 0; c < 4; ++c) P->class_pairs[c] = plan.class_pairs[c];
+    for (int c = 0; c <= kSensClasses; ++c) P->class_pos[c] = plan.class_pos[c];
+    for (int c = 0; c < kSensClasses; ++c) P->class_pairs[c] = plan.class_pairs[c];
     AMP_HIP(launch_prepare((const WorkUnit*)ws, (const uint32_t*)(ws + P->off_cb),
                            (const UnitSchedule*)(ws + t.schedule_offset()), P->n_units, P->n_chunks,
                            (ResolvedUnit*)(ws + L.runits), (ChunkRef*)(ws + L.map), stream));
@@ -188,7 +188,7 @@ amp_status_t sens_run(const PlanData& P, hipStream_t stream) {
     const ChunkRef* d_map = (const ChunkRef*)(ws + P.off_map);
     float* d_partials = (float*)(ws + P.off_partials);
     const WGroup* d_groups = (const WGroup*)(ws + P.off_groups);
-    const int nf = P.n_fmts, f0 = P.fmt0, f1 = P.fmt1;
+    const int nf = P.n_fmts, f0 = P.fmt0 & 0xFF, f1 = P.fmt1 & 0xFF;     // fmt0 / fmt1 may carry the scale rule
     AMP_HIP(launch_resolve(d_units, P.n_units, nf, d_runits, stream));
     // one pair of events around a fused kernel while the profile has room
     auto timed = [&](uint64_t pairs, uint64_t bytes, auto&& launch) -> hipError_t {
@@ -220,13 +220,13 @@ amp_status_t sens_run(const PlanData& P, hipStream_t stream) {
         g0 += P.w_groups[v];
     }
     // streaming kernels, one launch per class of units
-    for (int cls = 0; cls < 4; ++cls) {
+    for (int cls = 0; cls < kSensClasses; ++cls) {
         const uint64_t n_pos = P.class_pos[cls + 1] - P.class_pos[cls];
         if (n_pos == 0) continue;
         const int grid = persistent_grid(n_pos, sens_resident(nf, f0, f1, cls), P.grid_limit);
         AMP_HIP(timed(P.class_pairs[cls], P.class_pairs[cls] * 4, [&]() {
-            return launch_sens(d_runits, d_map + P.class_pos[cls], (uint32_t)n_pos, nf, f0, f1, cls, d_partials,
-                               grid, stream);
+            return launch_sens(d_runits, d_map + P.class_pos[cls], (uint32_t)n_pos, nf, P.fmt0, P.fmt1, cls,
+                               d_partials, grid, stream);
         }));
     }
     AMP_HIP(launch_sens_finalize(d_runits, d_cb, P.n_units, nf, d_partials, P.d_out, stream));
@@ -499,7 +499,7 @@ amp_status_t amp_sens_block_setup(const amp_linear_desc_t* linears, int n_linear
                                   amp_plan_t* plan) {
     if (!plan) return AMP_ERR_INVALID_ARG;
     std::memset(plan, 0, sizeof(*plan));
-    amp_status_t st = check_fmts(fmts, n_fmts);
+    amp_status_t st = check_fmts(fmts, n_fmts, true);
     if (st != AMP_OK) return st;
     WorkTable t;
     st = build_block(linears, n_linears, bgemms, n_bgemms, n_fmts, &t);
@@ -524,7 +524,7 @@ amp_status_t amp_sens_block(const amp_linear_desc_t* linears, int n_linears, con
 amp_status_t amp_sens_block_static(const amp_linear_desc_t* linears, int n_linears, const amp_bgemm_desc_t* bgemms,
                                    int n_bgemms, const amp_fp8_format_t* fmts, int n_fmts, float* d_out,
                                    void* stream) {
-    amp_status_t st = check_fmts(fmts, n_fmts);
+    amp_status_t st = check_fmts(fmts, n_fmts, true);
     if (st != AMP_OK) return st;
     WorkTable t;
     st = build_block(linears, n_linears, bgemms, n_bgemms, n_fmts, &t);

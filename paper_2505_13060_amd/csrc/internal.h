@@ -36,7 +36,58 @@ enum : uint32_t {
                                      // first row is the unit's first row; dense units keep the row
                                      // length in `cols` and their number of rows in `rows`, causal
                                      // units use their own rows and cols
+    kUnitFused = 16u,                // with kUnitRowScale: the pass itself computes the row scales (each row
+                                     // is read once, kept in registers, reduced, scaled) and writes them to
+                                     // the tables; `head` holds the FusedGeom of the unit
 };
+
+// Single-read pass over an operand with one scale per row: a workgroup handles a tile of
+// rows_per_tile = 256 / lanes rows at a time, `lanes` (a power of two, 16..256) threads per row, each
+// thread keeping up to `nv` (<= 16) 8-element vectors of its row in registers; a chunk is
+// `tiles` consecutive tiles (dense) or `tiles` slots of a lower triangle, a slot being tile t of a
+// matrix and its mirror tile T - 1 - t (equal work per slot).
+constexpr int kFusedMaxNv = 16;
+constexpr int kFusedShortNv = 2;             // units with nv <= this go to the short-row variant,
+constexpr int kFusedMidNv = 8;               // with nv <= this to the middle one (fewer registers, more waves)
+constexpr int kFusedMinLanesLog2 = 4;
+constexpr int64_t kFusedMaxRowLen = (int64_t)kWG * kFusedMaxNv * kVec;     // 32768 elements
+struct FusedGeom {
+    int lanes_log2, nv, tiles;
+    __host__ __device__ uint32_t pack() const { return (uint32_t)lanes_log2 | ((uint32_t)nv << 8) | ((uint32_t)tiles << 16); }
+    static __host__ __device__ FusedGeom unpack(uint32_t h) {
+        FusedGeom g;
+        g.lanes_log2 = (int)(h & 0xFFu);
+        g.nv = (int)((h >> 8) & 0xFFu);
+        g.tiles = (int)(h >> 16);
+        return g;
+    }
+    __host__ __device__ int rows_per_tile() const { return kWG >> lanes_log2; }
+};
+// Geometry for rows of row_len elements (a multiple of 8, at most kFusedMaxRowLen): about eight
+// vectors per thread, about 4096 vectors per chunk.
+inline FusedGeom fused_geometry(int64_t row_len, bool causal) {
+    const int64_t row_vecs = row_len / kVec;
+    FusedGeom g;
+    g.lanes_log2 = kFusedMinLanesLog2;
+    while (g.lanes_log2 < 8 && ((int64_t)8 << g.lanes_log2) < row_vecs) ++g.lanes_log2;
+    const int64_t lanes = (int64_t)1 << g.lanes_log2;
+    g.nv = (int)((row_vecs + lanes - 1) / lanes);
+    if (g.nv < 1) g.nv = 1;
+    // vectors per tile (dense) or per slot (causal: two tiles of, together, one full row length per row pair)
+    const int64_t per = (int64_t)g.rows_per_tile() * (causal ? row_vecs + 1 : row_vecs);
+    int64_t t = per > 0 ? (kChunkVecs + per / 2) / per : 1;
+    g.tiles = (int)(t < 1 ? 1 : (t > 64 ? 64 : t));
+    return g;
+}
+inline uint64_t fused_chunks_dense(int64_t rows, const FusedGeom& g) {
+    const uint64_t per = (uint64_t)g.rows_per_tile() * (uint64_t)g.tiles;
+    return rows > 0 ? ((uint64_t)rows + per - 1) / per : 0;
+}
+inline uint32_t fused_chunks_per_mat(int64_t rows, const FusedGeom& g) {
+    const uint64_t tiles = ((uint64_t)rows + g.rows_per_tile() - 1) / g.rows_per_tile();
+    const uint64_t slots = (tiles + 1) / 2;
+    return (uint32_t)((slots + g.tiles - 1) / g.tiles);
+}
 
 struct alignas(16) WorkUnit {        // 64 bytes
     const uint16_t* x;               // first element of the block
@@ -137,7 +188,9 @@ inline uint32_t causal_chunks_per_mat(int64_t rows) {
 // Persistent-grid size for the streaming kernels on the current device (resident workgroups).
 // cls: the class of units the variant is for: 0 = one scale per tensor; 1 = row scales, rows of at
 // least 512 elements or aligned causal rows; 2 = row scales, any other shape; 3 = row scales, rows
-// of a power-of-two length below 512.
+// of a power-of-two length below 512; 4 / 5 / 6 = row scales computed by the pass itself (single read),
+// up to kFusedMidNv / kFusedShortNv / kFusedMaxNv vectors of a row per thread.
+constexpr int kSensClasses = 7;
 int sens_resident_blocks(int n_fmts, int fmt0, int fmt1, int cls, int cus);
 int absmax_resident_blocks(int cus);
 int absmax_rows_resident_blocks(int cus);
@@ -162,6 +215,7 @@ hipError_t launch_absmax_finalize(const uint32_t* d_chunk_begin, const uint32_t*
                                   hipStream_t stream);
 hipError_t launch_fake_quant(const uint16_t* d_x, int64_t n, float scale, float inv, int fmt,
                              uint8_t* d_codes, float* d_dequant, int grid, hipStream_t stream);
+// fmt0 / fmt1 may carry the scale-rule flag (used by classes 4 and 5 only, which compute scales).
 hipError_t launch_sens(const ResolvedUnit* d_runits, const ChunkRef* d_map, uint32_t n_chunks,
                        int n_fmts, int fmt0, int fmt1, int rows, float* d_partials, int grid,
                        hipStream_t stream);

@@ -1168,6 +1168,229 @@ __global__ __launch_bounds__(kWG) void absmax_rows_kernel(const RowTensor* __res
     }
 }
 
+// ---- the single-read pass for operands with one scale per row ------------------------------------
+// The row-scaled pass without a separate absmax pass: a workgroup takes a tile of rows, `lanes`
+// threads per row; every thread loads its (up to NVMAX) vectors of the row once and keeps them in
+// registers, the row's absmax is reduced over its threads (cross-lane moves inside a wave, LDS and one
+// barrier when a row spans several waves), the scales of every format are derived with the
+// arithmetic of write_scales, written to the operand's tables by one thread per row, and the row's
+// gradient is streamed against the resident row.  Geometry per unit: FusedGeom in `head`.
+// Causal units: a slot is tile t of a matrix and its mirror tile T - 1 - t; the vector holding a
+// row's end is loaded whole and the entries past the end are cleared before any arithmetic.
+
+// One of the four numbers write_scales derives from a row's amax: scale (want_inv false) or
+// reciprocal (true) of format `code` (which may carry kScalePow2).  Same results bit for bit; the
+// case "the reciprocal overflows fp32, so both are 1" is decided from amax alone: FMAX / amax rounds
+// to infinity exactly for amax <= 1.75 * 2^-120 (E4M3, bits 0x03E0) and 1.75 * 2^-113 (E5M2, 0x0760).
+__device__ __forceinline__ float scale_quantity(uint32_t bits, int code, bool want_inv) {
+    const int fmt = code & 0xFF;
+    if (code & kScalePow2) {
+        const int e_field = (int)(bits >> 7) & 0xFF;
+        if (e_field == 0 || e_field == 0xFF) return 1.0f;
+        const int k = e_field - 127 - (fmt == 0 ? 8 : 15) + ((bits & 0x7Fu) > 96u ? 1 : 0);
+        if (k < -127 || k > 127) return 1.0f;
+        if (want_inv) return __uint_as_float((uint32_t)(127 - k) << 23);
+        return k >= -126 ? __uint_as_float((uint32_t)(k + 127) << 23) : __uint_as_float(1u << (k + 149));
+    }
+    if (bits <= (fmt == 0 ? 0x03E0u : 0x0760u)) return 1.0f;     // amax == 0, or the reciprocal would be infinite
+    const float amax = __uint_as_float(bits << 16);
+    const float fm = fmax_of(fmt);
+    return want_inv ? fm / amax : amax / fm;
+}
+
+template <int CTRL>
+__device__ __forceinline__ float quad_broadcast(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
+}
+
+template <int NF, int F0, int F1, int NVMAX>
+struct FusedRows {
+    gptr16_t x, g;
+    float* ts;                                     // scale[row][NF]
+    float* ti;                                     // inv[row][NF]
+    int32_t cols;
+    int lanes_log2, nv;
+    int j, rt;                                     // this thread's lane inside its row, its row inside the tile
+    int code0, code1;
+    float E[NF], A;
+    int pk[NF];
+    uint32_t* red;                                 // LDS, [2][kWaves]: wave maxima of rows that span waves
+    int parity;
+
+    __device__ __forceinline__ void quad(uint32_t xw0, uint32_t xw1, uint32_t gw0, uint32_t gw1,
+                                         const float (&iv)[NF], const float (&sc)[NF]) {
+        const float xv[4] = {bf16_lo(xw0), bf16_hi(xw0), bf16_lo(xw1), bf16_hi(xw1)};
+        const float gv[4] = {bf16_lo(gw0), bf16_hi(gw0), bf16_lo(gw1), bf16_hi(gw1)};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float a = gv[q] * xv[q];
+            A = fmaf(a, a, A);
+        }
+        one_format<F0>(xv, gv, iv[0], sc[0], E[0], pk[0]);
+        if constexpr (NF > 1) one_format<F1>(xv, gv, iv[1], sc[1], E[1], pk[1]);
+    }
+
+    // One row per group of `lanes` threads: row `row` of the unit (table index), `len` valid
+    // elements starting at element `e0` of the unit; live = this thread's row exists.
+    __device__ __forceinline__ void row(int64_t row, int64_t e0, int32_t len, bool live) {
+        const int L = 1 << lanes_log2;
+        const int nvr = live ? (len + kVec - 1) / kVec : 0;
+        const int tail = len - (nvr - 1) * kVec;
+        const gptr128_t px = reinterpret_cast<gptr128_t>(x + e0);
+        const gptr128_t pg = reinterpret_cast<gptr128_t>(g + e0);
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+        u32x4 xr[NVMAX];
+#pragma unroll
+        for (int k = 0; k < NVMAX; ++k) {
+            const int v = j + (k << lanes_log2);
+            xr[k] = (k < nv && v < nvr) ? load128<true>(px + v) : zero;
+        }
+        if (tail < kVec) {
+#pragma unroll
+            for (int k = 0; k < NVMAX; ++k)
+                if (k < nv && j + (k << lanes_log2) == nvr - 1) xr[k] = keep_leading(xr[k], tail);
+        }
+        // absmax of the row: packed 16-bit maxima per thread, then across the row's threads
+        uint32_t m2 = 0;
+#pragma unroll
+        for (int k = 0; k < NVMAX; ++k) {
+            const uint32_t w[4] = {xr[k].x, xr[k].y, xr[k].z, xr[k].w};
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const u16x2 a = __builtin_bit_cast(u16x2, m2), b = __builtin_bit_cast(u16x2, w[q] & 0x7FFF7FFFu);
+                m2 = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(a, b));
+            }
+        }
+        uint32_t m = (m2 & 0xFFFFu) > (m2 >> 16) ? (m2 & 0xFFFFu) : (m2 >> 16);
+        for (int o = 1; o < L && o < 64; o <<= 1) {
+            const uint32_t w = (uint32_t)__shfl_xor((int)m, o);
+            m = m > w ? m : w;
+        }
+        if (lanes_log2 > 6) {                          // the row spans 2 or 4 waves (uniform over the workgroup)
+            const int wave = threadIdx.x >> 6;
+            if ((threadIdx.x & 63) == 0) red[parity * kWaves + wave] = m;
+            __syncthreads();
+            const int w0 = lanes_log2 == 7 ? (wave & 2) : 0, wn = lanes_log2 == 7 ? 2 : 4;
+            for (int w = 0; w < wn; ++w) {
+                const uint32_t v = red[parity * kWaves + w0 + w];
+                m = m > v ? m : v;
+            }
+            parity ^= 1;
+        }
+        // the scales: each thread of a quad derives one of (scale_0, inv_0, scale_1, inv_1), then the quad shares them
+        float sc[NF], iv[NF];
+        {
+            const int q = j & 3;
+            const int f = NF > 1 ? (q >> 1) : 0;
+            const float mine = scale_quantity(m, f == 0 ? code0 : code1, (q & 1) != 0);
+            sc[0] = quad_broadcast<0x00>(mine);
+            iv[0] = quad_broadcast<0x55>(mine);
+            if constexpr (NF > 1) {
+                sc[1] = quad_broadcast<0xAA>(mine);
+                iv[1] = quad_broadcast<0xFF>(mine);
+            }
+        }
+        if (live && j == 0) {
+#pragma unroll
+            for (int f = 0; f < NF; ++f) {
+                ts[row * NF + f] = sc[f];
+                ti[row * NF + f] = iv[f];
+            }
+        }
+        // the gradient against the resident row, four vectors in flight at a time
+#pragma unroll
+        for (int k0 = 0; k0 < NVMAX; k0 += 4) {
+            u32x4 gr[4];
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                const int k = k0 + kk;
+                const int v = j + (k << lanes_log2);
+                gr[kk] = (k < NVMAX && k < nv && v < nvr) ? load128<true>(pg + v) : zero;
+            }
+            if (tail < kVec) {
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk)
+                    if (k0 + kk < nv && j + ((k0 + kk) << lanes_log2) == nvr - 1) gr[kk] = keep_leading(gr[kk], tail);
+            }
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                const int k = k0 + kk;
+                if (k < NVMAX && k < nv) {               // absent vectors are (0, 0): they add exactly 0
+                    quad(xr[k].x, xr[k].y, gr[kk].x, gr[kk].y, iv, sc);
+                    quad(xr[k].z, xr[k].w, gr[kk].z, gr[kk].w, iv, sc);
+                }
+            }
+        }
+    }
+};
+
+template <int NF, int F0, int F1, int NVMAX>
+__global__ __launch_bounds__(kWG) void sens_fused_rows_kernel(const ResolvedUnit* __restrict__ runits,
+                                                              const ChunkRef* __restrict__ map, uint32_t n_chunks,
+                                                              float* __restrict__ partials, int code0, int code1) {
+    __shared__ uint32_t red[2 * kWaves];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    for (uint32_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+        const ChunkRef ref = map[c];
+        const ResolvedUnit u = runits[ref.unit];
+        const FusedGeom geo = FusedGeom::unpack(u.head);
+        FusedRows<NF, F0, F1, NVMAX> ctx;
+        ctx.x = (gptr16_t)u.x;
+        ctx.g = (gptr16_t)u.dx;
+        ctx.ts = const_cast<float*>(u.row_scale);
+        ctx.ti = const_cast<float*>(u.row_inv);
+        ctx.cols = u.cols;
+        ctx.lanes_log2 = geo.lanes_log2;
+        ctx.nv = geo.nv < NVMAX ? geo.nv : NVMAX;
+        ctx.j = tid & ((1 << geo.lanes_log2) - 1);
+        ctx.rt = tid >> geo.lanes_log2;
+        ctx.code0 = code0;
+        ctx.code1 = code1;
+        ctx.red = red;
+        ctx.parity = 0;
+#pragma unroll
+        for (int f = 0; f < NF; ++f) { ctx.E[f] = 0.0f; ctx.pk[f] = 0; }
+        ctx.A = 0.0f;
+        const int RT = geo.rows_per_tile();
+        if (!(u.flags & kUnitCausal)) {
+            const int64_t t0 = (int64_t)ref.local * geo.tiles;
+            for (int t = 0; t < geo.tiles; ++t) {
+                const int64_t r0 = (t0 + t) * RT;
+                if (r0 >= u.rows) break;                            // uniform over the workgroup
+                const int64_t r = r0 + ctx.rt;
+                const bool live = r < u.rows;
+                ctx.row(live ? r : 0, (live ? r : 0) * (int64_t)u.cols, u.cols, live);
+            }
+        } else {
+            const uint32_t mat = ref.local / u.chunks_per_mat;
+            const int32_t slot0 = (int32_t)(ref.local % u.chunks_per_mat) * geo.tiles;
+            const int32_t T = (u.rows + RT - 1) / RT;
+            for (int s = 0; s < geo.tiles; ++s) {
+                const int32_t slot = slot0 + s, mirror = T - 1 - slot;
+                if (slot > mirror) break;                           // uniform over the workgroup
+                for (int h = 0; h < 2; ++h) {
+                    if (h == 1 && mirror == slot) break;
+                    const int32_t i = (h == 0 ? slot : mirror) * RT + ctx.rt;
+                    const bool live = i < u.rows;
+                    const int64_t r = (int64_t)mat * u.rows + (live ? i : 0);
+                    ctx.row(r, r * (int64_t)u.cols, live ? causal_row_len(i, u.rows, u.cols) : 0, live);
+                }
+            }
+        }
+        float v[NF + 1];
+#pragma unroll
+        for (int f = 0; f < NF; ++f) v[f] = wave_sum(ctx.E[f]);
+        v[NF] = wave_sum(ctx.A);
+        if (lane == 0) {
+            float* slot = partials + ((size_t)ref.slot * kWaves + wave) * (NF + 1);
+#pragma unroll
+            for (int k = 0; k <= NF; ++k) slot[k] = v[k];
+        }
+        __syncthreads();                                            // the LDS words are free for the next chunk
+    }
+}
+
 // ---- standalone fake quantisation -------------------------------------------------------------
 
 template <int FMT>
@@ -1213,6 +1436,19 @@ __global__ __launch_bounds__(kWG) void fake_quant_kernel(const uint16_t* __restr
 // ---- launch helpers -----------------------------------------------------------------------------
 
 typedef void (*sens_fn_t)(const ResolvedUnit*, const ChunkRef*, uint32_t, float*);
+typedef void (*sens_fused_fn_t)(const ResolvedUnit*, const ChunkRef*, uint32_t, float*, int, int);
+
+template <int NVMAX>
+sens_fused_fn_t sens_fused_variant_of(int n_fmts, int fmt0, int fmt1) {
+    if (n_fmts == 1) return fmt0 == 0 ? sens_fused_rows_kernel<1, 0, 0, NVMAX> : sens_fused_rows_kernel<1, 1, 1, NVMAX>;
+    if (fmt0 == 0) return fmt1 == 0 ? sens_fused_rows_kernel<2, 0, 0, NVMAX> : sens_fused_rows_kernel<2, 0, 1, NVMAX>;
+    return fmt1 == 0 ? sens_fused_rows_kernel<2, 1, 0, NVMAX> : sens_fused_rows_kernel<2, 1, 1, NVMAX>;
+}
+sens_fused_fn_t sens_fused_variant(int n_fmts, int fmt0, int fmt1, int cls) {
+    if (cls == 5) return sens_fused_variant_of<kFusedShortNv>(n_fmts, fmt0, fmt1);
+    if (cls == 4) return sens_fused_variant_of<kFusedMidNv>(n_fmts, fmt0, fmt1);
+    return sens_fused_variant_of<kFusedMaxNv>(n_fmts, fmt0, fmt1);
+}
 
 sens_fn_t sens_variant(int n_fmts, int fmt0, int fmt1, int cls) {
     if (cls == 1) {
@@ -1245,6 +1481,7 @@ int resident_blocks(const void* fn, int cus) {
 }  // namespace
 
 int sens_resident_blocks(int n_fmts, int fmt0, int fmt1, int rows, int cus) {
+    if (rows >= 4) return resident_blocks((const void*)sens_fused_variant(n_fmts, fmt0, fmt1, rows), cus);
     return resident_blocks((const void*)sens_variant(n_fmts, fmt0, fmt1, rows), cus);
 }
 
@@ -1351,8 +1588,12 @@ hipError_t launch_fake_quant(const uint16_t* d_x, int64_t n, float scale, float 
 hipError_t launch_sens(const ResolvedUnit* d_runits, const ChunkRef* d_map, uint32_t n_chunks,
                        int n_fmts, int fmt0, int fmt1, int rows, float* d_partials, int grid,
                        hipStream_t stream) {
-    hipLaunchKernelGGL(sens_variant(n_fmts, fmt0, fmt1, rows), dim3(grid), dim3(kWG), 0, stream, d_runits,
-                       d_map, n_chunks, d_partials);
+    if (rows >= 4)
+        hipLaunchKernelGGL(sens_fused_variant(n_fmts, fmt0 & 0xFF, fmt1 & 0xFF, rows), dim3(grid), dim3(kWG), 0, stream,
+                           d_runits, d_map, n_chunks, d_partials, fmt0, fmt1);
+    else
+        hipLaunchKernelGGL(sens_variant(n_fmts, fmt0 & 0xFF, fmt1 & 0xFF, rows), dim3(grid), dim3(kWG), 0, stream,
+                           d_runits, d_map, n_chunks, d_partials);
     return hipGetLastError();
 }
 

@@ -72,7 +72,7 @@ struct WorkTable {
     // x / dx may be null only for blocks without elements.
     amp_status_t add(const uint16_t* x, const uint16_t* dx, const amp_layout_t& L, int64_t batch_mul,
                      const float* scale, const float* inv, uint32_t out, uint32_t extra_flags = 0,
-                     uint32_t group_id = 0, int64_t row_len = 0) {
+                     uint32_t group_id = 0, int64_t row_len = 0, bool fused = false) {
         // row_len != 0: scale / inv are [rows][n_fmts] tables starting at this unit's first row;
         // a dense unit is [n / row_len, row_len], a causal unit uses its own rows (row_len = cols).
         WorkUnit u;
@@ -82,6 +82,14 @@ struct WorkTable {
         if (row_len != 0) {
             u.flags |= kUnitRowScale;
             any_rows = true;
+        }
+        // fused: the pass computes the row scales itself (scale / inv are then outputs); only for rows
+        // made of whole, aligned vectors that fit a workgroup's registers
+        if (fused) {
+            const int64_t len = L.causal ? L.cols : row_len;
+            const bool nice = ((uintptr_t)x % 16 == 0) && ((uintptr_t)dx % 16 == 0) && len % kVec == 0;
+            if (row_len == 0 || !nice || len > kFusedMaxRowLen) return AMP_ERR_INVALID_ARG;
+            u.flags |= kUnitFused;
         }
         uint64_t chunks;
         if (L.causal) {
@@ -94,6 +102,11 @@ struct WorkTable {
                               (L.cols % kVec == 0);
             if (!nice) u.flags |= kUnitScalar;
             u.chunks_per_mat = (L.rows > 0 && L.cols > 0) ? causal_chunks_per_mat(L.rows) : 0;
+            if (fused) {
+                const FusedGeom g = fused_geometry(L.cols, true);
+                u.head = g.pack();
+                u.chunks_per_mat = (L.rows > 0 && L.cols > 0) ? fused_chunks_per_mat(L.rows, g) : 0;
+            }
             chunks = (uint64_t)batch * u.chunks_per_mat;
             if (chunks == 0) u.chunks_per_mat = 1;         // never divide by zero on the device
             const uint64_t valid = causal_valid(L.rows, L.cols);
@@ -115,6 +128,11 @@ struct WorkTable {
             }
             u.chunks_per_mat = 1;
             chunks = unit_chunks_dense(n, u.head);
+            if (fused) {
+                const FusedGeom g = fused_geometry(row_len, false);
+                u.head = g.pack();
+                chunks = fused_chunks_dense(u.rows, g);
+            }
             n_pairs += (uint64_t)n;
             unit_pairs.push_back((uint64_t)n);
         }
@@ -152,6 +170,10 @@ struct WorkTable {
     // 2 = any other unit with row scales (other short rows, rows not made of whole vectors).
     static int unit_class(const WorkUnit& u) {
         if (!(u.flags & kUnitRowScale)) return 0;
+        if (u.flags & kUnitFused) {
+            const int nv = FusedGeom::unpack(u.head).nv;
+            return nv <= kFusedShortNv ? 5 : (nv <= kFusedMidNv ? 4 : 6);
+        }
         if (u.flags & kUnitScalar) return 2;
         if (u.flags & kUnitCausal) return 1;
         if (u.cols >= kVec * 64) return 1;
@@ -164,8 +186,8 @@ struct WorkTable {
         std::vector<WGroup> wgroups;              // work of the weight kernel: groups with one scale per
                                                   // tensor first, then those with row scales; item_begin
                                                   // counts from the first item of the group's launch
-        uint64_t class_pos[5] = {0, 0, 0, 0, 0};     // streaming kernel of class c: positions [class_pos[c], class_pos[c+1])
-        uint64_t class_pairs[4] = {0, 0, 0, 0};
+        uint64_t class_pos[kSensClasses + 1] = {};   // streaming kernel of class c: positions [class_pos[c], class_pos[c+1])
+        uint64_t class_pairs[kSensClasses] = {};
         uint64_t n_positions = 0;
         size_t w_groups[2] = {0, 0};              // weight kernel launch v: groups, items, pairs, bytes
         uint64_t w_items[2] = {0, 0};
@@ -184,7 +206,7 @@ struct WorkTable {
         for (size_t u = 0; u < units.size(); ++u)
             if (group[u] != 0) by_group[group[u]].push_back(u);
         std::vector<char> done(units.size(), 0);
-        for (int cls = 0; cls < 4; ++cls) {
+        for (int cls = 0; cls < kSensClasses; ++cls) {
             P.class_pos[cls] = P.n_positions;
             for (size_t u = 0; u < units.size(); ++u) {
                 if (done[u] || unit_class(units[u]) != cls) continue;
@@ -233,7 +255,7 @@ struct WorkTable {
                 P.n_positions += (chunks_of(u) - skip) * members.size();
             }
         }
-        P.class_pos[4] = P.n_positions;
+        P.class_pos[kSensClasses] = P.n_positions;
         return P;
     }
 
@@ -286,8 +308,12 @@ inline amp_status_t build_linear(const amp_linear_desc_t* ops, int n_ops, int n_
     for (int k = 0; k < n_ops; ++k) {
         const amp_linear_desc_t& op = ops[k];
         if (op.R < 0 || op.C < 0 || op.K < 0 || op.tokens < 0) return AMP_ERR_INVALID_ARG;
-        if (op.scale_rows & ~(AMP_ROWS_OPERAND0 | AMP_ROWS_OPERAND1)) return AMP_ERR_INVALID_ARG;
-        const bool x_rows = (op.scale_rows & AMP_ROWS_OPERAND0) != 0, w_rows = (op.scale_rows & AMP_ROWS_OPERAND1) != 0;
+        // a weight is shared by the samples and small next to its R gradients: its row scales come from
+        // amp_absmax_scale_rows, only the activations' can be computed by the pass itself
+        if (op.scale_rows & ~(AMP_ROWS_OPERAND0 | AMP_ROWS_OPERAND1 | AMP_ROWS_COMPUTE0)) return AMP_ERR_INVALID_ARG;
+        const bool x_fused = (op.scale_rows & AMP_ROWS_COMPUTE0) != 0;
+        const bool x_rows = (op.scale_rows & AMP_ROWS_OPERAND0) != 0 || x_fused;
+        const bool w_rows = (op.scale_rows & AMP_ROWS_OPERAND1) != 0;
         if ((x_rows || w_rows) && op.C > kMaxDim) return AMP_ERR_TOO_LARGE;
         if (op.C > kMaxElems || op.K > kMaxElems || (op.C && op.K > kMaxElems / op.C)) return AMP_ERR_TOO_LARGE;
         if (!aligned2(op.x) || !aligned2(op.dx) || !aligned2(op.w) || !aligned2(op.dw)) return AMP_ERR_INVALID_ARG;
@@ -315,7 +341,7 @@ inline amp_status_t build_linear(const amp_linear_desc_t* ops, int n_ops, int n_
             const int64_t xs = x_rows ? r0 * n_fmts : 0;         // the sample's first token in the table
             amp_status_t st = t->add(xn ? op.x + r0 * op.C : op.x, xn ? op.dx + r0 * op.C : op.dx, Lx, 1,
                                      op.x_scale ? op.x_scale + xs : op.x_scale, op.x_inv ? op.x_inv + xs : op.x_inv,
-                                     (uint32_t)o, 0u, 0u, x_rows && xn > 0 ? op.C : 0);
+                                     (uint32_t)o, 0u, 0u, x_rows && xn > 0 ? op.C : 0, x_fused && xn > 0);
             if (st != AMP_OK) return st;
             st = t->add(op.w, wn ? op.dw + (int64_t)r * wn : op.dw, Lw, 1, op.w_scale, op.w_inv, (uint32_t)o + 2,
                         op.R > 1 ? kUnitKeepX : 0u, op.R > 1 ? (uint32_t)k + 1u : 0u, w_rows && wn > 0 ? op.C : 0);
@@ -359,13 +385,15 @@ inline amp_status_t build_bgemm(const amp_bgemm_desc_t* ops, int n_ops, int n_fm
         if (op.R > 0 && n0 > 0 && (!op.x0 || !op.dx0 || !op.scale0 || !op.inv0)) return AMP_ERR_INVALID_ARG;
         if (op.R > 0 && n1 > 0 && (!op.x1 || !op.dx1 || !op.scale1 || !op.inv1)) return AMP_ERR_INVALID_ARG;
         if (op.R > 0 && (n0 > kMaxElems / op.R || n1 > kMaxElems / op.R)) return AMP_ERR_TOO_LARGE;
-        if (op.scale_rows & ~(AMP_ROWS_OPERAND0 | AMP_ROWS_OPERAND1)) return AMP_ERR_INVALID_ARG;
+        if (op.scale_rows & ~(AMP_ROWS_OPERAND0 | AMP_ROWS_OPERAND1 | AMP_ROWS_COMPUTE0 | AMP_ROWS_COMPUTE1))
+            return AMP_ERR_INVALID_ARG;
+        const bool fused0 = (op.scale_rows & AMP_ROWS_COMPUTE0) != 0, fused1 = (op.scale_rows & AMP_ROWS_COMPUTE1) != 0;
         int64_t len0 = 0, len1 = 0, rows0 = 0, rows1 = 0;    // row length and rows per sample, 0 = one scale
-        if (op.scale_rows & AMP_ROWS_OPERAND0) {
+        if ((op.scale_rows & AMP_ROWS_OPERAND0) || fused0) {
             st = row_geometry(op.layout0, &len0, &rows0);
             if (st != AMP_OK) return st;
         }
-        if (op.scale_rows & AMP_ROWS_OPERAND1) {
+        if ((op.scale_rows & AMP_ROWS_OPERAND1) || fused1) {
             st = row_geometry(op.layout1, &len1, &rows1);
             if (st != AMP_OK) return st;
         }
@@ -375,11 +403,11 @@ inline amp_status_t build_bgemm(const amp_bgemm_desc_t* ops, int n_ops, int n_fm
             const int64_t s0 = r * rows0 * n_fmts, s1 = r * rows1 * n_fmts;
             st = t->add(n0 ? op.x0 + r * n0 : op.x0, n0 ? op.dx0 + r * n0 : op.dx0, op.layout0, 1,
                         op.scale0 ? op.scale0 + s0 : op.scale0, op.inv0 ? op.inv0 + s0 : op.inv0, (uint32_t)o, 0u, 0u,
-                        n0 > 0 ? len0 : 0);
+                        n0 > 0 ? len0 : 0, fused0 && n0 > 0);
             if (st != AMP_OK) return st;
             st = t->add(n1 ? op.x1 + r * n1 : op.x1, n1 ? op.dx1 + r * n1 : op.dx1, op.layout1, 1,
                         op.scale1 ? op.scale1 + s1 : op.scale1, op.inv1 ? op.inv1 + s1 : op.inv1, (uint32_t)o + 2, 0u,
-                        0u, n1 > 0 ? len1 : 0);
+                        0u, n1 > 0 ? len1 : 0, fused1 && n1 > 0);
             if (st != AMP_OK) return st;
         }
         base += (uint64_t)op.R;

@@ -7,7 +7,7 @@ tensors allocated once; every number is produced by libampsens' kernels.
 import numpy as np
 import torch
 
-from . import (ROWS_OPERAND0, ROWS_OPERAND1, amp_absmax_rows_workspace_bytes, amp_absmax_scale,
+from . import (ROWS_COMPUTE0, ROWS_COMPUTE1, ROWS_OPERAND0, ROWS_OPERAND1, amp_absmax_rows_workspace_bytes, amp_absmax_scale,
                amp_absmax_scale_rows, amp_absmax_scale_rows_setup, amp_absmax_scale_setup,
                amp_absmax_workspace_bytes, amp_plan_limit_grid, amp_run, amp_sens_bgemm,
                amp_sens_bgemm_workspace_bytes, amp_sens_block, amp_sens_block_setup,
@@ -146,7 +146,11 @@ class RowSensPass:
     scale per tensor go through amp_absmax_scale as in SensPass."""
 
     def __init__(self, workload, device, x_rows=True, w_rows=True, bgemm_rows=True, one_call=False, plan=False,
-                 flags=0):
+                 flags=0, single_read=False):
+        """single_read: the row scales of the activations and of the BGEMM operands are computed by the
+        sensitivity pass itself (AMP_ROWS_COMPUTE0 / 1: every row is fetched once); only the weights'
+        per-channel scales then come from amp_absmax_scale_rows."""
+        self.single_read = single_read
         self.plan = plan or flags != 0
         one_call = one_call or self.plan
         self.one_call = one_call
@@ -162,14 +166,18 @@ class RowSensPass:
             for side, (x, lay) in enumerate(((op.x0, op.lay0), (op.x1, op.lay1))):
                 t = tensor(x, _layout(lay, x.shape[-1]), op.R)
                 (per_row if bgemm_rows else per_tensor).append((("bg", k, side), t))
+        # operands whose row scales the sensitivity pass computes itself: their tables sit behind the others'
+        self.computed = set(key for key, _ in per_row if single_read and (key[0] == "bg" or key[2] == 0))
+        per_row = [kt for kt in per_row if kt[0] not in self.computed] + [kt for kt in per_row if kt[0] in self.computed]
         self.t_tensors = [t for _, t in per_tensor]
-        self.r_tensors = [t for _, t in per_row]
+        self.r_tensors = [t for key, t in per_row if key not in self.computed]
         nt = max(len(self.t_tensors), 1)
         self.d_amax = torch.zeros(nt, **f32)
         self.d_scale = torch.zeros(nt, nf, **f32)
         self.d_inv = torch.zeros(nt, nf, **f32)
         self.d_flags = torch.zeros(nt, device=device, dtype=torch.int32)
-        ws_rows, n_rows = amp_absmax_rows_workspace_bytes(self.r_tensors)
+        ws_rows, _ = amp_absmax_rows_workspace_bytes(self.r_tensors)
+        n_rows = sum(amp_absmax_rows_workspace_bytes([t])[1] for _, t in per_row)
         self.n_rows = n_rows
         self.r_amax = torch.zeros(max(n_rows, 1), **f32)
         self.r_scale = torch.zeros(max(n_rows, 1), nf, **f32)
@@ -200,13 +208,15 @@ class RowSensPass:
                 op.x, op.dx, op.w, op.dw, op.C, op.K, op.R, xs, xi, ws_, wi,
                 tokens=int(op.row_offsets[1]) if (uniform and op.R) else 0,
                 sample_row_offsets=None if uniform else op.row_offsets,
-                scale_rows=(ROWS_OPERAND0 if xr else 0) | (ROWS_OPERAND1 if wr else 0)))
+                scale_rows=((ROWS_COMPUTE0 if ("lin", k, 0) in self.computed else ROWS_OPERAND0) if xr else 0) |
+                           (ROWS_OPERAND1 if wr else 0)))
         for k, op in enumerate(workload.bgemms):
             s0, i0, r0 = scales(("bg", k, 0))
             s1, i1, r1 = scales(("bg", k, 1))
             self.bg_desc.append(bgemm_desc(op.x0, op.dx0, _layout(op.lay0, op.x0.shape[-1]), op.x1, op.dx1,
                                            _layout(op.lay1, op.x1.shape[-1]), op.R, s0, i0, s1, i1,
-                                           scale_rows=(ROWS_OPERAND0 if r0 else 0) | (ROWS_OPERAND1 if r1 else 0)))
+                                           scale_rows=((ROWS_COMPUTE0 if ("bg", k, 0) in self.computed else ROWS_OPERAND0) if r0 else 0) |
+                                                      ((ROWS_COMPUTE1 if ("bg", k, 1) in self.computed else ROWS_OPERAND1) if r1 else 0)))
         self.lin_R = [op.R for op in workload.linears]
         self.bg_R = [op.R for op in workload.bgemms]
         nlr, nbr = sum(self.lin_R), sum(self.bg_R)
@@ -274,7 +284,7 @@ class RowSensPass:
             bg_ops.append(bg[o:o + R])
             o += R
         out = dict(flags=self.d_flags.cpu().numpy(), row_flags=self.r_flags.cpu().numpy(),
-                   where=dict(self.where), linear=lin_ops, bgemm=bg_ops)
+                   where=dict(self.where), computed=set(self.computed), linear=lin_ops, bgemm=bg_ops)
         if scales:
             out.update(amax=self.d_amax.cpu().numpy(), scale=self.d_scale.cpu().numpy(),
                        inv=self.d_inv.cpu().numpy(), row_amax=self.r_amax.cpu().numpy(),

@@ -117,15 +117,19 @@ def _operand_scales(res, key, x_bits, n_rows, row_len, fmts, causal_rows, what):
         return out
     _, base, rows, ti = w
     assert rows == n_rows, (what, rows, n_rows)
+    # scales computed by the sensitivity pass itself (single read) come without amax and flag words
+    computed = key in res.get("computed", ())
     flags = 0
     for fi, f in enumerate(fmts):
         am, sc, iv, fl = oracle.absmax_scale_rows(x_bits, n_rows, row_len, f, causal_rows=causal_rows)
         flags |= fl
-        assert np.array_equal(bits32(res["row_amax"][base:base + n_rows]), bits32(am)), what
+        if not computed:
+            assert np.array_equal(bits32(res["row_amax"][base:base + n_rows]), bits32(am)), what
         assert np.array_equal(bits32(res["row_scale"][base:base + n_rows, fi]), bits32(sc)), (what, fi)
         assert np.array_equal(bits32(res["row_inv"][base:base + n_rows, fi]), bits32(iv)), (what, fi)
         out.append((sc, iv))
-    assert res["row_flags"][ti] == flags, what
+    if not computed:
+        assert res["row_flags"][ti] == flags, what
     return out
 
 

@@ -69,11 +69,11 @@ def test_argument_validation_without_a_gpu():
     assert L.amp_fake_quant_fp8(8, 16, 1.0, 1.0, 7, 8, None, None) == amp.ERR_BAD_FORMAT
     assert L.amp_absmax_scale(None, 0, fm, 3, None, None, None, None, None, 0, None) == amp.ERR_BAD_FORMAT
     assert L.amp_sens_linear(None, 0, (C.c_int * 1)(5), 1, None, None, 0, None) == amp.ERR_BAD_FORMAT
-    # the power-of-two scale flag belongs to the absmax calls only
+    # the power-of-two scale flag
     pw = (C.c_int * 2)(0 | amp.SCALE_POW2, 1 | amp.SCALE_POW2)
     assert L.amp_absmax_scale(None, 0, pw, 2, None, None, None, None, None, 0, None) == amp.OK
     assert L.amp_absmax_scale_rows(None, 0, pw, 2, None, None, None, None, None, 0, None) == amp.OK
-    assert L.amp_sens_linear(None, 0, pw, 2, None, None, 0, None) == amp.ERR_BAD_FORMAT
+    assert L.amp_sens_linear(None, 0, pw, 2, None, None, 0, None) == amp.OK     # the rule serves AMP_ROWS_COMPUTE operands
     assert L.amp_absmax_scale(None, 0, (C.c_int * 1)(2 | amp.SCALE_POW2), 1, None, None, None, None, None, 0, None) == amp.ERR_BAD_FORMAT
     # nothing to do is fine and launches nothing
     assert L.amp_fake_quant_fp8(None, 0, 1.0, 1.0, 0, None, None, None) == amp.OK
@@ -141,7 +141,7 @@ def test_block_call_is_validated_like_its_two_halves():
     b.R = -1
     assert L.amp_sens_block(C.byref(d), 1, C.byref(b), 1, fm, 2, 4096, 4096, n.value, None) == amp.ERR_INVALID_ARG
     b.R = 3
-    d.scale_rows = 4
+    d.scale_rows = 8                                           # a weight's scales are never computed by the pass
     assert L.amp_sens_block(C.byref(d), 1, C.byref(b), 1, fm, 2, 4096, 4096, n.value, None) == amp.ERR_INVALID_ARG
 
 
@@ -233,7 +233,7 @@ def test_row_scale_descriptors_are_validated():
     d.x = d.dx = d.w = d.dw = 4096
     d.x_scale = d.x_inv = d.w_scale = d.w_inv = 4096
     assert L.amp_sens_linear_workspace_bytes(C.byref(d), 1, 2, C.byref(n)) == amp.OK
-    d.scale_rows = 4
+    d.scale_rows = 8                                           # a weight's scales are never computed by the pass
     assert L.amp_sens_linear_workspace_bytes(C.byref(d), 1, 2, C.byref(n)) == amp.ERR_INVALID_ARG
     # a dense BGEMM operand with one scale per row must say its row length, and it must divide the block
     b = amp.bgemm_desc(None, None, amp.dense(4 * 64 * 16), None, None, amp.dense(4 * 64 * 16, 16), 2,
