@@ -106,14 +106,15 @@ typedef enum amp_fp8_format {
 /* Single-read variant: the sensitivity pass itself finds each row's absmax, derives the scales with
  * the arithmetic of amp_absmax_scale_rows (the rule, amax / FMAX or power of two, is taken from the
  * formats passed to the sensitivity call, which may carry AMP_SCALE_POW2 for this purpose) and casts the
- * row with them: every row is fetched once, kept in registers while it is reduced, and its
- * gradient streamed against it.  The operand's scale / reciprocal tables are then OUTPUTS of the
- * pass (same [rows][n_fmts] layout), no absmax call is needed for it, and no amax or non-finite
- * flag is produced (a NaN or Inf in a row shows in that sample's sums).  Requires rows made of whole
- * 16-byte vectors (row length a multiple of 8, 16-byte aligned buffers) of at most 32768 elements;
- * anything else is AMP_ERR_INVALID_ARG (use the two-pass form).  For a linear layer only the
- * activations can be computed this way: the weight is shared by the samples and small next to its R
- * gradients, its table comes from amp_absmax_scale_rows. */
+ * row with them.  The threads that reduce a row keep it in on-chip memory and stream its gradient
+ * against it, so every byte of the operand is fetched once and no separate absmax pass runs over it.  The operand's scale / reciprocal tables are then OUTPUTS of the pass (same
+ * [rows][n_fmts] layout), and no amax or non-finite flag is produced (a NaN or Inf in a row shows in
+ * that sample's sums).  Requires rows made of whole 16-byte vectors (row length a multiple of 8,
+ * 16-byte aligned buffers) of at most AMP_ROWS_COMPUTE_MAX_ROW_LEN elements; anything else is
+ * AMP_ERR_INVALID_ARG (use the two-pass form).  For a
+ * linear layer only the activations can be computed this way: the weight is shared by the samples and
+ * small next to its R gradients, its table comes from amp_absmax_scale_rows. */
+#define AMP_ROWS_COMPUTE_MAX_ROW_LEN 24576
 #define AMP_ROWS_COMPUTE0 4          /* operand 0: one scale per row, computed by the pass */
 #define AMP_ROWS_COMPUTE1 8          /* operand 1 of a BGEMM, likewise */
 

@@ -20,6 +20,7 @@ ROWS_OPERAND0 = 1          # one scale per row of X (linear) / X0 (BGEMM)
 ROWS_OPERAND1 = 2          # one scale per row of W (linear) / X1 (BGEMM)
 ROWS_COMPUTE0 = 4          # operand 0: one scale per row, computed by the sensitivity pass itself (single read)
 ROWS_COMPUTE1 = 8          # operand 1 of a BGEMM, likewise
+ROWS_COMPUTE_MAX_ROW_LEN = 24576
 PLAN_STREAM_WEIGHTS = 1    # amp_sens_block_setup flag: read W with every sample's gradient
 
 

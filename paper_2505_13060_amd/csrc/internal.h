@@ -41,40 +41,111 @@ enum : uint32_t {
                                      // the tables; `head` holds the FusedGeom of the unit
 };
 
-// Single-read pass over an operand with one scale per row: a workgroup handles a tile of
-// rows_per_tile = 256 / lanes rows at a time, `lanes` (a power of two, 16..256) threads per row, each
-// thread keeping up to `nv` (<= 16) 8-element vectors of its row in registers; a chunk is
-// `tiles` consecutive tiles (dense) or `tiles` slots of a lower triangle, a slot being tile t of a
-// matrix and its mirror tile T - 1 - t (equal work per slot).
-constexpr int kFusedMaxNv = 16;
-constexpr int kFusedShortNv = 2;             // units with nv <= this go to the short-row variant,
-constexpr int kFusedMidNv = 8;               // with nv <= this to the middle one (fewer registers, more waves)
-constexpr int kFusedMinLanesLog2 = 4;
-constexpr int64_t kFusedMaxRowLen = (int64_t)kWG * kFusedMaxNv * kVec;     // 32768 elements
+// Single-read pass over an operand with one scale per row.  A workgroup handles a tile of rows at
+// a time: `lanes` (a power of two, 4..256) threads per row, 256 / lanes rows per tile, each thread
+// owning up to kFusedNv 8-element vectors of its row (more only for rows beyond 256 * kFusedNv
+// vectors).  A thread stages its vectors of x in LDS while the row's absmax is found, then streams the
+// row's gradient against them: HBM delivers every byte once.  Dense units: every tile has the lanes
+// the row length asks for.  Causal units: row i owns i + 1 + (cols - rows) entries, so the lanes
+// follow the row: the rows of a matrix fall into classes (lanes = 4, 8, ..., 256) by length, tiles are
+// consecutive rows of one class, and a tile's work is about the same whatever its class.  A chunk is
+// `tiles` consecutive tiles of a unit (dense) or of a matrix (causal).
+#ifndef AMPSENS_FUSED_NV
+#define AMPSENS_FUSED_NV 8
+#endif
+#ifndef AMPSENS_FUSED_GROUP
+#define AMPSENS_FUSED_GROUP 4
+#endif
+constexpr int kFusedNv = AMPSENS_FUSED_NV;         // vectors of a row per thread the geometry aims at
+constexpr int kFusedGroup = AMPSENS_FUSED_GROUP;   // vectors per thread handled (and in flight) together
+constexpr int kFusedMaxNv = 12;                    // LDS: 256 threads x 16 bytes x nv <= 48 KiB per workgroup
+constexpr int64_t kFusedMaxRowLen = (int64_t)kWG * kFusedMaxNv * kVec;     // 24576 elements
+static_assert(kFusedNv % kFusedGroup == 0 && kFusedMaxNv % kFusedGroup == 0, "whole groups");
+
+// lanes (as log2) for a row of row_vecs vectors
+inline __host__ __device__ int fused_lanes_log2(int64_t row_vecs) {
+    int lg = 2;
+    while (lg < 8 && ((int64_t)kFusedNv << lg) < row_vecs) ++lg;
+    return lg;
+}
+// causal [rows, cols] matrix: rows whose valid length is at most `cap` elements
+inline __host__ __device__ int64_t fused_causal_rows_upto(int64_t rows, int64_t cols, int64_t cap) {
+    // row i owns clamp(i + 1 + cols - rows, 0, cols) entries
+    if (cap >= cols) return rows;
+    int64_t n = cap - (cols - rows);             // i + 1 + off <= cap  <=>  i < cap - off
+    return n < 0 ? 0 : (n > rows ? rows : n);
+}
+// Tile q of a causal matrix: its lanes, first row and number of rows.  Returns false past the last tile.
+struct FusedCausalTile { int lanes_log2; int64_t row0; int32_t n_rows; };
+inline __host__ __device__ bool fused_causal_tile(int64_t rows, int64_t cols, int64_t q, FusedCausalTile* out) {
+    int64_t a = 0;
+    for (int lg = 2; lg <= 8; ++lg) {
+        const int64_t b = lg == 8 ? rows : fused_causal_rows_upto(rows, cols, (int64_t)kVec * ((int64_t)kFusedNv << lg));
+        const int64_t rt = kWG >> lg;
+        const int64_t cnt = (b - a + rt - 1) / rt;
+        if (q < cnt) {
+            out->lanes_log2 = lg;
+            out->row0 = a + q * rt;
+            out->n_rows = (int32_t)(b - out->row0 < rt ? b - out->row0 : rt);
+            return true;
+        }
+        q -= cnt;
+        a = b;
+    }
+    return false;
+}
+inline __host__ __device__ int64_t fused_causal_tiles(int64_t rows, int64_t cols) {
+    int64_t a = 0, total = 0;
+    for (int lg = 2; lg <= 8; ++lg) {
+        const int64_t b = lg == 8 ? rows : fused_causal_rows_upto(rows, cols, (int64_t)kVec * ((int64_t)kFusedNv << lg));
+        const int64_t rt = kWG >> lg;
+        total += (b - a + rt - 1) / rt;
+        a = b;
+    }
+    return total;
+}
+
 struct FusedGeom {
-    int lanes_log2, nv, tiles;
-    __host__ __device__ uint32_t pack() const { return (uint32_t)lanes_log2 | ((uint32_t)nv << 8) | ((uint32_t)tiles << 16); }
+    int lanes_log2, nv, tiles;                     // dense: lanes and vectors per thread; tiles per chunk
+    __host__ __device__ uint32_t pack() const { return (uint32_t)lanes_log2 | ((uint32_t)tiles << 4) | ((uint32_t)nv << 12); }
     static __host__ __device__ FusedGeom unpack(uint32_t h) {
         FusedGeom g;
-        g.lanes_log2 = (int)(h & 0xFFu);
-        g.nv = (int)((h >> 8) & 0xFFu);
-        g.tiles = (int)(h >> 16);
+        g.lanes_log2 = (int)(h & 0xFu);
+        g.tiles = (int)((h >> 4) & 0xFFu);
+        g.nv = (int)(h >> 12);
         return g;
     }
     __host__ __device__ int rows_per_tile() const { return kWG >> lanes_log2; }
 };
-// Geometry for rows of row_len elements (a multiple of 8, at most kFusedMaxRowLen): about eight
-// vectors per thread, about 4096 vectors per chunk.
+// Geometry for rows of row_len elements (a multiple of 8): about kFusedNv vectors per thread, about
+// 4096 vectors per chunk.  nv is rounded up to whole groups (what lies past a row's end is masked).
 inline FusedGeom fused_geometry(int64_t row_len, bool causal) {
     const int64_t row_vecs = row_len / kVec;
     FusedGeom g;
-    g.lanes_log2 = kFusedMinLanesLog2;
-    while (g.lanes_log2 < 8 && ((int64_t)8 << g.lanes_log2) < row_vecs) ++g.lanes_log2;
-    const int64_t lanes = (int64_t)1 << g.lanes_log2;
-    g.nv = (int)((row_vecs + lanes - 1) / lanes);
-    if (g.nv < 1) g.nv = 1;
-    // vectors per tile (dense) or per slot (causal: two tiles of, together, one full row length per row pair)
-    const int64_t per = (int64_t)g.rows_per_tile() * (causal ? row_vecs + 1 : row_vecs);
+    g.lanes_log2 = fused_lanes_log2(row_vecs);
+    auto nv_of = [&](int lg) {
+        const int64_t lanes = (int64_t)1 << lg;
+        int64_t nv = (row_vecs + lanes - 1) / lanes;
+        nv = (nv + kFusedGroup - 1) / kFusedGroup * kFusedGroup;
+        return nv < kFusedGroup ? (int64_t)kFusedGroup : nv;
+    };
+    if (!causal) {
+        // dense rows all have the same length: the lanes that waste the fewest vector slots (a thread's
+        // vectors come in whole groups), among those that leave at most kFusedMaxNv vectors per thread;
+        // ties go to the geometry the row length asks for, then to more lanes
+        int best = -1;
+        int64_t best_slots = 0;
+        for (int lg = 2; lg <= 8; ++lg) {
+            const int64_t nv = nv_of(lg);
+            if (nv > kFusedMaxNv) continue;
+            const int64_t slots = nv << lg;
+            if (best < 0 || slots < best_slots || (slots == best_slots && lg == g.lanes_log2)) { best = lg; best_slots = slots; }
+        }
+        if (best >= 0) g.lanes_log2 = best;
+    }
+    g.nv = (int)nv_of(g.lanes_log2);
+    // vectors per tile: dense rows_per_tile whole rows; causal about three quarters of 256 x kFusedNv
+    const int64_t per = causal ? (int64_t)kWG * kFusedNv * 3 / 4 : (int64_t)g.rows_per_tile() * row_vecs;
     int64_t t = per > 0 ? (kChunkVecs + per / 2) / per : 1;
     g.tiles = (int)(t < 1 ? 1 : (t > 64 ? 64 : t));
     return g;
@@ -83,11 +154,12 @@ inline uint64_t fused_chunks_dense(int64_t rows, const FusedGeom& g) {
     const uint64_t per = (uint64_t)g.rows_per_tile() * (uint64_t)g.tiles;
     return rows > 0 ? ((uint64_t)rows + per - 1) / per : 0;
 }
-inline uint32_t fused_chunks_per_mat(int64_t rows, const FusedGeom& g) {
-    const uint64_t tiles = ((uint64_t)rows + g.rows_per_tile() - 1) / g.rows_per_tile();
-    const uint64_t slots = (tiles + 1) / 2;
-    return (uint32_t)((slots + g.tiles - 1) / g.tiles);
+inline uint32_t fused_chunks_per_mat(int64_t rows, int64_t cols, const FusedGeom& g) {
+    const uint64_t tiles = (uint64_t)fused_causal_tiles(rows, cols);
+    return (uint32_t)((tiles + g.tiles - 1) / g.tiles);
 }
+// LDS bytes a workgroup needs for a unit: its threads' vectors of x
+inline size_t fused_lds_bytes(int nv) { return (size_t)kWG * 16 * (size_t)nv; }
 
 struct alignas(16) WorkUnit {        // 64 bytes
     const uint16_t* x;               // first element of the block
@@ -188,10 +260,9 @@ inline uint32_t causal_chunks_per_mat(int64_t rows) {
 // Persistent-grid size for the streaming kernels on the current device (resident workgroups).
 // cls: the class of units the variant is for: 0 = one scale per tensor; 1 = row scales, rows of at
 // least 512 elements or aligned causal rows; 2 = row scales, any other shape; 3 = row scales, rows
-// of a power-of-two length below 512; 4 / 5 / 6 = row scales computed by the pass itself (single read),
-// up to kFusedMidNv / kFusedShortNv / kFusedMaxNv vectors of a row per thread.
-constexpr int kSensClasses = 7;
-int sens_resident_blocks(int n_fmts, int fmt0, int fmt1, int cls, int cus);
+// of a power-of-two length below 512; 4 = row scales computed by the pass itself (single read).
+constexpr int kSensClasses = 5;
+int sens_resident_blocks(int n_fmts, int fmt0, int fmt1, int cls, int cus, size_t lds_bytes = 0);
 int absmax_resident_blocks(int cus);
 int absmax_rows_resident_blocks(int cus);
 
@@ -215,10 +286,11 @@ hipError_t launch_absmax_finalize(const uint32_t* d_chunk_begin, const uint32_t*
                                   hipStream_t stream);
 hipError_t launch_fake_quant(const uint16_t* d_x, int64_t n, float scale, float inv, int fmt,
                              uint8_t* d_codes, float* d_dequant, int grid, hipStream_t stream);
-// fmt0 / fmt1 may carry the scale-rule flag (used by classes 4 and 5 only, which compute scales).
+// fmt0 / fmt1 may carry the scale-rule flag and lds_bytes is the dynamic LDS of a workgroup (both
+// used by class 4 only, which computes scales and stages rows in LDS).
 hipError_t launch_sens(const ResolvedUnit* d_runits, const ChunkRef* d_map, uint32_t n_chunks,
                        int n_fmts, int fmt0, int fmt1, int rows, float* d_partials, int grid,
-                       hipStream_t stream);
+                       size_t lds_bytes, hipStream_t stream);
 int sens_w_resident_blocks(int n_fmts, int fmt0, int fmt1, int rows, int cus);
 hipError_t launch_sens_w(const WGroup* d_groups, uint32_t n_groups, uint32_t n_items,
                          const ResolvedUnit* d_runits, const uint32_t* d_chunk_begin, int n_fmts, int fmt0,

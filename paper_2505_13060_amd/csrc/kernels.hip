@@ -1170,13 +1170,12 @@ __global__ __launch_bounds__(kWG) void absmax_rows_kernel(const RowTensor* __res
 
 // ---- the single-read pass for operands with one scale per row ------------------------------------
 // The row-scaled pass without a separate absmax pass: a workgroup takes a tile of rows, `lanes`
-// threads per row; every thread loads its (up to NVMAX) vectors of the row once and keeps them in
-// registers, the row's absmax is reduced over its threads (cross-lane moves inside a wave, LDS and one
-// barrier when a row spans several waves), the scales of every format are derived with the
-// arithmetic of write_scales, written to the operand's tables by one thread per row, and the row's
-// gradient is streamed against the resident row.  Geometry per unit: FusedGeom in `head`.
-// Causal units: a slot is tile t of a matrix and its mirror tile T - 1 - t; the vector holding a
-// row's end is loaded whole and the entries past the end are cleared before any arithmetic.
+// threads per row; every thread loads its vectors of the row once, folds them into the row's absmax
+// and parks them in LDS (its own slots, so no barrier guards them); the absmax is reduced over the
+// row's threads (cross-lane moves inside a wave, LDS and one barrier when a row spans several waves),
+// the scales of every format are derived with the arithmetic of write_scales and written to the
+// operand's tables by one thread per row, and the row's gradient is streamed against the parked
+// vectors.  Geometry: FusedGeom in `head`; causal units choose the lanes tile by tile (internal.h).
 
 // One of the four numbers write_scales derives from a row's amax: scale (want_inv false) or
 // reciprocal (true) of format `code` (which may carry kScalePow2).  Same results bit for bit; the
@@ -1203,18 +1202,95 @@ __device__ __forceinline__ float quad_broadcast(float v) {
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
 }
 
-template <int NF, int F0, int F1, int NVMAX>
+// The row tiles of one chunk, in the order a workgroup takes them.  Uniform over the workgroup
+// except for live / row / len.
+struct FusedTile {
+    bool valid;                                    // there is such a tile
+    int lanes_log2;                                // threads per row
+    int nv_exact;                                  // vectors k < nv_exact of every thread are whole vectors of a live row
+    int nv;                                        // vectors per thread (whole groups); those past a row's end are masked
+    bool live;                                     // this thread's row exists
+    int64_t row;                                   // row of the unit (table index); 0 when not live
+    int32_t len;                                   // valid elements of the row
+};
+struct FusedTileWalk {
+    int32_t rows, cols;
+    bool causal;
+    FusedGeom geo;
+    int tid;
+    int64_t next_tile;                             // dense: tile of the unit; causal: tile of the matrix
+    int left;                                      // tiles still to come
+    int64_t mat_row0;                              // causal: first row of the matrix in the unit
+
+    __device__ __forceinline__ void begin(const ResolvedUnit& u, const FusedGeom& g, uint32_t local, int tid_) {
+        rows = u.rows; cols = u.cols; geo = g; tid = tid_;
+        causal = (u.flags & kUnitCausal) != 0;
+        left = g.tiles;
+        if (!causal) {
+            next_tile = (int64_t)local * g.tiles;
+            mat_row0 = 0;
+        } else {
+            const uint32_t mat = local / u.chunks_per_mat;
+            mat_row0 = (int64_t)mat * rows;
+            next_tile = (int64_t)(local % u.chunks_per_mat) * g.tiles;
+        }
+    }
+    static __device__ __forceinline__ int whole_groups_down(int v) { return v / kFusedGroup * kFusedGroup; }
+    static __device__ __forceinline__ int whole_groups_up(int v) { return (v + kFusedGroup - 1) / kFusedGroup * kFusedGroup; }
+    __device__ __forceinline__ FusedTile next() {
+        FusedTile t;
+        t.valid = false; t.lanes_log2 = 2; t.nv_exact = 0; t.nv = 0; t.live = false; t.row = 0; t.len = 0;
+        if (left <= 0) return t;
+        --left;
+        if (!causal) {
+            const int lg = geo.lanes_log2;
+            const int RT = kWG >> lg;
+            const int64_t r0 = next_tile * RT;
+            if (r0 >= rows) { left = 0; return t; }
+            ++next_tile;
+            const int64_t r = r0 + (tid >> lg);
+            const int32_t row_vecs = cols / kVec;
+            t.valid = true;
+            t.lanes_log2 = lg;
+            t.live = r < rows;
+            t.row = t.live ? r : 0;
+            t.len = cols;
+            t.nv = geo.nv;
+            t.nv_exact = r0 + RT <= rows ? whole_groups_down(row_vecs >> lg) : 0;
+            return t;
+        }
+        FusedCausalTile ct;
+        if (!fused_causal_tile(rows, cols, next_tile, &ct)) { left = 0; return t; }
+        ++next_tile;
+        const int lg = ct.lanes_log2;
+        const int RT = kWG >> lg;
+        const int32_t i = (int32_t)ct.row0 + (tid >> lg);
+        t.valid = true;
+        t.lanes_log2 = lg;
+        t.live = (tid >> lg) < ct.n_rows;
+        t.row = mat_row0 + (t.live ? i : (int32_t)ct.row0);
+        t.len = t.live ? causal_row_len(i, rows, cols) : 0;
+        const int32_t len_min = causal_row_len((int32_t)ct.row0, rows, cols);
+        const int32_t len_max = causal_row_len((int32_t)ct.row0 + ct.n_rows - 1, rows, cols);
+        const int32_t vec_max = (len_max + kVec - 1) / kVec;
+        t.nv = whole_groups_up((vec_max + (1 << lg) - 1) >> lg);
+        t.nv_exact = ct.n_rows == RT ? whole_groups_down((len_min / kVec) >> lg) : 0;
+        return t;
+    }
+};
+
+template <int NF, int F0, int F1>
 struct FusedRows {
+    static constexpr int kG = kFusedGroup;         // vectors of x (and of the gradient) in flight per thread
     gptr16_t x, g;
     float* ts;                                     // scale[row][NF]
     float* ti;                                     // inv[row][NF]
     int32_t cols;
-    int lanes_log2, nv;
-    int j, rt;                                     // this thread's lane inside its row, its row inside the tile
     int code0, code1;
     float E[NF], A;
     int pk[NF];
     uint32_t* red;                                 // LDS, [2][kWaves]: wave maxima of rows that span waves
+    u32x4* stage;                                  // LDS, [nv][kWG]: this workgroup's vectors of x
     int parity;
 
     __device__ __forceinline__ void quad(uint32_t xw0, uint32_t xw1, uint32_t gw0, uint32_t gw1,
@@ -1230,47 +1306,77 @@ struct FusedRows {
         if constexpr (NF > 1) one_format<F1>(xv, gv, iv[1], sc[1], E[1], pk[1]);
     }
 
-    // One row per group of `lanes` threads: row `row` of the unit (table index), `len` valid
-    // elements starting at element `e0` of the unit; live = this thread's row exists.
-    __device__ __forceinline__ void row(int64_t row, int64_t e0, int32_t len, bool live) {
-        const int L = 1 << lanes_log2;
-        const int nvr = live ? (len + kVec - 1) / kVec : 0;
-        const int tail = len - (nvr - 1) * kVec;
-        const gptr128_t px = reinterpret_cast<gptr128_t>(x + e0);
-        const gptr128_t pg = reinterpret_cast<gptr128_t>(g + e0);
-        const u32x4 zero = {0u, 0u, 0u, 0u};
-        u32x4 xr[NVMAX];
-#pragma unroll
-        for (int k = 0; k < NVMAX; ++k) {
-            const int v = j + (k << lanes_log2);
-            xr[k] = (k < nv && v < nvr) ? load128<true>(px + v) : zero;
-        }
-        if (tail < kVec) {
-#pragma unroll
-            for (int k = 0; k < NVMAX; ++k)
-                if (k < nv && j + (k << lanes_log2) == nvr - 1) xr[k] = keep_leading(xr[k], tail);
-        }
-        // absmax of the row: packed 16-bit maxima per thread, then across the row's threads
-        uint32_t m2 = 0;
-#pragma unroll
-        for (int k = 0; k < NVMAX; ++k) {
-            const uint32_t w[4] = {xr[k].x, xr[k].y, xr[k].z, xr[k].w};
+    // One tile.  First visit: every thread loads its vectors of its row (each byte of x leaves HBM
+    // here, once), folds them into the row's absmax and parks them in its own LDS slots; the absmax is
+    // reduced over the row's threads and the scales derived and written to the tables.  Second visit:
+    // the thread takes its vectors back from LDS and streams the gradient against them.  Loads are
+    // unconditional (a thread whose vector lies past the row's end re-reads the row's last vector,
+    // a thread without a row the tile's first); groups k >= nv_exact clear what does not belong to the
+    // row with per-vector masks, without branches.
+    __device__ __forceinline__ void tile(const FusedTile& t) {
+        const int lg = t.lanes_log2;
+        const int L = 1 << lg;
+        const int tid = threadIdx.x;
+        const int j = tid & (L - 1);
+        const int nvr = (t.len + kVec - 1) / kVec;
+        const int last = nvr > 0 ? nvr - 1 : 0;
+        const int32_t len = t.live ? t.len : 0;
+        const gptr128_t px = reinterpret_cast<gptr128_t>(x + t.row * (int64_t)cols);
+        const gptr128_t pg = reinterpret_cast<gptr128_t>(g + t.row * (int64_t)cols);
+        auto clamped = [&](int k) {
+            const int v = j + (k << lg);
+            return v < last ? v : last;
+        };
+        auto count = [&](int k) {                                  // elements of vector k that belong to the row
+            const int c = len - (j + (k << lg)) * kVec;
+            return c < 0 ? 0 : (c > kVec ? kVec : c);
+        };
+        auto fold = [](uint32_t m2, const u32x4& v) {
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const u16x2 a = __builtin_bit_cast(u16x2, m2), b = __builtin_bit_cast(u16x2, w[q] & 0x7FFF7FFFu);
                 m2 = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(a, b));
             }
+            return m2;
+        };
+        // first visit
+        uint32_t m2 = 0;
+        int k0 = 0;
+#pragma unroll 1
+        for (; k0 < t.nv_exact; k0 += kG) {
+            u32x4 xr[kG];
+#pragma unroll
+            for (int k = 0; k < kG; ++k) xr[k] = load128<true>(px + (j + ((k0 + k) << lg)));
+#pragma unroll
+            for (int k = 0; k < kG; ++k) {
+                m2 = fold(m2, xr[k]);
+                stage[(k0 + k) * kWG + tid] = xr[k];
+            }
+        }
+#pragma unroll 1
+        for (; k0 < t.nv; k0 += kG) {
+            u32x4 xr[kG];
+#pragma unroll
+            for (int k = 0; k < kG; ++k) xr[k] = load128<true>(px + clamped(k0 + k));
+#pragma unroll
+            for (int k = 0; k < kG; ++k) {
+                xr[k] = keep_leading(xr[k], count(k0 + k));
+                m2 = fold(m2, xr[k]);
+                stage[(k0 + k) * kWG + tid] = xr[k];
+            }
         }
         uint32_t m = (m2 & 0xFFFFu) > (m2 >> 16) ? (m2 & 0xFFFFu) : (m2 >> 16);
-        for (int o = 1; o < L && o < 64; o <<= 1) {
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {                         // partners outside the row's threads do not count
             const uint32_t w = (uint32_t)__shfl_xor((int)m, o);
-            m = m > w ? m : w;
+            m = (o < L && w > m) ? w : m;
         }
-        if (lanes_log2 > 6) {                          // the row spans 2 or 4 waves (uniform over the workgroup)
-            const int wave = threadIdx.x >> 6;
-            if ((threadIdx.x & 63) == 0) red[parity * kWaves + wave] = m;
+        if (lg > 6) {                                  // the row spans 2 or 4 waves (uniform over the workgroup)
+            const int wave = tid >> 6;
+            if ((tid & 63) == 0) red[parity * kWaves + wave] = m;
             __syncthreads();
-            const int w0 = lanes_log2 == 7 ? (wave & 2) : 0, wn = lanes_log2 == 7 ? 2 : 4;
+            const int w0 = lg == 7 ? (wave & 2) : 0, wn = lg == 7 ? 2 : 4;
             for (int w = 0; w < wn; ++w) {
                 const uint32_t v = red[parity * kWaves + w0 + w];
                 m = m > v ? m : v;
@@ -1290,44 +1396,54 @@ struct FusedRows {
                 iv[1] = quad_broadcast<0xFF>(mine);
             }
         }
-        if (live && j == 0) {
+        if (t.live && j == 0) {
 #pragma unroll
             for (int f = 0; f < NF; ++f) {
-                ts[row * NF + f] = sc[f];
-                ti[row * NF + f] = iv[f];
+                ts[t.row * NF + f] = sc[f];
+                ti[t.row * NF + f] = iv[f];
             }
         }
-        // the gradient against the resident row, four vectors in flight at a time
+        // second visit: x from this thread's LDS slots (already cleared where it had to be), the gradient from
+        // HBM.  Vectors outside the row are (0, 0) and add exactly 0.
+        k0 = 0;
+#pragma unroll 1
+        for (; k0 < t.nv_exact; k0 += kG) {
+            u32x4 xr[kG], gr[kG];
 #pragma unroll
-        for (int k0 = 0; k0 < NVMAX; k0 += 4) {
-            u32x4 gr[4];
+            for (int k = 0; k < kG; ++k) gr[k] = load128<true>(pg + (j + ((k0 + k) << lg)));
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                const int k = k0 + kk;
-                const int v = j + (k << lanes_log2);
-                gr[kk] = (k < NVMAX && k < nv && v < nvr) ? load128<true>(pg + v) : zero;
+            for (int k = 0; k < kG; ++k) xr[k] = stage[(k0 + k) * kWG + tid];
+#pragma unroll
+            for (int k = 0; k < kG; ++k) {
+                quad(xr[k].x, xr[k].y, gr[k].x, gr[k].y, iv, sc);
+                quad(xr[k].z, xr[k].w, gr[k].z, gr[k].w, iv, sc);
             }
-            if (tail < kVec) {
+        }
+#pragma unroll 1
+        for (; k0 < t.nv; k0 += kG) {
+            u32x4 xr[kG], gr[kG];
 #pragma unroll
-                for (int kk = 0; kk < 4; ++kk)
-                    if (k0 + kk < nv && j + ((k0 + kk) << lanes_log2) == nvr - 1) gr[kk] = keep_leading(gr[kk], tail);
-            }
+            for (int k = 0; k < kG; ++k) gr[k] = load128<true>(pg + clamped(k0 + k));
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                const int k = k0 + kk;
-                if (k < NVMAX && k < nv) {               // absent vectors are (0, 0): they add exactly 0
-                    quad(xr[k].x, xr[k].y, gr[kk].x, gr[kk].y, iv, sc);
-                    quad(xr[k].z, xr[k].w, gr[kk].z, gr[kk].w, iv, sc);
-                }
+            for (int k = 0; k < kG; ++k) xr[k] = stage[(k0 + k) * kWG + tid];
+#pragma unroll
+            for (int k = 0; k < kG; ++k) {
+                gr[k] = keep_leading(gr[k], count(k0 + k));
+                quad(xr[k].x, xr[k].y, gr[k].x, gr[k].y, iv, sc);
+                quad(xr[k].z, xr[k].w, gr[k].z, gr[k].w, iv, sc);
             }
         }
     }
 };
 
-template <int NF, int F0, int F1, int NVMAX>
-__global__ __launch_bounds__(kWG) void sens_fused_rows_kernel(const ResolvedUnit* __restrict__ runits,
-                                                              const ChunkRef* __restrict__ map, uint32_t n_chunks,
-                                                              float* __restrict__ partials, int code0, int code1) {
+#ifndef AMPSENS_FUSED_WAVES
+#define AMPSENS_FUSED_WAVES 6
+#endif
+template <int NF, int F0, int F1>
+__global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(AMPSENS_FUSED_WAVES, AMPSENS_FUSED_WAVES)))
+void sens_fused_rows_kernel(const ResolvedUnit* __restrict__ runits, const ChunkRef* __restrict__ map,
+                            uint32_t n_chunks, float* __restrict__ partials, int code0, int code1) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char fused_lds[];   // [nv][kWG] vectors, then 2 * kWaves words
     __shared__ uint32_t red[2 * kWaves];
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -1335,49 +1451,23 @@ __global__ __launch_bounds__(kWG) void sens_fused_rows_kernel(const ResolvedUnit
         const ChunkRef ref = map[c];
         const ResolvedUnit u = runits[ref.unit];
         const FusedGeom geo = FusedGeom::unpack(u.head);
-        FusedRows<NF, F0, F1, NVMAX> ctx;
+        FusedRows<NF, F0, F1> ctx;
         ctx.x = (gptr16_t)u.x;
         ctx.g = (gptr16_t)u.dx;
         ctx.ts = const_cast<float*>(u.row_scale);
         ctx.ti = const_cast<float*>(u.row_inv);
         ctx.cols = u.cols;
-        ctx.lanes_log2 = geo.lanes_log2;
-        ctx.nv = geo.nv < NVMAX ? geo.nv : NVMAX;
-        ctx.j = tid & ((1 << geo.lanes_log2) - 1);
-        ctx.rt = tid >> geo.lanes_log2;
         ctx.code0 = code0;
         ctx.code1 = code1;
         ctx.red = red;
+        ctx.stage = reinterpret_cast<u32x4*>(fused_lds);
         ctx.parity = 0;
 #pragma unroll
         for (int f = 0; f < NF; ++f) { ctx.E[f] = 0.0f; ctx.pk[f] = 0; }
         ctx.A = 0.0f;
-        const int RT = geo.rows_per_tile();
-        if (!(u.flags & kUnitCausal)) {
-            const int64_t t0 = (int64_t)ref.local * geo.tiles;
-            for (int t = 0; t < geo.tiles; ++t) {
-                const int64_t r0 = (t0 + t) * RT;
-                if (r0 >= u.rows) break;                            // uniform over the workgroup
-                const int64_t r = r0 + ctx.rt;
-                const bool live = r < u.rows;
-                ctx.row(live ? r : 0, (live ? r : 0) * (int64_t)u.cols, u.cols, live);
-            }
-        } else {
-            const uint32_t mat = ref.local / u.chunks_per_mat;
-            const int32_t slot0 = (int32_t)(ref.local % u.chunks_per_mat) * geo.tiles;
-            const int32_t T = (u.rows + RT - 1) / RT;
-            for (int s = 0; s < geo.tiles; ++s) {
-                const int32_t slot = slot0 + s, mirror = T - 1 - slot;
-                if (slot > mirror) break;                           // uniform over the workgroup
-                for (int h = 0; h < 2; ++h) {
-                    if (h == 1 && mirror == slot) break;
-                    const int32_t i = (h == 0 ? slot : mirror) * RT + ctx.rt;
-                    const bool live = i < u.rows;
-                    const int64_t r = (int64_t)mat * u.rows + (live ? i : 0);
-                    ctx.row(r, r * (int64_t)u.cols, live ? causal_row_len(i, u.rows, u.cols) : 0, live);
-                }
-            }
-        }
+        FusedTileWalk walk;
+        walk.begin(u, geo, ref.local, tid);
+        for (FusedTile t = walk.next(); t.valid; t = walk.next()) ctx.tile(t);
         float v[NF + 1];
 #pragma unroll
         for (int f = 0; f < NF; ++f) v[f] = wave_sum(ctx.E[f]);
@@ -1438,16 +1528,10 @@ __global__ __launch_bounds__(kWG) void fake_quant_kernel(const uint16_t* __restr
 typedef void (*sens_fn_t)(const ResolvedUnit*, const ChunkRef*, uint32_t, float*);
 typedef void (*sens_fused_fn_t)(const ResolvedUnit*, const ChunkRef*, uint32_t, float*, int, int);
 
-template <int NVMAX>
-sens_fused_fn_t sens_fused_variant_of(int n_fmts, int fmt0, int fmt1) {
-    if (n_fmts == 1) return fmt0 == 0 ? sens_fused_rows_kernel<1, 0, 0, NVMAX> : sens_fused_rows_kernel<1, 1, 1, NVMAX>;
-    if (fmt0 == 0) return fmt1 == 0 ? sens_fused_rows_kernel<2, 0, 0, NVMAX> : sens_fused_rows_kernel<2, 0, 1, NVMAX>;
-    return fmt1 == 0 ? sens_fused_rows_kernel<2, 1, 0, NVMAX> : sens_fused_rows_kernel<2, 1, 1, NVMAX>;
-}
-sens_fused_fn_t sens_fused_variant(int n_fmts, int fmt0, int fmt1, int cls) {
-    if (cls == 5) return sens_fused_variant_of<kFusedShortNv>(n_fmts, fmt0, fmt1);
-    if (cls == 4) return sens_fused_variant_of<kFusedMidNv>(n_fmts, fmt0, fmt1);
-    return sens_fused_variant_of<kFusedMaxNv>(n_fmts, fmt0, fmt1);
+sens_fused_fn_t sens_fused_variant(int n_fmts, int fmt0, int fmt1) {
+    if (n_fmts == 1) return fmt0 == 0 ? sens_fused_rows_kernel<1, 0, 0> : sens_fused_rows_kernel<1, 1, 1>;
+    if (fmt0 == 0) return fmt1 == 0 ? sens_fused_rows_kernel<2, 0, 0> : sens_fused_rows_kernel<2, 0, 1>;
+    return fmt1 == 0 ? sens_fused_rows_kernel<2, 1, 0> : sens_fused_rows_kernel<2, 1, 1>;
 }
 
 sens_fn_t sens_variant(int n_fmts, int fmt0, int fmt1, int cls) {
@@ -1471,17 +1555,17 @@ sens_fn_t sens_variant(int n_fmts, int fmt0, int fmt1, int cls) {
     return fmt1 == 0 ? sens_kernel<2, 1, 0> : sens_kernel<2, 1, 1>;
 }
 
-int resident_blocks(const void* fn, int cus) {
+int resident_blocks(const void* fn, int cus, size_t lds_bytes = 0) {
     int per_cu = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kWG, 0) != hipSuccess || per_cu < 1)
-        per_cu = 4;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kWG, lds_bytes) != hipSuccess || per_cu < 1)
+        per_cu = lds_bytes ? 2 : 4;
     return per_cu * cus;
 }
 
 }  // namespace
 
-int sens_resident_blocks(int n_fmts, int fmt0, int fmt1, int rows, int cus) {
-    if (rows >= 4) return resident_blocks((const void*)sens_fused_variant(n_fmts, fmt0, fmt1, rows), cus);
+int sens_resident_blocks(int n_fmts, int fmt0, int fmt1, int rows, int cus, size_t lds_bytes) {
+    if (rows >= 4) return resident_blocks((const void*)sens_fused_variant(n_fmts, fmt0, fmt1), cus, lds_bytes);
     return resident_blocks((const void*)sens_variant(n_fmts, fmt0, fmt1, rows), cus);
 }
 
@@ -1587,9 +1671,9 @@ hipError_t launch_fake_quant(const uint16_t* d_x, int64_t n, float scale, float 
 
 hipError_t launch_sens(const ResolvedUnit* d_runits, const ChunkRef* d_map, uint32_t n_chunks,
                        int n_fmts, int fmt0, int fmt1, int rows, float* d_partials, int grid,
-                       hipStream_t stream) {
+                       size_t lds_bytes, hipStream_t stream) {
     if (rows >= 4)
-        hipLaunchKernelGGL(sens_fused_variant(n_fmts, fmt0 & 0xFF, fmt1 & 0xFF, rows), dim3(grid), dim3(kWG), 0, stream,
+        hipLaunchKernelGGL(sens_fused_variant(n_fmts, fmt0 & 0xFF, fmt1 & 0xFF), dim3(grid), dim3(kWG), lds_bytes, stream,
                            d_runits, d_map, n_chunks, d_partials, fmt0, fmt1);
     else
         hipLaunchKernelGGL(sens_variant(n_fmts, fmt0 & 0xFF, fmt1 & 0xFF, rows), dim3(grid), dim3(kWG), 0, stream,

@@ -68,6 +68,7 @@ struct WorkTable {
     uint64_t n_chunks = 0;
     uint64_t n_pairs = 0;                         // elements that belong to the operands
     bool any_rows = false;                        // some unit has one scale per row
+    int fused_nv = 0;                             // most vectors of x a thread of the single-read pass stages in LDS
 
     // x / dx may be null only for blocks without elements.
     amp_status_t add(const uint16_t* x, const uint16_t* dx, const amp_layout_t& L, int64_t batch_mul,
@@ -84,7 +85,7 @@ struct WorkTable {
             any_rows = true;
         }
         // fused: the pass computes the row scales itself (scale / inv are then outputs); only for rows
-        // made of whole, aligned vectors that fit a workgroup's registers
+        // made of whole, aligned vectors
         if (fused) {
             const int64_t len = L.causal ? L.cols : row_len;
             const bool nice = ((uintptr_t)x % 16 == 0) && ((uintptr_t)dx % 16 == 0) && len % kVec == 0;
@@ -105,7 +106,8 @@ struct WorkTable {
             if (fused) {
                 const FusedGeom g = fused_geometry(L.cols, true);
                 u.head = g.pack();
-                u.chunks_per_mat = (L.rows > 0 && L.cols > 0) ? fused_chunks_per_mat(L.rows, g) : 0;
+                u.chunks_per_mat = (L.rows > 0 && L.cols > 0) ? fused_chunks_per_mat(L.rows, L.cols, g) : 0;
+                if (g.nv > fused_nv) fused_nv = g.nv;
             }
             chunks = (uint64_t)batch * u.chunks_per_mat;
             if (chunks == 0) u.chunks_per_mat = 1;         // never divide by zero on the device
@@ -132,6 +134,7 @@ struct WorkTable {
                 const FusedGeom g = fused_geometry(row_len, false);
                 u.head = g.pack();
                 chunks = fused_chunks_dense(u.rows, g);
+                if (g.nv > fused_nv) fused_nv = g.nv;
             }
             n_pairs += (uint64_t)n;
             unit_pairs.push_back((uint64_t)n);
@@ -170,10 +173,7 @@ struct WorkTable {
     // 2 = any other unit with row scales (other short rows, rows not made of whole vectors).
     static int unit_class(const WorkUnit& u) {
         if (!(u.flags & kUnitRowScale)) return 0;
-        if (u.flags & kUnitFused) {
-            const int nv = FusedGeom::unpack(u.head).nv;
-            return nv <= kFusedShortNv ? 5 : (nv <= kFusedMidNv ? 4 : 6);
-        }
+        if (u.flags & kUnitFused) return 4;
         if (u.flags & kUnitScalar) return 2;
         if (u.flags & kUnitCausal) return 1;
         if (u.cols >= kVec * 64) return 1;

@@ -7,7 +7,7 @@ tensors allocated once; every number is produced by libampsens' kernels.
 import numpy as np
 import torch
 
-from . import (ROWS_COMPUTE0, ROWS_COMPUTE1, ROWS_OPERAND0, ROWS_OPERAND1, amp_absmax_rows_workspace_bytes, amp_absmax_scale,
+from . import (ROWS_COMPUTE0, ROWS_COMPUTE1, ROWS_COMPUTE_MAX_ROW_LEN, ROWS_OPERAND0, ROWS_OPERAND1, amp_absmax_rows_workspace_bytes, amp_absmax_scale,
                amp_absmax_scale_rows, amp_absmax_scale_rows_setup, amp_absmax_scale_setup,
                amp_absmax_workspace_bytes, amp_plan_limit_grid, amp_run, amp_sens_bgemm,
                amp_sens_bgemm_workspace_bytes, amp_sens_block, amp_sens_block_setup,
@@ -167,7 +167,9 @@ class RowSensPass:
                 t = tensor(x, _layout(lay, x.shape[-1]), op.R)
                 (per_row if bgemm_rows else per_tensor).append((("bg", k, side), t))
         # operands whose row scales the sensitivity pass computes itself: their tables sit behind the others'
-        self.computed = set(key for key, _ in per_row if single_read and (key[0] == "bg" or key[2] == 0))
+        # (rows too long for the single-read pass, or not made of whole vectors, keep the two-pass form)
+        self.computed = set(key for key, t in per_row if single_read and (key[0] == "bg" or key[2] == 0)
+                            and t.layout.cols % 8 == 0 and t.layout.cols <= ROWS_COMPUTE_MAX_ROW_LEN)
         per_row = [kt for kt in per_row if kt[0] not in self.computed] + [kt for kt in per_row if kt[0] in self.computed]
         self.t_tensors = [t for _, t in per_tensor]
         self.r_tensors = [t for key, t in per_row if key not in self.computed]
