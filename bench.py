@@ -219,6 +219,10 @@ def main():
                          "output channel / per row of a BGEMM operand); rows-single-read: the sensitivity "
                          "pass computes the row scales of the activations and BGEMM operands itself, "
                          "every row is fetched once")
+    ap.add_argument("--scale-rule", choices=["amax", "pow2"], default="amax",
+                    help="amax: scale = amax / FMAX (headline); pow2: the smallest power of two that is large "
+                         "enough (AMP_SCALE_POW2 on both calls: the sensitivity kernels then cast with gfx950's "
+                         "scaled FP8 conversions)")
     ap.add_argument("--settle", type=float, default=6.0,
                     help="seconds to leave the GPU idle between generating the inputs and the warm-up: for a "
                          "few seconds after a process has freed tens of GB of device memory every kernel on "
@@ -245,13 +249,14 @@ def main():
     log("generating %d block(s) of %s on %s" % (n_blocks, args.workload, torch.cuda.get_device_name(0)))
     t0 = time.perf_counter()
     workloads, passes = [], []
+    rule = amp.SCALE_POW2 if args.scale_rule == "pow2" else 0
     for b in range(n_blocks):
         workload, label = build_workload(args.workload, dev, block=b)
         workloads.append(workload)
         # linears and BGEMMs of the block in one call: one table, one set-up, one streaming launch
         plan = args.calls == "plan"
-        passes.append(SensPass(workload, dev, one_call=True, plan=plan) if args.scales == "tensor"
-                      else RowSensPass(workload, dev, one_call=True, plan=plan,
+        passes.append(SensPass(workload, dev, one_call=True, plan=plan, rule=rule) if args.scales == "tensor"
+                      else RowSensPass(workload, dev, one_call=True, plan=plan, rule=rule,
                                        single_read=args.scales == "rows-single-read"))
     torch.cuda.synchronize()
     workload = workloads[0]
@@ -259,6 +264,8 @@ def main():
     log("%.1f M pairs per step (%.2f GB), generated in %.1f s" % (pairs / 1e6, pairs * 4 / 1e9, time.perf_counter() - t0))
     if args.scales != "tensor":
         label += "; one scale per row" + (", computed by the sensitivity pass (single read)" if args.scales != "rows" else "")
+    if rule:
+        label += "; power-of-two scales, cast by the scaled FP8 conversions"
     label += "; steps rotate over %d distinct resident block(s)" % n_blocks
     # elements the absmax passes of a step read: every operand once, except those whose row scales
     # the sensitivity pass computes itself
@@ -361,7 +368,7 @@ def main():
     # its buffers pays, and what the set-up costs (secondary line; the headline does the set-up per step)
     other = None
     if args.calls == "oneshot" and args.scales == "tensor":
-        plans = [SensPass(w, dev, plan=True) for w in workloads]
+        plans = [SensPass(w, dev, plan=True, rule=rule) for w in workloads]
         for k in range(min(args.warmup, 2 * n_blocks)):
             plans[k % n_blocks].run()
         torch.cuda.synchronize()
@@ -383,7 +390,7 @@ def main():
         "config": {"workload": label, "pairs_per_step": pairs, "bytes_per_step": bytes_step,
                    "bytes_per_step_absmax": abs_bytes_step, "bytes_per_step_sens": sens_bytes_step,
                    "formats": ["E4M3" if f == 0 else "E5M2" for f in workload.fmts],
-                   "resident_blocks": n_blocks, "calls": args.calls,
+                   "resident_blocks": n_blocks, "calls": args.calls, "scale_rule": args.scale_rule,
                    "weights": "resident mode: all R weight gradients of an op are in HBM, W is read "
                               "once per batch of 8 samples; activations and BGEMM operands 4 B per pair"},
         "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBS,

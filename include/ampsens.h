@@ -96,9 +96,15 @@ typedef enum amp_fp8_format {
 /* Scale rule.  Or-ed into a format passed to amp_absmax_scale / amp_absmax_scale_rows: the scale
  * is the smallest power of two s with amax / s <= FMAX_f and the reciprocal is 1 / s, both exact
  * (exponent-only scale factors), instead of amax / FMAX_f and FMAX_f / amax.  amax == 0, a
- * non-finite amax, or an s whose reciprocal is not an fp32 number give scale = inv = 1.  The
- * sensitivity calls take scales as inputs; they accept the flag too, and use it only for operands
- * whose row scales they compute themselves (AMP_ROWS_COMPUTE0 / 1 below). */
+ * non-finite amax, or an s whose reciprocal is not an fp32 number give scale = inv = 1.
+ * On a sensitivity call the flag, set on every format, says two things.  (1) Operands whose row
+ * scales the call computes itself (AMP_ROWS_COMPUTE0 / 1 below) get them by this rule.  (2) It is a
+ * promise about the operands that come with one scale per tensor: their scales are powers of two s
+ * with reciprocal 1 / s and no element exceeds FMAX_f * s in magnitude, which is what the absmax
+ * calls give under this rule for the data they scanned.  The pass then casts with gfx950's scaled
+ * FP8 conversions (packed bf16 in, exponent-only scale), which saves about a fifth of its vector
+ * instructions and gives the same codes and the same sums as the general cast, bit for bit; an element that breaks the promise is not saturated but
+ * turns into the format's NaN / Inf code, and the sums of its operand are then NaN. */
 #define AMP_SCALE_POW2 0x100
 
 #define AMP_ROWS_OPERAND0 1          /* X of a linear layer / X0 of a BGEMM */

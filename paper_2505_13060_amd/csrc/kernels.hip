@@ -33,6 +33,8 @@ namespace {
 constexpr int kWLoad = AMPSENS_W_LOAD;       // gradient vectors of one step in flight per lane
 
 typedef float float2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef short short2_t __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));             // one 128-bit load
 typedef const uint16_t __attribute__((address_space(1)))* gptr16_t;   // global address space
 typedef const u32x4 __attribute__((address_space(1)))* gptr128_t;
@@ -50,6 +52,17 @@ template <> struct Fp8<0> {                       // OCP E4M3
         return hi ? __builtin_amdgcn_cvt_pk_f32_fp8(pk, true)
                   : __builtin_amdgcn_cvt_pk_f32_fp8(pk, false);
     }
+    // gfx950's scaled conversions.  Measured over all bf16 patterns: pack_scaled gives the code of
+    // RNE(x / 2^exponent(scale)) for both elements of a packed bf16 pair, WITHOUT saturation (a quotient
+    // beyond the format's range gives the NaN code); unpack_scaled gives decode(code) * 2^exponent(scale).
+    static __device__ __forceinline__ short2_t pack_scaled(uint32_t xw, float scale, short2_t old, bool hi) {
+        return hi ? __builtin_amdgcn_cvt_scalef32_pk_fp8_bf16(old, __builtin_bit_cast(bf16x2_t, xw), scale, true)
+                  : __builtin_amdgcn_cvt_scalef32_pk_fp8_bf16(old, __builtin_bit_cast(bf16x2_t, xw), scale, false);
+    }
+    static __device__ __forceinline__ float2_t unpack_scaled(uint32_t pk, float scale, bool hi) {
+        return hi ? __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(pk, scale, true)
+                  : __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(pk, scale, false);
+    }
 };
 template <> struct Fp8<1> {                       // OCP E5M2
     static constexpr float kMax = 57344.0f;
@@ -60,6 +73,14 @@ template <> struct Fp8<1> {                       // OCP E5M2
     static __device__ __forceinline__ float2_t unpack(int pk, bool hi) {
         return hi ? __builtin_amdgcn_cvt_pk_f32_bf8(pk, true)
                   : __builtin_amdgcn_cvt_pk_f32_bf8(pk, false);
+    }
+    static __device__ __forceinline__ short2_t pack_scaled(uint32_t xw, float scale, short2_t old, bool hi) {   // overflow: the Inf code
+        return hi ? __builtin_amdgcn_cvt_scalef32_pk_bf8_bf16(old, __builtin_bit_cast(bf16x2_t, xw), scale, true)
+                  : __builtin_amdgcn_cvt_scalef32_pk_bf8_bf16(old, __builtin_bit_cast(bf16x2_t, xw), scale, false);
+    }
+    static __device__ __forceinline__ float2_t unpack_scaled(uint32_t pk, float scale, bool hi) {
+        return hi ? __builtin_amdgcn_cvt_scalef32_pk_f32_bf8(pk, scale, true)
+                  : __builtin_amdgcn_cvt_scalef32_pk_f32_bf8(pk, scale, false);
     }
 };
 
@@ -224,13 +245,42 @@ __device__ __forceinline__ void one_format(const float (&xv)[4], const float (&g
     }
 }
 
-template <int NF, int F0, int F1>
+// The same four elements when the scale is a power of two s, the reciprocal is 1 / s, and no element
+// exceeds FMAX * s in magnitude (all true for scales the power-of-two rule derives from the absmax of
+// the same data): the scaled conversions take the packed bf16 pair straight to its codes and the
+// codes straight back to q * s, both exact, so the multiply and the clamp of the general path go away
+// (16 instead of 24 operations per four elements and format).  q * s itself can be 2^128 (a value in
+// bf16's top binade that rounds up), which fp32 does not hold while x - q * s does: the codes are
+// taken back with sq = s / 4 and the error formed as fma(mul, q * sq, x), mul = -4, which is
+// x - q * s rounded once, exactly what the general path computes.  Scales too small for a normal
+// quarter (below 2^-100, where nothing can overflow) come as sq = s, mul = -1.
+template <int F>
+__device__ __forceinline__ void one_format_pow2(uint32_t xw0, uint32_t xw1, const float (&xv)[4],
+                                                const float (&gv)[4], float sc, float sq, float mul,
+                                                float& Ef, int& p) {
+    short2_t c = __builtin_bit_cast(short2_t, p);
+    c = Fp8<F>::pack_scaled(xw0, sc, c, false);
+    c = Fp8<F>::pack_scaled(xw1, sc, c, true);
+    p = __builtin_bit_cast(int, c);
+    const float2_t q01 = Fp8<F>::unpack_scaled((uint32_t)p, sq, false);
+    const float2_t q23 = Fp8<F>::unpack_scaled((uint32_t)p, sq, true);
+    const float e0 = fmaf(mul, q01.x, xv[0]), e1 = fmaf(mul, q01.y, xv[1]);
+    const float e2 = fmaf(mul, q23.x, xv[2]), e3 = fmaf(mul, q23.y, xv[3]);
+    const float t0 = gv[0] * e0, t1 = gv[1] * e1, t2 = gv[2] * e2, t3 = gv[3] * e3;
+    Ef = fmaf(t0, t0, Ef);
+    Ef = fmaf(t1, t1, Ef);
+    Ef = fmaf(t2, t2, Ef);
+    Ef = fmaf(t3, t3, Ef);
+}
+
+template <int NF, int F0, int F1, bool POW2 = false>
 struct SensCtx {
     static constexpr bool kRollDense = false;
     gptr16_t x;
     gptr16_t g;
     bool keep_x;                                   // x is re-read soon: ordinary caching
-    float inv[NF], scale[NF];
+    float inv[NF], scale[NF];                      // POW2: inv holds the scale the codes are taken back with
+    float mul;                                     // POW2 only: see one_format_pow2
     float E[NF];
     float A;
     int pk[NF];
@@ -246,6 +296,13 @@ struct SensCtx {
             E[f] = 0.0f;
             pk[f] = 0;
         }
+        mul = -1.0f;
+        if constexpr (POW2) {                          // one multiplier for both formats
+            const bool roomy = scale[0] >= 0x1p-100f && scale[NF - 1] >= 0x1p-100f;
+            mul = roomy ? -4.0f : -1.0f;
+#pragma unroll
+            for (int f = 0; f < NF; ++f) inv[f] = roomy ? scale[f] * 0.25f : scale[f];
+        }
         A = 0.0f;
     }
     __device__ __forceinline__ void begin_dense(int64_t, int) {}
@@ -259,8 +316,13 @@ struct SensCtx {
             const float a = gv[j] * xv[j];
             A = fmaf(a, a, A);
         }
-        one_format<F0>(xv, gv, inv[0], scale[0], E[0], pk[0]);
-        if constexpr (NF > 1) one_format<F1>(xv, gv, inv[1], scale[1], E[1], pk[1]);
+        if constexpr (POW2) {
+            one_format_pow2<F0>(xw0, xw1, xv, gv, scale[0], inv[0], mul, E[0], pk[0]);
+            if constexpr (NF > 1) one_format_pow2<F1>(xw0, xw1, xv, gv, scale[1], inv[1], mul, E[1], pk[1]);
+        } else {
+            one_format<F0>(xv, gv, inv[0], scale[0], E[0], pk[0]);
+            if constexpr (NF > 1) one_format<F1>(xv, gv, inv[1], scale[1], E[1], pk[1]);
+        }
     }
 
     __device__ __forceinline__ void vec(const u32x4& xv, const u32x4& gv) {
@@ -701,11 +763,11 @@ __device__ __forceinline__ void sens_body(const ResolvedUnit* __restrict__ runit
 #ifndef AMPSENS_SENS_WAVES
 #define AMPSENS_SENS_WAVES 7
 #endif
-template <int NF, int F0, int F1>
+template <int NF, int F0, int F1, bool POW2>
 __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(AMPSENS_SENS_WAVES, AMPSENS_SENS_WAVES))) void sens_kernel(const ResolvedUnit* __restrict__ runits,
                                                    const ChunkRef* __restrict__ map,
                                                    uint32_t n_chunks, float* __restrict__ partials) {
-    sens_body<SensCtx<NF, F0, F1>, NF>(runits, map, n_chunks, partials);
+    sens_body<SensCtx<NF, F0, F1, POW2>, NF>(runits, map, n_chunks, partials);
 }
 
 #ifndef AMPSENS_WROWS_WAVES
@@ -1279,7 +1341,7 @@ struct FusedTileWalk {
     }
 };
 
-template <int NF, int F0, int F1>
+template <int NF, int F0, int F1, bool POW2>
 struct FusedRows {
     static constexpr int kG = kFusedGroup;         // vectors of x (and of the gradient) in flight per thread
     gptr16_t x, g;
@@ -1293,8 +1355,9 @@ struct FusedRows {
     u32x4* stage;                                  // LDS, [nv][kWG]: this workgroup's vectors of x
     int parity;
 
+    // POW2: iv holds the scales the codes are taken back with and mul their multiplier (one_format_pow2)
     __device__ __forceinline__ void quad(uint32_t xw0, uint32_t xw1, uint32_t gw0, uint32_t gw1,
-                                         const float (&iv)[NF], const float (&sc)[NF]) {
+                                         const float (&iv)[NF], const float (&sc)[NF], float mul) {
         const float xv[4] = {bf16_lo(xw0), bf16_hi(xw0), bf16_lo(xw1), bf16_hi(xw1)};
         const float gv[4] = {bf16_lo(gw0), bf16_hi(gw0), bf16_lo(gw1), bf16_hi(gw1)};
 #pragma unroll
@@ -1302,8 +1365,13 @@ struct FusedRows {
             const float a = gv[q] * xv[q];
             A = fmaf(a, a, A);
         }
-        one_format<F0>(xv, gv, iv[0], sc[0], E[0], pk[0]);
-        if constexpr (NF > 1) one_format<F1>(xv, gv, iv[1], sc[1], E[1], pk[1]);
+        if constexpr (POW2) {                          // scales of the power-of-two rule, derived from this very row
+            one_format_pow2<F0>(xw0, xw1, xv, gv, sc[0], iv[0], mul, E[0], pk[0]);
+            if constexpr (NF > 1) one_format_pow2<F1>(xw0, xw1, xv, gv, sc[1], iv[1], mul, E[1], pk[1]);
+        } else {
+            one_format<F0>(xv, gv, iv[0], sc[0], E[0], pk[0]);
+            if constexpr (NF > 1) one_format<F1>(xv, gv, iv[1], sc[1], E[1], pk[1]);
+        }
     }
 
     // One tile.  First visit: every thread loads its vectors of its row (each byte of x leaves HBM
@@ -1403,6 +1471,15 @@ struct FusedRows {
                 ti[t.row * NF + f] = iv[f];
             }
         }
+        float mul = -1.0f;
+        if constexpr (POW2) {
+            // a row whose absmax is at least 1 has scales of at least 2^-15 in either format: a quarter of
+            // them is a normal number; any other row is far from the overflow the quarter is for
+            const bool roomy = m >= 0x3F80u;
+            mul = roomy ? -4.0f : -1.0f;
+#pragma unroll
+            for (int f = 0; f < NF; ++f) iv[f] = roomy ? sc[f] * 0.25f : sc[f];
+        }
         // second visit: x from this thread's LDS slots (already cleared where it had to be), the gradient from
         // HBM.  Vectors outside the row are (0, 0) and add exactly 0.
         k0 = 0;
@@ -1415,8 +1492,8 @@ struct FusedRows {
             for (int k = 0; k < kG; ++k) xr[k] = stage[(k0 + k) * kWG + tid];
 #pragma unroll
             for (int k = 0; k < kG; ++k) {
-                quad(xr[k].x, xr[k].y, gr[k].x, gr[k].y, iv, sc);
-                quad(xr[k].z, xr[k].w, gr[k].z, gr[k].w, iv, sc);
+                quad(xr[k].x, xr[k].y, gr[k].x, gr[k].y, iv, sc, mul);
+                quad(xr[k].z, xr[k].w, gr[k].z, gr[k].w, iv, sc, mul);
             }
         }
 #pragma unroll 1
@@ -1429,8 +1506,8 @@ struct FusedRows {
 #pragma unroll
             for (int k = 0; k < kG; ++k) {
                 gr[k] = keep_leading(gr[k], count(k0 + k));
-                quad(xr[k].x, xr[k].y, gr[k].x, gr[k].y, iv, sc);
-                quad(xr[k].z, xr[k].w, gr[k].z, gr[k].w, iv, sc);
+                quad(xr[k].x, xr[k].y, gr[k].x, gr[k].y, iv, sc, mul);
+                quad(xr[k].z, xr[k].w, gr[k].z, gr[k].w, iv, sc, mul);
             }
         }
     }
@@ -1439,7 +1516,7 @@ struct FusedRows {
 #ifndef AMPSENS_FUSED_WAVES
 #define AMPSENS_FUSED_WAVES 6
 #endif
-template <int NF, int F0, int F1>
+template <int NF, int F0, int F1, bool POW2>
 __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(AMPSENS_FUSED_WAVES, AMPSENS_FUSED_WAVES)))
 void sens_fused_rows_kernel(const ResolvedUnit* __restrict__ runits, const ChunkRef* __restrict__ map,
                             uint32_t n_chunks, float* __restrict__ partials, int code0, int code1) {
@@ -1451,7 +1528,7 @@ void sens_fused_rows_kernel(const ResolvedUnit* __restrict__ runits, const Chunk
         const ChunkRef ref = map[c];
         const ResolvedUnit u = runits[ref.unit];
         const FusedGeom geo = FusedGeom::unpack(u.head);
-        FusedRows<NF, F0, F1> ctx;
+        FusedRows<NF, F0, F1, POW2> ctx;
         ctx.x = (gptr16_t)u.x;
         ctx.g = (gptr16_t)u.dx;
         ctx.ts = const_cast<float*>(u.row_scale);
@@ -1528,13 +1605,25 @@ __global__ __launch_bounds__(kWG) void fake_quant_kernel(const uint16_t* __restr
 typedef void (*sens_fn_t)(const ResolvedUnit*, const ChunkRef*, uint32_t, float*);
 typedef void (*sens_fused_fn_t)(const ResolvedUnit*, const ChunkRef*, uint32_t, float*, int, int);
 
-sens_fused_fn_t sens_fused_variant(int n_fmts, int fmt0, int fmt1) {
-    if (n_fmts == 1) return fmt0 == 0 ? sens_fused_rows_kernel<1, 0, 0> : sens_fused_rows_kernel<1, 1, 1>;
-    if (fmt0 == 0) return fmt1 == 0 ? sens_fused_rows_kernel<2, 0, 0> : sens_fused_rows_kernel<2, 0, 1>;
-    return fmt1 == 0 ? sens_fused_rows_kernel<2, 1, 0> : sens_fused_rows_kernel<2, 1, 1>;
+template <bool POW2>
+sens_fused_fn_t sens_fused_variant_of(int n_fmts, int fmt0, int fmt1) {
+    if (n_fmts == 1) return fmt0 == 0 ? sens_fused_rows_kernel<1, 0, 0, POW2> : sens_fused_rows_kernel<1, 1, 1, POW2>;
+    if (fmt0 == 0) return fmt1 == 0 ? sens_fused_rows_kernel<2, 0, 0, POW2> : sens_fused_rows_kernel<2, 0, 1, POW2>;
+    return fmt1 == 0 ? sens_fused_rows_kernel<2, 1, 0, POW2> : sens_fused_rows_kernel<2, 1, 1, POW2>;
+}
+// pow2: every format of the call carries the power-of-two scale rule
+sens_fused_fn_t sens_fused_variant(int n_fmts, int fmt0, int fmt1, bool pow2) {
+    return pow2 ? sens_fused_variant_of<true>(n_fmts, fmt0, fmt1) : sens_fused_variant_of<false>(n_fmts, fmt0, fmt1);
 }
 
-sens_fn_t sens_variant(int n_fmts, int fmt0, int fmt1, int cls) {
+template <bool POW2>
+sens_fn_t sens_tensor_variant_of(int n_fmts, int fmt0, int fmt1) {
+    if (n_fmts == 1) return fmt0 == 0 ? sens_kernel<1, 0, 0, POW2> : sens_kernel<1, 1, 1, POW2>;
+    if (fmt0 == 0) return fmt1 == 0 ? sens_kernel<2, 0, 0, POW2> : sens_kernel<2, 0, 1, POW2>;
+    return fmt1 == 0 ? sens_kernel<2, 1, 0, POW2> : sens_kernel<2, 1, 1, POW2>;
+}
+
+sens_fn_t sens_variant(int n_fmts, int fmt0, int fmt1, int cls, bool pow2 = false) {
     if (cls == 1) {
         if (n_fmts == 1) return fmt0 == 0 ? sens_wrows_kernel<1, 0, 0, false> : sens_wrows_kernel<1, 1, 1, false>;
         if (fmt0 == 0) return fmt1 == 0 ? sens_wrows_kernel<2, 0, 0, false> : sens_wrows_kernel<2, 0, 1, false>;
@@ -1550,9 +1639,7 @@ sens_fn_t sens_variant(int n_fmts, int fmt0, int fmt1, int cls) {
         if (fmt0 == 0) return fmt1 == 0 ? sens_rows_kernel<2, 0, 0> : sens_rows_kernel<2, 0, 1>;
         return fmt1 == 0 ? sens_rows_kernel<2, 1, 0> : sens_rows_kernel<2, 1, 1>;
     }
-    if (n_fmts == 1) return fmt0 == 0 ? sens_kernel<1, 0, 0> : sens_kernel<1, 1, 1>;
-    if (fmt0 == 0) return fmt1 == 0 ? sens_kernel<2, 0, 0> : sens_kernel<2, 0, 1>;
-    return fmt1 == 0 ? sens_kernel<2, 1, 0> : sens_kernel<2, 1, 1>;
+    return pow2 ? sens_tensor_variant_of<true>(n_fmts, fmt0, fmt1) : sens_tensor_variant_of<false>(n_fmts, fmt0, fmt1);
 }
 
 int resident_blocks(const void* fn, int cus, size_t lds_bytes = 0) {
@@ -1565,7 +1652,7 @@ int resident_blocks(const void* fn, int cus, size_t lds_bytes = 0) {
 }  // namespace
 
 int sens_resident_blocks(int n_fmts, int fmt0, int fmt1, int rows, int cus, size_t lds_bytes) {
-    if (rows >= 4) return resident_blocks((const void*)sens_fused_variant(n_fmts, fmt0, fmt1), cus, lds_bytes);
+    if (rows >= 4) return resident_blocks((const void*)sens_fused_variant(n_fmts, fmt0, fmt1, false), cus, lds_bytes);
     return resident_blocks((const void*)sens_variant(n_fmts, fmt0, fmt1, rows), cus);
 }
 
@@ -1672,11 +1759,13 @@ hipError_t launch_fake_quant(const uint16_t* d_x, int64_t n, float scale, float 
 hipError_t launch_sens(const ResolvedUnit* d_runits, const ChunkRef* d_map, uint32_t n_chunks,
                        int n_fmts, int fmt0, int fmt1, int rows, float* d_partials, int grid,
                        size_t lds_bytes, hipStream_t stream) {
+    // the scaled conversions serve calls whose formats all carry the power-of-two scale rule
+    const bool pow2 = (fmt0 & kScalePow2) != 0 && (fmt1 & kScalePow2) != 0;
     if (rows >= 4)
-        hipLaunchKernelGGL(sens_fused_variant(n_fmts, fmt0 & 0xFF, fmt1 & 0xFF), dim3(grid), dim3(kWG), lds_bytes, stream,
-                           d_runits, d_map, n_chunks, d_partials, fmt0, fmt1);
+        hipLaunchKernelGGL(sens_fused_variant(n_fmts, fmt0 & 0xFF, fmt1 & 0xFF, pow2), dim3(grid), dim3(kWG), lds_bytes,
+                           stream, d_runits, d_map, n_chunks, d_partials, fmt0, fmt1);
     else
-        hipLaunchKernelGGL(sens_variant(n_fmts, fmt0 & 0xFF, fmt1 & 0xFF, rows), dim3(grid), dim3(kWG), 0, stream,
+        hipLaunchKernelGGL(sens_variant(n_fmts, fmt0 & 0xFF, fmt1 & 0xFF, rows, pow2), dim3(grid), dim3(kWG), 0, stream,
                            d_runits, d_map, n_chunks, d_partials);
     return hipGetLastError();
 }

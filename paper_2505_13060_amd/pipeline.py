@@ -31,13 +31,16 @@ class SensPass:
     stream, and run() only replays the plans (kernel launches only); flags go to
     amp_sens_block_setup, grid_limit to amp_plan_limit_grid."""
 
-    def __init__(self, workload, device, one_call=False, plan=False, flags=0, grid_limit=0):
+    def __init__(self, workload, device, one_call=False, plan=False, flags=0, grid_limit=0, rule=0):
+        """rule: 0, or SCALE_POW2: power-of-two scales from the absmax call, and the promise to the
+        sensitivity call that goes with them (it then casts with the scaled FP8 conversions)."""
         self.plan = plan or flags != 0 or grid_limit != 0
         one_call = one_call or self.plan
         self.one_call = one_call
         self.w = workload
         self.device = device
-        self.fmts = list(workload.fmts)
+        self.rule = rule
+        self.fmts = [f | rule for f in workload.fmts]
         nf = len(self.fmts)
         nl, nb = len(workload.linears), len(workload.bgemms)
         self.tensors = []
@@ -132,7 +135,7 @@ class SensPass:
         for R in self.bg_R:
             bg_ops.append(bg[o:o + R])
             o += R
-        out = dict(flags=self.d_flags.cpu().numpy(), linear=lin_ops, bgemm=bg_ops)
+        out = dict(flags=self.d_flags.cpu().numpy(), linear=lin_ops, bgemm=bg_ops, pow2=self.rule != 0)
         if scales:
             out.update(amax=self.d_amax.cpu().numpy(), scale=self.d_scale.cpu().numpy(),
                        inv=self.d_inv.cpu().numpy())
@@ -146,15 +149,16 @@ class RowSensPass:
     scale per tensor go through amp_absmax_scale as in SensPass."""
 
     def __init__(self, workload, device, x_rows=True, w_rows=True, bgemm_rows=True, one_call=False, plan=False,
-                 flags=0, single_read=False):
-        """single_read: the row scales of the activations and of the BGEMM operands are computed by the
+                 flags=0, single_read=False, rule=0):
+        """rule: 0 or SCALE_POW2 (power-of-two scales everywhere, as in SensPass).  single_read: the row scales of the activations and of the BGEMM operands are computed by the
         sensitivity pass itself (AMP_ROWS_COMPUTE0 / 1: every row is fetched once); only the weights'
         per-channel scales then come from amp_absmax_scale_rows."""
         self.single_read = single_read
         self.plan = plan or flags != 0
         one_call = one_call or self.plan
         self.one_call = one_call
-        self.w, self.device, self.fmts = workload, device, list(workload.fmts)
+        self.w, self.device, self.fmts = workload, device, [f | rule for f in workload.fmts]
+        self.rule = rule
         nf = len(self.fmts)
         f32 = dict(device=device, dtype=torch.float32)
         per_tensor, per_row = [], []                 # (key, Tensor)

@@ -211,6 +211,34 @@ def test_results_do_not_depend_on_grid_and_repeat_bit_identically():
             assert np.array_equal(parity.bits32(a), parity.bits32(b))
 
 
+def test_power_of_two_rule_uses_the_scaled_conversions_and_matches_the_oracle():
+    """AMP_SCALE_POW2 on both calls: power-of-two scales from the absmax pass (bit for bit the oracle's
+    rule), then the sensitivity pass that casts with gfx950's scaled conversions; dense, causal, ragged
+    and misaligned operands (the misaligned ones take the element-wise path of the same kernel)."""
+    for w in (wl.config1("cpu", R=3, S=136, hidden=256, ffn=520, H=2, D=64),
+              wl.config4("cpu", R=4, experts=5, C=512, K=176, tok_lo=1, tok_hi=40, n_bgemm=4, S=72, H=2, D=32),
+              wl.config3("cpu", R=2, S=264, hidden=512, ffn=1800, Hq=8, Hkv=2, D=64)):
+        to_device(w)
+        say("power-of-two rule on %s" % w.name)
+        outs = []
+        for kw in (dict(), dict(one_call=True), dict(plan=True, flags=amp.PLAN_STREAM_WEIGHTS)):
+            p = SensPass(w, DEV, rule=amp.SCALE_POW2, **kw)
+            p.run()
+            res = p.results()
+            parity.check_workload(w, res)
+            outs.append(np.concatenate(res["linear"] + res["bgemm"]))
+        assert np.array_equal(parity.bits32(outs[0]), parity.bits32(outs[1]))
+        # the same scales without the promise: the general cast must give the same sums
+        q = SensPass(w, DEV, one_call=True)
+        q.d_scale.copy_(p.d_scale)
+        q.d_inv.copy_(p.d_inv)
+        q.sens()
+        torch.cuda.synchronize()
+        general = q.d_out.cpu().numpy()
+        assert general.shape == outs[1].shape
+        assert np.allclose(general, outs[1], rtol=1e-6, atol=0)
+
+
 def _mk(rng, n, sigma):
     return f32_to_bf16_bits((rng.standard_normal(n) * sigma).astype(np.float32))
 

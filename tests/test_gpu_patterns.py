@@ -42,6 +42,16 @@ RANGES = {
 }
 
 
+# value ranges for the scaled-conversion paths: a power-of-two scale s (reciprocal 1 / s) and only values
+# up to FMAX * s in magnitude, which is what the flag on the sensitivity call promises
+RANGES_POW2 = {
+    "pow2_unit": dict(lo=87, hi=134, scale=1.0, gexp=0),
+    "pow2_tiny": dict(lo=0, hi=86, scale=2.0 ** -48, gexp=100),
+    # the top values round to 256 s = 2^128, which fp32 does not hold, while x - 2^128 is an ordinary number
+    "pow2_huge": dict(lo=168, hi=254, scale=2.0 ** 120, gexp=-100),
+}
+
+
 def say(msg):
     print("[gpu-test] " + msg, flush=True)
     sys.stdout.flush()
@@ -53,6 +63,9 @@ def dev_bits(bits):
 
 def scales_of(rng_name):
     """[(scale, inv)] per format as float32."""
+    if rng_name in RANGES_POW2:
+        s_ = np.float32(RANGES_POW2[rng_name]["scale"])
+        return [(s_, np.float32(1.0) / s_) for _ in FMTS]
     amax = RANGES[rng_name]["amax"]
     out = []
     for f in FMTS:
@@ -67,7 +80,8 @@ def scales_of(rng_name):
 def patterns_of(rng_name):
     h = all_bf16_patterns().copy()
     e = (h >> 7) & 0xFF
-    keep = (e >= RANGES[rng_name]["lo"]) & (e <= RANGES[rng_name]["hi"])
+    rg = RANGES_POW2[rng_name] if rng_name in RANGES_POW2 else RANGES[rng_name]
+    keep = (e >= rg["lo"]) & (e <= rg["hi"])
     h[~keep] = 0
     return h
 
@@ -109,18 +123,27 @@ PATHS = {
                               computed=True),
     "single_read_causal": dict(n0=16384, hot=lambda r: hot_causal(r)[0], layout=lambda: amp.causal(1, 128, 128),
                                row_len=128, computed=True),
+    # the same with the power-of-two rule: scales by the rule from each row's absmax, cast by the scaled conversions
+    "single_read_512_pow2": dict(n0=32768, hot=hot_dense, layout=lambda: amp.dense(32768, 512), row_len=512,
+                                 computed=True, pow2_rule=True),
+    "single_read_causal_pow2": dict(n0=16384, hot=lambda r: hot_causal(r)[0], layout=lambda: amp.causal(1, 128, 128),
+                                    row_len=128, computed=True, pow2_rule=True),
 }
+# paths with one scale per tensor that have a scaled-conversion variant (streaming kernel)
+POW2_PATHS = ["dense", "dense_misaligned", "causal"]
 
 
 def run_path(path, rng_name):
     P = PATHS[path]
-    rg = RANGES[rng_name]
+    rg = RANGES_POW2[rng_name] if rng_name in RANGES_POW2 else RANGES[rng_name]
+    # scaled conversions: the flag on every format of the sensitivity call
+    call_fmts = [f | amp.SCALE_POW2 for f in FMTS] if (rng_name in RANGES_POW2 or P.get("pow2_rule")) else FMTS
     n0 = P["n0"]
     x_off = P.get("x_off", 0)
     linear = P.get("linear", False)
     row_len = P.get("row_len")
     computed = P.get("computed", False)
-    is_causal = path.endswith("causal")
+    is_causal = "causal" in path
     nf = len(FMTS)
     pat = patterns_of(rng_name)
     # the pattern buffer, repeated so that every window fits
@@ -165,10 +188,10 @@ def run_path(path, rng_name):
     out = torch.full((N_OPS * R, nf, 4), -1.0, dtype=torch.float32, device=DEV)
     if linear:
         ws = torch.empty(amp.amp_sens_linear_workspace_bytes(ops, nf), dtype=torch.uint8, device=DEV)
-        amp.amp_sens_linear(ops, FMTS, out, ws)
+        amp.amp_sens_linear(ops, call_fmts, out, ws)
     else:
         ws = torch.empty(amp.amp_sens_bgemm_workspace_bytes(ops, nf), dtype=torch.uint8, device=DEV)
-        amp.amp_sens_bgemm(ops, FMTS, out, ws)
+        amp.amp_sens_bgemm(ops, call_fmts, out, ws)
     torch.cuda.synchronize()
     got = out.cpu().numpy().reshape(N_OPS, R, nf, 4)
     col = 2 if linear else 0
@@ -191,7 +214,11 @@ def run_path(path, rng_name):
             rows_x = xbig[start[:, None] + np.arange(valid)[None, :]]
         for fi, f in enumerate(FMTS):
             if computed:
-                _, sc_k, iv_k, _ = oracle.absmax_scale_rows(rows_x.reshape(-1), N_OPS, valid, f)
+                am_k, sc_k, iv_k, _ = oracle.absmax_scale_rows(rows_x.reshape(-1), N_OPS, valid, f)
+                if P.get("pow2_rule"):
+                    both = [oracle.scale_pow2(int(b), f) for b in (parity.bits32(am_k) >> 16)]
+                    sc_k = np.array([b_[0] for b_ in both], dtype=np.float32)
+                    iv_k = np.array([b_[1] for b_ in both], dtype=np.float32)
                 E, A = np.empty(N_OPS), np.empty(N_OPS)
                 pairs_of = {}
                 for k in range(N_OPS):
@@ -217,4 +244,11 @@ def run_path(path, rng_name):
 @pytest.mark.parametrize("path", list(PATHS))
 def test_every_pattern_through_a_fused_kernel(path, rng_name):
     say("pattern sweep through %s, value range %s" % (path, rng_name))
+    run_path(path, rng_name)
+
+
+@pytest.mark.parametrize("rng_name", list(RANGES_POW2))
+@pytest.mark.parametrize("path", POW2_PATHS)
+def test_every_pattern_through_the_scaled_conversions(path, rng_name):
+    say("pattern sweep through %s with the scaled conversions, value range %s" % (path, rng_name))
     run_path(path, rng_name)
