@@ -63,17 +63,14 @@ int persistent_grid(uint64_t n_chunks, int resident, int limit) {
     return (int)(n_chunks < cap ? n_chunks : cap);
 }
 
-// fused_nv: vectors of x per thread the single-read kernel (class 4) stages in LDS, 0 for the others
-int sens_resident(int n_fmts, int f0, int f1, int cls, int fused_nv) {
+int sens_resident(int n_fmts, int f0, int f1, int cls) {
     static std::mutex mu;
-    static int cached[64][2][2][2][kSensClasses][kFusedMaxNv + 1];
+    static int cached[64][2][2][2][kSensClasses];
     const int dev = device_index();
-    const size_t lds = cls == 4 ? fused_lds_bytes(fused_nv) : 0;
-    if (fused_nv < 0 || fused_nv > kFusedMaxNv) fused_nv = kFusedMaxNv;
-    if (dev < 0) return sens_resident_blocks(n_fmts, f0, f1, cls, device_cus(), lds);
+    if (dev < 0) return sens_resident_blocks(n_fmts, f0, f1, cls, device_cus());
     std::lock_guard<std::mutex> lock(mu);
-    int& slot = cached[dev][n_fmts - 1][f0][f1][cls][cls == 4 ? fused_nv : 0];
-    if (slot == 0) slot = sens_resident_blocks(n_fmts, f0, f1, cls, device_cus(), lds);
+    int& slot = cached[dev][n_fmts - 1][f0][f1][cls];
+    if (slot == 0) slot = sens_resident_blocks(n_fmts, f0, f1, cls, device_cus());
     return slot;
 }
 
@@ -106,7 +103,6 @@ struct PlanData {
     uint32_t magic, kind;
     uint8_t* ws;                                   // the workspace the set-up wrote
     int32_t n_fmts, fmt0, fmt1, grid_limit;
-    int32_t fused_nv;                              // single-read pass: vectors of x per thread staged in LDS
     uint32_t n_units, n_chunks;
     uint64_t off_cb, off_groups, off_runits, off_map, off_partials;    // the unit table sits at offset 0
     // sensitivity pass
@@ -170,7 +166,6 @@ amp_status_t sens_setup(const WorkTable& t, const amp_fp8_format_t* fmts, int n_
     P->off_map = L.map;
     P->off_partials = L.partials;
     P->d_out = d_out;
-    P->fused_nv = t.fused_nv;
     for (int v = 0; v < 2; ++v) {
         P->w_groups[v] = (uint32_t)plan.w_groups[v];
         P->w_items[v] = (uint32_t)plan.w_items[v];
@@ -228,10 +223,10 @@ amp_status_t sens_run(const PlanData& P, hipStream_t stream) {
     for (int cls = 0; cls < kSensClasses; ++cls) {
         const uint64_t n_pos = P.class_pos[cls + 1] - P.class_pos[cls];
         if (n_pos == 0) continue;
-        const int grid = persistent_grid(n_pos, sens_resident(nf, f0, f1, cls, P.fused_nv), P.grid_limit);
+        const int grid = persistent_grid(n_pos, sens_resident(nf, f0, f1, cls), P.grid_limit);
         AMP_HIP(timed(P.class_pairs[cls], P.class_pairs[cls] * 4, [&]() {
             return launch_sens(d_runits, d_map + P.class_pos[cls], (uint32_t)n_pos, nf, P.fmt0, P.fmt1, cls,
-                               d_partials, grid, cls == 4 ? fused_lds_bytes(P.fused_nv) : 0, stream);
+                               d_partials, grid, stream);
         }));
     }
     AMP_HIP(launch_sens_finalize(d_runits, d_cb, P.n_units, nf, d_partials, P.d_out, stream));

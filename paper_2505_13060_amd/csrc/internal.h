@@ -50,16 +50,15 @@ enum : uint32_t {
 // follow the row: the rows of a matrix fall into classes (lanes = 4, 8, ..., 256) by length, tiles are
 // consecutive rows of one class, and a tile's work is about the same whatever its class.  A chunk is
 // `tiles` consecutive tiles of a unit (dense) or of a matrix (causal).
-#ifndef AMPSENS_FUSED_NV
-#define AMPSENS_FUSED_NV 8
-#endif
 #ifndef AMPSENS_FUSED_GROUP
 #define AMPSENS_FUSED_GROUP 4
 #endif
-constexpr int kFusedNv = AMPSENS_FUSED_NV;         // vectors of a row per thread the geometry aims at
-constexpr int kFusedGroup = AMPSENS_FUSED_GROUP;   // vectors per thread handled (and in flight) together
+constexpr int kFusedRegNv = 4;                     // rows that leave a thread at most this many vectors stay in registers
+constexpr int kFusedNv = kFusedRegNv;              // vectors of a row per thread the geometry aims at
+constexpr int kFusedGroup = AMPSENS_FUSED_GROUP;   // LDS path: vectors per thread handled (and in flight) together
 constexpr int kFusedMaxNv = 12;                    // LDS: 256 threads x 16 bytes x nv <= 48 KiB per workgroup
 constexpr int64_t kFusedMaxRowLen = (int64_t)kWG * kFusedMaxNv * kVec;     // 24576 elements
+constexpr int64_t kFusedChunkVecs = 8192;          // vectors per chunk the geometry aims at
 static_assert(kFusedNv % kFusedGroup == 0 && kFusedMaxNv % kFusedGroup == 0, "whole groups");
 
 // lanes (as log2) for a row of row_vecs vectors
@@ -129,24 +128,24 @@ inline FusedGeom fused_geometry(int64_t row_len, bool causal) {
         nv = (nv + kFusedGroup - 1) / kFusedGroup * kFusedGroup;
         return nv < kFusedGroup ? (int64_t)kFusedGroup : nv;
     };
-    if (!causal) {
-        // dense rows all have the same length: the lanes that waste the fewest vector slots (a thread's
-        // vectors come in whole groups), among those that leave at most kFusedMaxNv vectors per thread;
-        // ties go to the geometry the row length asks for, then to more lanes
+    if (!causal && nv_of(g.lanes_log2) > kFusedRegNv) {
+        // dense rows too long for the register path: the lanes that waste the fewest vector slots (a
+        // thread's vectors come in whole groups), among those that leave at most kFusedMaxNv vectors per
+        // thread; ties go to more lanes (less LDS per workgroup)
         int best = -1;
         int64_t best_slots = 0;
         for (int lg = 2; lg <= 8; ++lg) {
             const int64_t nv = nv_of(lg);
             if (nv > kFusedMaxNv) continue;
             const int64_t slots = nv << lg;
-            if (best < 0 || slots < best_slots || (slots == best_slots && lg == g.lanes_log2)) { best = lg; best_slots = slots; }
+            if (best < 0 || slots <= best_slots) { best = lg; best_slots = slots; }
         }
         if (best >= 0) g.lanes_log2 = best;
     }
     g.nv = (int)nv_of(g.lanes_log2);
     // vectors per tile: dense rows_per_tile whole rows; causal about three quarters of 256 x kFusedNv
     const int64_t per = causal ? (int64_t)kWG * kFusedNv * 3 / 4 : (int64_t)g.rows_per_tile() * row_vecs;
-    int64_t t = per > 0 ? (kChunkVecs + per / 2) / per : 1;
+    int64_t t = per > 0 ? (kFusedChunkVecs + per / 2) / per : 1;
     g.tiles = (int)(t < 1 ? 1 : (t > 64 ? 64 : t));
     return g;
 }
@@ -260,9 +259,17 @@ inline uint32_t causal_chunks_per_mat(int64_t rows) {
 // Persistent-grid size for the streaming kernels on the current device (resident workgroups).
 // cls: the class of units the variant is for: 0 = one scale per tensor; 1 = row scales, rows of at
 // least 512 elements or aligned causal rows; 2 = row scales, any other shape; 3 = row scales, rows
-// of a power-of-two length below 512; 4 = row scales computed by the pass itself (single read).
-constexpr int kSensClasses = 5;
-int sens_resident_blocks(int n_fmts, int fmt0, int fmt1, int cls, int cus, size_t lds_bytes = 0);
+// of a power-of-two length below 512; 4, 5, 6 = row scales computed by the pass itself (single read),
+// by the vectors of a row a thread holds: up to 4 (kept in registers), 8, 12 (parked in LDS; the launch
+// of each class asks for the LDS its units need and no more, which decides how many workgroups a
+// compute unit holds).
+constexpr int kSensClasses = 7;
+constexpr int kFirstFusedClass = 4;
+inline int fused_class_of(int nv) { return kFirstFusedClass + (nv > kFusedRegNv ? 1 : 0) + (nv > 8 ? 1 : 0); }
+inline size_t sens_class_lds_bytes(int cls) {
+    return cls > kFirstFusedClass ? fused_lds_bytes(4 * (cls - kFirstFusedClass + 1)) : 0;   // class 4 keeps its rows in registers
+}
+int sens_resident_blocks(int n_fmts, int fmt0, int fmt1, int cls, int cus);
 int absmax_resident_blocks(int cus);
 int absmax_rows_resident_blocks(int cus);
 
@@ -286,11 +293,11 @@ hipError_t launch_absmax_finalize(const uint32_t* d_chunk_begin, const uint32_t*
                                   hipStream_t stream);
 hipError_t launch_fake_quant(const uint16_t* d_x, int64_t n, float scale, float inv, int fmt,
                              uint8_t* d_codes, float* d_dequant, int grid, hipStream_t stream);
-// fmt0 / fmt1 may carry the scale-rule flag and lds_bytes is the dynamic LDS of a workgroup (both
-// used by class 4 only, which computes scales and stages rows in LDS).
+// fmt0 / fmt1 may carry the scale-rule flag: it selects the scaled-conversion variants (classes 0 and
+// 4 to 6) and is the rule by which classes 4 to 6 derive their row scales.
 hipError_t launch_sens(const ResolvedUnit* d_runits, const ChunkRef* d_map, uint32_t n_chunks,
-                       int n_fmts, int fmt0, int fmt1, int rows, float* d_partials, int grid,
-                       size_t lds_bytes, hipStream_t stream);
+                       int n_fmts, int fmt0, int fmt1, int cls, float* d_partials, int grid,
+                       hipStream_t stream);
 int sens_w_resident_blocks(int n_fmts, int fmt0, int fmt1, int rows, int cus);
 hipError_t launch_sens_w(const WGroup* d_groups, uint32_t n_groups, uint32_t n_items,
                          const ResolvedUnit* d_runits, const uint32_t* d_chunk_begin, int n_fmts, int fmt0,

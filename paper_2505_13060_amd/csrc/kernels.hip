@@ -89,6 +89,16 @@ __device__ __forceinline__ float clamp_fmax(float y) {
     return __builtin_amdgcn_fmed3f(y, -Fp8<FMT>::kMax, Fp8<FMT>::kMax);
 }
 
+// The sensitivity kernels leave the clamp to the conversion itself: while MODE.FP16_OVFL is set,
+// gfx950's FP8 conversions turn a finite input beyond the format's range into the largest finite code
+// (measured for every bf16 pattern as fp32 input and for fp32 values around 448 / 464 / 480 and
+// 57344 / 61440 / 65536: the same code as clamping to +-FMAX first; infinities and NaN keep their own
+// codes), which saves one instruction per element and format.  MODE belongs to the wave and ends with
+// it; every sensitivity kernel calls this before anything else.
+__device__ __forceinline__ void saturating_fp8_conversions() {
+    __builtin_amdgcn_s_setreg(1 | (23 << 6) | (0 << 11), 1);       // hwreg(HW_REG_MODE, offset 23, 1 bit) = FP16_OVFL
+}
+
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
@@ -225,10 +235,7 @@ template <int F>
 __device__ __forceinline__ void one_format(const float (&xv)[4], const float (&gv)[4], float iv,
                                            float sc, float& Ef, int& p) {
     {
-        const float y0 = clamp_fmax<F>(xv[0] * iv);
-        const float y1 = clamp_fmax<F>(xv[1] * iv);
-        const float y2 = clamp_fmax<F>(xv[2] * iv);
-        const float y3 = clamp_fmax<F>(xv[3] * iv);
+        const float y0 = xv[0] * iv, y1 = xv[1] * iv, y2 = xv[2] * iv, y3 = xv[3] * iv;   // the conversion saturates
         p = Fp8<F>::pack(y0, y1, p, false);
         p = Fp8<F>::pack(y2, y3, p, true);
         const float2_t q01 = Fp8<F>::unpack(p, false);
@@ -459,12 +466,12 @@ struct SensRowCtx {
         const float a = gf * xf;
         A = fmaf(a, a, A);
         {
-            const int p = Fp8<F0>::pack(clamp_fmax<F0>(xf * iv[0]), 0.0f, 0, false);
+            const int p = Fp8<F0>::pack(xf * iv[0], 0.0f, 0, false);
             const float t = gf * fmaf(-Fp8<F0>::unpack(p, false).x, sc[0], xf);
             E[0] = fmaf(t, t, E[0]);
         }
         if constexpr (NF > 1) {
-            const int p = Fp8<F1>::pack(clamp_fmax<F1>(xf * iv[1]), 0.0f, 0, false);
+            const int p = Fp8<F1>::pack(xf * iv[1], 0.0f, 0, false);
             const float t = gf * fmaf(-Fp8<F1>::unpack(p, false).x, sc[1], xf);
             E[1] = fmaf(t, t, E[1]);
         }
@@ -767,6 +774,7 @@ template <int NF, int F0, int F1, bool POW2>
 __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(AMPSENS_SENS_WAVES, AMPSENS_SENS_WAVES))) void sens_kernel(const ResolvedUnit* __restrict__ runits,
                                                    const ChunkRef* __restrict__ map,
                                                    uint32_t n_chunks, float* __restrict__ partials) {
+    saturating_fp8_conversions();
     sens_body<SensCtx<NF, F0, F1, POW2>, NF>(runits, map, n_chunks, partials);
 }
 
@@ -777,6 +785,7 @@ template <int NF, int F0, int F1, bool SHORT>
 __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(AMPSENS_WROWS_WAVES, AMPSENS_WROWS_WAVES))) void sens_wrows_kernel(const ResolvedUnit* __restrict__ runits,
                                                         const ChunkRef* __restrict__ map,
                                                         uint32_t n_chunks, float* __restrict__ partials) {
+    saturating_fp8_conversions();
     sens_body<SensWaveRowCtx<NF, F0, F1, SHORT>, NF>(runits, map, n_chunks, partials);
 }
 
@@ -787,6 +796,7 @@ template <int NF, int F0, int F1>
 __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(AMPSENS_ROWS_WAVES, AMPSENS_ROWS_WAVES))) void sens_rows_kernel(const ResolvedUnit* __restrict__ runits,
                                                         const ChunkRef* __restrict__ map,
                                                         uint32_t n_chunks, float* __restrict__ partials) {
+    saturating_fp8_conversions();
     sens_body<SensRowCtx<NF, F0, F1>, NF>(runits, map, n_chunks, partials);
 }
 
@@ -805,6 +815,7 @@ __global__ __launch_bounds__(kWG) void sens_w_kernel(const WGroup* __restrict__ 
                                                      const ResolvedUnit* __restrict__ runits,
                                                      const uint32_t* __restrict__ chunk_begin,
                                                      float* __restrict__ partials) {
+    saturating_fp8_conversions();
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     for (uint32_t item = blockIdx.x; item < n_items; item += gridDim.x) {
@@ -885,13 +896,13 @@ __global__ __launch_bounds__(kWG) void sens_w_kernel(const WGroup* __restrict__ 
                 for (int f = 0; f < NF; ++f) {
                     float q4[4];
                     if (f == 0) {
-                        pk = Fp8<F0>::pack(clamp_fmax<F0>(x4[0] * inv[0]), clamp_fmax<F0>(x4[1] * inv[0]), pk, false);
-                        pk = Fp8<F0>::pack(clamp_fmax<F0>(x4[2] * inv[0]), clamp_fmax<F0>(x4[3] * inv[0]), pk, true);
+                        pk = Fp8<F0>::pack(x4[0] * inv[0], x4[1] * inv[0], pk, false);
+                        pk = Fp8<F0>::pack(x4[2] * inv[0], x4[3] * inv[0], pk, true);
                         const float2_t a = Fp8<F0>::unpack(pk, false), b = Fp8<F0>::unpack(pk, true);
                         q4[0] = a.x; q4[1] = a.y; q4[2] = b.x; q4[3] = b.y;
                     } else {
-                        pk = Fp8<F1>::pack(clamp_fmax<F1>(x4[0] * inv[f]), clamp_fmax<F1>(x4[1] * inv[f]), pk, false);
-                        pk = Fp8<F1>::pack(clamp_fmax<F1>(x4[2] * inv[f]), clamp_fmax<F1>(x4[3] * inv[f]), pk, true);
+                        pk = Fp8<F1>::pack(x4[0] * inv[f], x4[1] * inv[f], pk, false);
+                        pk = Fp8<F1>::pack(x4[2] * inv[f], x4[3] * inv[f], pk, true);
                         const float2_t a = Fp8<F1>::unpack(pk, false), b = Fp8<F1>::unpack(pk, true);
                         q4[0] = a.x; q4[1] = a.y; q4[2] = b.x; q4[3] = b.y;
                     }
@@ -1259,6 +1270,13 @@ __device__ __forceinline__ float scale_quantity(uint32_t bits, int code, bool wa
     return want_inv ? fm / amax : amax / fm;
 }
 
+// max(v, v of the lane a DPP pattern names); every lane has a source in the patterns used here
+template <int CTRL>
+__device__ __forceinline__ uint32_t max_with_dpp(uint32_t v) {
+    const uint32_t w = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
+    return w > v ? w : v;
+}
+
 template <int CTRL>
 __device__ __forceinline__ float quad_broadcast(float v) {
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
@@ -1374,6 +1392,139 @@ struct FusedRows {
         }
     }
 
+    // From the packed maxima a thread folded over its vectors of a row (m2) to the row's scales: the
+    // maximum over the row's threads, the scales by the call's rule (each thread of a quad derives one of
+    // the four numbers), the row's entries of the tables.  POW2: iv returns the scales the codes are
+    // taken back with and mul their multiplier (one_format_pow2).
+    __device__ __forceinline__ void row_scales(const FusedTile& t, uint32_t m2, float (&sc)[NF], float (&iv)[NF], float& mul) {
+        // maximum over the row's threads (L consecutive lanes, L a power of two >= 4): quads, then halves
+        // of a 16-lane row, then its mirror image, by DPP; the steps across 16-lane rows by lane shuffles
+        const int lg = t.lanes_log2;
+        const int tid = threadIdx.x;
+        const int j = tid & ((1 << lg) - 1);
+        uint32_t m = (m2 & 0xFFFFu) > (m2 >> 16) ? (m2 & 0xFFFFu) : (m2 >> 16);
+        m = max_with_dpp<0xB1>(m);                                 // quad_perm [1, 0, 3, 2]
+        m = max_with_dpp<0x4E>(m);                                 // quad_perm [2, 3, 0, 1]
+        if (lg > 2) m = max_with_dpp<0x141>(m);                    // row_half_mirror
+        if (lg > 3) m = max_with_dpp<0x140>(m);                    // row_mirror
+        if (lg > 4) {
+            const uint32_t w = (uint32_t)__shfl_xor((int)m, 16);
+            m = w > m ? w : m;
+        }
+        if (lg > 5) {
+            const uint32_t w = (uint32_t)__shfl_xor((int)m, 32);
+            m = w > m ? w : m;
+        }
+        if (lg > 6) {                                  // the row spans 2 or 4 waves (uniform over the workgroup)
+            const int wave = tid >> 6;
+            if ((tid & 63) == 0) red[parity * kWaves + wave] = m;
+            __syncthreads();
+            const int w0 = lg == 7 ? (wave & 2) : 0, wn = lg == 7 ? 2 : 4;
+            for (int w = 0; w < wn; ++w) {
+                const uint32_t v = red[parity * kWaves + w0 + w];
+                m = m > v ? m : v;
+            }
+            parity ^= 1;
+        }
+        // the scales: each thread of a quad derives one of (scale_0, inv_0, scale_1, inv_1), then the quad shares them
+        {
+            const int q = j & 3;
+            const int f = NF > 1 ? (q >> 1) : 0;
+            const float mine = scale_quantity(m, f == 0 ? code0 : code1, (q & 1) != 0);
+            sc[0] = quad_broadcast<0x00>(mine);
+            iv[0] = quad_broadcast<0x55>(mine);
+            if constexpr (NF > 1) {
+                sc[1] = quad_broadcast<0xAA>(mine);
+                iv[1] = quad_broadcast<0xFF>(mine);
+            }
+        }
+        if (t.live && j == 0) {
+#pragma unroll
+            for (int f = 0; f < NF; ++f) {
+                ts[t.row * NF + f] = sc[f];
+                ti[t.row * NF + f] = iv[f];
+            }
+        }
+        mul = -1.0f;
+        if constexpr (POW2) {
+            // a row whose absmax is at least 1 has scales of at least 2^-15 in either format: a quarter of
+            // them is a normal number; any other row is far from the overflow the quarter is for
+            const bool roomy = m >= 0x3F80u;
+            mul = roomy ? -4.0f : -1.0f;
+#pragma unroll
+            for (int f = 0; f < NF; ++f) iv[f] = roomy ? sc[f] * 0.25f : sc[f];
+        }
+    }
+
+    // Tiles whose threads hold at most kFusedRegNv vectors of their row stay in registers (no LDS): the
+    // vectors of x and of the gradient are all requested at once (regs_issue), and later (regs_finish) x
+    // is folded into the row's absmax, the scales are derived, and the sums formed from the registers.
+    // (Requesting the next tile's vectors before finishing the current one was measured and gave nothing:
+    // the pass is bound by vector-instruction issue, not by exposed latency.)  Addresses and masks as in tile().
+    struct Regs { u32x4 x[kFusedRegNv], g[kFusedRegNv]; };
+
+    __device__ __forceinline__ void regs_issue(const FusedTile& t, Regs& r) {
+        constexpr int NV = kFusedRegNv;
+        const int lg = t.lanes_log2;
+        const int j = threadIdx.x & ((1 << lg) - 1);
+        const gptr128_t px = reinterpret_cast<gptr128_t>(x + t.row * (int64_t)cols);
+        const gptr128_t pg = reinterpret_cast<gptr128_t>(g + t.row * (int64_t)cols);
+        if (t.nv_exact >= NV) {                        // every vector of every thread is a whole vector of a live row
+#pragma unroll
+            for (int k = 0; k < NV; ++k) r.x[k] = load128<true>(px + (j + (k << lg)));
+#pragma unroll
+            for (int k = 0; k < NV; ++k) r.g[k] = load128<true>(pg + (j + (k << lg)));
+        } else {
+            const int nvr = (t.len + kVec - 1) / kVec;
+            const int last = nvr > 0 ? nvr - 1 : 0;
+            int at[NV];
+#pragma unroll
+            for (int k = 0; k < NV; ++k) {
+                const int v = j + (k << lg);
+                at[k] = v < last ? v : last;
+            }
+#pragma unroll
+            for (int k = 0; k < NV; ++k) r.x[k] = load128<true>(px + at[k]);
+#pragma unroll
+            for (int k = 0; k < NV; ++k) r.g[k] = load128<true>(pg + at[k]);
+        }
+    }
+
+    __device__ __forceinline__ void regs_finish(const FusedTile& t, Regs& r) {
+        constexpr int NV = kFusedRegNv;
+        const int lg = t.lanes_log2;
+        const int j = threadIdx.x & ((1 << lg) - 1);
+        if (t.nv_exact < NV) {
+            const int32_t len = t.live ? t.len : 0;
+#pragma unroll
+            for (int k = 0; k < NV; ++k) {
+                int c = len - (j + (k << lg)) * kVec;
+                c = c < 0 ? 0 : (c > kVec ? kVec : c);
+                if (__builtin_amdgcn_ballot_w64(c != kVec) != 0) {   // most waves hold whole vectors only
+                    r.x[k] = keep_leading(r.x[k], c);
+                    r.g[k] = keep_leading(r.g[k], c);
+                }
+            }
+        }
+        uint32_t m2 = 0;
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+            const uint32_t w[4] = {r.x[k].x, r.x[k].y, r.x[k].z, r.x[k].w};
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const u16x2 a = __builtin_bit_cast(u16x2, m2), b = __builtin_bit_cast(u16x2, w[q] & 0x7FFF7FFFu);
+                m2 = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(a, b));
+            }
+        }
+        float sc[NF], iv[NF], mul;
+        row_scales(t, m2, sc, iv, mul);
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+            quad(r.x[k].x, r.x[k].y, r.g[k].x, r.g[k].y, iv, sc, mul);
+            quad(r.x[k].z, r.x[k].w, r.g[k].z, r.g[k].w, iv, sc, mul);
+        }
+    }
+
     // One tile.  First visit: every thread loads its vectors of its row (each byte of x leaves HBM
     // here, once), folds them into the row's absmax and parks them in its own LDS slots; the absmax is
     // reduced over the row's threads and the scales derived and written to the tables.  Second visit:
@@ -1429,57 +1580,14 @@ struct FusedRows {
             for (int k = 0; k < kG; ++k) xr[k] = load128<true>(px + clamped(k0 + k));
 #pragma unroll
             for (int k = 0; k < kG; ++k) {
-                xr[k] = keep_leading(xr[k], count(k0 + k));
+                const int c = count(k0 + k);                       // most waves hold whole vectors only: no masks then
+                if (__builtin_amdgcn_ballot_w64(c != kVec) != 0) xr[k] = keep_leading(xr[k], c);
                 m2 = fold(m2, xr[k]);
                 stage[(k0 + k) * kWG + tid] = xr[k];
             }
         }
-        uint32_t m = (m2 & 0xFFFFu) > (m2 >> 16) ? (m2 & 0xFFFFu) : (m2 >> 16);
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {                         // partners outside the row's threads do not count
-            const uint32_t w = (uint32_t)__shfl_xor((int)m, o);
-            m = (o < L && w > m) ? w : m;
-        }
-        if (lg > 6) {                                  // the row spans 2 or 4 waves (uniform over the workgroup)
-            const int wave = tid >> 6;
-            if ((tid & 63) == 0) red[parity * kWaves + wave] = m;
-            __syncthreads();
-            const int w0 = lg == 7 ? (wave & 2) : 0, wn = lg == 7 ? 2 : 4;
-            for (int w = 0; w < wn; ++w) {
-                const uint32_t v = red[parity * kWaves + w0 + w];
-                m = m > v ? m : v;
-            }
-            parity ^= 1;
-        }
-        // the scales: each thread of a quad derives one of (scale_0, inv_0, scale_1, inv_1), then the quad shares them
-        float sc[NF], iv[NF];
-        {
-            const int q = j & 3;
-            const int f = NF > 1 ? (q >> 1) : 0;
-            const float mine = scale_quantity(m, f == 0 ? code0 : code1, (q & 1) != 0);
-            sc[0] = quad_broadcast<0x00>(mine);
-            iv[0] = quad_broadcast<0x55>(mine);
-            if constexpr (NF > 1) {
-                sc[1] = quad_broadcast<0xAA>(mine);
-                iv[1] = quad_broadcast<0xFF>(mine);
-            }
-        }
-        if (t.live && j == 0) {
-#pragma unroll
-            for (int f = 0; f < NF; ++f) {
-                ts[t.row * NF + f] = sc[f];
-                ti[t.row * NF + f] = iv[f];
-            }
-        }
-        float mul = -1.0f;
-        if constexpr (POW2) {
-            // a row whose absmax is at least 1 has scales of at least 2^-15 in either format: a quarter of
-            // them is a normal number; any other row is far from the overflow the quarter is for
-            const bool roomy = m >= 0x3F80u;
-            mul = roomy ? -4.0f : -1.0f;
-#pragma unroll
-            for (int f = 0; f < NF; ++f) iv[f] = roomy ? sc[f] * 0.25f : sc[f];
-        }
+        float sc[NF], iv[NF], mul;
+        row_scales(t, m2, sc, iv, mul);
         // second visit: x from this thread's LDS slots (already cleared where it had to be), the gradient from
         // HBM.  Vectors outside the row are (0, 0) and add exactly 0.
         k0 = 0;
@@ -1505,7 +1613,8 @@ struct FusedRows {
             for (int k = 0; k < kG; ++k) xr[k] = stage[(k0 + k) * kWG + tid];
 #pragma unroll
             for (int k = 0; k < kG; ++k) {
-                gr[k] = keep_leading(gr[k], count(k0 + k));
+                const int c = count(k0 + k);
+                if (__builtin_amdgcn_ballot_w64(c != kVec) != 0) gr[k] = keep_leading(gr[k], c);
                 quad(xr[k].x, xr[k].y, gr[k].x, gr[k].y, iv, sc, mul);
                 quad(xr[k].z, xr[k].w, gr[k].z, gr[k].w, iv, sc, mul);
             }
@@ -1516,10 +1625,17 @@ struct FusedRows {
 #ifndef AMPSENS_FUSED_WAVES
 #define AMPSENS_FUSED_WAVES 6
 #endif
-template <int NF, int F0, int F1, bool POW2>
-__global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(AMPSENS_FUSED_WAVES, AMPSENS_FUSED_WAVES)))
+#ifndef AMPSENS_FUSED_REGS_WAVES
+#define AMPSENS_FUSED_REGS_WAVES 6
+#endif
+// REGS: the variant for units whose threads hold at most kFusedRegNv vectors of a row (tile_regs, no
+// dynamic LDS); otherwise rows are staged in LDS (tile).
+template <int NF, int F0, int F1, bool POW2, bool REGS>
+__global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(REGS ? AMPSENS_FUSED_REGS_WAVES : AMPSENS_FUSED_WAVES,
+                                                                    REGS ? AMPSENS_FUSED_REGS_WAVES : AMPSENS_FUSED_WAVES)))
 void sens_fused_rows_kernel(const ResolvedUnit* __restrict__ runits, const ChunkRef* __restrict__ map,
                             uint32_t n_chunks, float* __restrict__ partials, int code0, int code1) {
+    saturating_fp8_conversions();
     extern __shared__ __attribute__((aligned(16))) unsigned char fused_lds[];   // [nv][kWG] vectors, then 2 * kWaves words
     __shared__ uint32_t red[2 * kWaves];
     const int tid = threadIdx.x;
@@ -1544,7 +1660,15 @@ void sens_fused_rows_kernel(const ResolvedUnit* __restrict__ runits, const Chunk
         ctx.A = 0.0f;
         FusedTileWalk walk;
         walk.begin(u, geo, ref.local, tid);
-        for (FusedTile t = walk.next(); t.valid; t = walk.next()) ctx.tile(t);
+        if constexpr (REGS) {
+            typename FusedRows<NF, F0, F1, POW2>::Regs r;
+            for (FusedTile t = walk.next(); t.valid; t = walk.next()) {
+                ctx.regs_issue(t, r);
+                ctx.regs_finish(t, r);
+            }
+        } else {
+            for (FusedTile t = walk.next(); t.valid; t = walk.next()) ctx.tile(t);
+        }
         float v[NF + 1];
 #pragma unroll
         for (int f = 0; f < NF; ++f) v[f] = wave_sum(ctx.E[f]);
@@ -1605,15 +1729,17 @@ __global__ __launch_bounds__(kWG) void fake_quant_kernel(const uint16_t* __restr
 typedef void (*sens_fn_t)(const ResolvedUnit*, const ChunkRef*, uint32_t, float*);
 typedef void (*sens_fused_fn_t)(const ResolvedUnit*, const ChunkRef*, uint32_t, float*, int, int);
 
-template <bool POW2>
+template <bool POW2, bool REGS>
 sens_fused_fn_t sens_fused_variant_of(int n_fmts, int fmt0, int fmt1) {
-    if (n_fmts == 1) return fmt0 == 0 ? sens_fused_rows_kernel<1, 0, 0, POW2> : sens_fused_rows_kernel<1, 1, 1, POW2>;
-    if (fmt0 == 0) return fmt1 == 0 ? sens_fused_rows_kernel<2, 0, 0, POW2> : sens_fused_rows_kernel<2, 0, 1, POW2>;
-    return fmt1 == 0 ? sens_fused_rows_kernel<2, 1, 0, POW2> : sens_fused_rows_kernel<2, 1, 1, POW2>;
+    if (n_fmts == 1) return fmt0 == 0 ? sens_fused_rows_kernel<1, 0, 0, POW2, REGS> : sens_fused_rows_kernel<1, 1, 1, POW2, REGS>;
+    if (fmt0 == 0) return fmt1 == 0 ? sens_fused_rows_kernel<2, 0, 0, POW2, REGS> : sens_fused_rows_kernel<2, 0, 1, POW2, REGS>;
+    return fmt1 == 0 ? sens_fused_rows_kernel<2, 1, 0, POW2, REGS> : sens_fused_rows_kernel<2, 1, 1, POW2, REGS>;
 }
-// pow2: every format of the call carries the power-of-two scale rule
-sens_fused_fn_t sens_fused_variant(int n_fmts, int fmt0, int fmt1, bool pow2) {
-    return pow2 ? sens_fused_variant_of<true>(n_fmts, fmt0, fmt1) : sens_fused_variant_of<false>(n_fmts, fmt0, fmt1);
+// pow2: every format of the call carries the power-of-two scale rule; regs: the class whose rows stay in registers
+sens_fused_fn_t sens_fused_variant(int n_fmts, int fmt0, int fmt1, bool pow2, bool regs) {
+    if (regs)
+        return pow2 ? sens_fused_variant_of<true, true>(n_fmts, fmt0, fmt1) : sens_fused_variant_of<false, true>(n_fmts, fmt0, fmt1);
+    return pow2 ? sens_fused_variant_of<true, false>(n_fmts, fmt0, fmt1) : sens_fused_variant_of<false, false>(n_fmts, fmt0, fmt1);
 }
 
 template <bool POW2>
@@ -1651,9 +1777,11 @@ int resident_blocks(const void* fn, int cus, size_t lds_bytes = 0) {
 
 }  // namespace
 
-int sens_resident_blocks(int n_fmts, int fmt0, int fmt1, int rows, int cus, size_t lds_bytes) {
-    if (rows >= 4) return resident_blocks((const void*)sens_fused_variant(n_fmts, fmt0, fmt1, false), cus, lds_bytes);
-    return resident_blocks((const void*)sens_variant(n_fmts, fmt0, fmt1, rows), cus);
+int sens_resident_blocks(int n_fmts, int fmt0, int fmt1, int cls, int cus) {
+    if (cls >= kFirstFusedClass)
+        return resident_blocks((const void*)sens_fused_variant(n_fmts, fmt0, fmt1, false, cls == kFirstFusedClass), cus,
+                               sens_class_lds_bytes(cls));
+    return resident_blocks((const void*)sens_variant(n_fmts, fmt0, fmt1, cls), cus);
 }
 
 typedef void (*sens_w_fn_t)(const WGroup*, uint32_t, uint32_t, const ResolvedUnit*, const uint32_t*, float*);
@@ -1757,15 +1885,15 @@ hipError_t launch_fake_quant(const uint16_t* d_x, int64_t n, float scale, float 
 }
 
 hipError_t launch_sens(const ResolvedUnit* d_runits, const ChunkRef* d_map, uint32_t n_chunks,
-                       int n_fmts, int fmt0, int fmt1, int rows, float* d_partials, int grid,
-                       size_t lds_bytes, hipStream_t stream) {
+                       int n_fmts, int fmt0, int fmt1, int cls, float* d_partials, int grid,
+                       hipStream_t stream) {
     // the scaled conversions serve calls whose formats all carry the power-of-two scale rule
     const bool pow2 = (fmt0 & kScalePow2) != 0 && (fmt1 & kScalePow2) != 0;
-    if (rows >= 4)
-        hipLaunchKernelGGL(sens_fused_variant(n_fmts, fmt0 & 0xFF, fmt1 & 0xFF, pow2), dim3(grid), dim3(kWG), lds_bytes,
-                           stream, d_runits, d_map, n_chunks, d_partials, fmt0, fmt1);
+    if (cls >= kFirstFusedClass)
+        hipLaunchKernelGGL(sens_fused_variant(n_fmts, fmt0 & 0xFF, fmt1 & 0xFF, pow2, cls == kFirstFusedClass), dim3(grid), dim3(kWG),
+                           sens_class_lds_bytes(cls), stream, d_runits, d_map, n_chunks, d_partials, fmt0, fmt1);
     else
-        hipLaunchKernelGGL(sens_variant(n_fmts, fmt0 & 0xFF, fmt1 & 0xFF, rows, pow2), dim3(grid), dim3(kWG), 0, stream,
+        hipLaunchKernelGGL(sens_variant(n_fmts, fmt0 & 0xFF, fmt1 & 0xFF, cls, pow2), dim3(grid), dim3(kWG), 0, stream,
                            d_runits, d_map, n_chunks, d_partials);
     return hipGetLastError();
 }

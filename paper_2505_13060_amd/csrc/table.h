@@ -68,7 +68,6 @@ struct WorkTable {
     uint64_t n_chunks = 0;
     uint64_t n_pairs = 0;                         // elements that belong to the operands
     bool any_rows = false;                        // some unit has one scale per row
-    int fused_nv = 0;                             // most vectors of x a thread of the single-read pass stages in LDS
 
     // x / dx may be null only for blocks without elements.
     amp_status_t add(const uint16_t* x, const uint16_t* dx, const amp_layout_t& L, int64_t batch_mul,
@@ -107,7 +106,6 @@ struct WorkTable {
                 const FusedGeom g = fused_geometry(L.cols, true);
                 u.head = g.pack();
                 u.chunks_per_mat = (L.rows > 0 && L.cols > 0) ? fused_chunks_per_mat(L.rows, L.cols, g) : 0;
-                if (g.nv > fused_nv) fused_nv = g.nv;
             }
             chunks = (uint64_t)batch * u.chunks_per_mat;
             if (chunks == 0) u.chunks_per_mat = 1;         // never divide by zero on the device
@@ -134,7 +132,6 @@ struct WorkTable {
                 const FusedGeom g = fused_geometry(row_len, false);
                 u.head = g.pack();
                 chunks = fused_chunks_dense(u.rows, g);
-                if (g.nv > fused_nv) fused_nv = g.nv;
             }
             n_pairs += (uint64_t)n;
             unit_pairs.push_back((uint64_t)n);
@@ -170,10 +167,11 @@ struct WorkTable {
     // Which streaming kernel takes a unit: 0 = one scale per tensor; 1 = one scale per row with
     // rows long enough that a wave's 512 contiguous elements meet at most two of them, or an
     // aligned causal unit; 3 = short rows of a power-of-two length (a wave step covers whole rows);
-    // 2 = any other unit with row scales (other short rows, rows not made of whole vectors).
+    // 2 = any other unit with row scales (other short rows, rows not made of whole vectors);
+    // 4, 5, 6 = the single-read pass, by the LDS a workgroup needs for the unit's rows.
     static int unit_class(const WorkUnit& u) {
         if (!(u.flags & kUnitRowScale)) return 0;
-        if (u.flags & kUnitFused) return 4;
+        if (u.flags & kUnitFused) return fused_class_of(FusedGeom::unpack(u.head).nv);
         if (u.flags & kUnitScalar) return 2;
         if (u.flags & kUnitCausal) return 1;
         if (u.cols >= kVec * 64) return 1;

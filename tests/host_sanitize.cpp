@@ -12,7 +12,7 @@
 #include <vector>
 
 namespace ampsens {      // the kernels' launchers: never reached from the calls below
-int sens_resident_blocks(int, int, int, int, int cus, size_t) { return 8 * cus; }
+int sens_resident_blocks(int, int, int, int, int cus) { return 8 * cus; }
 int absmax_resident_blocks(int cus) { return 8 * cus; }
 int absmax_rows_resident_blocks(int cus) { return 8 * cus; }
 int sens_w_resident_blocks(int, int, int, int, int cus) { return 4 * cus; }
@@ -24,7 +24,7 @@ hipError_t launch_absmax(const ResolvedUnit*, const ChunkRef*, uint32_t, uint32_
 hipError_t launch_absmax_finalize(const uint32_t*, const uint32_t*, int, int, int, int, float*, float*, float*,
                                   uint32_t*, hipStream_t) { std::abort(); }
 hipError_t launch_fake_quant(const uint16_t*, int64_t, float, float, int, uint8_t*, float*, int, hipStream_t) { std::abort(); }
-hipError_t launch_sens(const ResolvedUnit*, const ChunkRef*, uint32_t, int, int, int, int, float*, int, size_t, hipStream_t) { std::abort(); }
+hipError_t launch_sens(const ResolvedUnit*, const ChunkRef*, uint32_t, int, int, int, int, float*, int, hipStream_t) { std::abort(); }
 hipError_t launch_sens_w(const WGroup*, uint32_t, uint32_t, const ResolvedUnit*, const uint32_t*, int, int, int, int,
                          float*, int, hipStream_t) { std::abort(); }
 hipError_t launch_absmax_rows(const RowTensor*, uint32_t, uint32_t, int, int, int, float*, float*, float*, uint32_t*,
