@@ -315,6 +315,7 @@ def main():
     log("enqueue %.2f ms, device done after %.2f ms, read-back + epilogue + selection %.2f ms" %
         ((t_enq - t0) * 1e3, (t_dev - t0) * 1e3, (t1 - t_dev) * 1e3))
 
+    kinds = amp.amp_profile_kinds(args.steps * launches_per_step)
     ms, lp, lb = amp.amp_profile_read(args.steps * launches_per_step)
     amp.amp_profile_enable(0)
     wall = t1 - t0
@@ -326,17 +327,18 @@ def main():
     bytes_step = sens_bytes_step + abs_bytes_step
     value = bytes_step * args.steps / wall / 1e9
     log("device steps + host tail: %.3f s over %d steps" % (wall, args.steps))
-    names = {2: ["sens_w_kernel (weights of the linears)",
-                 "sens_kernel (activations of the linears and BGEMM operands)"],
-             1: ["sens_kernel"]}.get(launches_per_step, ["launch %d" % i for i in range(launches_per_step)])
-    if args.scales == "rows" and launches_per_step == 3:
-        names = ["sens_w_kernel, per-channel scales (weights of the linears)",
-                 "sens_wrows_kernel (activations of the linears, causal BGEMM operands)",
-                 "sens_wrows_kernel, short-row variant (BGEMM operands with rows of 128)"]
-    if args.scales == "rows-single-read" and launches_per_step == 3:
-        names = ["sens_w_kernel, per-channel scales (weights of the linears)",
-                 "sens_fused_rows_kernel (activations of the linears, causal BGEMM operands: absmax, scales and sums in one read)",
-                 "sens_fused_rows_kernel, short-row variant (BGEMM operands with rows of 128)"]
+    kernel_of = {
+        amp.KERNEL_WEIGHTS: "sens_w_kernel (weights of the linears)",
+        amp.KERNEL_WEIGHTS + 1: "sens_w_kernel, per-channel scales (weights of the linears)",
+        amp.KERNEL_STREAM: "sens_kernel (activations of the linears and BGEMM operands)",
+        amp.KERNEL_STREAM + 1: "sens_wrows_kernel (one scale per row: long and causal rows)",
+        amp.KERNEL_STREAM + 2: "sens_rows_kernel (one scale per row: other row shapes)",
+        amp.KERNEL_STREAM + 3: "sens_wrows_kernel, short-row variant (one scale per row: rows of a power-of-two length below 512)",
+        amp.KERNEL_STREAM + 4: "sens_fused_rows_kernel (absmax, scales and sums in one read; rows held in registers)",
+        amp.KERNEL_STREAM + 5: "sens_fused_rows_kernel, rows staged in LDS (up to 32 KiB per workgroup)",
+        amp.KERNEL_STREAM + 6: "sens_fused_rows_kernel, rows staged in LDS (up to 48 KiB per workgroup)",
+    }
+    names = [kernel_of.get(int(k), "launch of kind %d" % k) for k in kinds[:launches_per_step]]
     launch_detail = []
     per_ms = ms.reshape(args.steps, launches_per_step).mean(axis=0)
     per_min = ms.reshape(args.steps, launches_per_step).min(axis=0)

@@ -50,7 +50,10 @@
  *   - Every call returns amp_status_t.  After AMP_ERR_DEVICE, amp_last_device_error() gives
  *     the hipError_t of the failing runtime call (per host thread).
  *   - Non-finite inputs: amp_absmax_scale raises bit 0 of the tensor's flag word; the sums of
- *     an operand that holds NaN or Inf are unspecified.
+ *     an operand that holds NaN or Inf are unspecified.  The sensitivity kernels leave the clamp to
+ *     +-FMAX to the FP8 conversion, which saturates finite values but not infinities: the scales passed
+ *     to a sensitivity call must keep |z_k| * inv below 2^128 (any scale derived from an absmax of
+ *     data within a factor 2^88 of these does); otherwise that operand's sums are NaN.
  */
 #ifndef AMPSENS_H
 #define AMPSENS_H
@@ -379,16 +382,24 @@ amp_status_t amp_run(const amp_plan_t* plan, void* stream);
  * the weight kernel (W read once per batch of samples) if it has whole weight chunks for it, then
  * the streaming kernel for everything else (activations, BGEMM operands, ragged ends).  Operands
  * with one scale per row have kernels of their own: a run then launches up to two weight kernels
- * (per-tensor, per-channel) and up to four streaming kernels (one scale per tensor; long or
- * causal rows; short power-of-two rows; other shapes), in that order, each only if it has work.
+ * (per-tensor, per-channel) and up to seven streaming kernels (one scale per tensor; long or
+ * causal rows; other shapes; short power-of-two rows; three launches of the single-read pass), in that
+ * order, each only if it has work.
  * amp_profile_read waits for the recorded events, writes the elapsed milliseconds of each
  * launch to ms[0..*n_launches) and, if not NULL, to pairs[] the number of element pairs the
  * launch covered and to bytes[] the operand bytes it is defined to read (4 per pair for the
  * streaming kernel; for the weight kernel 2 per pair plus W's bytes once per batch of samples)
  * (host arrays; capacity must be >= the n given to enable), and resets the count.
+ * amp_profile_kinds (call it before amp_profile_read, which resets the count) tells which kernel each
+ * recorded launch was: AMP_KERNEL_WEIGHTS (+1 with per-channel scales), or AMP_KERNEL_STREAM + c with
+ * c = 0 one scale per tensor; 1 long or causal rows; 2 other row shapes; 3 short power-of-two rows;
+ * 4, 5, 6 the single-read pass (rows held in registers; staged in up to 32 KiB; in up to 48 KiB of LDS).
  * amp_profile_enable(0) destroys the events.  Meant for benchmarks: do not enable it around a
  * stream capture, and do not call enable / read while runs are being enqueued from other threads. */
+#define AMP_KERNEL_WEIGHTS 0
+#define AMP_KERNEL_STREAM 16
 amp_status_t amp_profile_enable(int max_launches);
+amp_status_t amp_profile_kinds(int* kinds /* host */, int capacity, int* n_launches);
 amp_status_t amp_profile_read(float* ms, uint64_t* pairs, uint64_t* bytes, int capacity, int* n_launches);
 
 /* ---- misc ---------------------------------------------------------------------------------*/

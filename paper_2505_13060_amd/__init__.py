@@ -440,6 +440,19 @@ def amp_profile_enable(max_launches):
     _check(lib().amp_profile_enable(int(max_launches)), "amp_profile_enable")
 
 
+KERNEL_WEIGHTS = 0
+KERNEL_STREAM = 16
+
+
+def amp_profile_kinds(capacity):
+    """Which kernel each recorded launch was (KERNEL_WEIGHTS + 0 / 1, KERNEL_STREAM + class); call before
+    amp_profile_read."""
+    kinds = np.zeros(max(capacity, 1), dtype=np.int32)
+    n = C.c_int()
+    _check(lib().amp_profile_kinds(kinds.ctypes.data_as(C.c_void_p), int(capacity), C.byref(n)), "amp_profile_kinds")
+    return kinds[:n.value].copy()
+
+
 def amp_profile_read(capacity):
     """(milliseconds, element pairs, bytes defined to be read) of every fused-kernel launch since the
     last read."""

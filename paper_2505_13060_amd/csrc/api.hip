@@ -131,6 +131,7 @@ struct Profile {
     std::mutex mu;
     std::vector<hipEvent_t> start, stop;
     std::vector<uint64_t> pairs, bytes;
+    std::vector<int> kinds;
     int used = 0;
 };
 Profile g_profile;
@@ -191,13 +192,14 @@ amp_status_t sens_run(const PlanData& P, hipStream_t stream) {
     const int nf = P.n_fmts, f0 = P.fmt0 & 0xFF, f1 = P.fmt1 & 0xFF;     // fmt0 / fmt1 may carry the scale rule
     AMP_HIP(launch_resolve(d_units, P.n_units, nf, d_runits, stream));
     // one pair of events around a fused kernel while the profile has room
-    auto timed = [&](uint64_t pairs, uint64_t bytes, auto&& launch) -> hipError_t {
+    auto timed = [&](int kind, uint64_t pairs, uint64_t bytes, auto&& launch) -> hipError_t {
         int slot = -1;
         {
             std::lock_guard<std::mutex> lock(g_profile.mu);
             if (g_profile.used < (int)g_profile.start.size()) {
                 slot = g_profile.used++;
                 g_profile.pairs[slot] = pairs;
+                g_profile.kinds[slot] = kind;
                 g_profile.bytes[slot] = bytes;
             }
         }
@@ -212,7 +214,7 @@ amp_status_t sens_run(const PlanData& P, hipStream_t stream) {
     for (int v = 0; v < 2; ++v) {
         if (P.w_items[v] > 0) {
             const int grid = persistent_grid(P.w_items[v], sens_w_resident(nf, f0, f1, v), P.grid_limit);
-            AMP_HIP(timed(P.w_pairs[v], P.w_bytes[v], [&]() {
+            AMP_HIP(timed(AMP_KERNEL_WEIGHTS + v, P.w_pairs[v], P.w_bytes[v], [&]() {
                 return launch_sens_w(d_groups + g0, P.w_groups[v], P.w_items[v], d_runits, d_cb, nf, f0, f1, v,
                                      d_partials, grid, stream);
             }));
@@ -224,7 +226,7 @@ amp_status_t sens_run(const PlanData& P, hipStream_t stream) {
         const uint64_t n_pos = P.class_pos[cls + 1] - P.class_pos[cls];
         if (n_pos == 0) continue;
         const int grid = persistent_grid(n_pos, sens_resident(nf, f0, f1, cls), P.grid_limit);
-        AMP_HIP(timed(P.class_pairs[cls], P.class_pairs[cls] * 4, [&]() {
+        AMP_HIP(timed(AMP_KERNEL_STREAM + cls, P.class_pairs[cls], P.class_pairs[cls] * 4, [&]() {
             return launch_sens(d_runits, d_map + P.class_pos[cls], (uint32_t)n_pos, nf, P.fmt0, P.fmt1, cls,
                                d_partials, grid, stream);
         }));
@@ -566,6 +568,7 @@ amp_status_t amp_profile_enable(int max_launches) {
     g_profile.stop.clear();
     g_profile.pairs.assign((size_t)max_launches, 0);
     g_profile.bytes.assign((size_t)max_launches, 0);
+    g_profile.kinds.assign((size_t)max_launches, 0);
     g_profile.used = 0;
     for (int i = 0; i < max_launches; ++i) {
         hipEvent_t a, b;
@@ -574,6 +577,15 @@ amp_status_t amp_profile_enable(int max_launches) {
         AMP_HIP(hipEventCreate(&b));
         g_profile.stop.push_back(b);
     }
+    return AMP_OK;
+}
+
+amp_status_t amp_profile_kinds(int* kinds, int capacity, int* n_launches) {
+    if (!n_launches || capacity < 0 || (capacity > 0 && !kinds)) return AMP_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(g_profile.mu);
+    if (capacity < g_profile.used) return AMP_ERR_INVALID_ARG;
+    for (int i = 0; i < g_profile.used; ++i) kinds[i] = g_profile.kinds[i];
+    *n_launches = g_profile.used;
     return AMP_OK;
 }
 

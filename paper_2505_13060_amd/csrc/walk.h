@@ -182,6 +182,7 @@ template <class Ctx>
 AMPSENS_HD void walk_causal_chunk_aligned(int32_t rows, int32_t cols, uint32_t chunks_per_mat,
                                           uint32_t chunk_local, int tid, Ctx& ctx) {
     static_assert(kBandsPerChunk == kWaves, "one wave per slot");
+    static_assert(kBandRows * (64 / kBandRows) == 64 && ((64 / kBandRows) & (64 / kBandRows - 1)) == 0, "lanes = rows x vectors");
     const uint32_t mat = chunk_local / chunks_per_mat;
     const int32_t slot = (int32_t)(chunk_local % chunks_per_mat) * kBandsPerChunk + (tid >> 6);
     const int32_t nbands = causal_bands(rows);
@@ -191,7 +192,7 @@ AMPSENS_HD void walk_causal_chunk_aligned(int32_t rows, int32_t cols, uint32_t c
     constexpr int kStep = 64 / kBandRows;                       // vectors of a row per wave step
     for (int b = 0; b < nb; ++b) {
         const int32_t i0 = bands[b] * kBandRows;
-        const int32_t i = i0 + (lane & (kBandRows - 1));
+        const int32_t i = i0 + (lane / kStep);                  // 8 adjacent lanes own 128 contiguous bytes of a row
         const int32_t ilast = (i0 + kBandRows - 1 < rows) ? i0 + kBandRows - 1 : rows - 1;
         const int32_t nv_band = (causal_row_len(ilast, rows, cols) + kVec - 1) / kVec;   // same for the wave
         const int32_t li = i < rows ? causal_row_len(i, rows, cols) : 0;
@@ -200,7 +201,7 @@ AMPSENS_HD void walk_causal_chunk_aligned(int32_t rows, int32_t cols, uint32_t c
         const int64_t e_row = ((int64_t)mat * rows + (i < rows ? i : 0)) * cols;
         ctx.set_row((int64_t)mat * rows + (i < rows ? i : 0));
         for (int32_t v0 = 0; v0 < nv_band; v0 += kStep * kUnroll) {
-            const int32_t v = v0 + (lane / kBandRows);
+            const int32_t v = v0 + (lane & (kStep - 1));
             int count = nv_row > v ? (nv_row - v + kStep - 1) / kStep : 0;
             if (count > kUnroll) count = kUnroll;
             const bool ends = count > 0 && v + (count - 1) * kStep == nv_row - 1;
