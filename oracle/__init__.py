@@ -143,6 +143,36 @@ def absmax_scale_rows(x, n_rows, row_len, fmt, causal_rows=None):
     return am, sc, iv, fl.value
 
 
+def absmax_scale_blocks(x, n_rows, row_len, block, fmt):
+    """(amax, scale, inv) float32 arrays [n_rows, row_len // block] of the 1 x block tiles, and the flag word."""
+    x = _u16(x)
+    assert x.size >= n_rows * row_len and row_len % block == 0
+    shape = (n_rows, row_len // block)
+    am = np.empty(shape, dtype=np.float32)
+    sc = np.empty(shape, dtype=np.float32)
+    iv = np.empty(shape, dtype=np.float32)
+    fl = C.c_uint32()
+    rc = lib().orc_absmax_scale_blocks(_p(x, C.c_uint16), C.c_int64(n_rows), C.c_int64(row_len), C.c_int64(block),
+                                       int(fmt), _p(am, C.c_float), _p(sc, C.c_float), _p(iv, C.c_float), C.byref(fl))
+    assert rc == 0
+    return am, sc, iv, fl.value
+
+
+def sens_operand_blocks(x, dx, n_rows, row_len, block, scale, inv, fmt):
+    """(E, A) of one sample's [n_rows, row_len] block, tile (i, b) cast with scale[i, b], inv[i, b]."""
+    x, dx = _u16(x), _u16(dx)
+    scale = np.ascontiguousarray(scale, dtype=np.float32)
+    inv = np.ascontiguousarray(inv, dtype=np.float32)
+    assert x.size >= n_rows * row_len and dx.size >= n_rows * row_len and row_len % block == 0
+    assert scale.size == n_rows * (row_len // block) and inv.size == scale.size
+    E, A = C.c_double(), C.c_double()
+    rc = lib().orc_sens_operand_blocks(_p(x, C.c_uint16), _p(dx, C.c_uint16), C.c_int64(n_rows), C.c_int64(row_len),
+                                       C.c_int64(block), _p(scale, C.c_float), _p(inv, C.c_float), int(fmt),
+                                       C.byref(E), C.byref(A))
+    assert rc == 0
+    return E.value, A.value
+
+
 def sens_operand_rows(x, dx, n_rows, row_len, scale, inv, fmt, causal_rows=None):
     """(E, A) of one sample's [n_rows, row_len] block, row i cast with scale[i], inv[i]."""
     x, dx = _u16(x), _u16(dx)

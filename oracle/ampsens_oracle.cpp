@@ -403,6 +403,58 @@ int orc_sens_operand_rows(const uint16_t* x, const uint16_t* dx, int64_t n_rows,
     return 0;
 }
 
+// ---- scale per block of a row (1 x B tiles) -----------------------------------------------
+// A finer granularity still, common for FP8 hardware with scale factors per tile: every row of the
+// [n_rows, row_len] operand is cut into row_len / B blocks of B consecutive elements and block
+// (i, b) is cast with its own scale, derived from the block's absmax by the same arithmetic as for
+// a whole tensor.  Outputs are [n_rows][row_len / B] arrays.  B must divide row_len.
+
+int orc_absmax_scale_blocks(const uint16_t* x, int64_t n_rows, int64_t row_len, int64_t B, int fmt,
+                            float* amax_out, float* scale_out, float* inv_out, uint32_t* flags_out) {
+    if (B <= 0 || row_len % B != 0) return 2;
+    const int64_t per_row = row_len / B;
+    uint32_t flags = 0;
+    for (int64_t i = 0; i < n_rows; ++i)
+        for (int64_t b = 0; b < per_row; ++b) {
+            uint32_t fl = 0;
+            const int64_t o = i * per_row + b;
+            int rc = orc_absmax_scale(x + i * row_len + b * B, B, 0, 0, 0, 0, fmt, &amax_out[o], &scale_out[o],
+                                      &inv_out[o], &fl);
+            if (rc) return rc;
+            flags |= fl;
+        }
+    *flags_out = flags;
+    return 0;
+}
+
+// E and A of one sample's block [n_rows, row_len] with one (scale, inv) per 1 x B block.
+int orc_sens_operand_blocks(const uint16_t* x, const uint16_t* dx, int64_t n_rows, int64_t row_len,
+                            int64_t B, const float* scale, const float* inv, int fmt, double* out_E,
+                            double* out_A) {
+    Fmt f;
+    if (!fmt_of(fmt, &f)) return 1;
+    if (B <= 0 || row_len % B != 0) return 2;
+    const int64_t per_row = row_len / B;
+    double E = 0.0, A = 0.0;
+    for (int64_t i = 0; i < n_rows; ++i)
+        for (int64_t j = 0; j < row_len; ++j) {
+            const int64_t idx = i * row_len + j;
+            const int64_t blk = i * per_row + j / B;        // the block element (i, j) lies in
+            float xf = bf16_val(x[idx]);
+            float gf = bf16_val(dx[idx]);
+            float y = xf * inv[blk];                        // the one fp32 multiply
+            double q = fp8_value(f, fp8_encode(f, y));
+            double e = (double)xf - q * (double)scale[blk];
+            double t = (double)gf * e;
+            E += t * t;
+            double a = (double)gf * (double)xf;
+            A += a * a;
+        }
+    *out_E = E;
+    *out_A = A;
+    return 0;
+}
+
 // ---- epilogue (Sec. 2.2) ---------------------------------------------------------------
 
 // s_l = (1/R) sum_r (A_0^r + A_1^r);  returns s_l.

@@ -405,3 +405,94 @@ def test_pow2_scale_commutes_with_the_cast(fmt):
     assert np.array_equal(bf16_bits_to_f64(on_grid), deq.astype(np.float64))        # FP8 values times 2^k are bf16
     E0, _ = oracle.sens_operand(on_grid, g, 1, x.size, sc, iv, fmt)
     assert E0[0] == 0.0
+
+
+# ---- one scale per 1 x B block of a row ----------------------------------------------------------
+
+def blocks_hand_case():
+    c = {}
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "sens_blocks_hand_case.txt")):
+        tok = line.split("#")[0].split()
+        if tok:
+            c[tok[0]] = [float(t) for t in tok[1:]]
+    return c
+
+
+def test_blocks_hand_worked_sums_and_absmax():
+    c = blocks_hand_case()
+    n_rows, row_len, B = int(c["rows"][0]), int(c["rows"][1]), int(c["block"][0])
+    x = f32_to_bf16_bits(np.array(c["x"], dtype=np.float32))
+    g = f32_to_bf16_bits(np.array(c["xdot"], dtype=np.float32))
+    assert np.array_equal(bf16_bits_to_f64(x), np.array(c["x"]))
+    assert np.array_equal(bf16_bits_to_f64(g), np.array(c["xdot"]))
+    E, A = oracle.sens_operand_blocks(x, g, n_rows, row_len, B, c["scale"], c["inv"], oracle.E4M3)
+    assert E == c["E"][0] and A == c["A"][0]
+    # any other assignment of the four scales to the four blocks makes some value saturate: a different E
+    import itertools
+    for perm in itertools.permutations(range(4)):
+        if perm == (0, 1, 2, 3):
+            continue
+        sc = [c["scale"][p] for p in perm]
+        iv = [c["inv"][p] for p in perm]
+        E2, A2 = oracle.sens_operand_blocks(x, g, n_rows, row_len, B, sc, iv, oracle.E4M3)
+        assert E2 != c["E"][0] and A2 == c["A"][0], perm
+    am, sc, iv, fl = oracle.absmax_scale_blocks(x, n_rows, row_len, B, oracle.E4M3)
+    assert fl == 0 and np.array_equal(am.reshape(-1).astype(np.float64), np.array(c["amax"]))
+    want = np.array(c["amax"], dtype=np.float32)
+    assert np.array_equal(sc.reshape(-1), want / np.float32(448.0))      # numpy's fp32 division, not the oracle's
+    assert np.array_equal(iv.reshape(-1), np.float32(448.0) / want)
+
+
+@pytest.mark.parametrize("fmt", [oracle.E4M3, oracle.E5M2])
+def test_blocks_are_the_rows_of_the_operand_reshaped(fmt):
+    """[n_rows, row_len] cut into 1 x B blocks is the same set of scale groups as [n_rows * row_len / B, B]
+    with one scale per row; a block as long as the row is one scale per row; one common scale is the
+    per-tensor sum."""
+    rng = np.random.default_rng(21)
+    n_rows, row_len, B = 6, 48, 16
+    x = f32_to_bf16_bits((rng.standard_normal((n_rows, row_len // B, B)) *
+                          np.exp(rng.normal(0, 2, (n_rows, row_len // B, 1)))).astype(np.float32)).reshape(-1)
+    g = rand_bf16(rng, n_rows * row_len, 1e-2)
+    am, sc, iv, fl = oracle.absmax_scale_blocks(x, n_rows, row_len, B, fmt)
+    am_r, sc_r, iv_r, _ = oracle.absmax_scale_rows(x, n_rows * row_len // B, B, fmt)
+    assert np.array_equal(am.reshape(-1), am_r) and np.array_equal(sc.reshape(-1), sc_r) and np.array_equal(iv.reshape(-1), iv_r)
+    E, A = oracle.sens_operand_blocks(x, g, n_rows, row_len, B, sc, iv, fmt)
+    Er, Ar = oracle.sens_operand_rows(x, g, n_rows * row_len // B, B, sc_r, iv_r, fmt)
+    assert E == pytest.approx(Er, rel=1e-13) and A == pytest.approx(Ar, rel=1e-13)
+    # B = row_len
+    am1, sc1, iv1, _ = oracle.absmax_scale_blocks(x, n_rows, row_len, row_len, fmt)
+    am2, sc2, iv2, _ = oracle.absmax_scale_rows(x, n_rows, row_len, fmt)
+    assert np.array_equal(sc1.reshape(-1), sc2) and np.array_equal(iv1.reshape(-1), iv2) and np.array_equal(am1.reshape(-1), am2)
+    E1, A1 = oracle.sens_operand_blocks(x, g, n_rows, row_len, row_len, sc1, iv1, fmt)
+    E2, A2 = oracle.sens_operand_rows(x, g, n_rows, row_len, sc2, iv2, fmt)
+    assert E1 == pytest.approx(E2, rel=1e-13) and A1 == pytest.approx(A2, rel=1e-13)
+    # one scale for all
+    a0, s0, i0, _ = oracle.absmax_scale(x, fmt)
+    Ec, Ac = oracle.sens_operand_blocks(x, g, n_rows, row_len, B, np.full(sc.shape, s0), np.full(sc.shape, i0), fmt)
+    Et, At = oracle.sens_operand(x, g, 1, x.size, s0, i0, fmt)
+    assert Ec == pytest.approx(Et[0], rel=1e-13) and Ac == pytest.approx(At[0], rel=1e-13)
+
+
+def test_blocks_keep_a_loud_channel_from_spoiling_its_row():
+    """An outlier channel costs the other blocks of its row nothing: with one scale per block every block
+    keeps E <= 3 alpha A (the bound of a normal-range cast), while with one scale per row the quiet blocks
+    of a row that holds the outlier lose it."""
+    rng = np.random.default_rng(22)
+    n_rows, row_len, B = 5, 64, 16
+    xf = rng.standard_normal((n_rows, row_len)).astype(np.float32)
+    xf[:, 3] *= 1.0e6                                         # the loud channel, in block 0 of every row: the others fall below E4M3's subnormals at its scale
+    x = f32_to_bf16_bits(xf).reshape(-1)
+    g = f32_to_bf16_bits(np.ones(n_rows * row_len, dtype=np.float32))
+    fmt = oracle.E4M3
+    alpha = oracle.alpha(oracle.fp8_mantissa_bits(fmt))
+    am, sc, iv, _ = oracle.absmax_scale_blocks(x, n_rows, row_len, B, fmt)
+    am_r, sc_r, iv_r, _ = oracle.absmax_scale_rows(x, n_rows, row_len, fmt)
+    xv = bf16_bits_to_f64(x).reshape(n_rows, row_len)
+    for i in range(n_rows):
+        for b in range(1, row_len // B):                      # the quiet blocks
+            xb = x.reshape(n_rows, row_len)[i, b * B:(b + 1) * B].copy()
+            gb = g[:B].copy()
+            Eb, Ab = oracle.sens_operand(xb, gb, 1, B, sc[i, b], iv[i, b], fmt)
+            assert Eb[0] <= 3 * alpha * Ab[0]
+            Er, Ar = oracle.sens_operand(xb, gb, 1, B, sc_r[i], iv_r[i], fmt)
+            assert Er[0] > Eb[0]
