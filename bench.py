@@ -219,6 +219,9 @@ def main():
                          "output channel / per row of a BGEMM operand); rows-single-read: the sensitivity "
                          "pass computes the row scales of the activations and BGEMM operands itself, "
                          "every row is fetched once")
+    ap.add_argument("--scale-block", type=int, default=0,
+                    help="with --scales rows / rows-single-read: one scale per 1 x N block of every dense row "
+                         "(N must divide the row lengths, e.g. 128) instead of one per row; causal rows keep one each")
     ap.add_argument("--scale-rule", choices=["amax", "pow2"], default="amax",
                     help="amax: scale = amax / FMAX (headline); pow2: the smallest power of two that is large "
                          "enough (AMP_SCALE_POW2 on both calls: the sensitivity kernels then cast with gfx950's "
@@ -232,6 +235,9 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference reading for HBM counters)")
     args = ap.parse_args()
+    if args.scale_block and args.scales == "tensor":
+        print("bench.py: --scale-block needs --scales rows or rows-single-read", file=sys.stderr)
+        sys.exit(2)
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (--gpus 1); multi-GPU runs are not part of it",
               file=sys.stderr)
@@ -256,14 +262,15 @@ def main():
         # linears and BGEMMs of the block in one call: one table, one set-up, one streaming launch
         plan = args.calls == "plan"
         passes.append(SensPass(workload, dev, one_call=True, plan=plan, rule=rule) if args.scales == "tensor"
-                      else RowSensPass(workload, dev, one_call=True, plan=plan, rule=rule,
+                      else RowSensPass(workload, dev, one_call=True, plan=plan, rule=rule, block=args.scale_block,
                                        single_read=args.scales == "rows-single-read"))
     torch.cuda.synchronize()
     workload = workloads[0]
     pairs = workload.pairs()
     log("%.1f M pairs per step (%.2f GB), generated in %.1f s" % (pairs / 1e6, pairs * 4 / 1e9, time.perf_counter() - t0))
     if args.scales != "tensor":
-        label += "; one scale per row" + (", computed by the sensitivity pass (single read)" if args.scales != "rows" else "")
+        label += ("; one scale per 1 x %d block of a row" % args.scale_block if args.scale_block else "; one scale per row") + \
+                 (", computed by the sensitivity pass (single read)" if args.scales != "rows" else "")
     if rule:
         label += "; power-of-two scales, cast by the scaled FP8 conversions"
     label += "; steps rotate over %d distinct resident block(s)" % n_blocks

@@ -126,6 +126,14 @@ typedef enum amp_fp8_format {
 #define AMP_ROWS_COMPUTE_MAX_ROW_LEN 24576
 #define AMP_ROWS_COMPUTE0 4          /* operand 0: one scale per row, computed by the pass */
 #define AMP_ROWS_COMPUTE1 8          /* operand 1 of a BGEMM, likewise */
+/* One scale per 1 x n block (tile scaling, e.g. n = 128): or-ed into scale_rows next to the bits above, it
+ * cuts every row of the operands those bits name into blocks of n consecutive elements, each cast with
+ * its own scale.  n must divide the row length (C of a linear layer, cols of a dense BGEMM operand;
+ * causal operands have no blocks: AMP_ERR_INVALID_ARG), 0 < n < 2^23.  The tables are then
+ * [rows * row_len / n][n_fmts], blocks of a row consecutive: exactly the tables amp_absmax_scale_rows
+ * writes for the same buffer described as a dense layout with cols = n.  Fast path: n a multiple of 8. */
+#define AMP_ROWS_BLOCK(n) ((int32_t)((uint32_t)(n) << 8))
+#define AMP_ROWS_BLOCK_OF(scale_rows) ((int64_t)((uint32_t)(scale_rows) >> 8))
 
 /* Shape of one sample's block of an operand.
  * causal == 0: n_elems consecutive elements (batch/rows/cols ignored).

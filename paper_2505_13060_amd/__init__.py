@@ -138,6 +138,13 @@ def _ptr(t):
     return None if t is None else t.data_ptr()
 
 
+def rows_block(n):
+    """AMP_ROWS_BLOCK(n): or into scale_rows to cut the rows of the row-scaled operands into 1 x n scale blocks."""
+    n = int(n)
+    assert 0 < n < (1 << 23)
+    return n << 8
+
+
 def dense(n_elems, cols=0):
     """cols: row length, needed only where the operand has one scale per row."""
     return Layout(int(n_elems), 0, 0, int(cols), 0, 0)

@@ -308,10 +308,15 @@ inline amp_status_t build_linear(const amp_linear_desc_t* ops, int n_ops, int n_
         if (op.R < 0 || op.C < 0 || op.K < 0 || op.tokens < 0) return AMP_ERR_INVALID_ARG;
         // a weight is shared by the samples and small next to its R gradients: its row scales come from
         // amp_absmax_scale_rows, only the activations' can be computed by the pass itself
-        if (op.scale_rows & ~(AMP_ROWS_OPERAND0 | AMP_ROWS_OPERAND1 | AMP_ROWS_COMPUTE0)) return AMP_ERR_INVALID_ARG;
-        const bool x_fused = (op.scale_rows & AMP_ROWS_COMPUTE0) != 0;
-        const bool x_rows = (op.scale_rows & AMP_ROWS_OPERAND0) != 0 || x_fused;
-        const bool w_rows = (op.scale_rows & AMP_ROWS_OPERAND1) != 0;
+        const int32_t how = op.scale_rows & 0xFF;
+        const int64_t blk = AMP_ROWS_BLOCK_OF(op.scale_rows);  // 0, or the length of a scale block inside a row
+        if (how & ~(AMP_ROWS_OPERAND0 | AMP_ROWS_OPERAND1 | AMP_ROWS_COMPUTE0)) return AMP_ERR_INVALID_ARG;
+        const bool x_fused = (how & AMP_ROWS_COMPUTE0) != 0;
+        const bool x_rows = (how & AMP_ROWS_OPERAND0) != 0 || x_fused;
+        const bool w_rows = (how & AMP_ROWS_OPERAND1) != 0;
+        if (blk != 0 && (!(x_rows || w_rows) || op.C % blk != 0)) return AMP_ERR_INVALID_ARG;
+        const int64_t scale_len = blk ? blk : op.C;          // elements that share a scale
+        const int64_t per_row = blk ? op.C / blk : 1;
         if ((x_rows || w_rows) && op.C > kMaxDim) return AMP_ERR_TOO_LARGE;
         if (op.C > kMaxElems || op.K > kMaxElems || (op.C && op.K > kMaxElems / op.C)) return AMP_ERR_TOO_LARGE;
         if (!aligned2(op.x) || !aligned2(op.dx) || !aligned2(op.w) || !aligned2(op.dw)) return AMP_ERR_INVALID_ARG;
@@ -336,13 +341,13 @@ inline amp_status_t build_linear(const amp_linear_desc_t* ops, int n_ops, int n_
             if (o + 4 * n_fmts > 0xFFFFFFFFull) return AMP_ERR_TOO_LARGE;
             amp_layout_t Lx = {xn, 0, 0, 0, 0, 0};
             amp_layout_t Lw = {wn, 0, 0, 0, 0, 0};
-            const int64_t xs = x_rows ? r0 * n_fmts : 0;         // the sample's first token in the table
+            const int64_t xs = x_rows ? r0 * per_row * n_fmts : 0;   // the sample's first token in the table
             amp_status_t st = t->add(xn ? op.x + r0 * op.C : op.x, xn ? op.dx + r0 * op.C : op.dx, Lx, 1,
                                      op.x_scale ? op.x_scale + xs : op.x_scale, op.x_inv ? op.x_inv + xs : op.x_inv,
-                                     (uint32_t)o, 0u, 0u, x_rows && xn > 0 ? op.C : 0, x_fused && xn > 0);
+                                     (uint32_t)o, 0u, 0u, x_rows && xn > 0 ? scale_len : 0, x_fused && xn > 0);
             if (st != AMP_OK) return st;
             st = t->add(op.w, wn ? op.dw + (int64_t)r * wn : op.dw, Lw, 1, op.w_scale, op.w_inv, (uint32_t)o + 2,
-                        op.R > 1 ? kUnitKeepX : 0u, op.R > 1 ? (uint32_t)k + 1u : 0u, w_rows && wn > 0 ? op.C : 0);
+                        op.R > 1 ? kUnitKeepX : 0u, op.R > 1 ? (uint32_t)k + 1u : 0u, w_rows && wn > 0 ? scale_len : 0);
             if (st != AMP_OK) return st;
         }
         base += (uint64_t)op.R;
@@ -383,16 +388,28 @@ inline amp_status_t build_bgemm(const amp_bgemm_desc_t* ops, int n_ops, int n_fm
         if (op.R > 0 && n0 > 0 && (!op.x0 || !op.dx0 || !op.scale0 || !op.inv0)) return AMP_ERR_INVALID_ARG;
         if (op.R > 0 && n1 > 0 && (!op.x1 || !op.dx1 || !op.scale1 || !op.inv1)) return AMP_ERR_INVALID_ARG;
         if (op.R > 0 && (n0 > kMaxElems / op.R || n1 > kMaxElems / op.R)) return AMP_ERR_TOO_LARGE;
-        if (op.scale_rows & ~(AMP_ROWS_OPERAND0 | AMP_ROWS_OPERAND1 | AMP_ROWS_COMPUTE0 | AMP_ROWS_COMPUTE1))
+        const int32_t how = op.scale_rows & 0xFF;
+        const int64_t blk = AMP_ROWS_BLOCK_OF(op.scale_rows);
+        if (how & ~(AMP_ROWS_OPERAND0 | AMP_ROWS_OPERAND1 | AMP_ROWS_COMPUTE0 | AMP_ROWS_COMPUTE1))
             return AMP_ERR_INVALID_ARG;
-        const bool fused0 = (op.scale_rows & AMP_ROWS_COMPUTE0) != 0, fused1 = (op.scale_rows & AMP_ROWS_COMPUTE1) != 0;
+        if (blk != 0 && how == 0) return AMP_ERR_INVALID_ARG;
+        const bool fused0 = (how & AMP_ROWS_COMPUTE0) != 0, fused1 = (how & AMP_ROWS_COMPUTE1) != 0;
         int64_t len0 = 0, len1 = 0, rows0 = 0, rows1 = 0;    // row length and rows per sample, 0 = one scale
-        if ((op.scale_rows & AMP_ROWS_OPERAND0) || fused0) {
-            st = row_geometry(op.layout0, &len0, &rows0);
+        // a block of a dense row is a shorter row of the same buffer
+        auto geometry = [&](const amp_layout_t& L, int64_t* len, int64_t* rows) -> amp_status_t {
+            amp_status_t g = row_geometry(L, len, rows);
+            if (g != AMP_OK || blk == 0 || (L.n_elems == 0 && !L.causal)) return g;
+            if (L.causal || *len % blk != 0) return AMP_ERR_INVALID_ARG;
+            *rows *= *len / blk;
+            *len = blk;
+            return AMP_OK;
+        };
+        if ((how & AMP_ROWS_OPERAND0) || fused0) {
+            st = geometry(op.layout0, &len0, &rows0);
             if (st != AMP_OK) return st;
         }
-        if ((op.scale_rows & AMP_ROWS_OPERAND1) || fused1) {
-            st = row_geometry(op.layout1, &len1, &rows1);
+        if ((how & AMP_ROWS_OPERAND1) || fused1) {
+            st = geometry(op.layout1, &len1, &rows1);
             if (st != AMP_OK) return st;
         }
         for (int r = 0; r < op.R; ++r) {

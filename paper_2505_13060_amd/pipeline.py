@@ -12,7 +12,7 @@ from . import (ROWS_COMPUTE0, ROWS_COMPUTE1, ROWS_COMPUTE_MAX_ROW_LEN, ROWS_OPER
                amp_absmax_workspace_bytes, amp_plan_limit_grid, amp_run, amp_sens_bgemm,
                amp_sens_bgemm_workspace_bytes, amp_sens_block, amp_sens_block_setup,
                amp_sens_block_workspace_bytes, amp_sens_linear, amp_sens_linear_workspace_bytes, bgemm_desc,
-               causal, dense, linear_desc, tensor)
+               causal, dense, linear_desc, rows_block, tensor)
 
 
 def _layout(lay, cols=0):
@@ -149,8 +149,10 @@ class RowSensPass:
     scale per tensor go through amp_absmax_scale as in SensPass."""
 
     def __init__(self, workload, device, x_rows=True, w_rows=True, bgemm_rows=True, one_call=False, plan=False,
-                 flags=0, single_read=False, rule=0):
-        """rule: 0 or SCALE_POW2 (power-of-two scales everywhere, as in SensPass).  single_read: the row scales of the activations and of the BGEMM operands are computed by the
+                 flags=0, single_read=False, rule=0, block=0):
+        """rule: 0 or SCALE_POW2 (power-of-two scales everywhere, as in SensPass).  block: 0, or the length
+        of the 1 x block scale tiles every dense row is cut into (it must divide the row lengths it meets;
+        causal rows keep one scale each).  single_read: the row scales of the activations and of the BGEMM operands are computed by the
         sensitivity pass itself (AMP_ROWS_COMPUTE0 / 1: every row is fetched once); only the weights'
         per-channel scales then come from amp_absmax_scale_rows."""
         self.single_read = single_read
@@ -161,14 +163,25 @@ class RowSensPass:
         self.rule = rule
         nf = len(self.fmts)
         f32 = dict(device=device, dtype=torch.float32)
+        self.block = int(block)
+
+        def scale_len(cols):                         # elements of a dense row that share a scale
+            if block:
+                assert cols % block == 0, "the scale block must divide every dense row it is applied to"
+                return block
+            return cols
+
+        def blocked(lay):
+            return dense(lay.n_elems, scale_len(lay.cols)) if not lay.causal else lay
+
         per_tensor, per_row = [], []                 # (key, Tensor)
         for k, op in enumerate(workload.linears):
             rows = int(op.row_offsets[-1])
-            (per_row if x_rows else per_tensor).append((("lin", k, 0), tensor(op.x, dense(rows * op.C, op.C))))
-            (per_row if w_rows else per_tensor).append((("lin", k, 1), tensor(op.w, dense(op.K * op.C, op.C))))
+            (per_row if x_rows else per_tensor).append((("lin", k, 0), tensor(op.x, dense(rows * op.C, scale_len(op.C)))))
+            (per_row if w_rows else per_tensor).append((("lin", k, 1), tensor(op.w, dense(op.K * op.C, scale_len(op.C)))))
         for k, op in enumerate(workload.bgemms):
             for side, (x, lay) in enumerate(((op.x0, op.lay0), (op.x1, op.lay1))):
-                t = tensor(x, _layout(lay, x.shape[-1]), op.R)
+                t = tensor(x, blocked(_layout(lay, x.shape[-1])), op.R)
                 (per_row if bgemm_rows else per_tensor).append((("bg", k, side), t))
         # operands whose row scales the sensitivity pass computes itself: their tables sit behind the others'
         # (rows too long for the single-read pass, or not made of whole vectors, keep the two-pass form)
@@ -215,12 +228,15 @@ class RowSensPass:
                 tokens=int(op.row_offsets[1]) if (uniform and op.R) else 0,
                 sample_row_offsets=None if uniform else op.row_offsets,
                 scale_rows=((ROWS_COMPUTE0 if ("lin", k, 0) in self.computed else ROWS_OPERAND0) if xr else 0) |
-                           (ROWS_OPERAND1 if wr else 0)))
+                           (ROWS_OPERAND1 if wr else 0) | (rows_block(block) if block and (xr or wr) else 0)))
         for k, op in enumerate(workload.bgemms):
             s0, i0, r0 = scales(("bg", k, 0))
             s1, i1, r1 = scales(("bg", k, 1))
-            self.bg_desc.append(bgemm_desc(op.x0, op.dx0, _layout(op.lay0, op.x0.shape[-1]), op.x1, op.dx1,
-                                           _layout(op.lay1, op.x1.shape[-1]), op.R, s0, i0, s1, i1,
+            # a dense BGEMM operand says its scale blocks through its row length
+            self.bg_desc.append(bgemm_desc(op.x0, op.dx0, blocked(_layout(op.lay0, op.x0.shape[-1])) if r0 else _layout(op.lay0, op.x0.shape[-1]),
+                                           op.x1, op.dx1,
+                                           blocked(_layout(op.lay1, op.x1.shape[-1])) if r1 else _layout(op.lay1, op.x1.shape[-1]),
+                                           op.R, s0, i0, s1, i1,
                                            scale_rows=((ROWS_COMPUTE0 if ("bg", k, 0) in self.computed else ROWS_OPERAND0) if r0 else 0) |
                                                       ((ROWS_COMPUTE1 if ("bg", k, 1) in self.computed else ROWS_OPERAND1) if r1 else 0)))
         self.lin_R = [op.R for op in workload.linears]

@@ -181,3 +181,78 @@ def check_workload_rows(workload, res):
                 assert_sum_close(got[r, fi, 3], vals[1][1], 0.0, tag + " A_1")
                 assert_sum_close(got[r, fi, 0], vals[0][0], E_FLOOR * vals[0][1], tag + " E_0")
                 assert_sum_close(got[r, fi, 2], vals[1][0], E_FLOOR * vals[1][1], tag + " E_1")
+
+
+def _block_scales(res, key, x_bits, n_rows, row_len, block, fmts, what):
+    """The library's scales of a dense operand cut into 1 x block tiles, bit for bit against the oracle's
+    block routine; returns per format (scale, inv) as [n_rows, row_len // block] arrays."""
+    _, base, rows, ti = res["where"][key]
+    per = row_len // block
+    assert rows == n_rows * per, (what, rows, n_rows, per)
+    computed = key in res.get("computed", ())
+    out, flags = [], 0
+    for fi, f in enumerate(fmts):
+        am, sc, iv, fl = oracle.absmax_scale_blocks(x_bits, n_rows, row_len, block, f)
+        flags |= fl
+        if not computed:
+            assert np.array_equal(bits32(res["row_amax"][base:base + rows]), bits32(am.reshape(-1))), what
+        assert np.array_equal(bits32(res["row_scale"][base:base + rows, fi]), bits32(sc.reshape(-1))), (what, fi)
+        assert np.array_equal(bits32(res["row_inv"][base:base + rows, fi]), bits32(iv.reshape(-1))), (what, fi)
+        out.append((sc, iv))
+    if not computed:
+        assert res["row_flags"][ti] == flags, what
+    return out
+
+
+def check_workload_blocks(workload, res, block):
+    """Every operand with one scale per 1 x block tile of its dense rows (causal rows: one scale each):
+    tables bit for bit, sums against the oracle's block routine."""
+    fmts = workload.fmts
+    for k, op in enumerate(workload.linears):
+        x, dx, w, dw = (to_bits(t).reshape(-1) for t in (op.x, op.dx, op.w, op.dw))
+        rows = int(op.row_offsets[-1])
+        sx = _block_scales(res, ("lin", k, 0), x, rows, op.C, block, fmts, op.name + ".x")
+        sw = _block_scales(res, ("lin", k, 1), w, op.K, op.C, block, fmts, op.name + ".w")
+        got = res["linear"][k]
+        n = op.K * op.C
+        for fi, f in enumerate(fmts):
+            for r in range(op.R):
+                r0, r1 = int(op.row_offsets[r]), int(op.row_offsets[r + 1])
+                Ex, Ax = oracle.sens_operand_blocks(x[r0 * op.C:r1 * op.C], dx[r0 * op.C:r1 * op.C], r1 - r0, op.C, block,
+                                                    sx[fi][0][r0:r1], sx[fi][1][r0:r1], f)
+                Ew, Aw = oracle.sens_operand_blocks(w, dw[r * n:(r + 1) * n], op.K, op.C, block, sw[fi][0], sw[fi][1], f)
+                tag = "%s r=%d fmt=%d" % (op.name, r, f)
+                assert_sum_close(got[r, fi, 1], Ax, 0.0, tag + " A_X")
+                assert_sum_close(got[r, fi, 3], Aw, 0.0, tag + " A_W")
+                assert_sum_close(got[r, fi, 0], Ex, E_FLOOR * Ax, tag + " E_X")
+                assert_sum_close(got[r, fi, 2], Ew, E_FLOOR * Aw, tag + " E_W")
+    for k, op in enumerate(workload.bgemms):
+        got = res["bgemm"][k]
+        vals = {}
+        for side, (xt, dxt, lay) in enumerate(((op.x0, op.dx0, op.lay0), (op.x1, op.dx1, op.lay1))):
+            xb, db = to_bits(xt).reshape(-1), to_bits(dxt).reshape(-1)
+            row_len = xt.shape[-1]
+            n_rows = xb.size // row_len
+            per = n_rows // op.R
+            what = "%s.x%d" % (op.name, side)
+            if lay[0] == "causal":
+                sc = _operand_scales(res, ("bg", k, side), xb, n_rows, row_len, fmts, lay[2], what)
+                for fi, f in enumerate(fmts):
+                    for r in range(op.R):
+                        a, b = r * per, (r + 1) * per
+                        vals[(side, fi, r)] = oracle.sens_operand_rows(xb[a * row_len:b * row_len], db[a * row_len:b * row_len], per,
+                                                                       row_len, sc[fi][0][a:b], sc[fi][1][a:b], f, causal_rows=lay[2])
+            else:
+                sc = _block_scales(res, ("bg", k, side), xb, n_rows, row_len, block, fmts, what)
+                for fi, f in enumerate(fmts):
+                    for r in range(op.R):
+                        a, b = r * per, (r + 1) * per
+                        vals[(side, fi, r)] = oracle.sens_operand_blocks(xb[a * row_len:b * row_len], db[a * row_len:b * row_len], per,
+                                                                         row_len, block, sc[fi][0][a:b], sc[fi][1][a:b], f)
+        for fi, f in enumerate(fmts):
+            for r in range(op.R):
+                tag = "%s r=%d fmt=%d" % (op.name, r, f)
+                assert_sum_close(got[r, fi, 1], vals[(0, fi, r)][1], 0.0, tag + " A_0")
+                assert_sum_close(got[r, fi, 3], vals[(1, fi, r)][1], 0.0, tag + " A_1")
+                assert_sum_close(got[r, fi, 0], vals[(0, fi, r)][0], E_FLOOR * vals[(0, fi, r)][1], tag + " E_0")
+                assert_sum_close(got[r, fi, 2], vals[(1, fi, r)][0], E_FLOOR * vals[(1, fi, r)][1], tag + " E_1")

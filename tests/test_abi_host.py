@@ -235,6 +235,12 @@ def test_row_scale_descriptors_are_validated():
     assert L.amp_sens_linear_workspace_bytes(C.byref(d), 1, 2, C.byref(n)) == amp.OK
     d.scale_rows = 8                                           # a weight's scales are never computed by the pass
     assert L.amp_sens_linear_workspace_bytes(C.byref(d), 1, 2, C.byref(n)) == amp.ERR_INVALID_ARG
+    # scale blocks inside the rows: the block must divide C and some operand must have row scales
+    for flags, want in ((3 | amp.rows_block(16), amp.OK), (1 | amp.rows_block(64), amp.OK), (2 | amp.rows_block(32), amp.OK),
+                        (4 | amp.rows_block(8), amp.OK), (3 | amp.rows_block(48), amp.ERR_INVALID_ARG),
+                        (amp.rows_block(16), amp.ERR_INVALID_ARG), (3 | amp.rows_block(128), amp.ERR_INVALID_ARG)):
+        d.scale_rows = flags
+        assert L.amp_sens_linear_workspace_bytes(C.byref(d), 1, 2, C.byref(n)) == want, hex(flags)
     # a dense BGEMM operand with one scale per row must say its row length, and it must divide the block
     b = amp.bgemm_desc(None, None, amp.dense(4 * 64 * 16), None, None, amp.dense(4 * 64 * 16, 16), 2,
                        None, None, None, None, scale_rows=amp.ROWS_OPERAND1)
