@@ -1047,9 +1047,12 @@ struct AbsmaxCtx {
     __device__ __forceinline__ void partial(int64_t e, int jlo, int jhi) { vec(gather8(x, e, jlo, jhi)); }
 };
 
+#ifndef AMPSENS_ABSMAX_WAVES
+#define AMPSENS_ABSMAX_WAVES 8
+#endif
 // Per-wave maxima of every chunk go to their own slots: integer max is exact and order-free,
 // and without atomics there is no contention on the few per-tensor words.
-__global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) void absmax_kernel(const ResolvedUnit* __restrict__ runits,
+__global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(AMPSENS_ABSMAX_WAVES, AMPSENS_ABSMAX_WAVES))) void absmax_kernel(const ResolvedUnit* __restrict__ runits,
                                                      const ChunkRef* __restrict__ map,
                                                      uint32_t n_chunks,
                                                      uint32_t* __restrict__ partial_max) {
@@ -1808,7 +1811,13 @@ hipError_t launch_sens_w(const WGroup* d_groups, uint32_t n_groups, uint32_t n_i
     return hipGetLastError();
 }
 
-int absmax_resident_blocks(int cus) { return resident_blocks((const void*)absmax_kernel, cus); }
+// Three workgroups per compute unit, not the eight that fit: on a 5.7 GB pass grids of 768 and 1024 workgroups
+// read 6 680-6 700 and 6 640-6 660 GB/s, 2048 workgroups 6 480 (grids that are not a multiple of the 256
+// compute units fall in between).
+int absmax_resident_blocks(int cus) {
+    const int fit = resident_blocks((const void*)absmax_kernel, cus);
+    return fit < 3 * cus ? fit : 3 * cus;
+}
 int absmax_rows_resident_blocks(int cus) { return resident_blocks((const void*)absmax_rows_kernel, cus); }
 
 hipError_t launch_absmax_rows(const RowTensor* d_tensors, uint32_t n_tensors, uint32_t n_items,
