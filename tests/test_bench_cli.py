@@ -33,7 +33,8 @@ import pytest
 
 
 @pytest.mark.gpu
-@pytest.mark.parametrize("extra", [(), ("--scales", "rows")])
+@pytest.mark.parametrize("extra", [(), ("--scales", "rows"), ("--scales", "rows-single-read", "--scale-rule", "pow2"),
+                                   ("--scales", "rows-single-read", "--scale-block", "128"), ("--calls", "plan")])
 def test_bench_prints_one_json_line_with_the_agreed_fields(extra):
     """A short run on the small single-linear workload: one JSON line on stdout, with the fields the
     benchmark contract names, a roofline object for the longest fused launch and the oracle's timing."""
@@ -57,3 +58,8 @@ def test_bench_prints_one_json_line_with_the_agreed_fields(extra):
     for key in ("value", "unit", "cores", "kind", "sample"):
         assert key in cpu, key
     assert cpu["kind"] == "oracle" and cpu["cores"] >= 1 and cpu["value"] > 0
+
+
+def test_scale_block_needs_row_scales():
+    r = run("--scale-block", "128")
+    assert r.returncode == 2 and "--scales rows" in r.stderr and r.stdout.strip() == ""
