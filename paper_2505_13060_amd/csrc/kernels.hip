@@ -1784,7 +1784,13 @@ int sens_resident_blocks(int n_fmts, int fmt0, int fmt1, int cls, int cus) {
     if (cls >= kFirstFusedClass)
         return resident_blocks((const void*)sens_fused_variant(n_fmts, fmt0, fmt1, false, cls == kFirstFusedClass), cus,
                                sens_class_lds_bytes(cls));
-    return resident_blocks((const void*)sens_variant(n_fmts, fmt0, fmt1, cls), cus);
+    const int fit = resident_blocks((const void*)sens_variant(n_fmts, fmt0, fmt1, cls), cus);
+    // The kernel for one scale per tensor is compiled for 7 waves per SIMD (the code the compiler writes for
+    // 72 registers is the fastest) but runs best on three workgroups per compute unit: 1.640 against 1.665 ms
+    // on the config-2 block, 4.35 against 4.42 on config 3, 4.02 against 4.11 on config 4 (two per unit:
+    // better on config 3, worse on config 2 and 4; one: far worse).
+    if (cls == 0 && fit > 3 * cus) return 3 * cus;
+    return fit;
 }
 
 typedef void (*sens_w_fn_t)(const WGroup*, uint32_t, uint32_t, const ResolvedUnit*, const uint32_t*, float*);
