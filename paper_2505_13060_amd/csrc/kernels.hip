@@ -1806,7 +1806,12 @@ static sens_w_fn_t sens_w_variant(int n_fmts, int fmt0, int fmt1, int rows) {
 }
 
 int sens_w_resident_blocks(int n_fmts, int fmt0, int fmt1, int rows, int cus) {
-    return resident_blocks((const void*)sens_w_variant(n_fmts, fmt0, fmt1, rows), cus);
+    const int fit = resident_blocks((const void*)sens_w_variant(n_fmts, fmt0, fmt1, rows), cus);
+    // With two formats two workgroups per compute unit stream faster than the four that fit (1.065 against
+    // 1.095 ms on the config-2 block, 3.86 against 3.94 on config 4, 0.573 against 0.592 on config 1); with one
+    // format they do not (2.70 against 2.26 ms on config 3).
+    if (n_fmts == 2 && fit > 2 * cus) return 2 * cus;
+    return fit;
 }
 
 hipError_t launch_sens_w(const WGroup* d_groups, uint32_t n_groups, uint32_t n_items,
