@@ -1273,6 +1273,29 @@ __device__ __forceinline__ float scale_quantity(uint32_t bits, int code, bool wa
     return want_inv ? fm / amax : amax / fm;
 }
 
+// The two divisions of scale_quantity, looked up.  amax = a * 2^(e-127) with a = 1 + m/128 one of 128 values:
+// table[(f * 2 + inv) * 128 + m] holds a / FMAX_f (inv = 0) or FMAX_f / a (inv = 1), computed by the same fp32
+// divisions, and scaling by a power of two commutes with a correctly rounded division as long as the result
+// is a normal number: amax / FMAX = table * 2^(e-127), FMAX / amax = table * 2^(127-e), bit for bit.  Exponent
+// fields below 20 (results that can be subnormal, the reciprocal-overflow rule) and 255 take the divisions.
+// The four numbers of a mantissa are neighbours, so the four threads of a quad, which ask for the four numbers
+// of one row, read four consecutive words (no bank conflict inside the quad).
+constexpr int kScaleTableWords = 128 * 4;
+__device__ __forceinline__ void fill_scale_table(float* table, int code0, int code1) {
+    for (int i = threadIdx.x; i < kScaleTableWords; i += kWG) {
+        const int which = i & 3;                               // format * 2 + reciprocal
+        const float fm = fmax_of(((which >> 1) == 0 ? code0 : code1) & 0xFF);
+        const float a = __uint_as_float(0x3F800000u | ((uint32_t)(i >> 2) << 16));
+        table[i] = (which & 1) ? fm / a : a / fm;
+    }
+}
+__device__ __forceinline__ float scale_quantity(uint32_t bits, int f, int code, bool want_inv, const float* table) {
+    const int e = (int)(bits >> 7);
+    if ((code & kScalePow2) || e < 20 || e >= 255) return scale_quantity(bits, code, want_inv);
+    const float t = table[((int)(bits & 127u) << 2) | (f * 2 + (want_inv ? 1 : 0))];
+    return __builtin_ldexpf(t, want_inv ? 127 - e : e - 127);
+}
+
 // max(v, v of the lane a DPP pattern names); every lane has a source in the patterns used here
 template <int CTRL>
 __device__ __forceinline__ uint32_t max_with_dpp(uint32_t v) {
@@ -1373,6 +1396,7 @@ struct FusedRows {
     float E[NF], A;
     int pk[NF];
     uint32_t* red;                                 // LDS, [2][kWaves]: wave maxima of rows that span waves
+    const float* scale_table;                      // LDS, fill_scale_table
     u32x4* stage;                                  // LDS, [nv][kWG]: this workgroup's vectors of x
     int parity;
 
@@ -1400,11 +1424,16 @@ struct FusedRows {
     // the four numbers), the row's entries of the tables.  POW2: iv returns the scales the codes are
     // taken back with and mul their multiplier (one_format_pow2).
     __device__ __forceinline__ void row_scales(const FusedTile& t, uint32_t m2, float (&sc)[NF], float (&iv)[NF], float& mul) {
-        // maximum over the row's threads (L consecutive lanes, L a power of two >= 4): quads, then halves
-        // of a 16-lane row, then its mirror image, by DPP; the steps across 16-lane rows by lane shuffles
-        const int lg = t.lanes_log2;
+        const uint32_t m = row_max(m2, t.lanes_log2);
+        scales_of_row(m, t.live && (threadIdx.x & ((1 << t.lanes_log2) - 1)) == 0, ts + t.row * NF, ti + t.row * NF, 0,
+                      sc, iv, mul);
+    }
+
+    // Maximum over the 2^lg threads of a row (consecutive lanes, lg >= 2): quads, then halves of a 16-lane
+    // row, then its mirror image, by DPP; the steps across 16-lane rows by lane shuffles; rows that span
+    // waves (lg > 6, uniform over the workgroup) through LDS and one barrier.
+    __device__ __forceinline__ uint32_t row_max(uint32_t m2, int lg) {
         const int tid = threadIdx.x;
-        const int j = tid & ((1 << lg) - 1);
         uint32_t m = (m2 & 0xFFFFu) > (m2 >> 16) ? (m2 & 0xFFFFu) : (m2 >> 16);
         m = max_with_dpp<0xB1>(m);                                 // quad_perm [1, 0, 3, 2]
         m = max_with_dpp<0x4E>(m);                                 // quad_perm [2, 3, 0, 1]
@@ -1429,11 +1458,17 @@ struct FusedRows {
             }
             parity ^= 1;
         }
-        // the scales: each thread of a quad derives one of (scale_0, inv_0, scale_1, inv_1), then the quad shares them
+        return m;
+    }
+
+    // The scales of the row whose absmax (as bits) is m: each thread of a quad derives one of (scale_0, inv_0,
+    // scale_1, inv_1), then the quad shares them; the thread with `writer` set stores the row's table entries.
+    __device__ __forceinline__ void scales_of_row(uint32_t m, bool writer, float* ts_base, float* ti_base, int row,
+                                                  float (&sc)[NF], float (&iv)[NF], float& mul) {
         {
-            const int q = j & 3;
+            const int q = threadIdx.x & 3;
             const int f = NF > 1 ? (q >> 1) : 0;
-            const float mine = scale_quantity(m, f == 0 ? code0 : code1, (q & 1) != 0);
+            const float mine = scale_quantity(m, f, f == 0 ? code0 : code1, (q & 1) != 0, scale_table);
             sc[0] = quad_broadcast<0x00>(mine);
             iv[0] = quad_broadcast<0x55>(mine);
             if constexpr (NF > 1) {
@@ -1441,11 +1476,11 @@ struct FusedRows {
                 iv[1] = quad_broadcast<0xFF>(mine);
             }
         }
-        if (t.live && j == 0) {
+        if (writer) {
 #pragma unroll
             for (int f = 0; f < NF; ++f) {
-                ts[t.row * NF + f] = sc[f];
-                ti[t.row * NF + f] = iv[f];
+                ts_base[row * NF + f] = sc[f];
+                ti_base[row * NF + f] = iv[f];
             }
         }
         mul = -1.0f;
@@ -1525,6 +1560,58 @@ struct FusedRows {
         for (int k = 0; k < NV; ++k) {
             quad(r.x[k].x, r.x[k].y, r.g[k].x, r.g[k].y, iv, sc, mul);
             quad(r.x[k].z, r.x[k].w, r.g[k].z, r.g[k].w, iv, sc, mul);
+        }
+    }
+
+    // Short dense rows of 2^p vectors (p = 2 .. 4: 32 to 128 elements).  With a few threads per row every
+    // load instruction of tile() touches many separate 64-byte pieces; here a tile is 1024 consecutive
+    // vectors of the unit and thread t takes vectors t, t + 256, t + 512, t + 768 of it, so that every load
+    // instruction of a wave reads 1 KiB of consecutive memory.  A thread's four vectors then lie in four
+    // different rows; the 2^p lanes that hold a row reduce its absmax and derive its scales, vector by vector.
+    __device__ __forceinline__ void wide_tile(int64_t v0, int64_t total, int p) {
+        constexpr int NV = kFusedRegNv;
+        const int tid = threadIdx.x;
+        const gptr128_t px = reinterpret_cast<gptr128_t>(x) + v0;
+        const gptr128_t pg = reinterpret_cast<gptr128_t>(g) + v0;
+        u32x4 xr[NV], gr[NV];
+        const bool whole = v0 + (int64_t)NV * kWG <= total;        // uniform
+        const int left = whole ? NV * kWG : (int)(total - v0);     // vectors of the tile that exist (>= 1)
+        const int64_t row0 = v0 >> p;                              // uniform
+        if (whole) {
+#pragma unroll
+            for (int k = 0; k < NV; ++k) xr[k] = load128<true>(px + (tid + k * kWG));
+#pragma unroll
+            for (int k = 0; k < NV; ++k) gr[k] = load128<true>(pg + (tid + k * kWG));
+        } else {
+            int at[NV];
+#pragma unroll
+            for (int k = 0; k < NV; ++k) at[k] = tid + k * kWG < left ? tid + k * kWG : left - 1;
+#pragma unroll
+            for (int k = 0; k < NV; ++k) xr[k] = load128<true>(px + at[k]);
+#pragma unroll
+            for (int k = 0; k < NV; ++k) gr[k] = load128<true>(pg + at[k]);
+            const u32x4 zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int k = 0; k < NV; ++k)
+                if (tid + k * kWG >= left) { xr[k] = zero; gr[k] = zero; }
+        }
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+            uint32_t m2 = 0;
+            const uint32_t w[4] = {xr[k].x, xr[k].y, xr[k].z, xr[k].w};
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const u16x2 a = __builtin_bit_cast(u16x2, m2), b = __builtin_bit_cast(u16x2, w[q] & 0x7FFF7FFFu);
+                m2 = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(a, b));
+            }
+            const uint32_t m = row_max(m2, p);
+            // the row's table entry: the tile's first row (uniform, 64 bits) + this vector's row inside the tile
+            const int in_tile = tid + k * kWG;
+            const bool writer = (tid & ((1 << p) - 1)) == 0 && (whole || in_tile < left);
+            float sc[NF], iv[NF], mul;
+            scales_of_row(m, writer, ts + row0 * NF, ti + row0 * NF, in_tile >> p, sc, iv, mul);
+            quad(xr[k].x, xr[k].y, gr[k].x, gr[k].y, iv, sc, mul);
+            quad(xr[k].z, xr[k].w, gr[k].z, gr[k].w, iv, sc, mul);
         }
     }
 
@@ -1641,8 +1728,11 @@ void sens_fused_rows_kernel(const ResolvedUnit* __restrict__ runits, const Chunk
     saturating_fp8_conversions();
     extern __shared__ __attribute__((aligned(16))) unsigned char fused_lds[];   // [nv][kWG] vectors, then 2 * kWaves words
     __shared__ uint32_t red[2 * kWaves];
+    __shared__ float scale_table[kScaleTableWords];
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
+    fill_scale_table(scale_table, code0, code1);
+    __syncthreads();
     for (uint32_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
         const ChunkRef ref = map[c];
         const ResolvedUnit u = runits[ref.unit];
@@ -1656,6 +1746,7 @@ void sens_fused_rows_kernel(const ResolvedUnit* __restrict__ runits, const Chunk
         ctx.code0 = code0;
         ctx.code1 = code1;
         ctx.red = red;
+        ctx.scale_table = scale_table;
         ctx.stage = reinterpret_cast<u32x4*>(fused_lds);
         ctx.parity = 0;
 #pragma unroll
@@ -1664,10 +1755,17 @@ void sens_fused_rows_kernel(const ResolvedUnit* __restrict__ runits, const Chunk
         FusedTileWalk walk;
         walk.begin(u, geo, ref.local, tid);
         if constexpr (REGS) {
-            typename FusedRows<NF, F0, F1, POW2>::Regs r;
-            for (FusedTile t = walk.next(); t.valid; t = walk.next()) {
-                ctx.regs_issue(t, r);
-                ctx.regs_finish(t, r);
+            if (geo.wide) {                              // short dense rows: tiles of 1024 consecutive vectors
+                const int64_t total = (int64_t)u.rows << geo.lanes_log2;
+                int64_t v0 = (int64_t)ref.local * geo.tiles * (kFusedRegNv * kWG);
+                for (int q = 0; q < geo.tiles && v0 < total; ++q, v0 += kFusedRegNv * kWG)
+                    ctx.wide_tile(v0, total, geo.lanes_log2);
+            } else {
+                typename FusedRows<NF, F0, F1, POW2>::Regs r;
+                for (FusedTile t = walk.next(); t.valid; t = walk.next()) {
+                    ctx.regs_issue(t, r);
+                    ctx.regs_finish(t, r);
+                }
             }
         } else {
             for (FusedTile t = walk.next(); t.valid; t = walk.next()) ctx.tile(t);

@@ -54,7 +54,7 @@ def test_single_read_reduced_blocks():
     run(wl.config4("cpu", R=5, experts=6, C=512, K=176, tok_lo=1, tok_hi=40, n_bgemm=4, S=72, H=2, D=32), plan=True)
 
 
-@pytest.mark.parametrize("C", [8, 128, 136, 1024, 4096, 8192, 11008, 16392, 24576])
+@pytest.mark.parametrize("C", [8, 32, 64, 128, 136, 256, 1024, 4096, 8192, 11008, 16392, 24576])
 def test_single_read_row_lengths(C):
     """Rows from one vector to the longest a workgroup can stage (12 vectors per thread); token counts
     that leave a ragged last tile; a sample without tokens."""
@@ -63,6 +63,47 @@ def test_single_read_row_lengths(C):
     w = wl.Workload("rows_%d" % C, [amp.E4M3, amp.E5M2],
                     [wl._linear("lin", 9000 + C, R, 0, C, K, "cpu", outliers=max(1, C // 100), row_offsets=off)])
     run(w)
+
+
+@pytest.mark.parametrize("row_len", [32, 64, 128, 256])
+@pytest.mark.parametrize("rule", [0, amp.SCALE_POW2])
+def test_single_read_short_rows_over_many_tiles(row_len, rule):
+    """Short power-of-two rows take the tiles of 1024 consecutive vectors (one lane per vector, four rows per
+    thread): row counts that fill several chunks, end in the middle of a tile, in the middle of a wave, and
+    a sample of a single row; every row's scales bit for bit, sums against the oracle."""
+    rng = np.random.default_rng(7 * row_len + rule)
+    for rows in (1, 3 * (1 << 16) // row_len + 5, 20000):
+        R = 2
+        n = rows * row_len
+        mags = np.exp(rng.uniform(-3, 3, (R * rows, 1)))
+        x = f32_to_bf16_bits((rng.standard_normal((R * rows, row_len)) * mags).astype(np.float32)).reshape(-1)
+        g = f32_to_bf16_bits((rng.standard_normal(R * n) * 1e-2).astype(np.float32))
+        X = torch.from_numpy(x.view(np.int16)).to(DEV)
+        G = torch.from_numpy(g.view(np.int16)).to(DEV)
+        ts = torch.full((R * rows, 2), float("nan"), device=DEV)
+        ti = torch.full((R * rows, 2), float("nan"), device=DEV)
+        fmts_plain = [amp.E4M3, amp.E5M2]
+        d = amp.bgemm_desc(X, G, amp.dense(n, row_len), None, None, amp.dense(0), R, ts, ti, None, None,
+                           scale_rows=amp.ROWS_COMPUTE0)
+        out = torch.zeros(R, 2, 4, device=DEV)
+        ws = torch.empty(amp.amp_sens_bgemm_workspace_bytes([d], 2), dtype=torch.uint8, device=DEV)
+        say("short rows of %d, %d rows per sample, rule %#x" % (row_len, rows, rule))
+        amp.amp_sens_bgemm([d], [f | rule for f in fmts_plain], out, ws)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+        for fi, f in enumerate(fmts_plain):
+            am, sc, iv, _ = oracle.absmax_scale_rows(x, R * rows, row_len, f)
+            if rule:
+                both = [oracle.scale_pow2(int(b), f) for b in (parity.bits32(am) >> 16)]
+                sc = np.array([b_[0] for b_ in both], dtype=np.float32)
+                iv = np.array([b_[1] for b_ in both], dtype=np.float32)
+            assert np.array_equal(parity.bits32(ts[:, fi].cpu().numpy()), parity.bits32(sc)), (fi, "scale")
+            assert np.array_equal(parity.bits32(ti[:, fi].cpu().numpy()), parity.bits32(iv)), (fi, "inv")
+            for r in range(R):
+                E, A = oracle.sens_operand_rows(x[r * n:(r + 1) * n], g[r * n:(r + 1) * n], rows, row_len,
+                                                sc[r * rows:(r + 1) * rows], iv[r * rows:(r + 1) * rows], f)
+                parity.assert_sum_close(got[r, fi, 1], A, 0.0, "A fmt %d sample %d" % (f, r))
+                parity.assert_sum_close(got[r, fi, 0], E, parity.E_FLOOR * A, "E fmt %d sample %d" % (f, r))
 
 
 def test_single_read_rejects_rows_it_cannot_stage():
