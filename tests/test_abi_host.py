@@ -159,6 +159,11 @@ REPLAY_CASES = [
     (("causal", 2, 512, 512), 0, 0, 1), (("causal", 1, 1024, 1024), 0, 0, 1), (("causal", 1, 4096, 4096), 0, 0, 1),
     (("causal", 2, 16, 16), 0, 0, 1), (("causal", 3, 24, 24), 0, 0, 1), (("causal", 1, 8, 8), 0, 0, 1),
     (("causal", 1, 1032, 1032), 0, 0, 1), (("causal", 1, 520, 1544), 0, 0, 1), (("causal", 1, 136, 136), 0, 0, 2),
+    # odd and even band counts, bands that end inside, at the start and at the end of a 32-vector
+    # group, rows that start empty, a ragged last band
+    (("causal", 2, 256, 256), 0, 0, 1), (("causal", 1, 264, 264), 0, 0, 1), (("causal", 1, 248, 256), 0, 0, 1),
+    (("causal", 1, 256, 264), 0, 0, 1), (("causal", 1, 300, 296), 0, 0, 1), (("causal", 1, 64, 512), 0, 0, 1),
+    (("causal", 1, 250, 256), 0, 0, 1), (("causal", 1, 509, 768), 0, 0, 1), (("causal", 1, 776, 520), 0, 0, 1),
 ]
 
 
