@@ -104,6 +104,8 @@ struct PlanData {
     uint8_t* ws;                                   // the workspace the set-up wrote
     int32_t n_fmts, fmt0, fmt1, grid_limit;
     uint32_t n_units, n_chunks;
+    uint32_t resolved;                             // the set-up launch resolved the scales: the run that follows at once skips that
+    uint32_t reserved;
     uint64_t off_cb, off_groups, off_runits, off_map, off_partials;    // the unit table sits at offset 0
     // sensitivity pass
     float* d_out;
@@ -138,9 +140,15 @@ Profile g_profile;
 
 // ---- set-up and run of the sensitivity pass ------------------------------------------------------
 
+// run_at_once: the caller runs the plan right after, on the same stream, and never again: a small
+// call then resolves its scales in the set-up launch.
+bool small_table(const WorkTable& t) {
+    return t.table_bytes() <= sizeof(TablePiece) && t.n_chunks <= kSmallSetupChunks;
+}
+
 amp_status_t sens_setup(const WorkTable& t, const amp_fp8_format_t* fmts, int n_fmts, float* d_out,
                         void* workspace, size_t workspace_bytes, uint32_t flags, hipStream_t stream,
-                        PlanData* P) {
+                        PlanData* P, bool run_at_once = false) {
     plan_clear(P, kPlanEmpty);
     if (flags & ~(AMP_PLAN_STREAM_WEIGHTS | 0xFF00u)) return AMP_ERR_INVALID_ARG;
     if (t.units.empty()) return AMP_OK;
@@ -152,7 +160,8 @@ amp_status_t sens_setup(const WorkTable& t, const amp_fp8_format_t* fmts, int n_
     const WorkTable::Plan plan = t.plan(block ? block : kDefaultScheduleBlock, !(flags & AMP_PLAN_STREAM_WEIGHTS));
     std::vector<uint8_t> blob(t.table_bytes());
     t.fill_blob(plan, blob.data());
-    AMP_HIP(launch_table_write(blob.data(), blob.size(), workspace, stream));
+    const bool small = small_table(t);
+    if (!small) AMP_HIP(launch_table_write(blob.data(), blob.size(), workspace, stream));
     uint8_t* ws = (uint8_t*)workspace;
     P->kind = kPlanSens;
     P->ws = ws;
@@ -175,6 +184,13 @@ amp_status_t sens_setup(const WorkTable& t, const amp_fp8_format_t* fmts, int n_
     }
     for (int c = 0; c <= kSensClasses; ++c) P->class_pos[c] = plan.class_pos[c];
     for (int c = 0; c < kSensClasses; ++c) P->class_pairs[c] = plan.class_pairs[c];
+    if (small) {
+        AMP_HIP(launch_small_setup(blob.data(), blob.size(), ws, P->off_cb, t.schedule_offset(), P->n_units,
+                                   P->n_chunks, (ResolvedUnit*)(ws + L.runits), (ChunkRef*)(ws + L.map),
+                                   run_at_once ? n_fmts : 0, stream));
+        P->resolved = run_at_once ? 1u : 0u;
+        return AMP_OK;
+    }
     AMP_HIP(launch_prepare((const WorkUnit*)ws, (const uint32_t*)(ws + P->off_cb),
                            (const UnitSchedule*)(ws + t.schedule_offset()), P->n_units, P->n_chunks,
                            (ResolvedUnit*)(ws + L.runits), (ChunkRef*)(ws + L.map), stream));
@@ -190,7 +206,7 @@ amp_status_t sens_run(const PlanData& P, hipStream_t stream) {
     float* d_partials = (float*)(ws + P.off_partials);
     const WGroup* d_groups = (const WGroup*)(ws + P.off_groups);
     const int nf = P.n_fmts, f0 = P.fmt0 & 0xFF, f1 = P.fmt1 & 0xFF;     // fmt0 / fmt1 may carry the scale rule
-    AMP_HIP(launch_resolve(d_units, P.n_units, nf, d_runits, stream));
+    if (!P.resolved) AMP_HIP(launch_resolve(d_units, P.n_units, nf, d_runits, stream));
     // one pair of events around a fused kernel while the profile has room
     auto timed = [&](int kind, uint64_t pairs, uint64_t bytes, auto&& launch) -> hipError_t {
         int slot = -1;
@@ -250,7 +266,8 @@ amp_status_t absmax_setup(const WorkTable& t, int n_tensors, const amp_fp8_forma
     const WorkTable::Plan plan = t.plan(kDefaultScheduleBlock, false);
     std::vector<uint8_t> blob(t.table_bytes());
     t.fill_blob(plan, blob.data());
-    AMP_HIP(launch_table_write(blob.data(), blob.size(), workspace, stream));
+    const bool small = small_table(t);
+    if (!small) AMP_HIP(launch_table_write(blob.data(), blob.size(), workspace, stream));
     uint8_t* ws = (uint8_t*)workspace;
     P->kind = kPlanAbsmax;
     P->ws = ws;
@@ -265,6 +282,11 @@ amp_status_t absmax_setup(const WorkTable& t, int n_tensors, const amp_fp8_forma
     P->off_partials = L.partials;
     P->d_amax = d_amax; P->d_scale = d_scale; P->d_inv = d_inv; P->d_flags = d_flags;
     P->n_tensors = n_tensors;
+    if (small) {
+        AMP_HIP(launch_small_setup(blob.data(), blob.size(), ws, P->off_cb, t.schedule_offset(), P->n_units,
+                                   P->n_chunks, (ResolvedUnit*)(ws + L.runits), (ChunkRef*)(ws + L.map), 0, stream));
+        return AMP_OK;
+    }
     AMP_HIP(launch_prepare((const WorkUnit*)ws, (const uint32_t*)(ws + P->off_cb),
                            (const UnitSchedule*)(ws + t.schedule_offset()), P->n_units, P->n_chunks,
                            (ResolvedUnit*)(ws + L.runits), (ChunkRef*)(ws + L.map), stream));
@@ -516,11 +538,15 @@ amp_status_t amp_sens_block_setup(const amp_linear_desc_t* linears, int n_linear
 amp_status_t amp_sens_block(const amp_linear_desc_t* linears, int n_linears, const amp_bgemm_desc_t* bgemms,
                             int n_bgemms, const amp_fp8_format_t* fmts, int n_fmts, float* d_out,
                             void* workspace, size_t workspace_bytes, void* stream) {
-    amp_plan_t plan;
-    amp_status_t st = amp_sens_block_setup(linears, n_linears, bgemms, n_bgemms, fmts, n_fmts, d_out, workspace,
-                                           workspace_bytes, 0u, stream, &plan);
+    amp_status_t st = check_fmts(fmts, n_fmts, true);
     if (st != AMP_OK) return st;
-    return amp_run(&plan, stream);
+    WorkTable t;
+    st = build_block(linears, n_linears, bgemms, n_bgemms, n_fmts, &t);
+    if (st != AMP_OK) return st;
+    PlanData P;
+    st = sens_setup(t, fmts, n_fmts, d_out, workspace, workspace_bytes, 0u, (hipStream_t)stream, &P, true);
+    if (st != AMP_OK) return st;
+    return run_plan(P, (hipStream_t)stream);
 }
 
 amp_status_t amp_sens_block_static(const amp_linear_desc_t* linears, int n_linears, const amp_bgemm_desc_t* bgemms,
@@ -537,7 +563,7 @@ amp_status_t amp_sens_block_static(const amp_linear_desc_t* linears, int n_linea
     st = static_scratch(&ws);
     if (st != AMP_OK) return st;
     PlanData P;
-    st = sens_setup(t, fmts, n_fmts, d_out, ws, kStaticScratchBytes, 0u, (hipStream_t)stream, &P);
+    st = sens_setup(t, fmts, n_fmts, d_out, ws, kStaticScratchBytes, 0u, (hipStream_t)stream, &P, true);
     if (st != AMP_OK) return st;
     return run_plan(P, (hipStream_t)stream);
 }

@@ -293,6 +293,12 @@ int absmax_rows_resident_blocks(int cus);
 struct TablePiece { uint4 w[240]; };                   // 3840 bytes: fits the kernel-argument segment
 hipError_t launch_table_write(const void* host_src, size_t bytes, void* d_dst, hipStream_t stream);
 // Once per set-up: unit records for the streaming kernels (scales not yet filled in) and the chunk map.
+// Table, prepare and (resolve_fmts > 0) resolve of a small call in one launch of one workgroup: the
+// table must fit one piece and the call have at most kSmallSetupChunks chunks.
+constexpr uint32_t kSmallSetupChunks = 8192;
+hipError_t launch_small_setup(const void* host_src, size_t bytes, void* d_dst, size_t off_cb, size_t off_schedule,
+                              uint32_t n_units, uint32_t n_chunks, ResolvedUnit* d_runits, ChunkRef* d_map,
+                              int resolve_fmts, hipStream_t stream);
 hipError_t launch_prepare(const WorkUnit* d_units, const uint32_t* d_chunk_begin,
                           const UnitSchedule* d_schedule, uint32_t n_units, uint32_t n_chunks,
                           ResolvedUnit* d_runits, ChunkRef* d_map, hipStream_t stream);

@@ -177,13 +177,11 @@ __global__ __launch_bounds__(kWG) void table_write_kernel(TablePiece piece, uint
 // ---- prepare: the static part of a call (once per set-up) ----------------------------------------
 // Unit records in the form the streaming kernels read, and the chunk map: for every schedule
 // position its unit, its index inside that unit and its partial slot, so that no kernel searches.
-__global__ __launch_bounds__(kWG) void prepare_kernel(const WorkUnit* __restrict__ units,
-                                                      const uint32_t* __restrict__ chunk_begin,
-                                                      const UnitSchedule* __restrict__ schedule,
-                                                      uint32_t n_units, uint32_t n_chunks,
-                                                      ResolvedUnit* __restrict__ runits,
-                                                      ChunkRef* __restrict__ map) {
-    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+__device__ __forceinline__ void prepare_item(uint32_t i, const WorkUnit* __restrict__ units,
+                                             const uint32_t* __restrict__ chunk_begin,
+                                             const UnitSchedule* __restrict__ schedule, uint32_t n_units,
+                                             uint32_t n_chunks, ResolvedUnit* __restrict__ runits,
+                                             ChunkRef* __restrict__ map) {
     if (i < n_units) {
         const WorkUnit u = units[i];
         ResolvedUnit r;
@@ -211,19 +209,56 @@ __global__ __launch_bounds__(kWG) void prepare_kernel(const WorkUnit* __restrict
     }
 }
 
+__global__ __launch_bounds__(kWG) void prepare_kernel(const WorkUnit* __restrict__ units,
+                                                      const uint32_t* __restrict__ chunk_begin,
+                                                      const UnitSchedule* __restrict__ schedule,
+                                                      uint32_t n_units, uint32_t n_chunks,
+                                                      ResolvedUnit* __restrict__ runits,
+                                                      ChunkRef* __restrict__ map) {
+    prepare_item(blockIdx.x * blockDim.x + threadIdx.x, units, chunk_begin, schedule, n_units, n_chunks, runits, map);
+}
+
 // ---- resolve: the scales of a run (every run) ------------------------------------------------------
 // Units with one scale per tensor get the values their scale pointers hold now (an absmax run on
 // the same stream may just have written them); units with row scales keep their table pointers.
-__global__ __launch_bounds__(kWG) void resolve_kernel(const WorkUnit* __restrict__ units, uint32_t n_units,
-                                                      int n_fmts, ResolvedUnit* __restrict__ runits) {
-    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n_units) return;
+__device__ __forceinline__ void resolve_item(uint32_t i, const WorkUnit* __restrict__ units, int n_fmts,
+                                             ResolvedUnit* __restrict__ runits) {
     const WorkUnit u = units[i];
     if (u.flags & kUnitRowScale) return;
     for (int f = 0; f < kMaxFormats; ++f) {
         const bool have = f < n_fmts && u.inv != nullptr && u.scale != nullptr;
         runits[i].inv[f] = have ? u.inv[f] : 1.0f;
         runits[i].scale[f] = have ? u.scale[f] : 1.0f;
+    }
+}
+
+__global__ __launch_bounds__(kWG) void resolve_kernel(const WorkUnit* __restrict__ units, uint32_t n_units,
+                                                      int n_fmts, ResolvedUnit* __restrict__ runits) {
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n_units) resolve_item(i, units, n_fmts, runits);
+}
+
+// ---- small calls: table, prepare and (for a call that runs at once) resolve in one launch -------------
+// A table that fits one piece is written, and then read back by the same single workgroup after a
+// barrier: the set-up of a small call is one launch instead of two or three.  resolve_fmts > 0:
+// the scales are resolved too (the caller runs the pass right after, on the same stream).
+__global__ __launch_bounds__(kWG) void small_setup_kernel(TablePiece piece, uint32_t n_words, uint4* __restrict__ dst,
+                                                          uint32_t off_cb, uint32_t off_schedule, uint32_t n_units,
+                                                          uint32_t n_chunks, ResolvedUnit* __restrict__ runits,
+                                                          ChunkRef* __restrict__ map, int resolve_fmts) {
+    for (uint32_t i = threadIdx.x; i < n_words; i += kWG) dst[i] = piece.w[i];
+    __threadfence_block();
+    __syncthreads();
+    const uint8_t* base = reinterpret_cast<const uint8_t*>(dst);
+    const WorkUnit* units = reinterpret_cast<const WorkUnit*>(base);
+    const uint32_t* chunk_begin = reinterpret_cast<const uint32_t*>(base + off_cb);
+    const UnitSchedule* schedule = reinterpret_cast<const UnitSchedule*>(base + off_schedule);
+    const uint32_t n = n_units > n_chunks ? n_units : n_chunks;
+    for (uint32_t i = threadIdx.x; i < n; i += kWG)
+        prepare_item(i, units, chunk_begin, schedule, n_units, n_chunks, runits, map);
+    if (resolve_fmts > 0) {
+        // a thread resolves the units it has just prepared itself: no second barrier
+        for (uint32_t i = threadIdx.x; i < n_units; i += kWG) resolve_item(i, units, resolve_fmts, runits);
     }
 }
 
@@ -1955,6 +1990,19 @@ hipError_t launch_table_write(const void* host_src, size_t bytes, void* d_dst, h
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
+}
+
+hipError_t launch_small_setup(const void* host_src, size_t bytes, void* d_dst, size_t off_cb, size_t off_schedule,
+                              uint32_t n_units, uint32_t n_chunks, ResolvedUnit* d_runits, ChunkRef* d_map,
+                              int resolve_fmts, hipStream_t stream) {
+    if (bytes > sizeof(TablePiece) || n_chunks > kSmallSetupChunks) return hipErrorInvalidValue;
+    TablePiece piece;
+    std::memcpy(&piece, host_src, bytes);
+    if (bytes % 16) std::memset((uint8_t*)&piece + bytes, 0, 16 - bytes % 16);
+    hipLaunchKernelGGL(small_setup_kernel, dim3(1), dim3(kWG), 0, stream, piece, (uint32_t)((bytes + 15) / 16),
+                       (uint4*)d_dst, (uint32_t)off_cb, (uint32_t)off_schedule, n_units, n_chunks, d_runits, d_map,
+                       resolve_fmts);
+    return hipGetLastError();
 }
 
 hipError_t launch_prepare(const WorkUnit* d_units, const uint32_t* d_chunk_begin,
