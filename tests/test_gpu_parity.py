@@ -145,6 +145,37 @@ def test_absmax_scale_bit_exact_many_tensors():
             assert parity.bits32(res["inv"][t, fi]) == parity.bits32(ref[fi][2]), (t, fi)
 
 
+def test_absmax_on_both_sides_of_the_one_launch_set_up_limit():
+    """The absmax call sets up in one launch up to 8 192 chunks (2^29 elements) and with a launch of its
+    own per step beyond: one buffer, its first 8 192 chunks and one vector more, the largest value in the
+    last element of each, amax and scales bit for bit against the oracle."""
+    n0 = 8192 * 65536
+    g = torch.Generator(device=DEV)
+    g.manual_seed(77)
+    x = (torch.randn(n0 + 8, device=DEV, generator=g) * 0.5).to(torch.bfloat16)
+    x[n0 - 1] = 9.5
+    x[n0 + 7] = -11.0
+    host = x.view(torch.int16).cpu().numpy().view(np.uint16)
+    fmts = [amp.E4M3, amp.E5M2]
+    for n in (n0, n0 + 8):
+        say("absmax of %d elements (%d chunks)" % (n, (n + 65535) // 65536))
+        tensors = [amp.tensor(x, amp.dense(n), 1)]
+        d_amax = torch.zeros(1, device=DEV)
+        d_scale = torch.zeros(1, 2, device=DEV)
+        d_inv = torch.zeros(1, 2, device=DEV)
+        d_flags = torch.zeros(1, dtype=torch.int32, device=DEV)
+        ws = torch.empty(amp.amp_absmax_workspace_bytes(tensors), dtype=torch.uint8, device=DEV)
+        amp.amp_absmax_scale(tensors, fmts, d_amax, d_scale, d_inv, d_flags, ws)
+        torch.cuda.synchronize()
+        for fi, f in enumerate(fmts):
+            am, sc, iv, fl = oracle.absmax_scale(host[:n], f)
+            assert fl == 0 and int(d_flags[0]) == 0
+            assert am == (9.5 if n == n0 else 11.0)
+            assert parity.bits32(d_amax.cpu().numpy()[0]) == parity.bits32(am)
+            assert parity.bits32(d_scale.cpu().numpy()[0, fi]) == parity.bits32(sc)
+            assert parity.bits32(d_inv.cpu().numpy()[0, fi]) == parity.bits32(iv)
+
+
 # ---------------------------------------------------------------------------------------------
 # the fused pass on the benchmark configurations (reduced where the oracle would take minutes)
 # ---------------------------------------------------------------------------------------------
@@ -175,6 +206,25 @@ def test_config3_reduced_gqa_student_t():
 
 def test_config4_reduced_ragged_many_small():
     run_and_check(wl.config4("cpu", R=5, experts=6, C=512, K=176, tok_lo=1, tok_hi=40, n_bgemm=4, S=72, H=2, D=32))
+
+
+@pytest.mark.parametrize("R", [12, 18, 19, 26])
+def test_set_up_in_one_launch_and_in_several(R):
+    """A call whose table fits one kernel-argument piece (up to 18 samples of one linear layer) is set up
+    by a single launch that, for a one-shot call, also resolves the scales; larger tables travel piece by
+    piece.  Sample counts on both sides of the limit: every unit against the oracle through the one-shot
+    calls, and the plan (set-up once, scales resolved by the run) bit for bit the same."""
+    w = wl.Workload("setup_R%d" % R, [amp.E4M3, amp.E5M2],
+                    [wl._linear("linear", 40 + R, R, 24, 256, 136, "cpu", outliers=2)])
+    p, res = run_and_check(w)
+    q = SensPass(w, DEV, plan=True)
+    for _ in range(2):
+        q.d_out.zero_()
+        q.run()
+        again = q.results()
+        assert np.array_equal(np.concatenate(again["linear"]).view(np.uint32),
+                              np.concatenate(res["linear"]).view(np.uint32))
+        assert np.array_equal(again["scale"].view(np.uint32), res["scale"].view(np.uint32))
 
 
 def test_single_format_e5m2_and_format_order():
