@@ -155,17 +155,21 @@ def test_rows_one_call_for_linears_and_bgemms():
             assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
 
 
-def test_rows_config2_block_at_full_size_every_unit():
+@pytest.mark.parametrize("single_read", [False, True])
+def test_rows_config2_block_at_full_size_every_unit(single_read):
     """One whole block of the benchmark's workload with one scale per row on every operand (per token,
-    per output channel, per row of the BGEMM operands), in the launch configuration
-    `bench.py --scales rows` times: every row's scales bit for bit and every (op, operand, sample,
-    format) sum against the oracle, fanned over host threads."""
+    per output channel, per row of the BGEMM operands), in the launch configurations
+    `bench.py --scales rows` (two passes) and `bench.py --scales rows-single-read` (the pass that
+    derives the row scales itself) time: every row's scales bit for bit and every (op, operand,
+    sample, format) sum against the oracle, fanned over host threads."""
     import os
     from concurrent.futures import ThreadPoolExecutor
-    say("rows, config2 block 2 (one of the blocks bench.py times) at full size: generating on the GPU")
-    w = wl.config2_block(DEV, 2)
+    block = 3 if single_read else 2
+    say("rows%s, config2 block %d (one of the blocks bench.py times) at full size: generating on the GPU" %
+        (", single read" if single_read else "", block))
+    w = wl.config2_block(DEV, block)
     torch.cuda.synchronize()
-    p = RowSensPass(w, DEV, one_call=True)
+    p = RowSensPass(w, DEV, one_call=True, single_read=single_read)
     p.run()
     res = p.results()
     fmts = w.fmts
