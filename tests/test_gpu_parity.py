@@ -463,17 +463,22 @@ def test_full_size_sampled_units(which):
             assert np.all(arr[:, 0, 0] < arr[:, 1, 0]) and np.all(arr[:, 0, 2] < arr[:, 1, 2])
 
 
-def test_config2_block_at_full_size_every_unit():
-    """One whole block of the benchmark's workload in the benchmark's launch configuration: every
-    (op, operand, sample, format) sum against the oracle, and every scale bit for bit.  The oracle's
-    routine is single-threaded; the units are fanned over host threads (ctypes releases the GIL)."""
+@pytest.mark.parametrize("rule", [0, amp.SCALE_POW2])
+def test_config2_block_at_full_size_every_unit(rule):
+    """One whole block of the benchmark's workload in the benchmark's launch configuration, with the
+    amax / FMAX scales (the headline) and with power-of-two scales (`bench.py --scale-rule pow2`: the
+    kernels that cast with the scaled conversions): every (op, operand, sample, format) sum against the
+    oracle, and every scale bit for bit.  The oracle's routine is single-threaded; the units are
+    fanned over host threads (ctypes releases the GIL)."""
     import os
     from concurrent.futures import ThreadPoolExecutor
-    say("config2 block 0 (the first block bench.py times) at full size: generating on the GPU")
-    w = wl.config2_block(DEV, 0)
+    block = 1 if rule else 0
+    say("config2 block %d (one of the blocks bench.py times) at full size, scale rule %d: generating on the GPU" %
+        (block, rule))
+    w = wl.config2_block(DEV, block)
     torch.cuda.synchronize()
     say("running the pass over %.1f M pairs" % (w.pairs() / 1e6))
-    p = SensPass(w, DEV, one_call=True)
+    p = SensPass(w, DEV, one_call=True, rule=rule)
     p.run()
     res = p.results()
     fmts = w.fmts
