@@ -155,22 +155,29 @@ def test_rows_one_call_for_linears_and_bgemms():
             assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
 
 
-@pytest.mark.parametrize("single_read", [False, True])
-def test_rows_config2_block_at_full_size_every_unit(single_read):
+@pytest.mark.parametrize("single_read,block", [(False, 0), (True, 0), (True, 128)])
+def test_rows_config2_block_at_full_size_every_unit(single_read, block):
     """One whole block of the benchmark's workload with one scale per row on every operand (per token,
     per output channel, per row of the BGEMM operands), in the launch configurations
     `bench.py --scales rows` (two passes) and `bench.py --scales rows-single-read` (the pass that
     derives the row scales itself) time: every row's scales bit for bit and every (op, operand,
-    sample, format) sum against the oracle, fanned over host threads."""
+    sample, format) sum against the oracle, fanned over host threads.  block = 128: one scale per
+    1 x 128 tile of every dense row (`--scale-block 128`), causal rows one scale each."""
     import os
     from concurrent.futures import ThreadPoolExecutor
-    block = 3 if single_read else 2
-    say("rows%s, config2 block %d (one of the blocks bench.py times) at full size: generating on the GPU" %
-        (", single read" if single_read else "", block))
-    w = wl.config2_block(DEV, block)
+    which = (3 if single_read else 2) if block == 0 else 0
+    say("rows%s%s, config2 block %d (one of the blocks bench.py times) at full size: generating on the GPU" %
+        (", single read" if single_read else "", ", 1 x %d tiles" % block if block else "", which))
+    w = wl.config2_block(DEV, which)
     torch.cuda.synchronize()
-    p = RowSensPass(w, DEV, one_call=True, single_read=single_read)
+    p = RowSensPass(w, DEV, one_call=True, single_read=single_read, block=block)
     p.run()
+
+    def scales_of(key, bits, n_rows, row_len, causal_rows, what):
+        if block and causal_rows is None:
+            return parity._block_scales(res, key, bits, n_rows, row_len, block, fmts, what)
+        return parity._operand_scales(res, key, bits, n_rows, row_len, fmts, causal_rows, what)
+
     res = p.results()
     fmts = w.fmts
     units = []                  # (tag, got [nf, 2], x, dx, n_rows, row_len, causal_rows, scales of those rows)
@@ -178,8 +185,8 @@ def test_rows_config2_block_at_full_size_every_unit(single_read):
         say("  %s: copying to the host, scales of every row" % op.name)
         x, dx, wt, dw = (wl.to_bits(t).reshape(-1) for t in (op.x, op.dx, op.w, op.dw))
         rows = int(op.row_offsets[-1])
-        sx = parity._operand_scales(res, ("lin", k, 0), x, rows, op.C, fmts, None, op.name + ".x")
-        sw = parity._operand_scales(res, ("lin", k, 1), wt, op.K, op.C, fmts, None, op.name + ".w")
+        sx = scales_of(("lin", k, 0), x, rows, op.C, None, op.name + ".x")
+        sw = scales_of(("lin", k, 1), wt, op.K, op.C, None, op.name + ".w")
         n = op.K * op.C
         for r in range(op.R):
             r0, r1 = int(op.row_offsets[r]), int(op.row_offsets[r + 1])
@@ -194,8 +201,7 @@ def test_rows_config2_block_at_full_size_every_unit(single_read):
             row_len = xt.shape[-1]
             causal_rows = lay[2] if lay[0] == "causal" else None
             n_rows = xb.size // row_len
-            sc = parity._operand_scales(res, ("bg", k, side), xb, n_rows, row_len, fmts, causal_rows,
-                                        "%s.x%d" % (op.name, side))
+            sc = scales_of(("bg", k, side), xb, n_rows, row_len, causal_rows, "%s.x%d" % (op.name, side))
             per = n_rows // op.R
             for r in range(op.R):
                 a, b = r * per, (r + 1) * per
@@ -206,7 +212,10 @@ def test_rows_config2_block_at_full_size_every_unit(single_read):
     def one(u):
         tag, got, xb, gb, n_rows, row_len, causal_rows, sc = u
         for fi, f in enumerate(fmts):
-            E, A = oracle.sens_operand_rows(xb, gb, n_rows, row_len, sc[fi][0], sc[fi][1], f, causal_rows=causal_rows)
+            if block and causal_rows is None:
+                E, A = oracle.sens_operand_blocks(xb, gb, n_rows, row_len, block, sc[fi][0], sc[fi][1], f)
+            else:
+                E, A = oracle.sens_operand_rows(xb, gb, n_rows, row_len, sc[fi][0], sc[fi][1], f, causal_rows=causal_rows)
             parity.assert_sum_close(got[fi, 1], A, 0.0, tag + " A fmt=%d" % f)
             parity.assert_sum_close(got[fi, 0], E, parity.E_FLOOR * A, tag + " E fmt=%d" % f)
         return tag
