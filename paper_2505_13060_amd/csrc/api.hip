@@ -140,12 +140,43 @@ Profile g_profile;
 
 // ---- set-up and run of the sensitivity pass ------------------------------------------------------
 
-// run_at_once: the caller runs the plan right after, on the same stream, and never again: a small
-// call then resolves its scales in the set-up launch.
 bool small_table(const WorkTable& t) {
     return t.table_bytes() <= sizeof(TablePiece) && t.n_chunks <= kSmallSetupChunks;
 }
 
+// A table of several pieces: units and schedule as runs with fixed steps and literal units, the rest
+// raw, when that takes fewer launches (and reproduces the table byte for byte, which is checked here
+// on the host); else piece by piece.
+hipError_t send_table(const WorkTable& t, const std::vector<uint8_t>& blob, void* workspace, hipStream_t stream) {
+    const size_t n = t.units.size(), off_cb = n * sizeof(WorkUnit), off_sched = t.schedule_offset();
+    const size_t off_groups = t.groups_offset(), tail = blob.size() - off_groups;
+    const size_t cb_bytes = (off_sched - off_cb + 15) / 16 * 16;            // chunk_begin[n + 1] and its padding
+    const TableRecords rec = table_records(blob.data(), n, off_sched);
+    const size_t raw = (blob.size() + sizeof(TablePiece) - 1) / sizeof(TablePiece);
+    const size_t pieces = sizeof(TablePiece);
+    if (rec.launches(0) + (cb_bytes + pieces - 1) / pieces + (tail + pieces - 1) / pieces < raw) {
+        std::vector<uint8_t> check(blob);
+        std::memset(check.data(), 0xEE, off_cb);
+        std::memset(check.data() + off_sched, 0xEE, n * sizeof(UnitSchedule));
+        table_expand(rec, check.data(), off_sched);
+        if (std::memcmp(check.data(), blob.data(), blob.size()) == 0) {
+            hipError_t e = launch_table_runs(rec.runs.data(), rec.runs.size(), workspace, off_sched, stream);
+            if (e != hipSuccess) return e;
+            e = launch_table_literals(rec.literals.data(), rec.literals.size(), workspace, off_sched, stream);
+            if (e != hipSuccess) return e;
+            // chunk_begin in whole 16-byte words: the word that also holds the first schedule entry's
+            // bytes carries the same bytes the records have written (unit tables are multiples of 64)
+            e = launch_table_write(blob.data() + off_cb, cb_bytes, (uint8_t*)workspace + off_cb, stream);
+            if (e != hipSuccess) return e;
+            return tail ? launch_table_write(blob.data() + off_groups, tail, (uint8_t*)workspace + off_groups, stream)
+                        : hipSuccess;
+        }
+    }
+    return launch_table_write(blob.data(), blob.size(), workspace, stream);
+}
+
+// run_at_once: the caller runs the plan right after, on the same stream, and never again: a small
+// call then resolves its scales in the set-up launch.
 amp_status_t sens_setup(const WorkTable& t, const amp_fp8_format_t* fmts, int n_fmts, float* d_out,
                         void* workspace, size_t workspace_bytes, uint32_t flags, hipStream_t stream,
                         PlanData* P, bool run_at_once = false) {
@@ -161,7 +192,7 @@ amp_status_t sens_setup(const WorkTable& t, const amp_fp8_format_t* fmts, int n_
     std::vector<uint8_t> blob(t.table_bytes());
     t.fill_blob(plan, blob.data());
     const bool small = small_table(t);
-    if (!small) AMP_HIP(launch_table_write(blob.data(), blob.size(), workspace, stream));
+    if (!small) AMP_HIP(send_table(t, blob, workspace, stream));
     uint8_t* ws = (uint8_t*)workspace;
     P->kind = kPlanSens;
     P->ws = ws;

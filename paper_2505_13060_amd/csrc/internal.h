@@ -292,6 +292,34 @@ int absmax_rows_resident_blocks(int cus);
 // aligned and has room for `bytes` rounded up to 16.  The source is read before the call returns.
 struct TablePiece { uint4 w[240]; };                   // 3840 bytes: fits the kernel-argument segment
 hipError_t launch_table_write(const void* host_src, size_t bytes, void* d_dst, hipStream_t stream);
+// The same table in fewer launches when its records repeat with fixed steps (the units of the R
+// samples of one operand: pointers, output slots and schedule members advance by the same amount
+// from sample to sample).  A run record stands for `count` units a fixed stride apart: the k-th is,
+// 64-bit word by word of its WorkUnit and its UnitSchedule, first + k * step in wrapping arithmetic;
+// a literal record is one unit as it stands.  Records travel as kernel arguments like the raw pieces
+// and are expanded on the device to exactly the bytes launch_table_write would have written; the
+// chunk_begin array (4 bytes per unit, a running sum that ragged samples make irregular) and the
+// weight groups travel raw.
+struct TableRun {                    // 176 bytes
+    uint32_t first_unit, count;      // units first_unit + k * stride, k < count
+    uint32_t stride, reserved;       // (the two operands of an op alternate in the table: stride 2)
+    uint64_t unit[8], unit_step[8];  // WorkUnit
+    uint64_t sched[2], sched_step[2];   // UnitSchedule
+};
+struct TableLiteral {                // 88 bytes
+    uint32_t unit_index, reserved;
+    uint64_t unit[8];
+    uint64_t sched[2];
+};
+static_assert(sizeof(TableRun) == 176 && sizeof(TableLiteral) == 88, "record layout");
+constexpr int kRunsPerPiece = (int)(sizeof(TablePiece) / sizeof(TableRun));            // 21
+constexpr int kLiteralsPerPiece = (int)(sizeof(TablePiece) / sizeof(TableLiteral));    // 43
+// Expands `n` run records (n literal records) taken from host memory into the unit table at d_table
+// (units at offset 0, schedule at off_schedule), one launch per piece, one workgroup per record.
+hipError_t launch_table_runs(const TableRun* host_runs, size_t n, void* d_table, size_t off_schedule,
+                             hipStream_t stream);
+hipError_t launch_table_literals(const TableLiteral* host_literals, size_t n, void* d_table, size_t off_schedule,
+                                 hipStream_t stream);
 // Once per set-up: unit records for the streaming kernels (scales not yet filled in) and the chunk map.
 // Table, prepare and (resolve_fmts > 0) resolve of a small call in one launch of one workgroup: the
 // table must fit one piece and the call have at most kSmallSetupChunks chunks.

@@ -174,6 +174,34 @@ __global__ __launch_bounds__(kWG) void table_write_kernel(TablePiece piece, uint
     for (uint32_t i = threadIdx.x; i < n_words; i += kWG) dst[i] = piece.w[i];
 }
 
+// Records that stand for runs of units whose fields advance by fixed steps (internal.h): one
+// workgroup per record, one thread per 64-bit word of the expanded units.
+__global__ __launch_bounds__(64) void table_runs_kernel(TablePiece piece, uint8_t* __restrict__ table,
+                                                        uint32_t off_schedule) {
+    const TableRun& R = reinterpret_cast<const TableRun*>(&piece)[blockIdx.x];
+    constexpr uint32_t kWords = 8 + 2;                 // unit, schedule
+    for (uint32_t i = threadIdx.x; i < R.count * kWords; i += 64) {
+        const uint32_t k = i / kWords, w = i % kWords;
+        const uint64_t u = (uint64_t)R.first_unit + (uint64_t)k * R.stride;
+        if (w < 8)
+            reinterpret_cast<uint64_t*>(table)[u * 8 + w] = R.unit[w] + (uint64_t)k * R.unit_step[w];
+        else
+            reinterpret_cast<uint64_t*>(table + off_schedule)[u * 2 + (w - 8)] =
+                R.sched[w - 8] + (uint64_t)k * R.sched_step[w - 8];
+    }
+}
+
+__global__ __launch_bounds__(64) void table_literals_kernel(TablePiece piece, uint8_t* __restrict__ table,
+                                                            uint32_t off_schedule) {
+    const TableLiteral& L = reinterpret_cast<const TableLiteral*>(&piece)[blockIdx.x];
+    const uint32_t w = threadIdx.x;
+    const uint64_t u = L.unit_index;
+    if (w < 8)
+        reinterpret_cast<uint64_t*>(table)[u * 8 + w] = L.unit[w];
+    else if (w < 10)
+        reinterpret_cast<uint64_t*>(table + off_schedule)[u * 2 + (w - 8)] = L.sched[w - 8];
+}
+
 // ---- prepare: the static part of a call (once per set-up) ----------------------------------------
 // Unit records in the form the streaming kernels read, and the chunk map: for every schedule
 // position its unit, its index inside that unit and its partial slot, so that no kernel searches.
@@ -1986,6 +2014,34 @@ hipError_t launch_table_write(const void* host_src, size_t bytes, void* d_dst, h
         if (n % 16) std::memset((uint8_t*)&piece + n, 0, 16 - n % 16);
         hipLaunchKernelGGL(table_write_kernel, dim3(1), dim3(kWG), 0, stream, piece, (uint4*)(dst + off),
                            (uint32_t)((n + 15) / 16));
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+hipError_t launch_table_runs(const TableRun* host_runs, size_t n, void* d_table, size_t off_schedule,
+                             hipStream_t stream) {
+    TablePiece piece;
+    for (size_t i = 0; i < n; i += kRunsPerPiece) {
+        const size_t m = n - i < (size_t)kRunsPerPiece ? n - i : (size_t)kRunsPerPiece;
+        std::memcpy(&piece, host_runs + i, m * sizeof(TableRun));
+        hipLaunchKernelGGL(table_runs_kernel, dim3((unsigned)m), dim3(64), 0, stream, piece, (uint8_t*)d_table,
+                           (uint32_t)off_schedule);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+hipError_t launch_table_literals(const TableLiteral* host_literals, size_t n, void* d_table, size_t off_schedule,
+                                 hipStream_t stream) {
+    TablePiece piece;
+    for (size_t i = 0; i < n; i += kLiteralsPerPiece) {
+        const size_t m = n - i < (size_t)kLiteralsPerPiece ? n - i : (size_t)kLiteralsPerPiece;
+        std::memcpy(&piece, host_literals + i, m * sizeof(TableLiteral));
+        hipLaunchKernelGGL(table_literals_kernel, dim3((unsigned)m), dim3(64), 0, stream, piece, (uint8_t*)d_table,
+                           (uint32_t)off_schedule);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

@@ -272,6 +272,87 @@ struct WorkTable {
     }
 };
 
+// ---- the table as runs (internal.h: TableRun, TableLiteral) ------------------------------------------
+// Cuts the units of a filled blob (units | chunk_begin | schedule) into runs of units, a fixed stride
+// apart, whose 64-bit words (WorkUnit and UnitSchedule) advance by fixed steps; what is left of runs
+// shorter than kMinRun becomes literals.
+struct TableRecords {
+    std::vector<TableRun> runs;
+    std::vector<TableLiteral> literals;
+    // launches the records need, with what travels raw (chunk_begin, weight groups)
+    size_t launches(size_t raw_bytes) const {
+        return (runs.size() + kRunsPerPiece - 1) / kRunsPerPiece +
+               (literals.size() + kLiteralsPerPiece - 1) / kLiteralsPerPiece +
+               (raw_bytes + sizeof(TablePiece) - 1) / sizeof(TablePiece);
+    }
+};
+constexpr size_t kMinRun = 3;
+constexpr size_t kMaxRunStride = 2;         // the two operands of an op alternate in the table
+
+inline TableRecords table_records(const uint8_t* blob, size_t n_units, size_t off_schedule) {
+    TableRecords T;
+    auto unit_word = [&](size_t u, int w) { uint64_t v; std::memcpy(&v, blob + u * 64 + (size_t)w * 8, 8); return v; };
+    auto sched_word = [&](size_t u, int w) { uint64_t v; std::memcpy(&v, blob + off_schedule + u * 16 + (size_t)w * 8, 8); return v; };
+    // units a, a + s and b, b + s differ by the same steps
+    auto same_step = [&](size_t a, size_t b, size_t s) {
+        for (int w = 0; w < 8; ++w)
+            if (unit_word(b + s, w) - unit_word(b, w) != unit_word(a + s, w) - unit_word(a, w)) return false;
+        for (int w = 0; w < 2; ++w)
+            if (sched_word(b + s, w) - sched_word(b, w) != sched_word(a + s, w) - sched_word(a, w)) return false;
+        return true;
+    };
+    std::vector<char> done(n_units, 0);
+    for (size_t u = 0; u < n_units; ++u) {
+        if (done[u]) continue;
+        size_t best_len = 1, best_stride = 1;
+        for (size_t s = 1; s <= kMaxRunStride; ++s) {           // the longest run of units not yet covered
+            size_t len = 1;
+            while (u + len * s < n_units && !done[u + len * s] &&
+                   (len == 1 || same_step(u, u + (len - 1) * s, s)))
+                ++len;
+            if (len > best_len) { best_len = len; best_stride = s; }
+        }
+        if (best_len >= kMinRun) {
+            const size_t s = best_stride;
+            TableRun R;
+            std::memset(&R, 0, sizeof(R));
+            R.first_unit = (uint32_t)u;
+            R.count = (uint32_t)best_len;
+            R.stride = (uint32_t)s;
+            for (int w = 0; w < 8; ++w) { R.unit[w] = unit_word(u, w); R.unit_step[w] = unit_word(u + s, w) - unit_word(u, w); }
+            for (int w = 0; w < 2; ++w) { R.sched[w] = sched_word(u, w); R.sched_step[w] = sched_word(u + s, w) - sched_word(u, w); }
+            T.runs.push_back(R);
+            for (size_t k = 0; k < best_len; ++k) done[u + k * s] = 1;
+        } else {
+            TableLiteral L;
+            std::memset(&L, 0, sizeof(L));
+            L.unit_index = (uint32_t)u;
+            for (int w = 0; w < 8; ++w) L.unit[w] = unit_word(u, w);
+            for (int w = 0; w < 2; ++w) L.sched[w] = sched_word(u, w);
+            T.literals.push_back(L);
+            done[u] = 1;
+        }
+    }
+    return T;
+}
+
+// What the device makes of the records, on the host: the bytes of the units and of the schedule;
+// everything else in `blob` is left as it is.
+inline void table_expand(const TableRecords& T, uint8_t* blob, size_t off_schedule) {
+    auto put = [&](size_t u, const uint64_t* unit, const uint64_t* sched) {
+        std::memcpy(blob + u * 64, unit, 64);
+        std::memcpy(blob + off_schedule + u * 16, sched, 16);
+    };
+    for (const TableRun& R : T.runs)
+        for (uint32_t k = 0; k < R.count; ++k) {
+            uint64_t unit[8], sched[2];
+            for (int w = 0; w < 8; ++w) unit[w] = R.unit[w] + (uint64_t)k * R.unit_step[w];
+            for (int w = 0; w < 2; ++w) sched[w] = R.sched[w] + (uint64_t)k * R.sched_step[w];
+            put((size_t)R.first_unit + (size_t)k * R.stride, unit, sched);
+        }
+    for (const TableLiteral& L : T.literals) put(L.unit_index, L.unit, L.sched);
+}
+
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // Workspace layout shared by the absmax and the sensitivity calls:

@@ -135,6 +135,34 @@ int64_t hooks_check_linear_schedule(const amp_linear_desc_t* ops, int n_ops, int
     return bad;
 }
 
+// The table of a linear call as run and literal records: expands them on the host and compares with
+// the table itself; returns the number of differing bytes (or -1), and reports the record counts and
+// the launches the raw table would take.
+int64_t hooks_table_records(const amp_linear_desc_t* ops, int n_ops, int n_fmts, uint64_t* n_runs,
+                            uint64_t* n_literals, uint64_t* raw_pieces, uint64_t* n_units) {
+    WorkTable t;
+    if (build_linear(ops, n_ops, n_fmts, &t) != AMP_OK) return -1;
+    const WorkTable::Plan plan = t.plan(kDefaultScheduleBlock, true);
+    std::vector<uint8_t> blob(t.table_bytes());
+    t.fill_blob(plan, blob.data());
+    const size_t n = t.units.size(), off_cb = n * sizeof(WorkUnit), off_sched = t.schedule_offset();
+    const TableRecords rec = table_records(blob.data(), n, off_sched);
+    std::vector<uint8_t> check(blob);
+    std::memset(check.data(), 0xEE, off_cb);                                          // the units
+    std::memset(check.data() + off_sched, 0xEE, n * sizeof(UnitSchedule));
+    table_expand(rec, check.data(), off_sched);
+    int64_t bad = 0;
+    for (size_t i = 0; i < blob.size(); ++i) bad += blob[i] != check[i];
+    uint64_t covered = rec.literals.size();
+    for (const TableRun& R : rec.runs) covered += R.count;
+    if (covered != n) ++bad;
+    *n_runs = rec.runs.size();
+    *n_literals = rec.literals.size();
+    *raw_pieces = (blob.size() + sizeof(TablePiece) - 1) / sizeof(TablePiece);
+    *n_units = n;
+    return bad;
+}
+
 // row_len != 0 also replays the row tracking of a unit with one scale per row and counts every
 // vector whose tracked row differs from (element index / row_len), or that straddles two rows.
 int64_t hooks_replay_unit_rows(uint64_t x_addr, uint64_t dx_addr, const amp_layout_t* layout,

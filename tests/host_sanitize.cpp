@@ -17,6 +17,8 @@ int absmax_resident_blocks(int cus) { return 8 * cus; }
 int absmax_rows_resident_blocks(int cus) { return 8 * cus; }
 int sens_w_resident_blocks(int, int, int, int, int cus) { return 4 * cus; }
 hipError_t launch_table_write(const void*, size_t, void*, hipStream_t) { std::abort(); }
+hipError_t launch_table_runs(const TableRun*, size_t, void*, size_t, hipStream_t) { std::abort(); }
+hipError_t launch_table_literals(const TableLiteral*, size_t, void*, size_t, hipStream_t) { std::abort(); }
 hipError_t launch_small_setup(const void*, size_t, void*, size_t, size_t, uint32_t, uint32_t, ResolvedUnit*, ChunkRef*,
                               int, hipStream_t) { std::abort(); }
 hipError_t launch_prepare(const WorkUnit*, const uint32_t*, const UnitSchedule*, uint32_t, uint32_t,

@@ -300,6 +300,45 @@ def test_schedule_is_a_permutation_of_the_chunks(shapes):
         assert inter.value > 0
 
 
+@pytest.mark.parametrize("shapes,ragged,max_records", [
+    ([(16, 2048, 4096, 4096), (16, 2048, 4096, 11008), (16, 2048, 11008, 4096)], False, 6),   # x and w of each op: a run
+    ([(4, 256, 1024, 1024)], False, 2),
+    ([(32, 100, 512, 176)] * 6, True, None),                   # ragged samples: the x units do not repeat
+    ([(3, 5, 8, 9), (1, 7, 64, 64), (5, 1, 4099, 33), (2, 9, 16, 16)], False, None),
+])
+def test_table_travels_as_runs_and_expands_to_the_same_bytes(shapes, ragged, max_records):
+    """The unit table of a call, cut into runs of units whose fields advance by fixed steps plus
+    literal units, expands to the table byte for byte; the samples of a uniform op collapse into one
+    run per operand."""
+    L = host_hooks()
+    L.hooks_table_records.restype = C.c_int64
+    descs, keep = [], []
+    base = 0x100000
+    rng = np.random.default_rng(11)
+    for (R, tokens, Cd, K) in shapes:
+        d = amp.LinearDesc()
+        d.x = d.dx = d.w = base
+        d.dw = base + 64
+        d.C, d.K, d.tokens, d.R = Cd, K, tokens, R
+        if ragged:
+            offs = np.concatenate([[0], np.cumsum(rng.integers(1, tokens + 1, R))]).astype(np.int64)
+            keep.append(offs)
+            d.tokens = 0
+            d.sample_row_offsets = offs.ctypes.data_as(C.POINTER(C.c_int64))
+        d.x_scale = d.x_inv = d.w_scale = d.w_inv = base
+        descs.append(d)
+        base += 0x10000000
+    arr = (amp.LinearDesc * len(descs))(*descs)
+    runs, lits, raw, units = C.c_uint64(), C.c_uint64(), C.c_uint64(), C.c_uint64()
+    bad = L.hooks_table_records(arr, len(descs), 2, C.byref(runs), C.byref(lits), C.byref(raw), C.byref(units))
+    assert bad == 0
+    assert units.value == 2 * sum(s_[0] for s_ in shapes)
+    if max_records is not None:
+        assert lits.value == 0 and runs.value <= max_records
+    if ragged:
+        assert lits.value > 0 and runs.value >= len(shapes)    # the weights' units still form runs
+
+
 def test_epilogue_matches_oracle():
     rng = np.random.default_rng(4)
     R, nf = 5, 2
