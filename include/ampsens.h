@@ -40,8 +40,9 @@
  *     stream).  They launch kernels and nothing else: no device or pinned memory is allocated or
  *     freed, no copy engine is used, nothing waits for the GPU, and nothing of the host arguments
  *     is referenced after the call returns (the small descriptor table of a call travels to the
- *     head of the workspace as kernel arguments, 3840 bytes per launch).  Such calls may be
- *     recorded into a HIP graph by stream capture.
+ *     head of the workspace as kernel arguments, at most 3840 bytes per launch; the records of
+ *     an operand's samples, which differ by fixed steps, travel as one record that a kernel
+ *     expands).  Such calls may be recorded into a HIP graph by stream capture.
  *   - Every device call is a set-up (host work per op, the table, the chunk map) followed by a run
  *     (kernel launches only).  Callers that repeat a call on the same buffers keep the set-up:
  *     amp_*_setup fills a caller-owned amp_plan_t, amp_run replays it (see "plans" below).
