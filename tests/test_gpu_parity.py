@@ -146,10 +146,10 @@ def test_absmax_scale_bit_exact_many_tensors():
 
 
 def test_absmax_on_both_sides_of_the_one_launch_set_up_limit():
-    """The absmax call sets up in one launch up to 8 192 chunks (2^29 elements) and with a launch of its
+    """The absmax call sets up in one launch up to 8 192 chunks (2^28 elements) and with a launch of its
     own per step beyond: one buffer, its first 8 192 chunks and one vector more, the largest value in the
     last element of each, amax and scales bit for bit against the oracle."""
-    n0 = 8192 * 65536
+    n0 = 8192 * 32768
     g = torch.Generator(device=DEV)
     g.manual_seed(77)
     x = (torch.randn(n0 + 8, device=DEV, generator=g) * 0.5).to(torch.bfloat16)
@@ -158,7 +158,7 @@ def test_absmax_on_both_sides_of_the_one_launch_set_up_limit():
     host = x.view(torch.int16).cpu().numpy().view(np.uint16)
     fmts = [amp.E4M3, amp.E5M2]
     for n in (n0, n0 + 8):
-        say("absmax of %d elements (%d chunks)" % (n, (n + 65535) // 65536))
+        say("absmax of %d elements (%d chunks)" % (n, (n + 32767) // 32768))
         tensors = [amp.tensor(x, amp.dense(n), 1)]
         d_amax = torch.zeros(1, device=DEV)
         d_scale = torch.zeros(1, 2, device=DEV)
