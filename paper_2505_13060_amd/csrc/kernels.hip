@@ -40,6 +40,7 @@ typedef const uint16_t __attribute__((address_space(1)))* gptr16_t;   // global 
 typedef const u32x4 __attribute__((address_space(1)))* gptr128_t;
 typedef const float __attribute__((address_space(1)))* gptrf_t;
 typedef const float2_t __attribute__((address_space(1)))* gptrf2_t;
+typedef const char __attribute__((address_space(1)))* gptr8_t;
 
 template <int FMT> struct Fp8;
 template <> struct Fp8<0> {                       // OCP E4M3
@@ -1381,6 +1382,7 @@ struct FusedTile {
     bool live;                                     // this thread's row exists
     int64_t row;                                   // row of the unit (table index); 0 when not live
     int32_t len;                                   // valid elements of the row
+    int64_t row0;                                  // the tile's first row (thread t holds row0 + (t >> lanes_log2)): the same for the workgroup
 };
 struct FusedTileWalk {
     int32_t rows, cols;
@@ -1408,7 +1410,7 @@ struct FusedTileWalk {
     static __device__ __forceinline__ int whole_groups_up(int v) { return (v + kFusedGroup - 1) / kFusedGroup * kFusedGroup; }
     __device__ __forceinline__ FusedTile next() {
         FusedTile t;
-        t.valid = false; t.lanes_log2 = 2; t.nv_exact = 0; t.nv = 0; t.live = false; t.row = 0; t.len = 0;
+        t.valid = false; t.lanes_log2 = 2; t.nv_exact = 0; t.nv = 0; t.live = false; t.row = 0; t.len = 0; t.row0 = 0;
         if (left <= 0) return t;
         --left;
         if (!causal) {
@@ -1423,6 +1425,7 @@ struct FusedTileWalk {
             t.lanes_log2 = lg;
             t.live = r < rows;
             t.row = t.live ? r : 0;
+            t.row0 = r0;
             t.len = cols;
             t.nv = geo.nv;
             t.nv_exact = r0 + RT <= rows ? whole_groups_down(row_vecs >> lg) : 0;
@@ -1438,6 +1441,7 @@ struct FusedTileWalk {
         t.lanes_log2 = lg;
         t.live = (tid >> lg) < ct.n_rows;
         t.row = mat_row0 + (t.live ? i : (int32_t)ct.row0);
+        t.row0 = mat_row0 + (int32_t)ct.row0;
         t.len = t.live ? causal_row_len(i, rows, cols) : 0;
         const int32_t len_min = causal_row_len((int32_t)ct.row0, rows, cols);
         const int32_t len_max = causal_row_len((int32_t)ct.row0 + ct.n_rows - 1, rows, cols);
@@ -1488,8 +1492,7 @@ struct FusedRows {
     // taken back with and mul their multiplier (one_format_pow2).
     __device__ __forceinline__ void row_scales(const FusedTile& t, uint32_t m2, float (&sc)[NF], float (&iv)[NF], float& mul) {
         const uint32_t m = row_max(m2, t.lanes_log2);
-        scales_of_row(m, t.live && (threadIdx.x & ((1 << t.lanes_log2) - 1)) == 0, ts + t.row * NF, ti + t.row * NF, 0,
-                      sc, iv, mul);
+        scales_of_row(m, t.live && (threadIdx.x & ((1 << t.lanes_log2) - 1)) == 0, ts, ti, t.row, sc, iv, mul);
     }
 
     // Maximum over the 2^lg threads of a row (consecutive lanes, lg >= 2): quads, then halves of a 16-lane
@@ -1526,7 +1529,7 @@ struct FusedRows {
 
     // The scales of the row whose absmax (as bits) is m: each thread of a quad derives one of (scale_0, inv_0,
     // scale_1, inv_1), then the quad shares them; the thread with `writer` set stores the row's table entries.
-    __device__ __forceinline__ void scales_of_row(uint32_t m, bool writer, float* ts_base, float* ti_base, int row,
+    __device__ __forceinline__ void scales_of_row(uint32_t m, bool writer, float* ts_base, float* ti_base, int64_t row,
                                                   float (&sc)[NF], float (&iv)[NF], float& mul) {
         {
             const int q = threadIdx.x & 3;
@@ -1571,10 +1574,17 @@ struct FusedRows {
         const gptr128_t px = reinterpret_cast<gptr128_t>(x + t.row * (int64_t)cols);
         const gptr128_t pg = reinterpret_cast<gptr128_t>(g + t.row * (int64_t)cols);
         if (t.nv_exact >= NV) {                        // every vector of every thread is a whole vector of a live row
+            // (a tile of a dense unit, or the one-row tile of a causal row that is as long as the tile).  One base
+            // for the workgroup, the tile's first row, and a 32-bit byte offset per lane that does not change
+            // from tile to tile
+            const gptr8_t bx = reinterpret_cast<gptr8_t>(x + t.row0 * (int64_t)cols);
+            const gptr8_t bg = reinterpret_cast<gptr8_t>(g + t.row0 * (int64_t)cols);
+            const uint32_t off = ((uint32_t)(threadIdx.x >> lg) * (uint32_t)cols + (uint32_t)j * kVec) * 2u;
+            const uint32_t step = (uint32_t)(kVec * 2) << lg;
 #pragma unroll
-            for (int k = 0; k < NV; ++k) r.x[k] = load128<true>(px + (j + (k << lg)));
+            for (int k = 0; k < NV; ++k) r.x[k] = load128<true>(reinterpret_cast<gptr128_t>(bx + (off + (uint32_t)k * step)));
 #pragma unroll
-            for (int k = 0; k < NV; ++k) r.g[k] = load128<true>(pg + (j + (k << lg)));
+            for (int k = 0; k < NV; ++k) r.g[k] = load128<true>(reinterpret_cast<gptr128_t>(bg + (off + (uint32_t)k * step)));
         } else {
             const int nvr = (t.len + kVec - 1) / kVec;
             const int last = nvr > 0 ? nvr - 1 : 0;
