@@ -1380,7 +1380,7 @@ struct FusedTile {
     int nv_exact;                                  // vectors k < nv_exact of every thread are whole vectors of a live row
     int nv;                                        // vectors per thread (whole groups); those past a row's end are masked
     bool live;                                     // this thread's row exists
-    int64_t row;                                   // row of the unit (table index); 0 when not live
+    int64_t row;                                   // row of the unit (table index); the tile's first row when not live
     int32_t len;                                   // valid elements of the row
     int64_t row0;                                  // the tile's first row (thread t holds row0 + (t >> lanes_log2)): the same for the workgroup
 };
@@ -1424,7 +1424,7 @@ struct FusedTileWalk {
             t.valid = true;
             t.lanes_log2 = lg;
             t.live = r < rows;
-            t.row = t.live ? r : 0;
+            t.row = t.live ? r : r0;
             t.row0 = r0;
             t.len = cols;
             t.nv = geo.nv;
@@ -1571,8 +1571,6 @@ struct FusedRows {
         constexpr int NV = kFusedRegNv;
         const int lg = t.lanes_log2;
         const int j = threadIdx.x & ((1 << lg) - 1);
-        const gptr128_t px = reinterpret_cast<gptr128_t>(x + t.row * (int64_t)cols);
-        const gptr128_t pg = reinterpret_cast<gptr128_t>(g + t.row * (int64_t)cols);
         if (t.nv_exact >= NV) {                        // every vector of every thread is a whole vector of a live row
             // (a tile of a dense unit, or the one-row tile of a causal row that is as long as the tile).  One base
             // for the workgroup, the tile's first row, and a 32-bit byte offset per lane that does not change
@@ -1586,18 +1584,24 @@ struct FusedRows {
 #pragma unroll
             for (int k = 0; k < NV; ++k) r.g[k] = load128<true>(reinterpret_cast<gptr128_t>(bg + (off + (uint32_t)k * step)));
         } else {
+            // vectors past a row's end are fetched from its last vector and masked later; a thread without a
+            // row takes the tile's first.  The same base and 32-bit offsets (a tile spans at most 256 rows of at
+            // most 8 192 elements)
+            const gptr8_t bx = reinterpret_cast<gptr8_t>(x + t.row0 * (int64_t)cols);
+            const gptr8_t bg = reinterpret_cast<gptr8_t>(g + t.row0 * (int64_t)cols);
+            const uint32_t row_off = (uint32_t)(t.row - t.row0) * (uint32_t)cols * 2u;
             const int nvr = (t.len + kVec - 1) / kVec;
             const int last = nvr > 0 ? nvr - 1 : 0;
-            int at[NV];
+            uint32_t at[NV];
 #pragma unroll
             for (int k = 0; k < NV; ++k) {
                 const int v = j + (k << lg);
-                at[k] = v < last ? v : last;
+                at[k] = row_off + (uint32_t)(v < last ? v : last) * (uint32_t)(kVec * 2);
             }
 #pragma unroll
-            for (int k = 0; k < NV; ++k) r.x[k] = load128<true>(px + at[k]);
+            for (int k = 0; k < NV; ++k) r.x[k] = load128<true>(reinterpret_cast<gptr128_t>(bx + at[k]));
 #pragma unroll
-            for (int k = 0; k < NV; ++k) r.g[k] = load128<true>(pg + at[k]);
+            for (int k = 0; k < NV; ++k) r.g[k] = load128<true>(reinterpret_cast<gptr128_t>(bg + at[k]));
         }
     }
 
